@@ -1,0 +1,168 @@
+"""Seeded synthetic inputs and parameter sets for the five benchmark workloads.
+
+This module holds no arithmetic of the method itself: it draws random numbers,
+lays out rays, and derives the per-level grid descriptor that both the HIP
+library and the CPU oracle receive as plain integers.  It depends on numpy only
+and is the one module the tests hand to both sides.
+
+The paper trains on calibrated multi-view image sets that are not available
+here; the ray batches below stand in for them (Sec. 3 "Background": n samples
+p(t_i) = o + t_i v along each camera ray).  What is kept from the real workload
+is the structure that matters to the kernels: 64 consecutive samples are
+collinear, samples concentrate near the centre of the unit cube, tables start as
+tiny uniform noise.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+
+MAX_LEVELS = 32
+
+
+@dataclass
+class Config:
+    """Shape descriptor shared by oracle and library (mirrors `neus2_config`)."""
+    n_levels: int
+    n_features: int
+    log2_table_size: int
+    active_levels: int
+    table_dtype: str                 # "f32" | "f16"
+    res: List[int]
+    dense: List[int]
+    sdf_dims: List[int]              # e.g. [32, 64, 64, 16]
+    color_dims: List[int]            # e.g. [38, 64, 64, 3] or [] when there is no colour net
+    samples_per_ray: int
+    loss_kind: int                   # 0: mean(d^2) + beta*eikonal ; 1: L1 colour + beta*eikonal
+    s: float
+    beta: float
+    name: str = ""
+
+    @property
+    def table_size(self) -> int:
+        return 1 << self.log2_table_size
+
+    @property
+    def enc_dim(self) -> int:
+        return self.n_levels * self.n_features
+
+
+def level_resolutions(n_levels: int, res_min: int, res_max: Optional[int] = None,
+                      growth: Optional[float] = None) -> List[int]:
+    """Grid resolution per level, geometric between res_min and res_max."""
+    if growth is None:
+        growth = math.exp(math.log(res_max / res_min) / (n_levels - 1))
+    res = [int(math.floor(res_min * growth ** l + 1e-9)) for l in range(n_levels)]
+    if res_max is not None:
+        res[-1] = int(res_max)
+    return res
+
+
+def dense_flags(res: List[int], table_size: int) -> List[int]:
+    """A level is stored densely when all (res+1)^3 vertices fit in its table."""
+    return [1 if (r + 1) ** 3 <= table_size else 0 for r in res]
+
+
+def make_config(k: int) -> Config:
+    """Descriptor of benchmark workload k (1..5)."""
+    if k == 1:
+        res = level_resolutions(8, 16, growth=1.5)
+        return Config(8, 2, 14, 8, "f32", res, dense_flags(res, 1 << 14), [16, 64, 16], [],
+                      1, 0, 20.0, 0.1, "cfg1-tiny-sdf")
+    if k in (2, 3, 5):
+        res = level_resolutions(16, 16, 2048)
+        return Config(16, 2, 19, 8 if k == 3 else 16, "f16", res, dense_flags(res, 1 << 19),
+                      [32, 64, 64, 16], [38, 64, 64, 3], 64, 1, 20.0, 0.1,
+                      {2: "cfg2-static-4096x64", 3: "cfg3-progressive-8192x64",
+                       5: "cfg5-dynamic-20x8192x64"}[k])
+    if k == 4:
+        res = level_resolutions(16, 16, 4096)
+        return Config(16, 2, 21, 16, "f16", res, dense_flags(res, 1 << 21),
+                      [32, 64, 64, 16], [38, 64, 64, 3], 64, 1, 20.0, 0.1, "cfg4-large-16384x64")
+    raise ValueError(f"unknown workload {k}")
+
+
+def default_rays(k: int) -> int:
+    return {1: 4096, 2: 4096, 3: 8192, 4: 16384, 5: 8192}[k]
+
+
+def _xavier(rng: np.random.Generator, n_out: int, n_in: int) -> np.ndarray:
+    bound = math.sqrt(6.0 / (n_in + n_out))
+    return rng.uniform(-bound, bound, size=(n_out, n_in)).astype(np.float32)
+
+
+def make_params(cfg: Config, seed: int) -> Dict[str, object]:
+    """Tables (stored dtype), SDF matrices H_l [n_l, n_{l-1}], colour matrices W_l."""
+    rng = np.random.default_rng(seed)
+    T, L, F = cfg.table_size, cfg.n_levels, cfg.n_features
+    tab = rng.uniform(-1e-4, 1e-4, size=(L, T, F))
+    tables = tab.astype(np.float16 if cfg.table_dtype == "f16" else np.float32)
+    H = [_xavier(rng, cfg.sdf_dims[i + 1], cfg.sdf_dims[i]) for i in range(len(cfg.sdf_dims) - 1)]
+    W = [_xavier(rng, cfg.color_dims[i + 1], cfg.color_dims[i]) for i in range(len(cfg.color_dims) - 1)]
+    return {"tables": tables, "H": H, "W": W}
+
+
+def make_points(n: int, seed: int) -> np.ndarray:
+    """Workload 1: points uniform in the unit cube, fp32."""
+    rng = np.random.default_rng(seed)
+    pos = rng.uniform(0.0, 1.0, size=(n, 3)).astype(np.float32)
+    return np.minimum(pos, np.float32(1.0 - 2.0 ** -24))
+
+
+def make_rays(n_rays: int, samples_per_ray: int, seed: int, to_cube: bool = True) -> Dict[str, np.ndarray]:
+    """Workloads 2-5: cameras on a radius-3 sphere looking at the origin with
+    +-0.3 jitter, stratified samples between the two unit-sphere intersections.
+
+    Returns pos [R*n,3] (unit-cube coordinates if `to_cube`, else world), dirs
+    [R,3], target rgb [R,3], all fp32.
+    """
+    rng = np.random.default_rng(seed)
+    u = rng.normal(size=(n_rays, 3))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    o = 3.0 * u
+    tgt = rng.uniform(-0.3, 0.3, size=(n_rays, 3))
+    v = tgt - o
+    v /= np.linalg.norm(v, axis=1, keepdims=True)
+    # |o + t v| = 1  ->  t^2 + 2 (o.v) t + |o|^2 - 1 = 0
+    b = np.sum(o * v, axis=1)
+    disc = b * b - (np.sum(o * o, axis=1) - 1.0)
+    root = np.sqrt(disc)
+    near, far = -b - root, -b + root
+    jit = rng.uniform(0.0, 1.0, size=(n_rays, samples_per_ray))
+    kk = np.arange(samples_per_ray)[None, :]
+    t = near[:, None] + (kk + jit) * ((far - near)[:, None] / samples_per_ray)
+    p = o[:, None, :] + t[:, :, None] * v[:, None, :]
+    if to_cube:
+        p = np.clip((p + 1.0) * 0.5, 0.0, 1.0 - 2.0 ** -24)
+    rgb = rng.uniform(0.0, 1.0, size=(n_rays, 3))
+    return {"pos": p.reshape(-1, 3).astype(np.float32), "dirs": v.astype(np.float32),
+            "target": rgb.astype(np.float32)}
+
+
+def make_rigid(seed: int, max_angle_deg: float = 5.0, max_shift: float = 0.05) -> Dict[str, np.ndarray]:
+    """Workload 5: a small axis-angle vector omega and a translation, float64."""
+    rng = np.random.default_rng(seed)
+    axis = rng.normal(size=3)
+    axis /= np.linalg.norm(axis)
+    angle = math.radians(rng.uniform(0.0, max_angle_deg))
+    shift = rng.normal(size=3)
+    shift *= rng.uniform(0.0, max_shift) / np.linalg.norm(shift)
+    return {"omega": axis * angle, "shift": shift}
+
+
+def make_workload(k: int, n_rays: Optional[int] = None, frame: int = 0) -> Dict[str, object]:
+    """Config, parameters and one batch for workload k; sizes may be overridden."""
+    cfg = make_config(k)
+    params = make_params(cfg, 2000 + k)
+    R = default_rays(k) if n_rays is None else n_rays
+    if k == 1:
+        batch = {"pos": make_points(R, 1000 + k)}
+    elif k == 5:
+        batch = make_rays(R, cfg.samples_per_ray, 1000 + k + 100 * frame, to_cube=False)
+        batch.update(make_rigid(3000 + k + 100 * frame))
+    else:
+        batch = make_rays(R, cfg.samples_per_ray, 1000 + k)
+    return {"cfg": cfg, "params": params, "batch": batch}

@@ -1,0 +1,190 @@
+/*
+ * neus2.h - C ABI of libneus2: the training-step hot path of NeuS2 (arXiv 2212.05231)
+ * as hand-written HIP kernels for gfx950 (MI355X), one GPU.
+ *
+ * Conventions for every call
+ *  - Returns NEUS2_OK (0) or a negative NEUS2_ERR_* code; neus2_last_error() gives a
+ *    thread-local message.  Arguments are validated on the host before anything is
+ *    launched; a call that fails validation touches no device memory.
+ *  - Pointers marked [device] are device pointers owned by the caller, 16-byte aligned,
+ *    row-major, valid until the work queued on `stream` has finished.  Pointers marked
+ *    [host] are read during the call only.  The library allocates no device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; they never synchronise.
+ *  - n is the number of sample points; for ray workloads n = rays * samples_per_ray and a
+ *    ray's samples are consecutive.
+ *
+ * Layouts
+ *  - tables  [L][T][F]   F = 2 features per entry, fp16 or fp32 (cfg->table_dtype).
+ *  - enc, q, d_enc: level-major [L][n][F] fp32 ("feature k = level*F + f of point i" is at
+ *    (level*n + i)*F + f).  jac: [L][n][F][3] fp32.
+ *  - y, d_y [n][16]; normal, d_normal, pos, d_pos [n][3]; rgb, d_rgb [n][3].
+ *  - SDF matrices H_l [n_l][n_{l-1}] and colour matrices W_l likewise, row-major fp32,
+ *    bias-free (Definition 1 of the paper).
+ */
+#ifndef NEUS2_H
+#define NEUS2_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NEUS2_MAX_LEVELS 32
+#define NEUS2_MAX_MATS 4
+
+enum {
+    NEUS2_OK = 0,
+    NEUS2_ERR_NULL = -1,        /* a required pointer is NULL */
+    NEUS2_ERR_SHAPE = -2,       /* a size is negative, too large, or not a multiple it must be */
+    NEUS2_ERR_CONFIG = -3,      /* the descriptor is inconsistent */
+    NEUS2_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned */
+    NEUS2_ERR_UNSUPPORTED = -5, /* a valid request this build has no kernel for */
+    NEUS2_ERR_HIP = -6          /* the HIP runtime reported an error at launch */
+};
+
+/* Shape descriptor.  Per-level resolution and dense flag are inputs, so that the caller's
+ * reference computation and the kernels can never disagree on them.  A level is dense
+ * (lexicographic vertex index) only if (res+1)^3 <= T; otherwise vertices are hashed. */
+typedef struct neus2_config {
+    int32_t n_levels;          /* L, 1..32 */
+    int32_t n_features;        /* F, must be 2 */
+    int32_t log2_table_size;   /* T = 1 << log2_table_size entries per level, 4..24 */
+    int32_t active_levels;     /* lambda of Sec. 4.3: levels >= this contribute zeros */
+    int32_t table_dtype;       /* 0 = fp32, 1 = fp16 */
+    int32_t res[NEUS2_MAX_LEVELS];
+    int32_t dense[NEUS2_MAX_LEVELS];
+    int32_t n_sdf_mats;        /* K: 2 or 3 */
+    int32_t sdf_dims[NEUS2_MAX_MATS + 1];   /* {L*F, 64, (64,) 16} */
+    int32_t n_color_mats;      /* 0 (no colour network) or 3 */
+    int32_t color_dims[NEUS2_MAX_MATS + 1]; /* {38, 64, 64, 3} */
+    int32_t samples_per_ray;   /* 1..64 */
+    int32_t loss_kind;         /* 0: mean(d^2) + beta*eikonal; 1: L1 colour + beta*eikonal */
+    float s;                   /* slope of the logistic CDF Phi_s (held fixed) */
+    float beta;                /* weight of the eikonal term in Eq. 4 */
+} neus2_config;
+
+const char* neus2_last_error(void);
+int neus2_version(void);
+
+/* Check a descriptor without a GPU.  Returns NEUS2_OK or the error a compute call would give. */
+int neus2_validate_config(const neus2_config* cfg /*[host]*/);
+
+/* Multi-resolution hash encoding (Sec. 3 "InstantNGP", Sec. 4.1) and its Jacobian de/dx,
+ * which Eq. 2 (n = grad_x d) and Eq. 7 need.  Per level: the point is clamped to [0,1], the
+ * grid coordinate is the single binary32 product x*res, the cell is its floor (at most
+ * res-1), and the 8 cell vertices are interpolated trilinearly.  Levels >= active_levels
+ * write zeros (Sec. 4.3).
+ *   pos [device, n*3]  tables [device]  enc [device, L*n*F]  jac [device, L*n*F*3]
+ *   dbg_idx [device, n*L*8 uint32] or NULL: the table slot of every corner, corner
+ *   c = dx + 2*dy + 4*dz. */
+int neus2_hash_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
+                      float* enc, float* jac, uint32_t* dbg_idx, void* stream);
+
+/* SDF network forward (Eq. 1: (d,g) = f_Theta(e)) and analytic normal (Eq. 2) via
+ * dd/de = H_K^(0,_) G ... G H_1 (supplement Sec. B).
+ *   H [host array of K device pointers]
+ *   y [device, n*16] (d = y[.,0]);  q [device, L*n*F] = dd/de;  normal [device, n*3] = q*jac. */
+int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* jac,
+                       const float* const* H, int64_t n, float* y, float* q, float* normal,
+                       void* stream);
+
+/* Colour network forward (Eq. 3): rgb = sigmoid(W_3 relu(W_2 relu(W_1 cin))),
+ * cin = [pos(3), normal(3), SH16(dir)(16), y(16)]; dirs [device, rays*3] are unit vectors,
+ * sample i uses ray i / samples_per_ray.  rgb [device, n*3]. */
+int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal,
+                    const float* dirs, const float* y, const float* const* W, int64_t n,
+                    float* rgb, void* stream);
+
+/* First-order backward of the colour network (the paper needs no second-order term for
+ * Upsilon, text after Eq. 6).
+ *   d_rgb [device, n*3] in;  d_sdf [device, n] in or NULL (render's dL/dd, added to d_y[.,0]);
+ *   dW [host array of 3 device pointers]: gradients are ADDED into them;
+ *   d_y [device, n*16] is OVERWRITTEN with the colour network's dL/d(d,g) (+ d_sdf);
+ *   d_normal [device, n*3] is ADDED into (it already holds the eikonal part);
+ *   d_pos [device, n*3] or NULL is OVERWRITTEN with the colour network's dL/dx. */
+int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal,
+                    const float* dirs, const float* y, const float* const* W,
+                    const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
+                    float* d_y, float* d_normal, float* d_pos, void* stream);
+
+/* NeuS compositing (supplement Sec. E.3): alpha_i = max((Phi(d_i)-Phi(d_{i+1}))/Phi(d_i), 0),
+ * alpha of the last sample is 0, T_i = prod_{j<i}(1-alpha_j), C = sum T_i alpha_i c_i.
+ *   sdf [device]: d of sample i at sdf[i*sdf_stride];  rgb [device, n*3];
+ *   C [device, rays*3];  weights [device, n] = T_i alpha_i. */
+int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_stride,
+                      const float* rgb, int64_t rays, float* C, float* weights, void* stream);
+
+/* Backward of neus2_render_rays: dC [device, rays*3] -> d_sdf [device, n], d_rgb [device, n*3]
+ * (both overwritten). */
+int neus2_render_rays_bwd(const neus2_config* cfg, const float* sdf, int64_t sdf_stride,
+                          const float* rgb, const float* dC, int64_t rays, float* d_sdf,
+                          float* d_rgb, void* stream);
+
+/* Loss of Eq. 4 and its first adjoints.
+ *   loss_kind 1: loss = sum|C - target| / rays + beta * mean((|n|-1)^2); C, target
+ *     [device, rays*3]; dC [device, rays*3] = sign(C-target)/rays.
+ *   loss_kind 0: loss = mean(d^2) + beta * mean((|n|-1)^2); C, target, dC are NULL and
+ *     d_y [device, n*16] is overwritten with (2 d / n) e_0.  For loss_kind 1 d_y may be NULL.
+ *   d_normal [device, n*3] is overwritten with the eikonal part (2 beta / n)(|n|-1) n/|n|.
+ *   loss [device, 2 floats]: {first term, beta * eikonal term}; ADDED into (zero it first). */
+int neus2_loss(const neus2_config* cfg, const float* C, const float* target, const float* normal,
+               const float* y, int64_t rays, int64_t n, float* loss, float* dC, float* d_normal,
+               float* d_y, void* stream);
+
+/* Backward through the SDF network and the encoding, first order plus the second-order term
+ * of Eqs. 7-8 / Theorem 1:
+ *   dH_l += delta_l a_{l-1}^T + S_l^T t_{l-1}^T,  t_0 = (de/dx) dL/dn,  t_l = G_l H_l t_{l-1};
+ *   d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a * d_a w_c.
+ *   d_y [device, n*16], d_normal [device, n*3]: total adjoints of (d,g) and n.
+ *   dH [host array of K device pointers], d_tables [device, L*T*F fp32]: ADDED into.
+ *   d_enc [device, L*n*F]: overwritten with dL/de (also the scratch between the two kernels).
+ *   d_pos [device, n*3] or NULL: if given, ADDED into with (de/dx)^T dL/de plus the mixed
+ *   second derivative of the interpolation contracted with q and dL/dn (needed only when
+ *   positions are themselves functions of a learnable transform, Eq. 9). */
+int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables,
+                      const float* enc, const float* jac, const float* const* H, const float* q,
+                      const float* d_y, const float* d_normal, int64_t n, float* const* dH,
+                      float* d_tables, float* d_enc, float* d_pos, void* stream);
+
+/* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
+ *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
+ *   the full-precision copy, is updated, and param receives its round-to-nearest-even.
+ *   grad, m, v [device, fp32].  t >= 1 is the step number.  zero_grad != 0 clears grad. */
+int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count,
+                    int dtype, float lr, float beta1, float beta2, float eps, int t,
+                    int zero_grad, void* stream);
+
+/* Global rigid transform of Eq. 9, x_c = R (x + T), then the affine map scale*x_c + offset
+ * that takes world coordinates to the unit cube.  R [host, 9 row-major], T [host, 3]. */
+int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset,
+                    int64_t n, float* out, void* stream);
+
+/* Reductions for the transform's gradient: with g = scale * d_out,
+ * Mb[0..8] += sum g (x+T)^T (= dL/dR, row-major), Mb[9..11] += sum g.  Mb [device, 12]. */
+int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float scale, int64_t n,
+                    float* Mb, void* stream);
+
+/* All buffers of one training step, for neus2_train_step.  Every pointer is [device] except
+ * H, W, dH, dW, which are [host] arrays of device pointers.  Sizes as in the calls above;
+ * rays * samples_per_ray = n. */
+typedef struct neus2_step_buffers {
+    const float* pos; const float* dirs; const float* target; const void* tables;
+    const float* const* H; const float* const* W;
+    float* enc; float* jac; float* y; float* q; float* normal; float* rgb;
+    float* C; float* weights; float* loss;
+    float* dC; float* d_sdf; float* d_rgb; float* d_y; float* d_normal; float* d_enc;
+    float* d_pos;              /* NULL unless the position gradient is wanted */
+    float* const* dH; float* const* dW; float* d_tables;
+} neus2_step_buffers;
+
+/* One forward + backward pass (everything above except Adam and the rigid transform), in the
+ * order encode, SDF, colour, render, loss, render bwd, colour bwd, SDF bwd + scatter.
+ * loss is zeroed first; dH, dW and d_tables are ADDED into. */
+int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* buf, int64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NEUS2_H */

@@ -1,0 +1,247 @@
+"""ctypes binding of libneus2.so: the same names as include/neus2.h, argument marshalling
+only.  Tensors are torch tensors on the GPU (torch owns memory and streams); every step of
+the computation runs inside the library's HIP kernels.  There is no fallback: if the
+library has not been built, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libneus2.so")
+
+MAX_LEVELS = 32
+MAX_MATS = 4
+
+ERROR_NAMES = {0: "OK", -1: "ERR_NULL", -2: "ERR_SHAPE", -3: "ERR_CONFIG", -4: "ERR_ALIGN",
+               -5: "ERR_UNSUPPORTED", -6: "ERR_HIP"}
+
+
+class Neus2Config(C.Structure):
+    _fields_ = [
+        ("n_levels", C.c_int32), ("n_features", C.c_int32), ("log2_table_size", C.c_int32),
+        ("active_levels", C.c_int32), ("table_dtype", C.c_int32),
+        ("res", C.c_int32 * MAX_LEVELS), ("dense", C.c_int32 * MAX_LEVELS),
+        ("n_sdf_mats", C.c_int32), ("sdf_dims", C.c_int32 * (MAX_MATS + 1)),
+        ("n_color_mats", C.c_int32), ("color_dims", C.c_int32 * (MAX_MATS + 1)),
+        ("samples_per_ray", C.c_int32), ("loss_kind", C.c_int32),
+        ("s", C.c_float), ("beta", C.c_float),
+    ]
+
+
+_P = C.c_void_p
+
+
+class Neus2StepBuffers(C.Structure):
+    _fields_ = [(name, _P) for name in (
+        "pos", "dirs", "target", "tables", "H", "W",
+        "enc", "jac", "y", "q", "normal", "rgb", "C", "weights", "loss",
+        "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables")]
+
+
+class Neus2Error(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libneus2: {ERROR_NAMES.get(code, code)}: {message}")
+        self.code = code
+
+
+_lib = None
+
+_SIGNATURES = {
+    "neus2_last_error": (C.c_char_p, []),
+    "neus2_version": (C.c_int, []),
+    "neus2_validate_config": (C.c_int, [C.POINTER(Neus2Config)]),
+    "neus2_hash_encode": (C.c_int, [C.POINTER(Neus2Config), _P, _P, C.c_int64, _P, _P, _P, _P]),
+    "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
+    "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
+    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, C.c_int64, _P, _P, _P]),
+    "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
+    "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
+                                  C.c_float, C.c_int, C.c_int, _P]),
+    "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
+    "neus2_rigid_bwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
+    "neus2_train_step": (C.c_int, [C.POINTER(Neus2Config), C.POINTER(Neus2StepBuffers), C.c_int64, _P]),
+}
+
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2212_05231_amd.build` first")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        raise Neus2Error(code, lib().neus2_last_error().decode())
+
+
+def make_config(cfg) -> Neus2Config:
+    """`cfg` is a workloads.Config (or anything with the same attributes)."""
+    c = Neus2Config()
+    c.n_levels, c.n_features, c.log2_table_size = cfg.n_levels, cfg.n_features, cfg.log2_table_size
+    c.active_levels = cfg.active_levels
+    c.table_dtype = 1 if cfg.table_dtype == "f16" else 0
+    for l in range(cfg.n_levels):
+        c.res[l] = cfg.res[l]
+        c.dense[l] = cfg.dense[l]
+    c.n_sdf_mats = len(cfg.sdf_dims) - 1
+    for i, d in enumerate(cfg.sdf_dims):
+        c.sdf_dims[i] = d
+    c.n_color_mats = max(len(cfg.color_dims) - 1, 0)
+    for i, d in enumerate(cfg.color_dims):
+        c.color_dims[i] = d
+    c.samples_per_ray, c.loss_kind, c.s, c.beta = cfg.samples_per_ray, cfg.loss_kind, cfg.s, cfg.beta
+    return c
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to libneus2 must be contiguous")
+    return t.data_ptr()
+
+
+def _ptr_array(ts: Sequence):
+    arr = (C.c_void_p * max(len(ts), 1))()
+    for i, t in enumerate(ts):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def validate_config(c: Neus2Config) -> int:
+    return lib().neus2_validate_config(C.byref(c))
+
+
+def hash_encode(c, pos, tables, enc, jac, dbg_idx=None):
+    _check(lib().neus2_hash_encode(C.byref(c), _ptr(pos), _ptr(tables), pos.shape[0], _ptr(enc), _ptr(jac),
+                                   _ptr(dbg_idx), _stream()))
+
+
+def sdf_fwd_grad(c, enc, jac, H, n, y, q, normal):
+    _check(lib().neus2_sdf_fwd_grad(C.byref(c), _ptr(enc), _ptr(jac), _ptr_array(H), n, _ptr(y), _ptr(q),
+                                    _ptr(normal), _stream()))
+
+
+def color_fwd(c, pos, normal, dirs, y, W, n, rgb):
+    _check(lib().neus2_color_fwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(y), _ptr_array(W), n,
+                                 _ptr(rgb), _stream()))
+
+
+def color_bwd(c, pos, normal, dirs, y, W, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None):
+    _check(lib().neus2_color_bwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(y), _ptr_array(W),
+                                 _ptr(d_rgb), _ptr(d_sdf), n, _ptr_array(dW), _ptr(d_y), _ptr(d_normal),
+                                 _ptr(d_pos), _stream()))
+
+
+def render_rays(c, sdf, sdf_stride, rgb, rays, Cout, weights):
+    _check(lib().neus2_render_rays(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), rays, _ptr(Cout), _ptr(weights),
+                                   _stream()))
+
+
+def render_rays_bwd(c, sdf, sdf_stride, rgb, dC, rays, d_sdf, d_rgb):
+    _check(lib().neus2_render_rays_bwd(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), _ptr(dC), rays, _ptr(d_sdf),
+                                       _ptr(d_rgb), _stream()))
+
+
+def loss(c, Cimg, target, normal, y, rays, n, loss_out, dC, d_normal, d_y):
+    _check(lib().neus2_loss(C.byref(c), _ptr(Cimg), _ptr(target), _ptr(normal), _ptr(y), rays, n, _ptr(loss_out),
+                            _ptr(dC), _ptr(d_normal), _ptr(d_y), _stream()))
+
+
+def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos=None):
+    _check(lib().neus2_sdf_bwd_2nd(C.byref(c), _ptr(pos), _ptr(tables), _ptr(enc), _ptr(jac), _ptr_array(H),
+                                   _ptr(q), _ptr(d_y), _ptr(d_normal), n, _ptr_array(dH), _ptr(d_tables),
+                                   _ptr(d_enc), _ptr(d_pos), _stream()))
+
+
+def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True):
+    _check(lib().neus2_adam_step(_ptr(param), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), grad.numel(), dtype,
+                                 lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
+
+
+def rigid_fwd(pos, R, T, scale, offset, out):
+    Ra = (C.c_float * 9)(*[float(x) for x in R])
+    Ta = (C.c_float * 3)(*[float(x) for x in T])
+    _check(lib().neus2_rigid_fwd(_ptr(pos), Ra, Ta, scale, offset, pos.shape[0], _ptr(out), _stream()))
+
+
+def rigid_bwd(pos, T, d_out, scale, Mb):
+    Ta = (C.c_float * 3)(*[float(x) for x in T])
+    _check(lib().neus2_rigid_bwd(_ptr(pos), Ta, _ptr(d_out), scale, pos.shape[0], _ptr(Mb), _stream()))
+
+
+class Step:
+    """All device buffers of one training step, allocated once with torch, plus the
+    `neus2_step_buffers` struct that `train_step` hands to the library."""
+
+    def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda"):
+        import torch
+        self.cfg, self.c, self.n = cfg, make_config(cfg), n
+        L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
+        self.rays = n // cfg.samples_per_ray
+        f32 = dict(dtype=torch.float32, device=device)
+        tdt = torch.float16 if cfg.table_dtype == "f16" else torch.float32
+        self.tables = torch.as_tensor(params["tables"]).to(device=device, dtype=tdt).contiguous()
+        self.H = [torch.as_tensor(h).to(**f32).contiguous() for h in params["H"]]
+        self.W = [torch.as_tensor(w).to(**f32).contiguous() for w in params["W"]]
+        self.pos = torch.zeros(n, 3, **f32)
+        self.dirs = torch.zeros(max(self.rays, 1), 3, **f32)
+        self.target = torch.zeros(max(self.rays, 1), 3, **f32)
+        z = lambda *shape: torch.zeros(*shape, **f32)
+        self.enc, self.jac, self.q, self.d_enc = z(L, n, F), z(L, n, F, 3), z(L, n, F), z(L, n, F)
+        self.y, self.d_y = z(n, 16), z(n, 16)
+        self.normal, self.d_normal = z(n, 3), z(n, 3)
+        self.rgb, self.d_rgb = z(n, 3), z(n, 3)
+        self.C, self.dC = z(max(self.rays, 1), 3), z(max(self.rays, 1), 3)
+        self.weights, self.d_sdf = z(n), z(n)
+        self.loss = z(4)
+        self.d_pos = z(n, 3) if want_pos_grad else None
+        self.dH = [torch.zeros_like(h) for h in self.H]
+        self.dW = [torch.zeros_like(w) for w in self.W]
+        self.d_tables = z(L, T, F)
+        self._H, self._W = _ptr_array(self.H), _ptr_array(self.W)
+        self._dH, self._dW = _ptr_array(self.dH), _ptr_array(self.dW)
+        b = Neus2StepBuffers()
+        for name in ("pos", "dirs", "target", "tables", "enc", "jac", "y", "q", "normal", "rgb", "C", "weights",
+                     "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables"):
+            setattr(b, name, _ptr(getattr(self, name)))
+        b.H, b.W = C.cast(self._H, _P), C.cast(self._W, _P)
+        b.dH, b.dW = C.cast(self._dH, _P), C.cast(self._dW, _P)
+        self.buffers = b
+
+    def set_batch(self, batch: Dict[str, object]) -> None:
+        import torch
+        self.pos.copy_(torch.as_tensor(batch["pos"], dtype=torch.float32))
+        if "dirs" in batch:
+            self.dirs.copy_(torch.as_tensor(batch["dirs"], dtype=torch.float32))
+            self.target.copy_(torch.as_tensor(batch["target"], dtype=torch.float32))
+
+    def zero_grads(self) -> None:
+        for g in self.dH + self.dW:
+            g.zero_()
+        self.d_tables.zero_()
+
+    def train_step(self) -> None:
+        _check(lib().neus2_train_step(C.byref(self.c), C.byref(self.buffers), self.n, _stream()))

@@ -1,0 +1,219 @@
+// Host side of the C ABI: argument validation, error reporting, and the calls that are
+// sequences of the kernels in the other translation units.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace neus2 {
+
+namespace {
+thread_local char g_error[512] = "";
+}
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_ptr(const void* p, const char* name, bool required) {
+    if (!p) return required ? fail(NEUS2_ERR_NULL, "%s is NULL", name) : NEUS2_OK;
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) != 0) return fail(NEUS2_ERR_ALIGN, "%s is not 16-byte aligned", name);
+    return NEUS2_OK;
+}
+
+int check_launch(const char* what) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(NEUS2_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return NEUS2_OK;
+}
+
+int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+int persistent_blocks(const void* kernel, int threads, int64_t want) {
+    int per_cu = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) {
+        (void)hipGetLastError();
+        per_cu = 1;
+    }
+    const int64_t cap = (int64_t)per_cu * compute_units();
+    const int64_t b = want < cap ? want : cap;
+    return (int)(b < 1 ? 1 : b);
+}
+
+int check_config(const neus2_config* c) {
+    if (!c) return fail(NEUS2_ERR_NULL, "cfg is NULL");
+    if (c->n_levels < 1 || c->n_levels > NEUS2_MAX_LEVELS)
+        return fail(NEUS2_ERR_CONFIG, "n_levels = %d, must be 1..%d", c->n_levels, NEUS2_MAX_LEVELS);
+    if (c->n_features != 2) return fail(NEUS2_ERR_UNSUPPORTED, "n_features = %d, only 2 is built", c->n_features);
+    if (c->log2_table_size < 4 || c->log2_table_size > 24)
+        return fail(NEUS2_ERR_CONFIG, "log2_table_size = %d, must be 4..24", c->log2_table_size);
+    if (c->active_levels < 0 || c->active_levels > c->n_levels)
+        return fail(NEUS2_ERR_CONFIG, "active_levels = %d outside 0..n_levels", c->active_levels);
+    if (c->table_dtype != 0 && c->table_dtype != 1)
+        return fail(NEUS2_ERR_CONFIG, "table_dtype = %d, must be 0 (fp32) or 1 (fp16)", c->table_dtype);
+    const int64_t T = (int64_t)1 << c->log2_table_size;
+    for (int l = 0; l < c->n_levels; ++l) {
+        const int64_t r = c->res[l];
+        if (r < 1 || r > (1 << 20)) return fail(NEUS2_ERR_CONFIG, "res[%d] = %d, must be 1..2^20", l, (int)r);
+        if (c->dense[l] != 0 && c->dense[l] != 1) return fail(NEUS2_ERR_CONFIG, "dense[%d] must be 0 or 1", l);
+        if (c->dense[l] && (r + 1) * (r + 1) * (r + 1) > T)
+            return fail(NEUS2_ERR_CONFIG, "level %d is marked dense but (res+1)^3 = %lld exceeds T = %lld", l,
+                        (long long)((r + 1) * (r + 1) * (r + 1)), (long long)T);
+    }
+    if (c->n_sdf_mats != 2 && c->n_sdf_mats != 3)
+        return fail(NEUS2_ERR_UNSUPPORTED, "n_sdf_mats = %d, kernels exist for 2 and 3", c->n_sdf_mats);
+    if (c->sdf_dims[0] != c->n_levels * c->n_features)
+        return fail(NEUS2_ERR_CONFIG, "sdf_dims[0] = %d must equal n_levels * n_features = %d", c->sdf_dims[0],
+                    c->n_levels * c->n_features);
+    if (c->sdf_dims[0] != 16 && c->sdf_dims[0] != 32)
+        return fail(NEUS2_ERR_UNSUPPORTED, "encoding width %d, kernels exist for 16 and 32", c->sdf_dims[0]);
+    for (int l = 1; l < c->n_sdf_mats; ++l)
+        if (c->sdf_dims[l] != 64) return fail(NEUS2_ERR_UNSUPPORTED, "sdf hidden width %d, only 64 is built", c->sdf_dims[l]);
+    if (c->sdf_dims[c->n_sdf_mats] != 16)
+        return fail(NEUS2_ERR_UNSUPPORTED, "sdf output width %d, must be 16 (d and 15 features)", c->sdf_dims[c->n_sdf_mats]);
+    if (c->n_color_mats != 0) {
+        if (c->n_color_mats != 3 || c->color_dims[0] != 38 || c->color_dims[1] != 64 || c->color_dims[2] != 64 ||
+            c->color_dims[3] != 3)
+            return fail(NEUS2_ERR_UNSUPPORTED, "colour network must be 38-64-64-3 (or absent)");
+    }
+    if (c->samples_per_ray < 1 || c->samples_per_ray > 64)
+        return fail(NEUS2_ERR_CONFIG, "samples_per_ray = %d, must be 1..64", c->samples_per_ray);
+    if (c->loss_kind != 0 && c->loss_kind != 1) return fail(NEUS2_ERR_CONFIG, "loss_kind = %d, must be 0 or 1", c->loss_kind);
+    if (!(c->s > 0.f)) return fail(NEUS2_ERR_CONFIG, "s must be positive");
+    if (!(c->beta >= 0.f)) return fail(NEUS2_ERR_CONFIG, "beta must be non-negative");
+    return NEUS2_OK;
+}
+
+GridDesc make_grid_desc(const neus2_config* cfg) {
+    GridDesc g;
+    memset(&g, 0, sizeof(g));
+    g.n_levels = cfg->n_levels;
+    g.active_levels = cfg->active_levels;
+    g.table_size = 1u << cfg->log2_table_size;
+    g.table_mask = g.table_size - 1u;
+    for (int l = 0; l < cfg->n_levels; ++l) {
+        g.res[l] = cfg->res[l];
+        if (cfg->dense[l]) g.dense_bits |= 1u << l;
+    }
+    return g;
+}
+
+int check_count(int64_t n, const char* name) {
+    if (n < 0) return fail(NEUS2_ERR_SHAPE, "%s = %lld is negative", name, (long long)n);
+    if (n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "%s = %lld exceeds 2^28", name, (long long)n);
+    return NEUS2_OK;
+}
+
+int check_mats(const void* const* M, int count, const char* name) {
+    if (!M) return fail(NEUS2_ERR_NULL, "%s is NULL", name);
+    char buf[32];
+    for (int l = 0; l < count; ++l) {
+        snprintf(buf, sizeof(buf), "%s[%d]", name, l);
+        NEUS2_TRY(check_ptr(M[l], buf));
+    }
+    return NEUS2_OK;
+}
+
+}  // namespace neus2
+
+using namespace neus2;
+
+extern "C" {
+
+const char* neus2_last_error(void) { return g_error; }
+int neus2_version(void) { return 1; }
+int neus2_validate_config(const neus2_config* cfg) { return check_config(cfg); }
+
+int neus2_hash_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n, float* enc,
+                      float* jac, uint32_t* dbg_idx, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_ptr(dbg_idx, "dbg_idx", false));
+    return launch_encode(cfg, pos, tables, n, enc, jac, dbg_idx, (hipStream_t)stream);
+}
+
+int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
+                       int64_t n, float* y, float* q, float* normal, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, cfg->n_sdf_mats, "H"));
+    NEUS2_TRY(check_ptr(y, "y"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(normal, "normal"));
+    return launch_sdf_fwd(cfg, enc, jac, H, n, y, q, normal, (hipStream_t)stream);
+}
+
+int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
+                      const float* jac, const float* const* H, const float* q, const float* d_y,
+                      const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
+                      float* d_pos, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, cfg->n_sdf_mats, "H"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(d_y, "d_y"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_mats((const void* const*)dH, cfg->n_sdf_mats, "dH"));
+    NEUS2_TRY(check_ptr(d_tables, "d_tables"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    hipStream_t st = (hipStream_t)stream;
+    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, st));
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, st);
+}
+
+}  // extern "C"
+
+extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* b, int64_t n, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (!b) return fail(NEUS2_ERR_NULL, "buf is NULL");
+    if (n < 0 || n % cfg->samples_per_ray != 0)
+        return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
+    if (cfg->loss_kind == 1 && cfg->n_color_mats != 3)
+        return fail(NEUS2_ERR_CONFIG, "loss_kind 1 needs the colour network");
+    NEUS2_TRY(check_ptr(b->loss, "loss"));
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t rays = n / cfg->samples_per_ray;
+    NEUS2_TRY(launch_zero(b->loss, 2, st));
+    NEUS2_TRY(neus2_hash_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, stream));
+    NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
+    if (cfg->loss_kind == 1) {
+        NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, n, b->rgb, stream));
+        NEUS2_TRY(neus2_render_rays(cfg, b->y, 16, b->rgb, rays, b->C, b->weights, stream));
+        NEUS2_TRY(neus2_loss(cfg, b->C, b->target, b->normal, b->y, rays, n, b->loss, b->dC, b->d_normal, nullptr, stream));
+        NEUS2_TRY(neus2_render_rays_bwd(cfg, b->y, 16, b->rgb, b->dC, rays, b->d_sdf, b->d_rgb, stream));
+        NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
+                                  b->d_normal, b->d_pos, stream));
+    } else {
+        NEUS2_TRY(neus2_loss(cfg, nullptr, nullptr, b->normal, b->y, 0, n, b->loss, nullptr, b->d_normal, b->d_y, stream));
+        if (b->d_pos) NEUS2_TRY(launch_zero(b->d_pos, 3 * n, st));
+    }
+    return neus2_sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
+                             b->d_tables, b->d_enc, b->d_pos, stream);
+}

@@ -1,0 +1,322 @@
+// Colour network c = c_Upsilon(x, n, v, d, g) (Eq. 3 of the paper): forward and first-order
+// backward, fused per 32-point tile on the fp32 matrix cores.  The paper needs no
+// second-order term for Upsilon (text after Eq. 6): the normal enters here as a plain input
+// and its adjoint dL/dn is handed on to the SDF backward.
+//
+// Input, as the caller sees it: [x(3), n(3), SH16(v)(16), (d,g)(16)] = 38 columns of W_1.
+// Inside the kernel the columns are walked in the order [(d,g), SH16, x, n, 0, 0] so that
+// each lane's registers map to contiguous loads; W_1 is permuted to match when it is copied
+// into LDS.
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace neus2 {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kLdIn = 44;      // row stride of W_1 in LDS (40 used columns)
+constexpr int kLdOutT = 12;    // row stride of W_3^T in LDS (3 used columns)
+
+struct ColorArgs {
+    const float* pos; const float* normal; const float* dirs; const float* y; const float* W[3];
+    const float* d_rgb; const float* d_sdf;
+    float* rgb; float* dW[3]; float* d_y; float* d_normal; float* d_pos;
+    int64_t n; int spr;
+};
+
+// caller's column of W_1 for internal column c (or -1 for padding)
+__device__ __forceinline__ int external_column(int c) {
+    if (c < 16) return 22 + c;          // (d, g)
+    if (c < 32) return 6 + (c - 16);    // SH16
+    if (c < 38) return c - 32;          // x (0..2), n (3..5)
+    return -1;
+}
+
+template <bool BWD>
+struct ColorWeights {
+    float W1f[64 * kLdIn];
+    float W2f[64 * kLd64];
+    float W3f[32 * kLd64];                       // rows >= 3 zero
+    float W1t[BWD ? 64 * kLd64 : 4];             // [40 -> 64 rows][64], rows >= 38 zero
+    float W2t[BWD ? 64 * kLd64 : 4];
+    float W3t[BWD ? 64 * kLdOutT : 4];           // [64][3 -> 8], columns >= 3 zero
+};
+
+template <bool BWD>
+__device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W3f[idx] = 0.f;
+    if (BWD) {
+        for (int idx = tid; idx < 64 * kLd64; idx += kThreads) w.W1t[idx] = 0.f;
+        for (int idx = tid; idx < 64 * kLdOutT; idx += kThreads) w.W3t[idx] = 0.f;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < 64 * 40; idx += kThreads) {
+        const int o = idx / 40, c = idx % 40;
+        const int e = external_column(c);
+        const float v = e >= 0 ? a.W[0][o * 38 + e] : 0.f;
+        w.W1f[o * kLdIn + c] = v;
+        if (BWD) w.W1t[c * kLd64 + o] = v;
+    }
+    for (int idx = tid; idx < 64 * 64; idx += kThreads) {
+        const int o = idx / 64, i = idx % 64;
+        const float v = a.W[1][idx];
+        w.W2f[o * kLd64 + i] = v;
+        if (BWD) w.W2t[i * kLd64 + o] = v;
+    }
+    for (int idx = tid; idx < 3 * 64; idx += kThreads) {
+        const int o = idx / 64, i = idx % 64;
+        const float v = a.W[2][idx];
+        w.W3f[o * kLd64 + i] = v;
+        if (BWD) w.W3t[i * kLdOutT + o] = v;
+    }
+    __syncthreads();
+}
+
+// real orthonormal spherical harmonics, degree 0..3, index l*l + l + m
+__device__ __forceinline__ void sh16(float x, float y, float z, float* sh) {
+    const float xx = x * x, yy = y * y, zz = z * z;
+    sh[0] = 0.28209479177387814f;
+    sh[1] = 0.4886025119029199f * y;
+    sh[2] = 0.4886025119029199f * z;
+    sh[3] = 0.4886025119029199f * x;
+    sh[4] = 1.0925484305920792f * x * y;
+    sh[5] = 1.0925484305920792f * y * z;
+    sh[6] = 0.31539156525252005f * (3.f * zz - 1.f);
+    sh[7] = 1.0925484305920792f * x * z;
+    sh[8] = 0.5462742152960396f * (xx - yy);
+    sh[9] = 0.5900435899266435f * y * (3.f * xx - yy);
+    sh[10] = 2.890611442640554f * x * y * z;
+    sh[11] = 0.4570457994644658f * y * (5.f * zz - 1.f);
+    sh[12] = 0.3731763325901154f * z * (5.f * zz - 3.f);
+    sh[13] = 0.4570457994644658f * x * (5.f * zz - 1.f);
+    sh[14] = 1.445305721320277f * z * (xx - yy);
+    sh[15] = 0.5900435899266435f * x * (xx - 3.f * yy);
+}
+
+// Gather one point's input into the register layout: block 0 = [(d,g), SH16], block 1 = [x, n].
+__device__ __forceinline__ void load_input(const ColorArgs& a, int64_t i, bool valid, int h, v16f* cin) {
+    cin[0] = zero16();
+    cin[1] = zero16();
+    if (!valid) return;
+    const float4 ya = *reinterpret_cast<const float4*>(a.y + i * 16 + 4 * h);
+    const float4 yb = *reinterpret_cast<const float4*>(a.y + i * 16 + 8 + 4 * h);
+    cin[0][0] = ya.x; cin[0][1] = ya.y; cin[0][2] = ya.z; cin[0][3] = ya.w;
+    cin[0][4] = yb.x; cin[0][5] = yb.y; cin[0][6] = yb.z; cin[0][7] = yb.w;
+    const int64_t ray = i / a.spr;
+    float sh[16];
+    sh16(a.dirs[3 * ray], a.dirs[3 * ray + 1], a.dirs[3 * ray + 2], sh);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        cin[0][8 + k] = h ? sh[4 + k] : sh[k];
+        cin[0][12 + k] = h ? sh[12 + k] : sh[8 + k];
+    }
+    const float p0 = a.pos[3 * i], p1 = a.pos[3 * i + 1], p2 = a.pos[3 * i + 2];
+    const float n0 = a.normal[3 * i], n1 = a.normal[3 * i + 1], n2 = a.normal[3 * i + 2];
+    cin[1][0] = h ? n1 : p0;
+    cin[1][1] = h ? n2 : p1;
+    cin[1][2] = h ? 0.f : p2;
+    cin[1][3] = h ? 0.f : n0;
+}
+
+__device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-u)); }
+
+template <bool BWD>
+__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, v16f* a1, v16f* a2,
+                                             uint32_t& m1, uint32_t& m2, v16f* u, int j, int h) {
+    matvec<2, 2, kLdIn, 4>(w.W1f, cin, a1, j, h);
+    m1 = relu_mask<2>(a1);
+    matvec<2, 2, kLd64>(w.W2f, a1, a2, j, h);
+    m2 = relu_mask<2>(a2);
+    matvec<1, 2, kLd64>(w.W3f, a2, u, j, h);
+}
+
+__global__ __launch_bounds__(kThreads) void color_fwd_kernel(ColorArgs a) {
+    __shared__ ColorWeights<false> w;
+    load_weights<false>(w, a);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        v16f cin[2], a1[2], a2[2], u[1];
+        uint32_t m1, m2;
+        load_input(a, i, valid, h, cin);
+        forward_tile<false>(w, cin, a1, a2, m1, m2, u, j, h);
+        if (valid && h == 0) {
+            a.rgb[3 * i + 0] = sigmoid(u[0][0]);
+            a.rgb[3 * i + 1] = sigmoid(u[0][1]);
+            a.rgb[3 * i + 2] = sigmoid(u[0][2]);
+        }
+    }
+}
+
+struct ColorBwdSmem {
+    ColorWeights<true> w;
+    float tiles[kWaves][2][32 * kLd64];
+};
+
+__global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
+    __shared__ ColorBwdSmem sm;
+    ColorWeights<true>& w = sm.w;
+    load_weights<true>(w, a);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    float* Zt = sm.tiles[wave][0];
+    float* Xt = sm.tiles[wave][1];
+    v16f G1[2][2], G2[2][2], G3[1][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) { G1[mb][nb] = zero16(); G2[mb][nb] = zero16(); G3[0][nb] = zero16(); }
+
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        v16f cin[2], a1[2], a2[2], u[1];
+        uint32_t m1, m2;
+        load_input(a, i, valid, h, cin);
+        forward_tile<true>(w, cin, a1, a2, m1, m2, u, j, h);
+        // adjoint of the pre-sigmoid output
+        v16f d3[1] = {zero16()};
+        if (valid && h == 0) {
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const float s = sigmoid(u[0][c]);
+                d3[0][c] = a.d_rgb[3 * i + c] * s * (1.f - s);
+            }
+        }
+        stage<1, kLd64>(Zt, d3, j, h);
+        stage<2, kLd64>(Xt, a2, j, h);
+        wave_lds_fence();
+        outer_accumulate<1, 2, kLd64, kLd64>(G3, Zt, Xt, j, h);
+        v16f d2[2], d1[2], dcin[2];
+        matvec<2, 1, kLdOutT, 4>(w.W3t, d3, d2, j, h);
+        apply_mask<2>(d2, m2);
+        wave_lds_fence();
+        stage<2, kLd64>(Zt, d2, j, h);
+        stage<2, kLd64>(Xt, a1, j, h);
+        wave_lds_fence();
+        outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+        matvec<2, 2, kLd64>(w.W2t, d2, d1, j, h);
+        apply_mask<2>(d1, m1);
+        wave_lds_fence();
+        stage<2, kLd64>(Zt, d1, j, h);
+        stage<2, kLd64>(Xt, cin, j, h);
+        wave_lds_fence();
+        outer_accumulate<2, 2, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        matvec<2, 2, kLd64>(w.W1t, d1, dcin, j, h);
+        wave_lds_fence();
+        if (valid) {
+            // block 0, registers 0..7: dL/d(d,g) columns 4h..4h+3 and 8+4h..8+4h+3
+            float4 lo = make_float4(dcin[0][0], dcin[0][1], dcin[0][2], dcin[0][3]);
+            const float4 hi = make_float4(dcin[0][4], dcin[0][5], dcin[0][6], dcin[0][7]);
+            if (h == 0 && a.d_sdf) lo.x += a.d_sdf[i];
+            *reinterpret_cast<float4*>(a.d_y + i * 16 + 4 * h) = lo;
+            *reinterpret_cast<float4*>(a.d_y + i * 16 + 8 + 4 * h) = hi;
+            // block 1: h = 0 -> x0 x1 x2 n0 ; h = 1 -> n1 n2
+            if (h == 0) {
+                if (a.d_pos) { a.d_pos[3 * i] = dcin[1][0]; a.d_pos[3 * i + 1] = dcin[1][1]; a.d_pos[3 * i + 2] = dcin[1][2]; }
+                a.d_normal[3 * i] += dcin[1][3];
+            } else {
+                a.d_normal[3 * i + 1] += dcin[1][0];
+                a.d_normal[3 * i + 2] += dcin[1][1];
+            }
+        }
+    }
+    __syncthreads();
+    float* scratch = &sm.tiles[0][0][0];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            G1[mb][nb] = block_sum<kWaves>(scratch, G1[mb][nb], wave, lane);
+            G2[mb][nb] = block_sum<kWaves>(scratch, G2[mb][nb], wave, lane);
+        }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) G3[0][nb] = block_sum<kWaves>(scratch, G3[0][nb], wave, lane);
+    if (wave == kWaves - 1) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int o = 32 * mb + neuron_of(r, h), c = 32 * nb + j;
+                    atomicAdd(a.dW[1] + o * 64 + c, G2[mb][nb][r]);
+                    const int e = external_column(c);
+                    if (e >= 0) atomicAdd(a.dW[0] + o * 38 + e, G1[mb][nb][r]);
+                }
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = neuron_of(r, h), c = 32 * nb + j;
+                if (o < 3) atomicAdd(a.dW[2] + o * 64 + c, G3[0][nb][r]);
+            }
+    }
+}
+
+int check_common(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
+                 const float* const* W, int64_t n) {
+    NEUS2_TRY(check_config(cfg));
+    if (cfg->n_color_mats != 3) return fail(NEUS2_ERR_CONFIG, "the descriptor has no colour network");
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    if (n % cfg->samples_per_ray != 0)
+        return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(normal, "normal"));
+    NEUS2_TRY(check_ptr(dirs, "dirs"));
+    NEUS2_TRY(check_ptr(y, "y"));
+    if (!W) return fail(NEUS2_ERR_NULL, "W is NULL");
+    for (int l = 0; l < 3; ++l) NEUS2_TRY(check_ptr(W[l], "W[l]"));
+    return NEUS2_OK;
+}
+
+}  // namespace
+
+}  // namespace neus2
+
+using namespace neus2;
+
+extern "C" {
+
+int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
+                    const float* const* W, int64_t n, float* rgb, void* stream) {
+    NEUS2_TRY(check_common(cfg, pos, normal, dirs, y, W, n));
+    NEUS2_TRY(check_ptr(rgb, "rgb"));
+    if (n == 0) return NEUS2_OK;
+    ColorArgs a = {};
+    a.pos = pos; a.normal = normal; a.dirs = dirs; a.y = y; a.rgb = rgb; a.n = n; a.spr = cfg->samples_per_ray;
+    for (int l = 0; l < 3; ++l) a.W[l] = W[l];
+    const int blocks = persistent_blocks((const void*)color_fwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
+    hipLaunchKernelGGL(color_fwd_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    return check_launch("colour forward");
+}
+
+int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
+                    const float* const* W, const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
+                    float* d_y, float* d_normal, float* d_pos, void* stream) {
+    NEUS2_TRY(check_common(cfg, pos, normal, dirs, y, W, n));
+    NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
+    NEUS2_TRY(check_ptr(d_sdf, "d_sdf", false));
+    if (!dW) return fail(NEUS2_ERR_NULL, "dW is NULL");
+    for (int l = 0; l < 3; ++l) NEUS2_TRY(check_ptr(dW[l], "dW[l]"));
+    NEUS2_TRY(check_ptr(d_y, "d_y"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    if (n == 0) return NEUS2_OK;
+    ColorArgs a = {};
+    a.pos = pos; a.normal = normal; a.dirs = dirs; a.y = y; a.n = n; a.spr = cfg->samples_per_ray;
+    a.d_rgb = d_rgb; a.d_sdf = d_sdf; a.d_y = d_y; a.d_normal = d_normal; a.d_pos = d_pos;
+    for (int l = 0; l < 3; ++l) { a.W[l] = W[l]; a.dW[l] = dW[l]; }
+    const int blocks = persistent_blocks((const void*)color_bwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
+    hipLaunchKernelGGL(color_bwd_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    return check_launch("colour backward");
+}
+
+}  // extern "C"

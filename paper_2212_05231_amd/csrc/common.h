@@ -1,0 +1,57 @@
+// Internal declarations shared by the translation units of libneus2 (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/neus2.h"
+
+namespace neus2 {
+
+// ---- host side ---------------------------------------------------------------------------
+int fail(int code, const char* fmt, ...);           // records the message, returns code
+int check_config(const neus2_config* cfg);
+int check_ptr(const void* p, const char* name, bool required = true);
+int check_launch(const char* what);                  // hipGetLastError -> NEUS2_ERR_HIP
+
+#define NEUS2_TRY(expr)                 \
+    do {                                \
+        int _rc = (expr);               \
+        if (_rc != NEUS2_OK) return _rc; \
+    } while (0)
+
+// ---- kernel-side descriptor of the grid ----------------------------------------------------
+struct GridDesc {
+    int n_levels;
+    int active_levels;
+    uint32_t table_mask;       // T - 1
+    uint32_t table_size;       // T
+    uint32_t dense_bits;       // bit l set: level l is dense
+    int res[NEUS2_MAX_LEVELS];
+};
+
+GridDesc make_grid_desc(const neus2_config* cfg);
+
+// Number of compute units, cached per process.
+int compute_units();
+
+// Grid size of a persistent kernel: as many workgroups as can be resident at once, but no
+// more than `want`.
+int persistent_blocks(const void* kernel, int threads, int64_t want);
+
+int launch_zero(float* p, int64_t count, hipStream_t st);
+
+// internal launchers (each validates nothing; the extern "C" wrappers do)
+int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st);
+int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
+                   const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
+                   float* d_pos, hipStream_t st);
+int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
+                   const float* const* H, int64_t n, float* y, float* q, float* normal, hipStream_t st);
+int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac,
+                   const float* const* H, const float* d_y, const float* d_normal, int64_t n,
+                   float* const* dH, float* d_enc, float* d_pos, hipStream_t st);
+
+}  // namespace neus2

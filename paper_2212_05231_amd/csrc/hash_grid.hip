@@ -1,0 +1,229 @@
+// Multi-resolution hash-grid encoding: forward gather (+ Jacobian) and backward scatter-add.
+//
+// Paper: Sec. 3 "InstantNGP" (levels of grid vertices mapped into tables of T feature
+// vectors, a point's feature is the interpolation of the surrounding vertices), Sec. 4.1,
+// Sec. 4.3 (levels above lambda give zeros), Eq. 7 (the term of dL/dOmega that comes through
+// the normal).
+//
+// Launch shape: one thread per (point, level), 256 points of ONE level per workgroup.
+// Workgroups are dealt round-robin to the 8 XCDs by the hardware, so the block index is
+// decoded as  xcd = bid % 8,  level = xcd + 8 * slot : every XCD works on one level at a
+// time and that level's table (2 MiB in fp16 at T = 2^19) stays in its private 4 MiB L2.
+#include "common.h"
+
+namespace neus2 {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kXcd = 8;
+constexpr uint32_t kPrimeY = 2654435761u;
+constexpr uint32_t kPrimeZ = 805459861u;
+
+struct Cell {
+    uint32_t slot[8];   // table slot of corner c = dx + 2 dy + 4 dz
+    float w[3];         // offset inside the cell
+};
+
+__device__ __forceinline__ float clamp01(float x) {
+    // fmaxf(NaN, 0) = 0, so NaN maps to 0 like the reference definition.
+    return fminf(fmaxf(x, 0.0f), 1.0f);
+}
+
+__device__ __forceinline__ Cell locate(const GridDesc& g, int level, float px, float py, float pz) {
+    const int res = g.res[level];
+    const float fres = (float)res;
+    // The grid coordinate is ONE binary32 multiply; it must not be fused with the
+    // subtraction below, hence the explicit rounding intrinsic.
+    const float gx = __fmul_rn(clamp01(px), fres);
+    const float gy = __fmul_rn(clamp01(py), fres);
+    const float gz = __fmul_rn(clamp01(pz), fres);
+    const int cx = min((int)floorf(gx), res - 1);
+    const int cy = min((int)floorf(gy), res - 1);
+    const int cz = min((int)floorf(gz), res - 1);
+    Cell c;
+    c.w[0] = gx - (float)cx;
+    c.w[1] = gy - (float)cy;
+    c.w[2] = gz - (float)cz;
+    if ((g.dense_bits >> level) & 1u) {
+        const uint32_t s = (uint32_t)(res + 1);
+        const uint32_t base = (uint32_t)cx + (uint32_t)cy * s + (uint32_t)cz * s * s;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            c.slot[k] = base + (k & 1) + ((k >> 1) & 1) * s + ((k >> 2) & 1) * s * s;
+    } else {
+        const uint32_t hx[2] = {(uint32_t)cx, (uint32_t)cx + 1u};
+        const uint32_t hy[2] = {(uint32_t)cy * kPrimeY, ((uint32_t)cy + 1u) * kPrimeY};
+        const uint32_t hz[2] = {(uint32_t)cz * kPrimeZ, ((uint32_t)cz + 1u) * kPrimeZ};
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            c.slot[k] = (hx[k & 1] ^ hy[(k >> 1) & 1] ^ hz[(k >> 2) & 1]) & g.table_mask;
+    }
+    return c;
+}
+
+template <typename T>
+__device__ __forceinline__ float2 load_entry(const T* level_table, uint32_t slot);
+
+template <>
+__device__ __forceinline__ float2 load_entry<float>(const float* t, uint32_t slot) {
+    return reinterpret_cast<const float2*>(t)[slot];
+}
+template <>
+__device__ __forceinline__ float2 load_entry<__half>(const __half* t, uint32_t slot) {
+    return __half22float2(reinterpret_cast<const __half2*>(t)[slot]);
+}
+
+// block index -> (level, point block); returns false for padding blocks
+__device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int& level, int& pb) {
+    const int bid = blockIdx.x;
+    const int xcd = bid % kXcd;
+    const int j = bid / kXcd;
+    level = xcd + kXcd * (j / point_blocks);
+    pb = j % point_blocks;
+    return level < n_levels;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, const float* __restrict__ pos,
+                                                        const T* __restrict__ tables, int64_t n,
+                                                        int point_blocks, float* __restrict__ enc,
+                                                        float* __restrict__ jac,
+                                                        uint32_t* __restrict__ dbg_idx) {
+    int level, pb;
+    if (!decode_block(g.n_levels, point_blocks, level, pb)) return;
+    const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const float px = pos[3 * i + 0], py = pos[3 * i + 1], pz = pos[3 * i + 2];
+    const Cell c = locate(g, level, px, py, pz);
+    if (dbg_idx) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dbg_idx[(i * g.n_levels + level) * 8 + k] = c.slot[k];
+    }
+    float e0 = 0.f, e1 = 0.f;
+    float j0[3] = {0.f, 0.f, 0.f}, j1[3] = {0.f, 0.f, 0.f};
+    if (level < g.active_levels) {
+        const T* tab = tables + (size_t)level * g.table_size * 2;
+        float2 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = load_entry<T>(tab, c.slot[k]);
+        const float fres = (float)g.res[level];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
+            const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
+            const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
+            const float sx = (k & 1) ? fres : -fres;
+            const float sy = (k & 2) ? fres : -fres;
+            const float sz = (k & 4) ? fres : -fres;
+            const float wk = fx * fy * fz;
+            const float dx = sx * fy * fz, dy = fx * sy * fz, dz = fx * fy * sz;
+            e0 += wk * v[k].x;
+            e1 += wk * v[k].y;
+            j0[0] += dx * v[k].x; j0[1] += dy * v[k].x; j0[2] += dz * v[k].x;
+            j1[0] += dx * v[k].y; j1[1] += dy * v[k].y; j1[2] += dz * v[k].y;
+        }
+    }
+    const int64_t o = (int64_t)level * n + i;
+    reinterpret_cast<float2*>(enc)[o] = make_float2(e0, e1);
+    float2* jo = reinterpret_cast<float2*>(jac) + o * 3;
+    jo[0] = make_float2(j0[0], j0[1]);
+    jo[1] = make_float2(j0[2], j1[0]);
+    jo[2] = make_float2(j1[1], j1[2]);
+}
+
+// Backward.  d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a d_a w_c
+// (first-order term, and the term Eq. 7 keeps).  With WANT_POS the mixed second derivative
+// of the interpolation, contracted with q and dL/dn, is added into d_pos.
+template <typename T, bool WANT_POS>
+__global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float* __restrict__ pos,
+                                                         const T* __restrict__ tables,
+                                                         const float* __restrict__ q,
+                                                         const float* __restrict__ d_enc,
+                                                         const float* __restrict__ d_normal, int64_t n,
+                                                         int point_blocks, float* __restrict__ d_tables,
+                                                         float* __restrict__ d_pos) {
+    int level, pb;
+    if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
+    const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const float px = pos[3 * i + 0], py = pos[3 * i + 1], pz = pos[3 * i + 2];
+    const Cell c = locate(g, level, px, py, pz);
+    const int64_t o = (int64_t)level * n + i;
+    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+    const float2 qq = reinterpret_cast<const float2*>(q)[o];
+    const float fres = (float)g.res[level];
+    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+    float* gt = d_tables + (size_t)level * g.table_size * 2;
+    float hp[3] = {0.f, 0.f, 0.f};
+    const T* tab = tables + (size_t)level * g.table_size * 2;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
+        const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
+        const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
+        const float sx = (k & 1) ? 1.f : -1.f;
+        const float sy = (k & 2) ? 1.f : -1.f;
+        const float sz = (k & 4) ? 1.f : -1.f;
+        const float wk = fx * fy * fz;
+        const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
+        atomicAdd(gt + 2 * (size_t)c.slot[k] + 0, wk * de.x + qq.x * dn);
+        atomicAdd(gt + 2 * (size_t)c.slot[k] + 1, wk * de.y + qq.y * dn);
+        if (WANT_POS) {
+            const float2 v = load_entry<T>(tab, c.slot[k]);
+            const float qv = qq.x * v.x + qq.y * v.y;
+            // d/dx_b of sum_a nbar_a res d_a w_c  (times res for the chain rule of b)
+            hp[0] += qv * fres * (ny * (sx * sy * fz) + nz * (sx * fy * sz));
+            hp[1] += qv * fres * (nx * (sx * sy * fz) + nz * (fx * sy * sz));
+            hp[2] += qv * fres * (nx * (sx * fy * sz) + ny * (fx * sy * sz));
+        }
+    }
+    if (WANT_POS) {
+        atomicAdd(d_pos + 3 * i + 0, hp[0]);
+        atomicAdd(d_pos + 3 * i + 1, hp[1]);
+        atomicAdd(d_pos + 3 * i + 2, hp[2]);
+    }
+}
+
+int grid_blocks(int levels, int point_blocks) {
+    const int slots = (levels + kXcd - 1) / kXcd;
+    return kXcd * slots * point_blocks;
+}
+
+}  // namespace
+
+int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st) {
+    if (n == 0) return NEUS2_OK;
+    const GridDesc g = make_grid_desc(cfg);
+    const int pbs = (int)((n + kBlock - 1) / kBlock);
+    const dim3 grid(grid_blocks(g.n_levels, pbs));
+    if (cfg->table_dtype == 1)
+        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, pos,
+                           (const __half*)tables, n, pbs, enc, jac, dbg_idx);
+    else
+        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, pos,
+                           (const float*)tables, n, pbs, enc, jac, dbg_idx);
+    return check_launch("hash encode");
+}
+
+int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
+                   const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
+                   float* d_pos, hipStream_t st) {
+    if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
+    const GridDesc g = make_grid_desc(cfg);
+    const int pbs = (int)((n + kBlock - 1) / kBlock);
+    const dim3 grid(grid_blocks(g.active_levels, pbs));
+#define NEUS2_SCATTER(T, WP)                                                                   \
+    hipLaunchKernelGGL((scatter_kernel<T, WP>), grid, dim3(kBlock), 0, st, g, pos, (const T*)tables, \
+                       q, d_enc, d_normal, n, pbs, d_tables, d_pos)
+    if (cfg->table_dtype == 1) {
+        if (d_pos) NEUS2_SCATTER(__half, true); else NEUS2_SCATTER(__half, false);
+    } else {
+        if (d_pos) NEUS2_SCATTER(float, true); else NEUS2_SCATTER(float, false);
+    }
+#undef NEUS2_SCATTER
+    return check_launch("hash scatter");
+}
+
+}  // namespace neus2

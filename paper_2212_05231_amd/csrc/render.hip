@@ -1,0 +1,364 @@
+// NeuS compositing along rays as wavefront scans, the loss of Eq. 4, Adam, and the rigid
+// transform of Eq. 9.
+//
+// Paper, supplement Sec. E.3: Phi_s(x) = 1/(1+e^{-sx});
+//   alpha_i = max((Phi_s(d_i) - Phi_s(d_{i+1})) / Phi_s(d_i), 0),  T_i = prod_{j<i}(1-alpha_j),
+//   C = sum_i T_i alpha_i c_i.
+// The quotient is evaluated in the algebraically identical form
+//   (1 - Phi_s(d_{i+1})) * (1 - exp(-s (d_i - d_{i+1}))),
+// which has no cancellation when both SDF values are close to zero (fp32).
+//
+// One ray = one wavefront, one sample = one lane (at most 64 samples per ray).
+#include "common.h"
+
+namespace neus2 {
+
+namespace {
+
+constexpr int kRayThreads = 256;
+
+struct RayLane {
+    float alpha, trans, dalpha_di, dalpha_dnext;   // dalpha_i/dd_i and dalpha_i/dd_{i+1}
+};
+
+__device__ __forceinline__ float shfl_down1(float v) { return __shfl_down(v, 1); }
+
+// inclusive product scan over the wave
+__device__ __forceinline__ float wave_scan_mul(float v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_up(v, d);
+        if (lane >= d) v *= o;
+    }
+    return v;
+}
+
+// inclusive suffix-sum scan over the wave (lane i gets sum over lanes >= i)
+__device__ __forceinline__ float wave_suffix_sum(float v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_down(v, d);
+        if (lane + d < 64) v += o;
+    }
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    return v;
+}
+
+__device__ __forceinline__ RayLane ray_lane(float d, int lane, int spr, float s) {
+    const float dn = shfl_down1(d);
+    RayLane r = {0.f, 1.f, 0.f, 0.f};
+    if (lane < spr - 1) {
+        const float delta = d - dn;
+        if (delta > 0.f) {
+            const float one_minus_phi_n = 1.f / (1.f + __expf(s * dn));   // 1 - Phi_s(d_{i+1})
+            const float phi_n = 1.f - one_minus_phi_n;
+            const float em = -expm1f(-s * delta);                           // 1 - e^{-s delta}
+            const float e = 1.f - em;
+            r.alpha = one_minus_phi_n * em;
+            r.dalpha_di = one_minus_phi_n * s * e;
+            r.dalpha_dnext = -s * phi_n * one_minus_phi_n * em - r.dalpha_di;
+        }
+    }
+    const float incl = wave_scan_mul(1.f - r.alpha, lane);
+    const float excl = __shfl_up(incl, 1);
+    r.trans = lane == 0 ? 1.f : excl;
+    return r;
+}
+
+__global__ __launch_bounds__(kRayThreads) void render_fwd_kernel(const float* __restrict__ sdf, int64_t stride,
+                                                                const float* __restrict__ rgb, int64_t rays, int spr,
+                                                                float s, float* __restrict__ C,
+                                                                float* __restrict__ weights) {
+    const int lane = threadIdx.x & 63;
+    const int64_t ray = (int64_t)blockIdx.x * (kRayThreads / 64) + (threadIdx.x >> 6);
+    if (ray >= rays) return;
+    const bool live = lane < spr;
+    const int64_t i = ray * spr + (live ? lane : 0);
+    const float d = live ? sdf[i * stride] : 0.f;
+    const RayLane r = ray_lane(d, lane, spr, s);
+    const float w = live ? r.trans * r.alpha : 0.f;
+    float c0 = 0.f, c1 = 0.f, c2 = 0.f;
+    if (live) {
+        weights[i] = w;
+        c0 = w * rgb[3 * i + 0]; c1 = w * rgb[3 * i + 1]; c2 = w * rgb[3 * i + 2];
+    }
+    c0 = wave_sum(c0); c1 = wave_sum(c1); c2 = wave_sum(c2);
+    if (lane == 0) { C[3 * ray + 0] = c0; C[3 * ray + 1] = c1; C[3 * ray + 2] = c2; }
+}
+
+// dC/dalpha_i = T_i (dC.c_i) - (sum_{j>i} T_j alpha_j (dC.c_j)) / (1 - alpha_i)
+__global__ __launch_bounds__(kRayThreads) void render_bwd_kernel(const float* __restrict__ sdf, int64_t stride,
+                                                                const float* __restrict__ rgb,
+                                                                const float* __restrict__ dC, int64_t rays, int spr,
+                                                                float s, float* __restrict__ d_sdf,
+                                                                float* __restrict__ d_rgb) {
+    const int lane = threadIdx.x & 63;
+    const int64_t ray = (int64_t)blockIdx.x * (kRayThreads / 64) + (threadIdx.x >> 6);
+    if (ray >= rays) return;
+    const bool live = lane < spr;
+    const int64_t i = ray * spr + (live ? lane : 0);
+    const float d = live ? sdf[i * stride] : 0.f;
+    const RayLane r = ray_lane(d, lane, spr, s);
+    const float w = live ? r.trans * r.alpha : 0.f;
+    const float g0 = dC[3 * ray + 0], g1 = dC[3 * ray + 1], g2 = dC[3 * ray + 2];
+    float cb = 0.f;
+    if (live) {
+        cb = g0 * rgb[3 * i + 0] + g1 * rgb[3 * i + 1] + g2 * rgb[3 * i + 2];
+        d_rgb[3 * i + 0] = w * g0; d_rgb[3 * i + 1] = w * g1; d_rgb[3 * i + 2] = w * g2;
+    }
+    const float wc = w * cb;
+    const float after = wave_suffix_sum(wc, lane) - wc;          // sum over j > i
+    const float d_alpha = r.trans * cb - after / (1.f - r.alpha);
+    const float from_prev = __shfl_up(d_alpha * r.dalpha_dnext, 1);
+    float ds = d_alpha * r.dalpha_di;
+    if (lane > 0) ds += from_prev;
+    if (live) d_sdf[i] = ds;
+}
+
+// ---- loss ---------------------------------------------------------------------------------
+__device__ __forceinline__ void block_add(float v, float* dst, float* red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int k = 0; k < (int)(blockDim.x >> 6); ++k) t += red[k];
+        atomicAdd(dst, t);
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
+                                                   const float* __restrict__ normal, const float* __restrict__ y,
+                                                   int64_t rays, int64_t n, float beta, float* __restrict__ loss,
+                                                   float* __restrict__ dC, float* __restrict__ d_normal,
+                                                   float* __restrict__ d_y) {
+    __shared__ float red[4];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const float inv_n = 1.f / (float)n;
+    float first = 0.f, eik = 0.f;
+    if (i < n) {
+        const float nx = normal[3 * i], ny = normal[3 * i + 1], nz = normal[3 * i + 2];
+        const float len = sqrtf(nx * nx + ny * ny + nz * nz);
+        const float dev = len - 1.f;
+        eik = beta * dev * dev * inv_n;
+        const float k = 2.f * beta * inv_n * dev / fmaxf(len, 1e-30f);
+        d_normal[3 * i] = k * nx; d_normal[3 * i + 1] = k * ny; d_normal[3 * i + 2] = k * nz;
+        if (kind == 0) {
+            const float d = y[16 * i];
+            first = d * d * inv_n;
+            float4* o = reinterpret_cast<float4*>(d_y + 16 * i);
+            o[0] = make_float4(2.f * d * inv_n, 0.f, 0.f, 0.f);
+            o[1] = o[2] = o[3] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    if (kind == 1 && i < rays) {
+        const float inv_r = 1.f / (float)rays;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float diff = C[3 * i + c] - target[3 * i + c];
+            first += fabsf(diff) * inv_r;
+            dC[3 * i + c] = diff > 0.f ? inv_r : (diff < 0.f ? -inv_r : 0.f);
+        }
+    }
+    block_add(first, loss + 0, red);
+    block_add(eik, loss + 1, red);
+}
+
+__global__ void zero_kernel(float* p, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// ---- Adam ---------------------------------------------------------------------------------
+struct AdamArgs {
+    float lr, b1, b2, eps, inv_c1, inv_c2;    // inv_c = 1 / (1 - beta^t)
+};
+
+template <bool HALF>
+__global__ __launch_bounds__(256) void adam_kernel(void* __restrict__ param, float* __restrict__ master,
+                                                   float* __restrict__ grad, float* __restrict__ m,
+                                                   float* __restrict__ v, int64_t count, AdamArgs a, int zero_grad) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const float g = grad[i];
+    const float mi = a.b1 * m[i] + (1.f - a.b1) * g;
+    const float vi = a.b2 * v[i] + (1.f - a.b2) * g * g;
+    m[i] = mi;
+    v[i] = vi;
+    float* full = HALF ? master : reinterpret_cast<float*>(param);
+    const float p = full[i] - a.lr * (mi * a.inv_c1) / (sqrtf(vi * a.inv_c2) + a.eps);
+    full[i] = p;
+    if (HALF) reinterpret_cast<__half*>(param)[i] = __float2half_rn(p);
+    if (zero_grad) grad[i] = 0.f;
+}
+
+// ---- rigid transform (Eq. 9) ---------------------------------------------------------------
+struct Rigid {
+    float R[9], T[3], scale, offset;
+};
+
+__global__ __launch_bounds__(256) void rigid_fwd_kernel(const float* __restrict__ pos, Rigid t, int64_t n,
+                                                        float* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float x = pos[3 * i] + t.T[0], y = pos[3 * i + 1] + t.T[1], z = pos[3 * i + 2] + t.T[2];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) out[3 * i + r] = t.scale * (t.R[3 * r] * x + t.R[3 * r + 1] * y + t.R[3 * r + 2] * z) + t.offset;
+}
+
+__global__ __launch_bounds__(256) void rigid_bwd_kernel(const float* __restrict__ pos, Rigid t,
+                                                        const float* __restrict__ d_out, int64_t n,
+                                                        float* __restrict__ Mb) {
+    __shared__ float red[4];
+    float acc[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) acc[k] = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const float x[3] = {pos[3 * i] + t.T[0], pos[3 * i + 1] + t.T[1], pos[3 * i + 2] + t.T[2]};
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float g = t.scale * d_out[3 * i + r];
+            acc[3 * r + 0] += g * x[0]; acc[3 * r + 1] += g * x[1]; acc[3 * r + 2] += g * x[2];
+            acc[9 + r] += g;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 12; ++k) block_add(acc[k], Mb + k, red);
+}
+
+}  // namespace
+
+}  // namespace neus2
+
+using namespace neus2;
+
+extern "C" {
+
+int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_stride, const float* rgb, int64_t rays,
+                      float* C, float* weights, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (rays < 0 || rays > ((int64_t)1 << 28) / cfg->samples_per_ray) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
+    if (sdf_stride < 1) return fail(NEUS2_ERR_SHAPE, "sdf_stride = %lld, must be >= 1", (long long)sdf_stride);
+    if (!sdf) return fail(NEUS2_ERR_NULL, "sdf is NULL");
+    NEUS2_TRY(check_ptr(rgb, "rgb"));
+    NEUS2_TRY(check_ptr(C, "C"));
+    NEUS2_TRY(check_ptr(weights, "weights"));
+    if (rays == 0) return NEUS2_OK;
+    const int per = kRayThreads / 64;
+    hipLaunchKernelGGL(render_fwd_kernel, dim3((unsigned)((rays + per - 1) / per)), dim3(kRayThreads), 0,
+                       (hipStream_t)stream, sdf, sdf_stride, rgb, rays, cfg->samples_per_ray, cfg->s, C, weights);
+    return check_launch("render rays");
+}
+
+int neus2_render_rays_bwd(const neus2_config* cfg, const float* sdf, int64_t sdf_stride, const float* rgb,
+                          const float* dC, int64_t rays, float* d_sdf, float* d_rgb, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (rays < 0 || rays > ((int64_t)1 << 28) / cfg->samples_per_ray) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
+    if (sdf_stride < 1) return fail(NEUS2_ERR_SHAPE, "sdf_stride = %lld, must be >= 1", (long long)sdf_stride);
+    if (!sdf) return fail(NEUS2_ERR_NULL, "sdf is NULL");
+    NEUS2_TRY(check_ptr(rgb, "rgb"));
+    NEUS2_TRY(check_ptr(dC, "dC"));
+    NEUS2_TRY(check_ptr(d_sdf, "d_sdf"));
+    NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
+    if (rays == 0) return NEUS2_OK;
+    const int per = kRayThreads / 64;
+    hipLaunchKernelGGL(render_bwd_kernel, dim3((unsigned)((rays + per - 1) / per)), dim3(kRayThreads), 0,
+                       (hipStream_t)stream, sdf, sdf_stride, rgb, dC, rays, cfg->samples_per_ray, cfg->s, d_sdf, d_rgb);
+    return check_launch("render rays backward");
+}
+
+int neus2_loss(const neus2_config* cfg, const float* C, const float* target, const float* normal, const float* y,
+               int64_t rays, int64_t n, float* loss, float* dC, float* d_normal, float* d_y, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    NEUS2_TRY(check_ptr(normal, "normal"));
+    NEUS2_TRY(check_ptr(loss, "loss"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    if (cfg->loss_kind == 1) {
+        if (rays < 0 || rays * cfg->samples_per_ray != n)
+            return fail(NEUS2_ERR_SHAPE, "rays * samples_per_ray = %lld differs from n = %lld",
+                        (long long)(rays * cfg->samples_per_ray), (long long)n);
+        NEUS2_TRY(check_ptr(C, "C"));
+        NEUS2_TRY(check_ptr(target, "target"));
+        NEUS2_TRY(check_ptr(dC, "dC"));
+    } else {
+        NEUS2_TRY(check_ptr(y, "y"));
+        NEUS2_TRY(check_ptr(d_y, "d_y"));
+    }
+    if (n == 0) return NEUS2_OK;
+    hipLaunchKernelGGL(loss_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, cfg->loss_kind,
+                       C, target, normal, y, cfg->loss_kind == 1 ? rays : 0, n, cfg->beta, loss, dC, d_normal, d_y);
+    return check_launch("loss");
+}
+
+int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count, int dtype, float lr,
+                    float beta1, float beta2, float eps, int t, int zero_grad, void* stream) {
+    if (count < 0 || count > ((int64_t)1 << 34)) return fail(NEUS2_ERR_SHAPE, "count = %lld out of range", (long long)count);
+    if (dtype != 0 && dtype != 1) return fail(NEUS2_ERR_CONFIG, "dtype = %d, must be 0 (fp32) or 1 (fp16)", dtype);
+    if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return fail(NEUS2_ERR_CONFIG, "beta1, beta2 must be in [0,1)");
+    NEUS2_TRY(check_ptr(param, "param"));
+    NEUS2_TRY(check_ptr(grad, "grad"));
+    NEUS2_TRY(check_ptr(m, "m"));
+    NEUS2_TRY(check_ptr(v, "v"));
+    if (dtype == 1) NEUS2_TRY(check_ptr(master, "master"));
+    if (count == 0) return NEUS2_OK;
+    AdamArgs a;
+    a.lr = lr; a.b1 = beta1; a.b2 = beta2; a.eps = eps;
+    a.inv_c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
+    a.inv_c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+    const dim3 grid((unsigned)((count + 255) / 256));
+    if (dtype == 1)
+        hipLaunchKernelGGL(adam_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, zero_grad);
+    else
+        hipLaunchKernelGGL(adam_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, zero_grad);
+    return check_launch("adam");
+}
+
+int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset, int64_t n, float* out,
+                    void* stream) {
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    if (!R || !T) return fail(NEUS2_ERR_NULL, "R or T is NULL");
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(out, "out"));
+    if (n == 0) return NEUS2_OK;
+    Rigid t;
+    for (int k = 0; k < 9; ++k) t.R[k] = R[k];
+    for (int k = 0; k < 3; ++k) t.T[k] = T[k];
+    t.scale = scale; t.offset = offset;
+    hipLaunchKernelGGL(rigid_fwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pos, t, n, out);
+    return check_launch("rigid transform");
+}
+
+int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float scale, int64_t n, float* Mb, void* stream) {
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    if (!T) return fail(NEUS2_ERR_NULL, "T is NULL");
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(d_out, "d_out"));
+    NEUS2_TRY(check_ptr(Mb, "Mb"));
+    if (n == 0) return NEUS2_OK;
+    Rigid t = {};
+    for (int k = 0; k < 3; ++k) t.T[k] = T[k];
+    t.scale = scale;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(rigid_bwd_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, pos, t, d_out, n, Mb);
+    return check_launch("rigid transform backward");
+}
+
+}  // extern "C"
+
+namespace neus2 {
+int launch_zero(float* p, int64_t count, hipStream_t st) {
+    if (count == 0) return NEUS2_OK;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, count);
+    return check_launch("zero");
+}
+}  // namespace neus2

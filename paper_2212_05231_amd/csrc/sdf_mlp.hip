@@ -1,0 +1,439 @@
+// SDF network: forward + analytic input gradient, and the backward pass with the
+// second-order term, fused per 32-point tile on the fp32 matrix cores.
+//
+// Paper: Eq. 1 ((d,g) = f_Theta(e)), Definition 1 (bias-free ReLU MLP, masks G_l, vectors
+// P_l^j and S_l^i), Eq. 2 (n = grad_x d), supplement Sec. B (dy/dx = H_L G_L ... G_2 H_1),
+// Theorem 1 (d(dy/dx)_(i,j)/dH_l = (P_l^j S_l^i)^T, second input derivative zero) and
+// Eqs. 7-8 (what is left of the chain rule).
+//
+// With i = 0 (the SDF output), S_l is the reverse sweep from row 0 of the last matrix and
+// the sum over j of P_l^j weighted by (de/dx) dL/dn is ONE forward-mode sweep t_l, so
+//     dL/dH_l = delta_l a_{l-1}^T  +  S_l^T t_{l-1}^T        (first + second order)
+// Both products contract over points and run as MFMA outer-product accumulations.
+// Activations and masks are recomputed in the backward kernel from the encoding (cheaper
+// than storing and re-reading four 64-wide vectors per point).
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace neus2 {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+struct SdfArgs {
+    const float* enc; const float* jac; const float* H[3];
+    const float* d_y; const float* d_normal;
+    float* y; float* q; float* normal;
+    float* dH[3]; float* d_enc; float* d_pos;
+    int64_t n; int active_levels;
+};
+
+// LDS copies of the matrices in both orientations ("f": rows = outputs, "t": rows = inputs).
+template <int D, int K>
+struct SdfWeights {
+    static constexpr int LDIN = D + 4;
+    float H1f[64 * LDIN];           // [64][D]
+    float H1t[32 * kLd64];          // [D][64], rows >= D zero
+    float H2f[K == 3 ? 64 * kLd64 : 4];
+    float H2t[K == 3 ? 64 * kLd64 : 4];
+    float HLf[32 * kLd64];          // last matrix [16][64], rows >= 16 zero
+    float HLt[64 * 20];             // its transpose [64][16]
+};
+
+template <int D, int K>
+__device__ void load_weights(SdfWeights<D, K>& w, const SdfArgs& a) {
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < 32 * kLd64; idx += kThreads) { w.H1t[idx] = 0.f; w.HLf[idx] = 0.f; }
+    __syncthreads();
+    for (int idx = tid; idx < 64 * D; idx += kThreads) {
+        const int o = idx / D, i = idx % D;
+        const float v = a.H[0][idx];
+        w.H1f[o * SdfWeights<D, K>::LDIN + i] = v;
+        w.H1t[i * kLd64 + o] = v;
+    }
+    if (K == 3) {
+        for (int idx = tid; idx < 64 * 64; idx += kThreads) {
+            const int o = idx / 64, i = idx % 64;
+            const float v = a.H[1][idx];
+            w.H2f[o * kLd64 + i] = v;
+            w.H2t[i * kLd64 + o] = v;
+        }
+    }
+    for (int idx = tid; idx < 16 * 64; idx += kThreads) {
+        const int o = idx / 64, i = idx % 64;
+        const float v = a.H[K - 1][idx];
+        w.HLf[o * kLd64 + i] = v;
+        w.HLt[i * 20 + o] = v;
+    }
+    __syncthreads();
+}
+
+// level-major [L][n][2] <-> register vector of width D.  Register r = 4g + 2u + f of lane half h
+// is feature f of level 4g + 2h + u.
+template <int D>
+__device__ __forceinline__ v16f load_levels(const float* __restrict__ src, int64_t n, int64_t i, bool valid,
+                                            int active, int h) {
+    v16f x = zero16();
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int level = 4 * g + 2 * h + u;
+            if (valid && level < active) {
+                const float2 v = reinterpret_cast<const float2*>(src)[(int64_t)level * n + i];
+                x[4 * g + 2 * u] = v.x;
+                x[4 * g + 2 * u + 1] = v.y;
+            }
+        }
+    return x;
+}
+
+template <int D>
+__device__ __forceinline__ void store_levels(float* __restrict__ dst, int64_t n, int64_t i, bool valid,
+                                             const v16f& x, int h) {
+    if (!valid) return;
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int level = 4 * g + 2 * h + u;
+            reinterpret_cast<float2*>(dst)[(int64_t)level * n + i] = make_float2(x[4 * g + 2 * u], x[4 * g + 2 * u + 1]);
+        }
+}
+
+// out_a = sum over this lane's features of x_k * J[k][a]   (J = de/dx, [L][n][2][3])
+template <int D>
+__device__ __forceinline__ void contract_jac(const float* __restrict__ jac, int64_t n, int64_t i, bool valid,
+                                             int active, int h, const v16f& x, float out[3]) {
+    out[0] = out[1] = out[2] = 0.f;
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int level = 4 * g + 2 * h + u;
+            if (valid && level < active) {
+                const float2* J = reinterpret_cast<const float2*>(jac) + ((int64_t)level * n + i) * 3;
+                const float2 a = J[0], b = J[1], c = J[2];     // (J00,J01) (J02,J10) (J11,J12)
+                const float x0 = x[4 * g + 2 * u], x1 = x[4 * g + 2 * u + 1];
+                out[0] += x0 * a.x + x1 * b.y;
+                out[1] += x0 * a.y + x1 * c.x;
+                out[2] += x0 * b.x + x1 * c.y;
+            }
+        }
+}
+
+// t_k = sum_a J[k][a] * v_a
+template <int D>
+__device__ __forceinline__ v16f apply_jac(const float* __restrict__ jac, int64_t n, int64_t i, bool valid,
+                                          int active, int h, const float v[3]) {
+    v16f t = zero16();
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int level = 4 * g + 2 * h + u;
+            if (valid && level < active) {
+                const float2* J = reinterpret_cast<const float2*>(jac) + ((int64_t)level * n + i) * 3;
+                const float2 a = J[0], b = J[1], c = J[2];
+                t[4 * g + 2 * u] = a.x * v[0] + a.y * v[1] + b.x * v[2];
+                t[4 * g + 2 * u + 1] = b.y * v[0] + c.x * v[1] + c.y * v[2];
+            }
+        }
+    return t;
+}
+
+// row 0 of the last matrix in register layout, masked: S_{K-1} of Definition 1 for output 0
+template <int D, int K>
+__device__ __forceinline__ void last_row_masked(const SdfWeights<D, K>& w, uint32_t m, int h, v16f* s) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 v = *reinterpret_cast<const float4*>(&w.HLf[32 * b + 8 * g + 4 * h]);
+            s[b][4 * g + 0] = v.x; s[b][4 * g + 1] = v.y; s[b][4 * g + 2] = v.z; s[b][4 * g + 3] = v.w;
+        }
+    apply_mask<2>(s, m);
+}
+
+// 16-wide per-point rows ([n][16]) <-> register vector: registers 0..7 of lane half h hold
+// columns 4h..4h+3 and 8+4h..8+4h+3.
+__device__ __forceinline__ v16f load_rows16(const float* __restrict__ src, int64_t i, bool valid, int h) {
+    v16f x = zero16();
+    if (valid) {
+        const float4 a = *reinterpret_cast<const float4*>(src + i * 16 + 4 * h);
+        const float4 b = *reinterpret_cast<const float4*>(src + i * 16 + 8 + 4 * h);
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+    return x;
+}
+
+__device__ __forceinline__ void store_rows16(float* __restrict__ dst, int64_t i, bool valid, int h, const v16f& x) {
+    if (!valid) return;
+    *reinterpret_cast<float4*>(dst + i * 16 + 4 * h) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<float4*>(dst + i * 16 + 8 + 4 * h) = make_float4(x[4], x[5], x[6], x[7]);
+}
+
+// ------------------------------------------------------------------------------------------
+template <int D, int K>
+__global__ __launch_bounds__(kThreads) void sdf_fwd_kernel(SdfArgs a) {
+    __shared__ SdfWeights<D, K> w;
+    load_weights<D, K>(w, a);
+    constexpr int LDIN = SdfWeights<D, K>::LDIN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        v16f x0[1] = {load_levels<D>(a.enc, a.n, i, valid, a.active_levels, h)};
+        v16f a1[2];
+        matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
+        const uint32_t m1 = relu_mask<2>(a1);
+        uint32_t m_last = m1;
+        v16f a2[2];
+        v16f yv[1];
+        if (K == 3) {
+            matvec<2, 2, kLd64>(w.H2f, a1, a2, j, h);
+            m_last = relu_mask<2>(a2);
+            matvec<1, 2, kLd64>(w.HLf, a2, yv, j, h);
+        } else {
+            matvec<1, 2, kLd64>(w.HLf, a1, yv, j, h);
+        }
+        store_rows16(a.y, i, valid, h, yv[0]);
+        // reverse sweep for dd/de
+        v16f s[2], s1[2];
+        last_row_masked<D, K>(w, m_last, h, s);
+        if (K == 3) {
+            matvec<2, 2, kLd64>(w.H2t, s, s1, j, h);
+            apply_mask<2>(s1, m1);
+        } else {
+            s1[0] = s[0]; s1[1] = s[1];
+        }
+        v16f qv[1];
+        matvec<1, 2, kLd64>(w.H1t, s1, qv, j, h);
+        store_levels<D>(a.q, a.n, i, valid, qv[0], h);
+        float nrm[3];
+        contract_jac<D>(a.jac, a.n, i, valid, a.active_levels, h, qv[0], nrm);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) nrm[c] += __shfl_xor(nrm[c], 32);
+        if (valid && h == 0) {
+            a.normal[3 * i + 0] = nrm[0]; a.normal[3 * i + 1] = nrm[1]; a.normal[3 * i + 2] = nrm[2];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+template <int D, int K>
+struct SdfBwdSmem {
+    SdfWeights<D, K> w;
+    float tiles[kWaves][2][32 * kLd64];
+};
+
+// add this wave's accumulator into dst[rows][cols] (row-major, ld = cols) with atomics
+template <int ZB, int XB>
+__device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, int cols, v16f (*G)[XB], int j, int h) {
+#pragma unroll
+    for (int mb = 0; mb < ZB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < XB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = 32 * mb + neuron_of(r, h), i = 32 * nb + j;
+                if (o < rows && i < cols) atomicAdd(dst + o * cols + i, G[mb][nb][r]);
+            }
+}
+
+template <int D, int K>
+__global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
+    __shared__ SdfBwdSmem<D, K> sm;
+    SdfWeights<D, K>& w = sm.w;
+    load_weights<D, K>(w, a);
+    constexpr int LDIN = SdfWeights<D, K>::LDIN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane & 31, h = lane >> 5;
+    float* Zt = sm.tiles[wave][0];
+    float* Xt = sm.tiles[wave][1];
+
+    v16f G1[2][1], G2[2][2], GL[1][2], tsum[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        G1[mb][0] = zero16();
+        G2[mb][0] = zero16(); G2[mb][1] = zero16();
+        GL[0][mb] = zero16();
+        tsum[mb] = zero16();
+    }
+
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        // ---- forward recompute
+        v16f x0[1] = {load_levels<D>(a.enc, a.n, i, valid, a.active_levels, h)};
+        v16f a1[2], a2[2];
+        matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
+        const uint32_t m1 = relu_mask<2>(a1);
+        uint32_t m_last = m1;
+        if (K == 3) {
+            matvec<2, 2, kLd64>(w.H2f, a1, a2, j, h);
+            m_last = relu_mask<2>(a2);
+        }
+        // ---- first-order chain delta_K .. delta_1, weight gradients as they appear
+        v16f dK[1] = {load_rows16(a.d_y, i, valid, h)};
+        v16f d2[2], d1[2];
+        stage<1, kLd64>(Zt, dK, j, h);
+        stage<2, kLd64>(Xt, K == 3 ? a2 : a1, j, h);
+        wave_lds_fence();
+        outer_accumulate<1, 2, kLd64, kLd64>(GL, Zt, Xt, j, h);
+        matvec<2, 1, 20, 8>(w.HLt, dK, d2, j, h);
+        apply_mask<2>(d2, m_last);
+        if (K == 3) {
+            wave_lds_fence();
+            stage<2, kLd64>(Zt, d2, j, h);
+            stage<2, kLd64>(Xt, a1, j, h);
+            wave_lds_fence();
+            outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+            matvec<2, 2, kLd64>(w.H2t, d2, d1, j, h);
+            apply_mask<2>(d1, m1);
+        } else {
+            d1[0] = d2[0]; d1[1] = d2[1];
+        }
+        wave_lds_fence();
+        stage<2, kLd64>(Zt, d1, j, h);
+        stage<1, kLd64>(Xt, x0, j, h);
+        wave_lds_fence();
+        outer_accumulate<2, 1, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        v16f de[1];
+        matvec<1, 2, kLd64>(w.H1t, d1, de, j, h);
+        store_levels<D>(a.d_enc, a.n, i, valid, de[0], h);
+        if (a.d_pos) {
+            float dp[3];
+            contract_jac<D>(a.jac, a.n, i, valid, a.active_levels, h, de[0], dp);
+#pragma unroll
+            for (int c = 0; c < 3; ++c) dp[c] += __shfl_xor(dp[c], 32);
+            if (valid && h == 0) {
+                a.d_pos[3 * i + 0] += dp[0]; a.d_pos[3 * i + 1] += dp[1]; a.d_pos[3 * i + 2] += dp[2];
+            }
+        }
+        // ---- second order: S sweep (reverse) and t sweep (forward mode), Theorem 1
+        float nb3[3] = {0.f, 0.f, 0.f};
+        if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }
+        v16f t0[1] = {apply_jac<D>(a.jac, a.n, i, valid, a.active_levels, h, nb3)};
+        v16f s2[2], s1[2];
+        last_row_masked<D, K>(w, m_last, h, s2);
+        if (K == 3) {
+            matvec<2, 2, kLd64>(w.H2t, s2, s1, j, h);
+            apply_mask<2>(s1, m1);
+        } else {
+            s1[0] = s2[0]; s1[1] = s2[1];
+        }
+        wave_lds_fence();
+        stage<2, kLd64>(Zt, s1, j, h);
+        stage<1, kLd64>(Xt, t0, j, h);
+        wave_lds_fence();
+        outer_accumulate<2, 1, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        v16f t1[2], t2[2];
+        matvec<2, 1, LDIN, D / 2>(w.H1f, t0, t1, j, h);
+        apply_mask<2>(t1, m1);
+        if (K == 3) {
+            wave_lds_fence();
+            stage<2, kLd64>(Zt, s2, j, h);
+            stage<2, kLd64>(Xt, t1, j, h);
+            wave_lds_fence();
+            outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+            matvec<2, 2, kLd64>(w.H2f, t1, t2, j, h);
+            apply_mask<2>(t2, m_last);
+            tsum[0] += t2[0]; tsum[1] += t2[1];
+        } else {
+            tsum[0] += t1[0]; tsum[1] += t1[1];
+        }
+        wave_lds_fence();
+    }
+    // S_K is the unit row selecting the SDF output: row 0 of the last matrix's gradient gets
+    // the sum of t_{K-1} over points.  One outer product with a one-hot factor does the
+    // cross-lane sum of the per-lane partials.
+    {
+        v16f onehot[1] = {zero16()};
+        if (h == 0) onehot[0][0] = 1.f;
+        stage<1, kLd64>(Zt, onehot, j, h);
+        stage<2, kLd64>(Xt, tsum, j, h);
+        wave_lds_fence();
+        outer_accumulate<1, 2, kLd64, kLd64>(GL, Zt, Xt, j, h);
+    }
+    __syncthreads();
+    // ---- reduce over the block's waves, then one atomic add per element and block
+    float* scratch = &sm.tiles[0][0][0];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        G1[mb][0] = block_sum<kWaves>(scratch, G1[mb][0], wave, lane);
+        GL[0][mb] = block_sum<kWaves>(scratch, GL[0][mb], wave, lane);
+        if (K == 3) {
+            G2[mb][0] = block_sum<kWaves>(scratch, G2[mb][0], wave, lane);
+            G2[mb][1] = block_sum<kWaves>(scratch, G2[mb][1], wave, lane);
+        }
+    }
+    if (wave == kWaves - 1) {
+        flush_grad<2, 1>(a.dH[0], 64, D, G1, j, h);
+        if (K == 3) flush_grad<2, 2>(a.dH[1], 64, 64, G2, j, h);
+        flush_grad<1, 2>(a.dH[K - 1], 16, 64, GL, j, h);
+    }
+}
+
+template <int D, int K>
+int run_fwd(const SdfArgs& a, hipStream_t st) {
+    const int64_t tiles = (a.n + 31) / 32;
+    const int64_t want = (tiles + kWaves - 1) / kWaves;
+    const int blocks = persistent_blocks((const void*)sdf_fwd_kernel<D, K>, kThreads, want);
+    hipLaunchKernelGGL((sdf_fwd_kernel<D, K>), dim3(blocks), dim3(kThreads), 0, st, a);
+    return check_launch("sdf forward");
+}
+
+template <int D, int K>
+int run_bwd(const SdfArgs& a, hipStream_t st) {
+    const int64_t tiles = (a.n + 31) / 32;
+    const int64_t want = (tiles + kWaves - 1) / kWaves;
+    const int blocks = persistent_blocks((const void*)sdf_bwd_kernel<D, K>, kThreads, want);
+    hipLaunchKernelGGL((sdf_bwd_kernel<D, K>), dim3(blocks), dim3(kThreads), 0, st, a);
+    return check_launch("sdf backward");
+}
+
+SdfArgs base_args(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H, int64_t n) {
+    SdfArgs a = {};
+    a.enc = enc; a.jac = jac; a.n = n; a.active_levels = cfg->active_levels;
+    for (int l = 0; l < cfg->n_sdf_mats; ++l) a.H[l] = H[l];
+    return a;
+}
+
+}  // namespace
+
+int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
+                   int64_t n, float* y, float* q, float* normal, hipStream_t st) {
+    if (n == 0) return NEUS2_OK;
+    SdfArgs a = base_args(cfg, enc, jac, H, n);
+    a.y = y; a.q = q; a.normal = normal;
+    const int D = cfg->sdf_dims[0], K = cfg->n_sdf_mats;
+    if (D == 32 && K == 3) return run_fwd<32, 3>(a, st);
+    if (D == 32 && K == 2) return run_fwd<32, 2>(a, st);
+    if (D == 16 && K == 3) return run_fwd<16, 3>(a, st);
+    if (D == 16 && K == 2) return run_fwd<16, 2>(a, st);
+    return fail(NEUS2_ERR_UNSUPPORTED, "sdf network: input width %d with %d matrices has no kernel", D, K);
+}
+
+int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
+                   const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
+                   float* d_pos, hipStream_t st) {
+    if (n == 0) return NEUS2_OK;
+    SdfArgs a = base_args(cfg, enc, jac, H, n);
+    a.d_y = d_y; a.d_normal = d_normal; a.d_enc = d_enc; a.d_pos = d_pos;
+    for (int l = 0; l < cfg->n_sdf_mats; ++l) a.dH[l] = dH[l];
+    const int D = cfg->sdf_dims[0], K = cfg->n_sdf_mats;
+    if (D == 32 && K == 3) return run_bwd<32, 3>(a, st);
+    if (D == 32 && K == 2) return run_bwd<32, 2>(a, st);
+    if (D == 16 && K == 3) return run_bwd<16, 3>(a, st);
+    if (D == 16 && K == 2) return run_bwd<16, 2>(a, st);
+    return fail(NEUS2_ERR_UNSUPPORTED, "sdf network: input width %d with %d matrices has no kernel", D, K);
+}
+
+}  // namespace neus2

@@ -1,0 +1,99 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2212_05231_amd import binding as nb
+from paper_2212_05231_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "neus2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(neus2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 15
+    handle = C.CDLL(nb.LIB_PATH)
+    for name in names:
+        assert hasattr(handle, name), name
+    assert set(names) == set(nb.EXPORTS)
+    assert nb.lib().neus2_version() >= 1
+
+
+def test_struct_layout_matches_header():
+    # 5 ints + 2*32 ints + (1+5) + (1+5) ints + 2 ints + 2 floats
+    assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 2)
+    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 25
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_benchmark_descriptors_validate(k):
+    assert nb.validate_config(nb.make_config(wl.make_config(k))) == 0
+
+
+def test_bad_descriptors_are_rejected_with_a_message():
+    def broken(**kw):
+        cfg = wl.make_config(2)
+        c = nb.make_config(cfg)
+        for name, v in kw.items():
+            setattr(c, name, v)
+        return c
+    cases = [
+        (broken(n_levels=0), -3), (broken(n_levels=33), -3), (broken(n_features=4), -5),
+        (broken(log2_table_size=30), -3), (broken(active_levels=17), -3), (broken(table_dtype=2), -3),
+        (broken(n_sdf_mats=5), -5), (broken(samples_per_ray=65), -3), (broken(loss_kind=3), -3),
+        (broken(s=0.0), -3), (broken(beta=-1.0), -3),
+    ]
+    c = broken()
+    c.dense[15] = 1          # (2049)^3 vertices do not fit 2^19 slots
+    cases.append((c, -3))
+    c = broken()
+    c.sdf_dims[1] = 128
+    cases.append((c, -5))
+    for c, code in cases:
+        assert nb.validate_config(c) == code
+        assert len(nb.lib().neus2_last_error()) > 0
+    assert nb.lib().neus2_validate_config(None) == -1
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
+    L = nb.lib()
+    c = nb.make_config(wl.make_config(2))
+    ok = 0x1000
+    assert L.neus2_hash_encode(C.byref(c), None, ok, 10, ok, ok, None, None) == -1
+    assert b"pos" in L.neus2_last_error()
+    assert L.neus2_hash_encode(C.byref(c), ok, ok, 10, ok + 4, ok, None, None) == -4
+    assert L.neus2_hash_encode(C.byref(c), ok, ok, -1, ok, ok, None, None) == -2
+    assert L.neus2_sdf_fwd_grad(C.byref(c), ok, ok, None, 10, ok, ok, ok, None) == -1
+    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, ok, None, 64, ok, None) == -1
+    arr = (C.c_void_p * 3)(ok, ok, ok)
+    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, ok, arr, 63, ok, None) == -2     # not a multiple of 64
+    assert L.neus2_render_rays(C.byref(c), ok, 0, ok, 4, ok, ok, None) == -2
+    assert L.neus2_loss(C.byref(c), ok, ok, ok, ok, 3, 100, ok, ok, ok, ok, None) == -2
+    assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 1, 0.01, 0.9, 0.99, 1e-15, 1, 1, None) == -1   # fp16 needs master
+    assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 0, 0.01, 0.9, 0.99, 1e-15, 0, 1, None) == -3   # t starts at 1
+    assert L.neus2_rigid_fwd(ok, None, None, 1.0, 0.0, 10, ok, None) == -1
+    assert L.neus2_train_step(C.byref(c), None, 64, None) == -1
+
+
+def test_workload_generators_are_seeded_and_in_range():
+    import numpy as np
+    a = wl.make_workload(2, n_rays=16)
+    b = wl.make_workload(2, n_rays=16)
+    assert np.array_equal(a["batch"]["pos"], b["batch"]["pos"])
+    assert np.array_equal(a["params"]["tables"], b["params"]["tables"])
+    pos = a["batch"]["pos"]
+    assert pos.dtype == np.float32 and pos.min() >= 0 and pos.max() < 1
+    assert np.allclose(np.linalg.norm(a["batch"]["dirs"], axis=1), 1, atol=1e-6)
+    assert a["params"]["tables"].dtype == np.float16 and abs(a["params"]["tables"]).max() <= 1e-4 + 1e-7
+    assert wl.make_config(2).res == [16, 22, 30, 42, 58, 80, 111, 153, 212, 294, 406, 561, 776, 1072, 1482, 2048]
+    assert wl.make_config(1).res == [16, 24, 36, 54, 81, 121, 182, 273]
+    assert wl.make_config(4).dense[:7] == [1, 1, 1, 1, 1, 1, 0]

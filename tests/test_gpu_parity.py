@@ -1,0 +1,411 @@
+"""Parity of the HIP library (through its C ABI) with the float64 oracle, element by element
+on the same seeded inputs.  All tests here need an MI355X.
+
+Tolerances (stated by the benchmark contract): table indices bit-exact; forward values
+relative L2 error <= 1e-5 per tensor; gradients <= 1e-4 per tensor (5e-3 / 2e-3 are allowed
+with fp16 tables, but the oracle sees the same fp16-rounded tables, so the fp32 bars are
+applied throughout).
+"""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import neus2_oracle as o
+from paper_2212_05231_amd import binding as nb
+from paper_2212_05231_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+FWD_TOL = 1e-5
+GRAD_TOL = 1e-4
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    nb.lib()
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def from_level_major(t, n):
+    """[L][n][F] -> [n, L*F]"""
+    a = t.detach().cpu().numpy().astype(np.float64)
+    return np.transpose(a, (1, 0, 2)).reshape(n, -1)
+
+
+def jac_from_level_major(t, n):
+    a = t.detach().cpu().numpy().astype(np.float64)        # [L][n][F][3]
+    return np.transpose(a, (1, 0, 2, 3)).reshape(n, -1, 3)
+
+
+def to_level_major(a, L):
+    """[n, L*F] -> torch [L][n][F]"""
+    n = a.shape[0]
+    return torch.as_tensor(np.ascontiguousarray(np.transpose(a.reshape(n, L, 2), (1, 0, 2))), dtype=torch.float32).cuda()
+
+
+def cuda(a, dtype=torch.float32):
+    return torch.as_tensor(np.ascontiguousarray(a)).to(dtype=dtype).cuda().contiguous()
+
+
+def run_step(k, n_rays, want_pos=False, scale_tables=None, active=None, spr=None):
+    w = wl.make_workload(k, n_rays=n_rays)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    if active is not None:
+        cfg.active_levels = active
+    if scale_tables is not None:
+        params["tables"] = (params["tables"].astype(np.float64) * scale_tables).astype(params["tables"].dtype)
+    if k == 5:
+        R = o.rotation_from_axis_angle(batch["omega"])
+        batch["pos"] = np.clip(o.rigid_forward(batch["pos"], R, batch["shift"], 0.5, 0.5), 0, 1 - 2.0 ** -24).astype(np.float32)
+    n = batch["pos"].shape[0]
+    step = nb.Step(cfg, params, n, want_pos_grad=want_pos)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.train_step()
+    torch.cuda.synchronize()
+    ref = o.train_step(cfg, params, batch, want_pos_grad=want_pos)
+    return cfg, step, ref, n
+
+
+def check_step(cfg, step, ref, n, want_pos=False):
+    errs = {}
+    errs["enc"] = rel(from_level_major(step.enc, n), ref["he"]["enc"])
+    errs["jac"] = rel(jac_from_level_major(step.jac, n), ref["he"]["jac"])
+    errs["y"] = rel(step.y.cpu().numpy(), ref["y"])
+    errs["q"] = rel(from_level_major(step.q, n), ref["q"])
+    errs["normal"] = rel(step.normal.cpu().numpy(), ref["normal"])
+    loss = step.loss.cpu().numpy()
+    errs["loss"] = abs(float(loss[0] + loss[1]) - ref["loss"]) / abs(ref["loss"])
+    if cfg.loss_kind == 1:
+        errs["rgb"] = rel(step.rgb.cpu().numpy(), ref["rgb"])
+        errs["C"] = rel(step.C.cpu().numpy(), ref["C"])
+        errs["weights"] = rel(step.weights.cpu().numpy().reshape(ref["weights"].shape), ref["weights"])
+    for name, e in errs.items():
+        assert e <= FWD_TOL, (name, e, errs)
+    g = {}
+    g["d_y"] = rel(step.d_y.cpu().numpy(), ref["d_y"])
+    g["d_normal"] = rel(step.d_normal.cpu().numpy(), ref["d_normal"])
+    act = cfg.active_levels * 2
+    g["d_enc"] = rel(from_level_major(step.d_enc, n)[:, :act], ref["d_enc"][:, :act])
+    for l, (a, b) in enumerate(zip(step.dH, ref["dH"])):
+        g[f"dH{l}"] = rel(a.cpu().numpy(), b)
+    for l, (a, b) in enumerate(zip(step.dW, ref["dW"])):
+        g[f"dW{l}"] = rel(a.cpu().numpy(), b)
+    g["d_tables"] = rel(step.d_tables.cpu().numpy(), ref["dtables"])
+    if want_pos:
+        g["d_pos"] = rel(step.d_pos.cpu().numpy(), ref["dpos"])
+    for name, e in g.items():
+        assert e <= GRAD_TOL, (name, e, g)
+    errs.update(g)
+    return errs
+
+
+# ------------------------------------------------------------------ encoding
+
+@pytest.mark.parametrize("k,n_rays", [(1, 4096 + 77), (2, 50), (4, 9)])
+def test_hash_encode_indices_bit_exact_and_values(k, n_rays):
+    w = wl.make_workload(k, n_rays=n_rays)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    pos = batch["pos"].copy()
+    pos[:4] = np.array([[0, 0, 0], [1, 1, 1], [1 - 2.0 ** -24, 0.5, 0.25], [np.nan, -1.0, 2.0]], dtype=np.float32)
+    n = pos.shape[0]
+    c = nb.make_config(cfg)
+    L = cfg.n_levels
+    tables = cuda(params["tables"], torch.float16 if cfg.table_dtype == "f16" else torch.float32)
+    enc = torch.empty(L, n, 2, device="cuda")
+    jac = torch.empty(L, n, 2, 3, device="cuda")
+    idx = torch.zeros(n, L, 8, dtype=torch.int32, device="cuda")
+    nb.hash_encode(c, cuda(pos), tables, enc, jac, idx)
+    torch.cuda.synchronize()
+    ref = o.hash_encode(cfg, params["tables"], pos)
+    got_idx = idx.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+    assert np.array_equal(got_idx, ref["idx"])
+    assert rel(from_level_major(enc, n), ref["enc"]) <= FWD_TOL
+    assert rel(jac_from_level_major(jac, n), ref["jac"]) <= FWD_TOL
+    # per-element check as well (fp32 sums of 8 products)
+    np.testing.assert_allclose(from_level_major(enc, n), ref["enc"], rtol=2e-5, atol=1e-9)
+
+
+def test_fp16_subnormal_table_entries_are_not_flushed():
+    cfg = wl.make_config(2)
+    c = nb.make_config(cfg)
+    tab = np.full((cfg.n_levels, cfg.table_size, 2), 3e-6, dtype=np.float16)      # subnormal in fp16
+    pos = wl.make_points(257, 5)
+    enc = torch.empty(cfg.n_levels, 257, 2, device="cuda")
+    jac = torch.empty(cfg.n_levels, 257, 2, 3, device="cuda")
+    nb.hash_encode(c, cuda(pos), cuda(tab, torch.float16), enc, jac)
+    np.testing.assert_allclose(enc.cpu().numpy(), float(np.float16(3e-6)), rtol=1e-6)
+
+
+def test_progressive_mask_zeroes_inactive_levels():
+    cfg, step, ref, n = run_step(3, 8)
+    assert torch.all(step.enc[cfg.active_levels:] == 0) and torch.all(step.jac[cfg.active_levels:] == 0)
+    assert torch.all(step.d_tables[cfg.active_levels:] == 0)
+    check_step(cfg, step, ref, n)
+
+
+# ------------------------------------------------------------------ single calls
+
+def test_sdf_fwd_grad_alone_with_large_values():
+    """Random encodings of order one (the workloads' are ~1e-4) so that masks are mixed."""
+    rng = np.random.default_rng(0)
+    for k, n in ((1, 1000 + 19), (2, 2048 + 5)):
+        cfg = wl.make_config(k)
+        c = nb.make_config(cfg)
+        L, D = cfg.n_levels, cfg.enc_dim
+        H = [rng.normal(size=(cfg.sdf_dims[i + 1], cfg.sdf_dims[i])).astype(np.float32) * 0.3 for i in range(len(cfg.sdf_dims) - 1)]
+        e = rng.normal(size=(n, D)).astype(np.float32)
+        J = rng.normal(size=(n, D, 3)).astype(np.float32)
+        y = torch.empty(n, 16, device="cuda")
+        q = torch.empty(L, n, 2, device="cuda")
+        nrm = torch.empty(n, 3, device="cuda")
+        jac_lm = cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+        nb.sdf_fwd_grad(c, to_level_major(e, L), jac_lm, [cuda(h) for h in H], n, y, q, nrm)
+        torch.cuda.synchronize()
+        yr, acts, masks = o.mlp_forward(H, e)
+        S, qr = o.mlp_input_gradient(H, masks, 0)
+        assert rel(y.cpu().numpy(), yr) <= FWD_TOL
+        assert rel(from_level_major(q, n), qr) <= FWD_TOL
+        assert rel(nrm.cpu().numpy(), np.einsum("nk,nka->na", qr, J.astype(np.float64))) <= FWD_TOL
+
+
+def test_render_forward_backward_alone():
+    rng = np.random.default_rng(1)
+    for spr, rays in ((64, 37), (17, 9), (1, 5), (2, 3)):
+        cfg = wl.make_config(2)
+        cfg.samples_per_ray = spr
+        c = nb.make_config(cfg)
+        n = rays * spr
+        sdf = (rng.normal(size=(rays, spr)) * 0.05).astype(np.float32)
+        if spr == 64:
+            sdf[0] = np.linspace(0.3, -0.3, spr)             # a ray that crosses the surface
+            sdf[1] = np.sort(sdf[1])                         # increasing: renders nothing
+        rgb = rng.uniform(size=(rays, spr, 3)).astype(np.float32)
+        dC = rng.normal(size=(rays, 3)).astype(np.float32)
+        y = np.zeros((n, 16), dtype=np.float32)
+        y[:, 0] = sdf.reshape(-1)
+        Cg = torch.empty(rays, 3, device="cuda")
+        wg = torch.empty(n, device="cuda")
+        yg = cuda(y)
+        nb.render_rays(c, yg, 16, cuda(rgb.reshape(n, 3)), rays, Cg, wg)
+        ds = torch.empty(n, device="cuda")
+        dr = torch.empty(n, 3, device="cuda")
+        nb.render_rays_bwd(c, yg, 16, cuda(rgb.reshape(n, 3)), cuda(dC), rays, ds, dr)
+        torch.cuda.synchronize()
+        Cr, wr, alpha, _ = o.render_rays(sdf.astype(np.float64), rgb.astype(np.float64), cfg.s)
+        d_sdf, d_rgb = o.render_rays_backward(sdf.astype(np.float64), rgb.astype(np.float64), cfg.s, dC.astype(np.float64))
+        assert rel(Cg.cpu().numpy(), Cr) <= FWD_TOL
+        assert rel(wg.cpu().numpy().reshape(rays, spr), wr) <= FWD_TOL
+        assert rel(dr.cpu().numpy().reshape(rays, spr, 3), d_rgb) <= GRAD_TOL
+        if spr > 1:
+            assert rel(ds.cpu().numpy().reshape(rays, spr), d_sdf) <= GRAD_TOL
+        else:
+            assert torch.all(ds == 0)
+        if spr == 64:
+            assert np.all(wg.cpu().numpy().reshape(rays, spr)[1] == 0)
+
+
+def test_color_forward_backward_alone():
+    rng = np.random.default_rng(2)
+    cfg = wl.make_config(2)
+    c = nb.make_config(cfg)
+    rays, spr = 21, cfg.samples_per_ray
+    n = rays * spr
+    W = [rng.normal(size=(cfg.color_dims[i + 1], cfg.color_dims[i])).astype(np.float32) * 0.3 for i in range(3)]
+    pos = rng.uniform(size=(n, 3)).astype(np.float32)
+    nrm = rng.normal(size=(n, 3)).astype(np.float32)
+    dirs = rng.normal(size=(rays, 3))
+    dirs = (dirs / np.linalg.norm(dirs, axis=1, keepdims=True)).astype(np.float32)
+    y = rng.normal(size=(n, 16)).astype(np.float32)
+    d_rgb = rng.normal(size=(n, 3)).astype(np.float32)
+    d_sdf = rng.normal(size=(n,)).astype(np.float32)
+    dn0 = rng.normal(size=(n, 3)).astype(np.float32)
+    Wg = [cuda(w) for w in W]
+    rgb = torch.empty(n, 3, device="cuda")
+    args = (cuda(pos), cuda(nrm), cuda(dirs), cuda(y))
+    nb.color_fwd(c, *args, Wg, n, rgb)
+    dW = [torch.zeros_like(w) for w in Wg]
+    d_y = torch.empty(n, 16, device="cuda")
+    d_normal = cuda(dn0)
+    d_pos = torch.empty(n, 3, device="cuda")
+    nb.color_bwd(c, *args, Wg, cuda(d_rgb), cuda(d_sdf), n, dW, d_y, d_normal, d_pos)
+    torch.cuda.synchronize()
+    cin = o.color_input(pos, nrm.astype(np.float64), dirs, y.astype(np.float64), spr)
+    rgb_r, acts, masks = o.color_forward(W, cin)
+    assert rel(rgb.cpu().numpy(), rgb_r) <= FWD_TOL
+    d_u = d_rgb * rgb_r * (1 - rgb_r)
+    gW, d_cin, _ = o.mlp_backward(W, acts, masks, d_u)
+    for a, b in zip(dW, gW):
+        assert rel(a.cpu().numpy(), b) <= GRAD_TOL
+    want_dy = d_cin[:, 22:38].copy()
+    want_dy[:, 0] += d_sdf
+    assert rel(d_y.cpu().numpy(), want_dy) <= GRAD_TOL
+    assert rel(d_normal.cpu().numpy(), dn0 + d_cin[:, 3:6]) <= GRAD_TOL
+    assert rel(d_pos.cpu().numpy(), d_cin[:, 0:3]) <= GRAD_TOL
+
+
+def test_adam_fp32_and_fp16():
+    rng = np.random.default_rng(3)
+    cnt = 100003
+    p = rng.normal(size=cnt).astype(np.float32) * 1e-3
+    g = rng.normal(size=cnt).astype(np.float32) * 1e-4
+    g[:10] = 0.0
+    m = rng.normal(size=cnt).astype(np.float32) * 1e-5
+    v = np.abs(rng.normal(size=cnt)).astype(np.float32) * 1e-9
+    for dtype in (0, 1):
+        for t in (1, 7):
+            m0 = np.zeros_like(m) if t == 1 else m
+            v0 = np.zeros_like(v) if t == 1 else v
+            pg, gg, mg, vg = cuda(p), cuda(g), cuda(m0), cuda(v0)
+            if dtype == 1:
+                half = cuda(p, torch.float16)
+                nb.adam_step(half, pg, gg, mg, vg, 1, 1e-2, 0.9, 0.99, 1e-15, t)
+            else:
+                nb.adam_step(pg, None, gg, mg, vg, 0, 1e-2, 0.9, 0.99, 1e-15, t)
+            torch.cuda.synchronize()
+            pr, mr, vr = o.adam_step(p, g, m0, v0, t, 1e-2, 0.9, 0.99, 1e-15)
+            np.testing.assert_allclose(pg.cpu().numpy(), pr, rtol=2e-6, atol=1e-9)
+            np.testing.assert_allclose(mg.cpu().numpy(), mr, rtol=2e-6, atol=1e-12)
+            np.testing.assert_allclose(vg.cpu().numpy(), vr, rtol=2e-6, atol=1e-16)
+            assert torch.all(gg == 0)
+            if t == 1:
+                assert np.array_equal(pg.cpu().numpy()[:10], p[:10])      # zero gradient: unchanged
+            if dtype == 1:
+                # the fp16 copy is the round-to-nearest-even of the fp32 master the kernel wrote
+                assert torch.equal(half, pg.to(torch.float16))
+
+
+def test_rigid_forward_backward():
+    rng = np.random.default_rng(4)
+    n = 5000
+    x = rng.uniform(-1, 1, size=(n, 3)).astype(np.float32)
+    tr = wl.make_rigid(9)
+    R = o.rotation_from_axis_angle(tr["omega"])
+    out = torch.empty(n, 3, device="cuda")
+    nb.rigid_fwd(cuda(x), R.reshape(-1), tr["shift"], 0.5, 0.5, out)
+    R32 = R.astype(np.float32).astype(np.float64)
+    T32 = tr["shift"].astype(np.float32).astype(np.float64)
+    assert rel(out.cpu().numpy(), o.rigid_forward(x, R32, T32, 0.5, 0.5)) <= 1e-6
+    d_out = rng.normal(size=(n, 3)).astype(np.float32)
+    Mb = torch.zeros(12, device="cuda")
+    nb.rigid_bwd(cuda(x), tr["shift"], cuda(d_out), 0.5, Mb)
+    torch.cuda.synchronize()
+    M, dT, b = o.rigid_backward(x, R32, T32, d_out, 0.5)
+    got = Mb.cpu().numpy()
+    assert rel(got[:9].reshape(3, 3), M) <= GRAD_TOL
+    assert rel(got[9:], b) <= GRAD_TOL
+
+
+# ------------------------------------------------------------------ whole steps
+
+def test_step_config1_full_size():
+    cfg, step, ref, n = run_step(1, 4096)
+    print(check_step(cfg, step, ref, n))
+
+
+def test_step_config1_ragged_tail_and_position_gradient():
+    cfg, step, ref, n = run_step(1, 1000 + 13, want_pos=True, scale_tables=3000.0)
+    print(check_step(cfg, step, ref, n, want_pos=True))
+
+
+@pytest.mark.parametrize("k,n_rays", [(2, 96), (3, 40), (4, 24)])
+def test_step_ray_configs_small(k, n_rays):
+    cfg, step, ref, n = run_step(k, n_rays)
+    print(check_step(cfg, step, ref, n))
+
+
+def test_step_config2_with_order_one_tables_and_position_gradient():
+    """Tables scaled so that SDF values, alphas and masks are non-degenerate."""
+    cfg, step, ref, n = run_step(2, 64, want_pos=True, scale_tables=2000.0)
+    assert np.any(ref["alpha"] > 0.05)
+    print(check_step(cfg, step, ref, n, want_pos=True))
+
+
+def test_step_config5_frames_with_transform_gradient():
+    w = wl.make_workload(5, n_rays=32, frame=1)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    params["tables"] = (params["tables"].astype(np.float64) * 2000).astype(np.float16)
+    world = batch["pos"]
+    n = world.shape[0]
+    R = o.rotation_from_axis_angle(batch["omega"]).astype(np.float32)
+    T = batch["shift"].astype(np.float32)
+    step = nb.Step(cfg, params, n, want_pos_grad=True)
+    step.set_batch(batch)
+    wg = cuda(world)
+    nb.rigid_fwd(wg, R.reshape(-1), T, 0.5, 0.5, step.pos)
+    step.zero_grads()
+    step.train_step()
+    Mb = torch.zeros(12, device="cuda")
+    nb.rigid_bwd(wg, T, step.d_pos, 0.5, Mb)
+    torch.cuda.synchronize()
+    # the oracle gets the SAME fp32 transformed positions (index parity), checked to 1e-6 against its own transform
+    pos_gpu = step.pos.cpu().numpy()
+    assert rel(pos_gpu, o.rigid_forward(world, R, T, 0.5, 0.5)) <= 1e-6
+    b2 = dict(batch)
+    b2["pos"] = pos_gpu
+    ref = o.train_step(cfg, params, b2, want_pos_grad=True)
+    check_step(cfg, step, ref, n, want_pos=True)
+    M, dT, bsum = o.rigid_backward(world, R, T, ref["dpos"], 0.5)
+    got = Mb.cpu().numpy()
+    assert rel(got[:9].reshape(3, 3), M) <= GRAD_TOL
+    assert rel(got[9:], bsum) <= GRAD_TOL
+
+
+def test_empty_batch_is_a_no_op():
+    cfg = wl.make_config(2)
+    params = wl.make_params(cfg, 1)
+    step = nb.Step(cfg, params, 0)
+    step.train_step()
+    torch.cuda.synchronize()
+    assert float(step.d_tables.abs().sum()) == 0.0
+
+
+def test_full_size_config2_sampled_rays():
+    """At the benchmark's full size and launch configuration: per-ray outputs of a random
+    sample of rays against the oracle run on those rays alone; adjoints scale with 1/rays."""
+    w = wl.make_workload(2)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    n = batch["pos"].shape[0]
+    spr = cfg.samples_per_ray
+    R = n // spr
+    step = nb.Step(cfg, params, n)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.train_step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    pick = np.sort(rng.choice(R, size=48, replace=False))
+    pts = (pick[:, None] * spr + np.arange(spr)[None, :]).reshape(-1)
+    sub = {"pos": batch["pos"][pts], "dirs": batch["dirs"][pick], "target": batch["target"][pick]}
+    ref = o.train_step(cfg, params, sub)
+    scale = len(pick) / R
+    ptsg = torch.as_tensor(pts).cuda()
+    assert rel(step.y[ptsg].cpu().numpy(), ref["y"]) <= FWD_TOL
+    assert rel(step.normal[ptsg].cpu().numpy(), ref["normal"]) <= FWD_TOL
+    assert rel(step.rgb[ptsg].cpu().numpy(), ref["rgb"]) <= FWD_TOL
+    assert rel(step.C[torch.as_tensor(pick).cuda()].cpu().numpy(), ref["C"]) <= FWD_TOL
+    assert rel(step.d_y[ptsg].cpu().numpy(), ref["d_y"] * scale) <= GRAD_TOL
+    assert rel(step.d_normal[ptsg].cpu().numpy(), ref["d_normal"] * scale) <= GRAD_TOL
+    assert rel(from_level_major(step.d_enc[:, ptsg], len(pts)), ref["d_enc"] * scale) <= GRAD_TOL
+    # properties that hold at any size: gradients are finite, inactive/untouched entries are zero
+    for g in step.dH + step.dW:
+        assert torch.isfinite(g).all() and float(g.abs().sum()) > 0
+    assert torch.isfinite(step.d_tables).all()
+
+
+def test_full_size_config2_against_full_oracle():
+    """The whole benchmark step, all gradients, against the oracle at full size (about a minute of CPU)."""
+    cfg, step, ref, n = run_step(2, None)
+    errs = check_step(cfg, step, ref, n)
+    print({k: f"{v:.2e}" for k, v in errs.items()})

@@ -201,6 +201,7 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     hipStream_t st = (hipStream_t)stream;
     const int64_t rays = n / cfg->samples_per_ray;
     NEUS2_TRY(launch_zero(b->loss, 2, st));
+    if (n == 0) return NEUS2_OK;   // an empty batch has no buffers to look at
     NEUS2_TRY(neus2_hash_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, stream));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
     if (cfg->loss_kind == 1) {

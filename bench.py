@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the NeuS2 training-step hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2]
+
+A step is one pass of the whole path over one synthetic batch: hash encode (+ Jacobian),
+SDF network forward + analytic normal, colour network, compositing, loss, the backward pass
+including the second-order term, scatter-add into the table gradient, and Adam on every
+parameter (which also clears the gradient buffers).  Inputs and parameters are resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+Besides the headline rate the line carries
+  roofline      for the kernel that takes the largest share of the step, its algorithmic
+                bytes (or flops) per launch divided by its average duration, measured here
+                with events on the stream the kernels run on;
+  kernels       the same figures for every kernel of the step;
+  cpu_baseline  the float64 numpy oracle timed on this machine's host cores on a bounded sample
+                of the same workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
+
+# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy
+# kernel of known size); see profiles/.  None = not measured for this build.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_cost(cfg, n):
+    """Per-launch algorithmic bytes and flops of every kernel, from per-sample figures.
+
+    Table gathers are counted at element size (8 corners x F x element bytes per level),
+    atomics as read + write, every streamed array once.  Flops count the multiply-adds the
+    method needs (2 per weight per use); recomputation inside the backward kernels and
+    padding of narrow layers are NOT counted.
+    """
+    lam, D, F = cfg.active_levels, cfg.enc_dim, cfg.n_features
+    et = 2 if cfg.table_dtype == "f16" else 4
+    K = len(cfg.sdf_dims) - 1
+    sd = cfg.sdf_dims
+    sdf_w = sum(sd[i] * sd[i + 1] for i in range(K))             # weights of the SDF network
+    sweep_w = sum(sd[i] * sd[i + 1] for i in range(K - 1))       # weights the reverse/forward sweeps use
+    cost = {
+        "hash_encode": {"bytes": 12 + lam * 8 * F * et + D * 4 + D * 12, "flops": 0},
+        "sdf_fwd_grad": {"bytes": D * 4 + D * 12 + 64 + D * 4 + 12, "flops": 2 * sdf_w + 2 * sweep_w + 2 * D * 3},
+        "sdf_mlp_bwd": {"bytes": D * 4 + D * 12 + 64 + 12 + D * 4,
+                        # first order: data + weight gradients; second order: t_0 = J nbar, the t sweep and the
+                        # outer products S_l^T t_{l-1}^T (S_K is a unit row: only row 0 of the last matrix)
+                        "flops": 4 * sdf_w + 2 * D * 3 + 2 * sweep_w + 2 * (sdf_w - sd[K - 1] * (sd[K] - 1))},
+        "hash_scatter_bwd": {"bytes": 12 + 12 + 2 * D * 4 + lam * 8 * F * 4 * 2, "flops": 0},
+    }
+    if cfg.loss_kind == 1:
+        cd = cfg.color_dims
+        col_w = sum(cd[i] * cd[i + 1] for i in range(3))
+        cost.update({
+            "color_fwd": {"bytes": 12 + 12 + 64 + 12, "flops": 2 * col_w},
+            "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 4 + 64 + 24, "flops": 2 * col_w + 4 * col_w},
+            "render_rays": {"bytes": 4 + 12 + 4, "flops": 0},
+            "render_rays_bwd": {"bytes": 4 + 12 + 4 + 12, "flops": 0},
+            "loss": {"bytes": 12 + 12, "flops": 0},
+        })
+    else:
+        cost["loss"] = {"bytes": 12 + 12 + 4 + 64, "flops": 0}
+    out = {k: {"bytes": v["bytes"] * n, "flops": v["flops"] * n} for k, v in cost.items()}
+    n_tab = cfg.n_levels * cfg.table_size * F
+    # read grad, m, v, fp32 value; write m, v, fp32 value, cleared grad (+ the fp16 copy)
+    per_param = 16 + 16 + (2 if cfg.table_dtype == "f16" else 0)
+    out["adam_tables"] = {"bytes": n_tab * per_param, "flops": 0}
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=2, help="1..4 (benchmark configuration number)")
+    ap.add_argument("--rays", type=int, default=None, help="override the number of rays (points for workload 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU; no multi-GPU path exists (see DESIGN.md, 'How it would shard').",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2212_05231_amd import binding as nb
+    from paper_2212_05231_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    nb.lib()                               # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    w = wl.make_workload(args.workload, n_rays=args.rays)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    n = batch["pos"].shape[0]
+    step = nb.Step(cfg, params, n)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.init_optimizer()
+
+    def one_step():
+        step.train_step()
+        step.adam()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = n * args.steps / dt
+    loss_now = [float(x) for x in step.loss.cpu().numpy()[:2]]
+
+    # ---- per-kernel durations, each call alone, events on the stream the kernels run on
+    kernels = {}
+    roofline = None
+    if not args.no_kernel_timing:
+        c, s = step.c, step
+        rays = s.rays
+        calls = {
+            "hash_encode": lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac),
+            "sdf_fwd_grad": lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal),
+            "sdf_mlp_bwd": lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc),
+            "hash_scatter_bwd": lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables),
+            "adam_tables": lambda: nb.adam_step(s.tables, s.opt["master"], s.d_tables, s.opt["m_t"], s.opt["v_t"],
+                                                1 if cfg.table_dtype == "f16" else 0, 0.0, 0.9, 0.99, 1e-15, 1, True),
+        }
+        if cfg.loss_kind == 1:
+            calls.update({
+                "color_fwd": lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb),
+                "render_rays": lambda: nb.render_rays(c, s.y, 16, s.rgb, rays, s.C, s.weights),
+                "loss": lambda: nb.loss(c, s.C, s.target, s.normal, s.y, rays, n, s.loss, s.dC, s.d_normal, None),
+                "render_rays_bwd": lambda: nb.render_rays_bwd(c, s.y, 16, s.rgb, s.dC, rays, s.d_sdf, s.d_rgb),
+                "color_bwd": lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.d_rgb, s.d_sdf, n, s.dW, s.d_y,
+                                                  torch.zeros_like(s.d_normal)),
+            })
+        else:
+            calls["loss"] = lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y)
+        # bring every buffer to the state it has inside a step
+        step.train_step()
+        torch.cuda.synchronize()
+        cost = algorithmic_cost(cfg, n)
+        reps = max(5, min(args.steps, 50))
+        for name, fn in calls.items():
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / reps
+            k = {"us": round(us, 2), "bytes": cost[name]["bytes"], "flops": cost[name]["flops"],
+                 "GBps": round(cost[name]["bytes"] / us * 1e-3, 1)}
+            if cost[name]["flops"]:
+                k["TFLOPs"] = round(cost[name]["flops"] / us * 1e-6, 2)
+            kernels[name] = k
+        dom = max(kernels, key=lambda kk: kernels[kk]["us"])
+        kd = kernels[dom]
+        if kd["flops"] and kd["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12) > kd["bytes"] / (HBM_PEAK_GBS * 1e9):
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": kd["TFLOPs"], "peak": MFMA_FP32_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(kd["TFLOPs"] / MFMA_FP32_PEAK_TFLOPS, 4)}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": kd["GBps"], "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(kd["GBps"] / HBM_PEAK_GBS, 4)}
+        roofline["us_per_launch"] = kd["us"]
+        roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((dom, cfg.name))
+
+    # ---- CPU baseline: the oracle as it stands, one thread, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_limits
+        from oracle import neus2_oracle as o
+        sample_rays = min(512, n // cfg.samples_per_ray)
+        ws = wl.make_workload(args.workload, n_rays=sample_rays)
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            reps = 0
+            while True:
+                o.train_step(ws["cfg"], ws["params"], ws["batch"])
+                reps += 1
+                el = time.perf_counter() - t0
+                if el > 10.0 or reps >= 8:
+                    break
+        ns = ws["batch"]["pos"].shape[0]
+        cpu = {"value": round(ns * reps / el, 1), "unit": "ray-samples/s", "cores": 1, "kind": "oracle",
+               "sample": f"{reps} forward+backward steps of the float64 numpy oracle on {sample_rays} rays x "
+                         f"{cfg.samples_per_ray} samples of the same workload (no Adam), {el:.1f} s, BLAS limited to 1 thread"}
+
+    line = {
+        "metric": "ray-samples/sec per training step (fwd+2nd-order bwd)",
+        "value": round(value, 1), "unit": "ray-samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "points_per_step": n, "rays": n // cfg.samples_per_ray,
+                   "samples_per_ray": cfg.samples_per_ray, "levels": cfg.n_levels, "active_levels": cfg.active_levels,
+                   "log2_table_size": cfg.log2_table_size, "table_dtype": cfg.table_dtype,
+                   "sdf_mlp": cfg.sdf_dims, "color_mlp": cfg.color_dims, "includes_adam": True},
+        "loss": loss_now,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -148,6 +148,18 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
                       const float* d_y, const float* d_normal, int64_t n, float* const* dH,
                       float* d_tables, float* d_enc, float* d_pos, void* stream);
 
+/* The two halves of neus2_sdf_bwd_2nd as calls of their own (same arguments, same meaning):
+ * the fused network backward (dH, d_enc, and the (de/dx)^T dL/de part of d_pos) ... */
+int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* jac,
+                      const float* const* H, const float* d_y, const float* d_normal, int64_t n,
+                      float* const* dH, float* d_enc, float* d_pos, void* stream);
+
+/* ... and the scatter-add into the table gradient (Eq. 7's term included; with d_pos, the
+ * mixed second derivative of the interpolation as well). */
+int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void* tables,
+                           const float* q, const float* d_enc, const float* d_normal, int64_t n,
+                           float* d_tables, float* d_pos, void* stream);
+
 /* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
  *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
  *   the full-precision copy, is updated, and param receives its round-to-nearest-even.

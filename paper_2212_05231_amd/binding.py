@@ -61,6 +61,8 @@ _SIGNATURES = {
     "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
+    "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
                                   C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
@@ -176,6 +178,16 @@ def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, 
                                    _ptr(d_enc), _ptr(d_pos), _stream()))
 
 
+def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None):
+    _check(lib().neus2_sdf_mlp_bwd(C.byref(c), _ptr(enc), _ptr(jac), _ptr_array(H), _ptr(d_y), _ptr(d_normal), n,
+                                   _ptr_array(dH), _ptr(d_enc), _ptr(d_pos), _stream()))
+
+
+def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None):
+    _check(lib().neus2_hash_scatter_bwd(C.byref(c), _ptr(pos), _ptr(tables), _ptr(q), _ptr(d_enc), _ptr(d_normal),
+                                        n, _ptr(d_tables), _ptr(d_pos), _stream()))
+
+
 def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True):
     _check(lib().neus2_adam_step(_ptr(param), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), grad.numel(), dtype,
                                  lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
@@ -204,8 +216,21 @@ class Step:
         f32 = dict(dtype=torch.float32, device=device)
         tdt = torch.float16 if cfg.table_dtype == "f16" else torch.float32
         self.tables = torch.as_tensor(params["tables"]).to(device=device, dtype=tdt).contiguous()
-        self.H = [torch.as_tensor(h).to(**f32).contiguous() for h in params["H"]]
-        self.W = [torch.as_tensor(w).to(**f32).contiguous() for w in params["W"]]
+        # all matrices of both networks live in one flat buffer (one Adam launch covers them);
+        # each matrix starts on a 16-byte boundary
+        mats = [torch.as_tensor(m, dtype=torch.float32) for m in list(params["H"]) + list(params["W"])]
+        offs, total = [], 0
+        for m in mats:
+            offs.append(total)
+            total += (m.numel() + 3) // 4 * 4
+        self.small = torch.zeros(max(total, 4), **f32)
+        self.d_small = torch.zeros_like(self.small)
+        views = [self.small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
+        gviews = [self.d_small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
+        for v, m in zip(views, mats):
+            v.copy_(m)
+        nH = len(params["H"])
+        self.H, self.W = views[:nH], views[nH:]
         self.pos = torch.zeros(n, 3, **f32)
         self.dirs = torch.zeros(max(self.rays, 1), 3, **f32)
         self.target = torch.zeros(max(self.rays, 1), 3, **f32)
@@ -218,8 +243,8 @@ class Step:
         self.weights, self.d_sdf = z(n), z(n)
         self.loss = z(4)
         self.d_pos = z(n, 3) if want_pos_grad else None
-        self.dH = [torch.zeros_like(h) for h in self.H]
-        self.dW = [torch.zeros_like(w) for w in self.W]
+        self.dH, self.dW = gviews[:nH], gviews[nH:]
+        self.opt = None
         self.d_tables = z(L, T, F)
         self._H, self._W = _ptr_array(self.H), _ptr_array(self.W)
         self._dH, self._dW = _ptr_array(self.dH), _ptr_array(self.dW)
@@ -239,9 +264,26 @@ class Step:
             self.target.copy_(torch.as_tensor(batch["target"], dtype=torch.float32))
 
     def zero_grads(self) -> None:
-        for g in self.dH + self.dW:
-            g.zero_()
+        self.d_small.zero_()
         self.d_tables.zero_()
+
+    def init_optimizer(self, lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-15) -> None:
+        """Adam state: moments for tables and matrices, fp32 master copy of fp16 tables."""
+        import torch
+        self.opt = {"lr": lr, "b1": beta1, "b2": beta2, "eps": eps, "t": 0,
+                    "m_t": torch.zeros_like(self.d_tables), "v_t": torch.zeros_like(self.d_tables),
+                    "m_s": torch.zeros_like(self.small), "v_s": torch.zeros_like(self.small),
+                    "master": self.tables.float() if self.tables.dtype == torch.float16 else None}
+
+    def adam(self) -> None:
+        """One Adam step on every parameter; the gradient buffers are cleared in the same pass."""
+        o = self.opt
+        o["t"] += 1
+        half = self.tables.dtype != self.d_tables.dtype
+        adam_step(self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"], 1 if half else 0,
+                  o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
+        adam_step(self.small, None, self.d_small, o["m_s"], o["v_s"], 0,
+                  o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
 
     def train_step(self) -> None:
         _check(lib().neus2_train_step(C.byref(self.c), C.byref(self.buffers), self.n, _stream()))

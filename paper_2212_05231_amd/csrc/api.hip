@@ -165,6 +165,37 @@ int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* j
     return launch_sdf_fwd(cfg, enc, jac, H, n, y, q, normal, (hipStream_t)stream);
 }
 
+int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
+                      const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
+                      float* d_pos, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, cfg->n_sdf_mats, "H"));
+    NEUS2_TRY(check_ptr(d_y, "d_y"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_mats((const void* const*)dH, cfg->n_sdf_mats, "dH"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    return launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, (hipStream_t)stream);
+}
+
+int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
+                           const float* d_enc, const float* d_normal, int64_t n, float* d_tables, float* d_pos,
+                           void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_ptr(d_tables, "d_tables"));
+    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, (hipStream_t)stream);
+}
+
 int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
                       const float* jac, const float* const* H, const float* q, const float* d_y,
                       const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,

@@ -135,6 +135,18 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, const float*
 // Backward.  d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a d_a w_c
 // (first-order term, and the term Eq. 7 keeps).  With WANT_POS the mixed second derivative
 // of the interpolation, contracted with q and dL/dn, is added into d_pos.
+//
+// The L2 executes float atomics at a fixed rate per (instruction, 64-byte line) request,
+// however many lanes of the instruction fall into that line.  So four adjacent lanes share
+// one point: lane (dx, f) of the group owns the corners with that x offset and feature f,
+// and each of its four atomic instructions (one per (dy, dz)) puts the group's four
+// addresses {slot(x), slot(x+1)} x {f0, f1} next to each other: the same 16 bytes on a
+// dense level, the same line for 7 of 8 cells on a hashed one.  On coarse levels, where
+// consecutive samples of a ray sit in the same cell, runs of equal cells inside the wave are
+// summed with a segmented scan first and only the last lane group of a run issues atomics.
+constexpr int kScatterPoints = kBlock / 4;     // points per workgroup
+constexpr int kMergeMaxRes = 128;              // run-merge only where runs exist
+
 template <typename T, bool WANT_POS>
 __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float* __restrict__ pos,
                                                          const T* __restrict__ tables,
@@ -145,43 +157,99 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
                                                          float* __restrict__ d_pos) {
     int level, pb;
     if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
-    const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
-    if (i >= n) return;
-    const float px = pos[3 * i + 0], py = pos[3 * i + 1], pz = pos[3 * i + 2];
-    const Cell c = locate(g, level, px, py, pz);
-    const int64_t o = (int64_t)level * n + i;
-    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-    const float2 qq = reinterpret_cast<const float2*>(q)[o];
-    const float fres = (float)g.res[level];
+    const int sub = threadIdx.x & 3;
+    const int dxb = sub >> 1, f = sub & 1;
+    const int64_t i_raw = (int64_t)pb * kScatterPoints + (threadIdx.x >> 2);
+    const bool valid = i_raw < n;
+    const int64_t i = valid ? i_raw : n - 1;       // keep every lane in the shuffles below
+    const int res = g.res[level];
+    const float fres = (float)res;
+    const float gx = __fmul_rn(clamp01(pos[3 * i + 0]), fres);
+    const float gy = __fmul_rn(clamp01(pos[3 * i + 1]), fres);
+    const float gz = __fmul_rn(clamp01(pos[3 * i + 2]), fres);
+    const int cx = min((int)floorf(gx), res - 1);
+    const int cy = min((int)floorf(gy), res - 1);
+    const int cz = min((int)floorf(gz), res - 1);
+    const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
+    const bool dense = (g.dense_bits >> level) & 1u;
+    uint32_t slot[4];
+    if (dense) {
+        const uint32_t s = (uint32_t)(res + 1);
+        const uint32_t base = (uint32_t)(cx + dxb) + (uint32_t)cy * s + (uint32_t)cz * s * s;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) slot[k] = base + (k & 1) * s + (k >> 1) * s * s;
+    } else {
+        const uint32_t hx = (uint32_t)(cx + dxb);
+        const uint32_t hy[2] = {(uint32_t)cy * kPrimeY, ((uint32_t)cy + 1u) * kPrimeY};
+        const uint32_t hz[2] = {(uint32_t)cz * kPrimeZ, ((uint32_t)cz + 1u) * kPrimeZ};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) slot[k] = (hx ^ hy[k & 1] ^ hz[k >> 1]) & g.table_mask;
+    }
+    const int64_t o = ((int64_t)level * n + i) * 2 + f;
+    const float de = d_enc[o];
+    const float qf = q[o];
     const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
-    float* gt = d_tables + (size_t)level * g.table_size * 2;
+    const float fx = dxb ? w0 : 1.f - w0;
+    const float sx = dxb ? 1.f : -1.f;
+    float val[4];
     float hp[3] = {0.f, 0.f, 0.f};
     const T* tab = tables + (size_t)level * g.table_size * 2;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
-        const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
-        const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
-        const float sx = (k & 1) ? 1.f : -1.f;
-        const float sy = (k & 2) ? 1.f : -1.f;
-        const float sz = (k & 4) ? 1.f : -1.f;
+    for (int k = 0; k < 4; ++k) {
+        const float fy = (k & 1) ? w1 : 1.f - w1;
+        const float fz = (k & 2) ? w2 : 1.f - w2;
+        const float sy = (k & 1) ? 1.f : -1.f;
+        const float sz = (k & 2) ? 1.f : -1.f;
         const float wk = fx * fy * fz;
         const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
-        atomicAdd(gt + 2 * (size_t)c.slot[k] + 0, wk * de.x + qq.x * dn);
-        atomicAdd(gt + 2 * (size_t)c.slot[k] + 1, wk * de.y + qq.y * dn);
+        val[k] = valid ? wk * de + qf * dn : 0.f;
         if (WANT_POS) {
-            const float2 v = load_entry<T>(tab, c.slot[k]);
-            const float qv = qq.x * v.x + qq.y * v.y;
-            // d/dx_b of sum_a nbar_a res d_a w_c  (times res for the chain rule of b)
-            hp[0] += qv * fres * (ny * (sx * sy * fz) + nz * (sx * fy * sz));
-            hp[1] += qv * fres * (nx * (sx * sy * fz) + nz * (fx * sy * sz));
-            hp[2] += qv * fres * (nx * (sx * fy * sz) + ny * (fx * sy * sz));
+            const float2 v2 = load_entry<T>(tab, slot[k]);
+            const float qv = qf * (f ? v2.y : v2.x) * fres;
+            hp[0] += qv * (ny * (sx * sy * fz) + nz * (sx * fy * sz));
+            hp[1] += qv * (nx * (sx * sy * fz) + nz * (fx * sy * sz));
+            hp[2] += qv * (nx * (sx * fy * sz) + ny * (fx * sy * sz));
         }
     }
+    bool issue = valid;
+    if (res <= kMergeMaxRes) {
+        // segmented inclusive scan over the wave's 16 lane groups, segments = runs of one cell
+        const int lane = threadIdx.x & 63, grp = lane >> 2;
+        const uint32_t cell = valid ? (uint32_t)cx + (uint32_t)res * ((uint32_t)cy + (uint32_t)res * (uint32_t)cz) : 0xFFFFFFFFu;
+        const uint32_t prev = __shfl_up(cell, 4);
+        const uint32_t next = __shfl_down(cell, 4);
+        bool head = grp == 0 || prev != cell;
+        const bool tail = grp == 15 || next != cell;
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+            float up[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) up[k] = __shfl_up(val[k], 4 * d);
+            const bool up_head = __shfl_up((int)head, 4 * d) != 0;
+            if (grp >= d && !head) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) val[k] += up[k];
+                head = up_head;
+            }
+        }
+        issue = valid && tail;
+    }
+    if (issue) {
+        float* gt = d_tables + (size_t)level * g.table_size * 2 + f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) atomicAdd(gt + 2 * (size_t)slot[k], val[k]);
+    }
     if (WANT_POS) {
-        atomicAdd(d_pos + 3 * i + 0, hp[0]);
-        atomicAdd(d_pos + 3 * i + 1, hp[1]);
-        atomicAdd(d_pos + 3 * i + 2, hp[2]);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            hp[c] += __shfl_xor(hp[c], 1);
+            hp[c] += __shfl_xor(hp[c], 2);
+        }
+        if (valid && sub == 0) {
+            atomicAdd(d_pos + 3 * i + 0, hp[0]);
+            atomicAdd(d_pos + 3 * i + 1, hp[1]);
+            atomicAdd(d_pos + 3 * i + 2, hp[2]);
+        }
     }
 }
 
@@ -212,7 +280,7 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
                    float* d_pos, hipStream_t st) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
-    const int pbs = (int)((n + kBlock - 1) / kBlock);
+    const int pbs = (int)((n + kScatterPoints - 1) / kScatterPoints);
     const dim3 grid(grid_blocks(g.active_levels, pbs));
 #define NEUS2_SCATTER(T, WP)                                                                   \
     hipLaunchKernelGGL((scatter_kernel<T, WP>), grid, dim3(kBlock), 0, st, g, pos, (const T*)tables, \

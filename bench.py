@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--rays", type=int, default=None, help="override the number of rays (points for workload 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a kernel of known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; no multi-GPU path exists (see DESIGN.md, 'How it would shard').",
@@ -116,6 +118,13 @@ def main() -> int:
     def one_step():
         step.train_step()
         step.adam()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 26, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         one_step()

@@ -9,6 +9,8 @@
 // Workgroups are dealt round-robin to the 8 XCDs by the hardware, so the block index is
 // decoded as  xcd = bid % 8,  level = xcd + 8 * slot : every XCD works on one level at a
 // time and that level's table (2 MiB in fp16 at T = 2^19) stays in its private 4 MiB L2.
+#include <cstring>
+
 #include "common.h"
 
 namespace neus2 {
@@ -253,6 +255,127 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
     }
 }
 
+// ---- scatter-add without global atomics: LDS-resident slot ranges ---------------------------
+//
+// Float atomics leave the L2 as one 32-byte read-modify-write per (instruction, line) and
+// the chip retires about 2e10 of them per second, which caps the kernel above at about four
+// requests per point and level.  For large batches the table gradient is therefore
+// accumulated in LDS instead: a level's T slots are cut into ranges of 16384 slots (128 KiB
+// of fp32 pairs, one workgroup's LDS), and the workgroup that owns a range walks over ALL
+// points of the level, keeps only the corners whose slot falls into its range, adds them
+// with LDS atomics, and finally adds its LDS image to the global gradient with plain
+// coalesced loads and stores (nobody else writes that range).  The index arithmetic is
+// repeated once per range, which is cheap next to the memory-side atomics it replaces.
+// Small dense levels need fewer ranges than there are compute units; their points are cut
+// into chunks handled by different workgroups, which then flush with (coalesced) atomics.
+constexpr int kOwnerThreads = 1024;
+constexpr int64_t kOwnerMinPoints = 1 << 16;
+constexpr int kOwnerSlotBits = 14;
+constexpr int kOwnerSlots = 1 << kOwnerSlotBits;
+
+struct OwnerPlan {
+    int n_entries;
+    int n_tasks;
+    int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries (hashed levels first)
+    short level[NEUS2_MAX_LEVELS];
+    short ranges[NEUS2_MAX_LEVELS];
+    short chunks[NEUS2_MAX_LEVELS];
+};
+
+__global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan,
+                                                                     const float* __restrict__ pos,
+                                                                     const float* __restrict__ q,
+                                                                     const float* __restrict__ d_enc,
+                                                                     const float* __restrict__ d_normal,
+                                                                     int64_t n, float* __restrict__ d_tables) {
+    __shared__ float acc[2 * kOwnerSlots];
+    for (int task = blockIdx.x; task < plan.n_tasks; task += gridDim.x) {
+        int e = 0;
+        while (e + 1 < plan.n_entries && task >= plan.first_task[e + 1]) ++e;
+        const int local = task - plan.first_task[e];
+        const int level = plan.level[e];
+        const int n_ranges = plan.ranges[e], n_chunks = plan.chunks[e];
+        const uint32_t range = (uint32_t)(local % n_ranges);
+        const int chunk = local / n_ranges;
+        const int64_t begin = n * chunk / n_chunks, end = n * (chunk + 1) / n_chunks;
+
+        for (int k = threadIdx.x; k < 2 * kOwnerSlots; k += kOwnerThreads) acc[k] = 0.f;
+        __syncthreads();
+
+        const float fres = (float)g.res[level];
+        for (int64_t i = begin + threadIdx.x; i < end; i += kOwnerThreads) {
+            const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
+            uint32_t match = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) match |= ((c.slot[k] >> kOwnerSlotBits) == range ? 1u : 0u) << k;
+            if (match) {
+                const int64_t o = (int64_t)level * n + i;
+                const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+                const float2 qq = reinterpret_cast<const float2*>(q)[o];
+                const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if ((match >> k) & 1u) {
+                        const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
+                        const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
+                        const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
+                        const float sx = (k & 1) ? 1.f : -1.f;
+                        const float sy = (k & 2) ? 1.f : -1.f;
+                        const float sz = (k & 4) ? 1.f : -1.f;
+                        const float wk = fx * fy * fz;
+                        const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
+                        float* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
+                        atomicAdd(a + 0, wk * de.x + qq.x * dn);
+                        atomicAdd(a + 1, wk * de.y + qq.y * dn);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+
+        const uint32_t first_slot = range << kOwnerSlotBits;
+        const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
+        float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
+        for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) {
+            const float v = acc[k];
+            if (v != 0.f) {
+                if (n_chunks == 1) dst[k] += v;
+                else atomicAdd(dst + k, v);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Which levels get how many ranges and point chunks.  Returns the cost in "all points of one
+// level" units so that the caller can compare with the atomic kernel.
+OwnerPlan make_owner_plan(const neus2_config* cfg, int workgroups) {
+    OwnerPlan p;
+    memset(&p, 0, sizeof(p));
+    const int64_t T = (int64_t)1 << cfg->log2_table_size;
+    int e = 0, tasks = 0;
+    for (int pass = 0; pass < 2; ++pass) {           // hashed (heavy, one chunk) first, then dense
+        for (int l = 0; l < cfg->active_levels; ++l) {
+            if ((cfg->dense[l] != 0) != (pass == 1)) continue;
+            const int64_t r1 = (int64_t)cfg->res[l] + 1;
+            const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
+            const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
+            int chunks = 1;
+            if (ranges * 2 <= workgroups / 8) chunks = workgroups / 8 / ranges;   // spread small levels over an eighth of the chip
+            p.level[e] = (short)l;
+            p.ranges[e] = (short)ranges;
+            p.chunks[e] = (short)chunks;
+            p.first_task[e] = tasks;
+            tasks += ranges * chunks;
+            ++e;
+        }
+    }
+    p.first_task[e] = tasks;
+    p.n_entries = e;
+    p.n_tasks = tasks;
+    return p;
+}
+
 int grid_blocks(int levels, int point_blocks) {
     const int slots = (levels + kXcd - 1) / kXcd;
     return kXcd * slots * point_blocks;
@@ -280,6 +403,15 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
                    float* d_pos, hipStream_t st) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
+    // Large batches: LDS-owner kernel (needs no global atomics on the big levels).  It does not
+    // produce the position gradient, and below ~2^16 points the atomic kernel is cheaper.
+    if (!d_pos && n >= kOwnerMinPoints && cfg->log2_table_size <= 15 + kOwnerSlotBits) {
+        const int wgs = compute_units();
+        const OwnerPlan plan = make_owner_plan(cfg, wgs);
+        hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0, st,
+                           g, plan, pos, q, d_enc, d_normal, n, d_tables);
+        return check_launch("hash scatter (owner)");
+    }
     const int pbs = (int)((n + kScatterPoints - 1) / kScatterPoints);
     const dim3 grid(grid_blocks(g.active_levels, pbs));
 #define NEUS2_SCATTER(T, WP)                                                                   \

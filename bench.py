@@ -148,7 +148,8 @@ def main() -> int:
             "hash_encode": lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac),
             "sdf_fwd_grad": lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal),
             "sdf_mlp_bwd": lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc),
-            "hash_scatter_bwd": lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables),
+            "hash_scatter_bwd": lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
+                                                              workspace=s.workspace),
             "adam_tables": lambda: nb.adam_step(s.tables, s.opt["master"], s.d_tables, s.opt["m_t"], s.opt["v_t"],
                                                 1 if cfg.table_dtype == "f16" else 0, 0.0, 0.9, 0.99, 1e-15, 1, True),
         }

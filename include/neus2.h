@@ -71,6 +71,11 @@ int neus2_version(void);
 /* Check a descriptor without a GPU.  Returns NEUS2_OK or the error a compute call would give. */
 int neus2_validate_config(const neus2_config* cfg /*[host]*/);
 
+/* Bytes of scratch the scatter-add wants for n points (0 if it would not use any; -1 on a bad
+ * descriptor).  The workspace is optional everywhere: without it (NULL, or too small) the
+ * scatter-add falls back to its atomic kernel, same results. */
+int64_t neus2_workspace_bytes(const neus2_config* cfg /*[host]*/, int64_t n);
+
 /* Multi-resolution hash encoding (Sec. 3 "InstantNGP", Sec. 4.1) and its Jacobian de/dx,
  * which Eq. 2 (n = grad_x d) and Eq. 7 need.  Per level: the point is clamped to [0,1], the
  * grid coordinate is the single binary32 product x*res, the cell is its floor (at most
@@ -142,11 +147,14 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
  *   d_enc [device, L*n*F]: overwritten with dL/de (also the scratch between the two kernels).
  *   d_pos [device, n*3] or NULL: if given, ADDED into with (de/dx)^T dL/de plus the mixed
  *   second derivative of the interpolation contracted with q and dL/dn (needed only when
- *   positions are themselves functions of a learnable transform, Eq. 9). */
+ *   positions are themselves functions of a learnable transform, Eq. 9).
+ *   workspace [device, workspace_bytes] or NULL: scratch for the scatter-add, see
+ *   neus2_workspace_bytes; contents are undefined afterwards. */
 int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables,
                       const float* enc, const float* jac, const float* const* H, const float* q,
                       const float* d_y, const float* d_normal, int64_t n, float* const* dH,
-                      float* d_tables, float* d_enc, float* d_pos, void* stream);
+                      float* d_tables, float* d_enc, float* d_pos, void* workspace,
+                      int64_t workspace_bytes, void* stream);
 
 /* The two halves of neus2_sdf_bwd_2nd as calls of their own (same arguments, same meaning):
  * the fused network backward (dH, d_enc, and the (de/dx)^T dL/de part of d_pos) ... */
@@ -158,7 +166,8 @@ int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* ja
  * mixed second derivative of the interpolation as well). */
 int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void* tables,
                            const float* q, const float* d_enc, const float* d_normal, int64_t n,
-                           float* d_tables, float* d_pos, void* stream);
+                           float* d_tables, float* d_pos, void* workspace, int64_t workspace_bytes,
+                           void* stream);
 
 /* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
  *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
@@ -189,6 +198,8 @@ typedef struct neus2_step_buffers {
     float* dC; float* d_sdf; float* d_rgb; float* d_y; float* d_normal; float* d_enc;
     float* d_pos;              /* NULL unless the position gradient is wanted */
     float* const* dH; float* const* dW; float* d_tables;
+    void* workspace;           /* optional scratch, see neus2_workspace_bytes */
+    int64_t workspace_bytes;
 } neus2_step_buffers;
 
 /* One forward + backward pass (everything above except Adam and the rigid transform), in the

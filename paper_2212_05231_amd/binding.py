@@ -38,7 +38,8 @@ class Neus2StepBuffers(C.Structure):
     _fields_ = [(name, _P) for name in (
         "pos", "dirs", "target", "tables", "H", "W",
         "enc", "jac", "y", "q", "normal", "rgb", "C", "weights", "loss",
-        "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables")]
+        "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables", "workspace")] + [
+        ("workspace_bytes", C.c_int64)]
 
 
 class Neus2Error(RuntimeError):
@@ -53,6 +54,7 @@ _SIGNATURES = {
     "neus2_last_error": (C.c_char_p, []),
     "neus2_version": (C.c_int, []),
     "neus2_validate_config": (C.c_int, [C.POINTER(Neus2Config)]),
+    "neus2_workspace_bytes": (C.c_int64, [C.POINTER(Neus2Config), C.c_int64]),
     "neus2_hash_encode": (C.c_int, [C.POINTER(Neus2Config), _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
@@ -60,9 +62,10 @@ _SIGNATURES = {
     "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, C.c_int64, _P, _P, _P]),
     "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
-    "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P,
+                                    C.c_int64, _P]),
     "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
-    "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P]),
+    "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
                                   C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
@@ -172,10 +175,15 @@ def loss(c, Cimg, target, normal, y, rays, n, loss_out, dC, d_normal, d_y):
                             _ptr(dC), _ptr(d_normal), _ptr(d_y), _stream()))
 
 
-def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos=None):
+def workspace_bytes(c, n) -> int:
+    return lib().neus2_workspace_bytes(C.byref(c), n)
+
+
+def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos=None, workspace=None):
     _check(lib().neus2_sdf_bwd_2nd(C.byref(c), _ptr(pos), _ptr(tables), _ptr(enc), _ptr(jac), _ptr_array(H),
                                    _ptr(q), _ptr(d_y), _ptr(d_normal), n, _ptr_array(dH), _ptr(d_tables),
-                                   _ptr(d_enc), _ptr(d_pos), _stream()))
+                                   _ptr(d_enc), _ptr(d_pos), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
 
 
 def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None):
@@ -183,9 +191,11 @@ def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None):
                                    _ptr_array(dH), _ptr(d_enc), _ptr(d_pos), _stream()))
 
 
-def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None):
+def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None, workspace=None):
     _check(lib().neus2_hash_scatter_bwd(C.byref(c), _ptr(pos), _ptr(tables), _ptr(q), _ptr(d_enc), _ptr(d_normal),
-                                        n, _ptr(d_tables), _ptr(d_pos), _stream()))
+                                        n, _ptr(d_tables), _ptr(d_pos), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                        _stream()))
 
 
 def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True):
@@ -208,7 +218,8 @@ class Step:
     """All device buffers of one training step, allocated once with torch, plus the
     `neus2_step_buffers` struct that `train_step` hands to the library."""
 
-    def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda"):
+    def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda",
+                 use_workspace: bool = True):
         import torch
         self.cfg, self.c, self.n = cfg, make_config(cfg), n
         L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
@@ -246,14 +257,17 @@ class Step:
         self.dH, self.dW = gviews[:nH], gviews[nH:]
         self.opt = None
         self.d_tables = z(L, T, F)
+        ws = workspace_bytes(self.c, n) if use_workspace else 0
+        self.workspace = torch.zeros(ws // 4, dtype=torch.int32, device=device) if ws > 0 else None
         self._H, self._W = _ptr_array(self.H), _ptr_array(self.W)
         self._dH, self._dW = _ptr_array(self.dH), _ptr_array(self.dW)
         b = Neus2StepBuffers()
         for name in ("pos", "dirs", "target", "tables", "enc", "jac", "y", "q", "normal", "rgb", "C", "weights",
-                     "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables"):
+                     "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables", "workspace"):
             setattr(b, name, _ptr(getattr(self, name)))
         b.H, b.W = C.cast(self._H, _P), C.cast(self._W, _P)
         b.dH, b.dW = C.cast(self._dH, _P), C.cast(self._dW, _P)
+        b.workspace_bytes = ws if self.workspace is not None else 0
         self.buffers = b
 
     def set_batch(self, batch: Dict[str, object]) -> None:

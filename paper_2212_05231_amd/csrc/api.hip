@@ -140,6 +140,11 @@ const char* neus2_last_error(void) { return g_error; }
 int neus2_version(void) { return 1; }
 int neus2_validate_config(const neus2_config* cfg) { return check_config(cfg); }
 
+int64_t neus2_workspace_bytes(const neus2_config* cfg, int64_t n) {
+    if (check_config(cfg) != NEUS2_OK || n < 0) return -1;
+    return scatter_workspace_bytes(cfg, n);
+}
+
 int neus2_hash_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n, float* enc,
                       float* jac, uint32_t* dbg_idx, void* stream) {
     NEUS2_TRY(check_config(cfg));
@@ -183,7 +188,7 @@ int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* ja
 
 int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                            const float* d_enc, const float* d_normal, int64_t n, float* d_tables, float* d_pos,
-                           void* stream) {
+                           void* workspace, int64_t workspace_bytes, void* stream) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
     NEUS2_TRY(check_ptr(pos, "pos"));
@@ -193,15 +198,18 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
     NEUS2_TRY(check_ptr(d_normal, "d_normal"));
     NEUS2_TRY(check_ptr(d_tables, "d_tables"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
-    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, (hipStream_t)stream);
+    NEUS2_TRY(check_ptr(workspace, "workspace", false));
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes,
+                          (hipStream_t)stream);
 }
 
 int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
                       const float* jac, const float* const* H, const float* q, const float* d_y,
                       const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
-                      float* d_pos, void* stream) {
+                      float* d_pos, void* workspace, int64_t workspace_bytes, void* stream) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(workspace, "workspace", false));
     NEUS2_TRY(check_ptr(pos, "pos"));
     NEUS2_TRY(check_ptr(tables, "tables"));
     NEUS2_TRY(check_ptr(enc, "enc"));
@@ -216,7 +224,7 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
     hipStream_t st = (hipStream_t)stream;
     NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, st));
-    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, st);
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, st);
 }
 
 }  // extern "C"
@@ -247,5 +255,5 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
         if (b->d_pos) NEUS2_TRY(launch_zero(b->d_pos, 3 * n, st));
     }
     return neus2_sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
-                             b->d_tables, b->d_enc, b->d_pos, stream);
+                             b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, stream);
 }

@@ -47,7 +47,8 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
                   float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st);
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, hipStream_t st);
+                   float* d_pos, void* workspace, int64_t workspace_bytes, hipStream_t st);
+int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
                    const float* const* H, int64_t n, float* y, float* q, float* normal, hipStream_t st);
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac,

@@ -32,14 +32,22 @@ __device__ __forceinline__ float clamp01(float x) {
     return fminf(fmaxf(x, 0.0f), 1.0f);
 }
 
+// The grid coordinate of a point at one level is ONE binary32 multiply, rounded to nearest.
+// The later subtraction of the cell index must see that rounded product, so contraction
+// into a fused multiply-add is switched off for this expression (the compiler's default for
+// device code would allow it, and then the interpolation weights differ from the definition
+// by up to res * 2^-24).
+__device__ __forceinline__ float grid_coord(float x, float fres) {
+#pragma clang fp contract(off)
+    float p = clamp01(x) * fres;
+    asm volatile("" : "+v"(p));      // opaque to the optimiser: nothing can be fused across this point
+    return p;
+}
+
 __device__ __forceinline__ Cell locate(const GridDesc& g, int level, float px, float py, float pz) {
     const int res = g.res[level];
     const float fres = (float)res;
-    // The grid coordinate is ONE binary32 multiply; it must not be fused with the
-    // subtraction below, hence the explicit rounding intrinsic.
-    const float gx = __fmul_rn(clamp01(px), fres);
-    const float gy = __fmul_rn(clamp01(py), fres);
-    const float gz = __fmul_rn(clamp01(pz), fres);
+    const float gx = grid_coord(px, fres), gy = grid_coord(py, fres), gz = grid_coord(pz, fres);
     const int cx = min((int)floorf(gx), res - 1);
     const int cy = min((int)floorf(gy), res - 1);
     const int cz = min((int)floorf(gz), res - 1);
@@ -166,9 +174,7 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
     const int64_t i = valid ? i_raw : n - 1;       // keep every lane in the shuffles below
     const int res = g.res[level];
     const float fres = (float)res;
-    const float gx = __fmul_rn(clamp01(pos[3 * i + 0]), fres);
-    const float gy = __fmul_rn(clamp01(pos[3 * i + 1]), fres);
-    const float gz = __fmul_rn(clamp01(pos[3 * i + 2]), fres);
+    const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
     const int cx = min((int)floorf(gx), res - 1);
     const int cy = min((int)floorf(gy), res - 1);
     const int cz = min((int)floorf(gz), res - 1);
@@ -264,32 +270,142 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
 // of fp32 pairs, one workgroup's LDS), and the workgroup that owns a range walks over ALL
 // points of the level, keeps only the corners whose slot falls into its range, adds them
 // with LDS atomics, and finally adds its LDS image to the global gradient with plain
-// coalesced loads and stores (nobody else writes that range).  The index arithmetic is
-// repeated once per range, which is cheap next to the memory-side atomics it replaces.
-// Small dense levels need fewer ranges than there are compute units; their points are cut
-// into chunks handled by different workgroups, which then flush with (coalesced) atomics.
+// coalesced loads and stores (nobody else writes that range).
+//
+// On a hashed level the range of a corner is the top bits of slot = x ^ y*P1 ^ z*P2; x is
+// smaller than 2^14, so the range depends on (dy, dz) only and both x corners of a row share
+// it.  A small kernel writes, once per point and level, the four range numbers as the four
+// bytes of a key; the owner workgroup's inner loop is then: load the key, xor with its own
+// range replicated into every byte, find zero bytes.  Points with a hit (one in eight on
+// average) are compacted into a per-wave LDS queue and only full batches of 64 run the
+// expensive part (locate the cell again, weights, four LDS atomics per row).
+// Dense levels need few ranges; they take the plain path (test all eight corners) on chunks
+// of the points and flush with coalesced atomics when several chunks share a range.
+// Workgroups take tasks from a counter, heaviest tasks first.
 constexpr int kOwnerThreads = 1024;
+constexpr int kOwnerWaves = kOwnerThreads / 64;
 constexpr int64_t kOwnerMinPoints = 1 << 16;
 constexpr int kOwnerSlotBits = 14;
 constexpr int kOwnerSlots = 1 << kOwnerSlotBits;
+constexpr int kWorkspaceHeader = 256;          // bytes in front of the keys (task counter)
 
 struct OwnerPlan {
     int n_entries;
     int n_tasks;
-    int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries (hashed levels first)
+    int n_keyed;                            // entries [0, n_keyed) are hashed levels with keys
+    int range_bits;                         // log2(T) - 14 for keyed levels
+    int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries
     short level[NEUS2_MAX_LEVELS];
     short ranges[NEUS2_MAX_LEVELS];
     short chunks[NEUS2_MAX_LEVELS];
 };
+
+__global__ __launch_bounds__(kBlock) void rowkey_kernel(GridDesc g, OwnerPlan plan, const float* __restrict__ pos,
+                                                        int64_t n, int point_blocks, uint32_t* __restrict__ keys,
+                                                        int* __restrict__ counter) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0;
+    const int e = blockIdx.x / point_blocks;
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const int level = plan.level[e];
+    const int res = g.res[level];
+    const float fres = (float)res;
+    const int cy = min((int)floorf(grid_coord(pos[3 * i + 1], fres)), res - 1);
+    const int cz = min((int)floorf(grid_coord(pos[3 * i + 2], fres)), res - 1);
+    const uint32_t rmask = (1u << plan.range_bits) - 1u;
+    const uint32_t a0 = (((uint32_t)cy * kPrimeY) >> kOwnerSlotBits) & rmask;
+    const uint32_t a1 = ((((uint32_t)cy + 1u) * kPrimeY) >> kOwnerSlotBits) & rmask;
+    const uint32_t b0 = (((uint32_t)cz * kPrimeZ) >> kOwnerSlotBits) & rmask;
+    const uint32_t b1 = ((((uint32_t)cz + 1u) * kPrimeZ) >> kOwnerSlotBits) & rmask;
+    // byte (dy + 2 dz) = range of the row (y + dy, z + dz)
+    keys[(int64_t)e * n + i] = (a0 ^ b0) | ((a1 ^ b0) << 8) | ((a0 ^ b1) << 16) | ((a1 ^ b1) << 24);
+}
+
+struct OwnerSmem {
+    float acc[2 * kOwnerSlots];
+    uint32_t q_point[kOwnerWaves][128];
+    uint32_t q_rows[kOwnerWaves][128];
+    int task;
+};
+
+// the expensive part for one queued point: rows = 0x80 in byte r for every row r that hits
+__device__ __forceinline__ void owner_accumulate(const GridDesc& g, int level, int64_t i, int64_t n, uint32_t rows,
+                                                 const float* __restrict__ pos, const float* __restrict__ q,
+                                                 const float* __restrict__ d_enc, const float* __restrict__ d_normal,
+                                                 float* acc) {
+    const int res = g.res[level];
+    const float fres = (float)res;
+    const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
+    const int cx = min((int)floorf(gx), res - 1);
+    const int cy = min((int)floorf(gy), res - 1);
+    const int cz = min((int)floorf(gz), res - 1);
+    const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
+    const int64_t o = (int64_t)level * n + i;
+    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+    const float2 qq = reinterpret_cast<const float2*>(q)[o];
+    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+    const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
+    while (rows) {
+        const int row = (__ffs(rows) - 1) >> 3;
+        rows &= rows - 1;
+        const int dy = row & 1, dz = row >> 1;
+        const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
+        const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
+        const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
+        const float fyz = fy * fz;
+        const float dn_x = nx * fyz;                         // times sx below
+        const float dn_yz = ny * (sy * fz) + nz * (fy * sz); // times fx below
+#pragma unroll
+        for (int dx = 0; dx < 2; ++dx) {
+            const float fx = dx ? w0 : 1.f - w0;
+            const float wk = fx * fyz;
+            const float dn = (dx ? dn_x : -dn_x) + fx * dn_yz;
+            const uint32_t slot = ((uint32_t)(cx + dx) ^ rh) & g.table_mask;
+            float* a = acc + 2 * (slot & (kOwnerSlots - 1));
+            atomicAdd(a + 0, wk * de.x + qq.x * dn);
+            atomicAdd(a + 1, wk * de.y + qq.y * dn);
+        }
+    }
+}
 
 __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan,
                                                                      const float* __restrict__ pos,
                                                                      const float* __restrict__ q,
                                                                      const float* __restrict__ d_enc,
                                                                      const float* __restrict__ d_normal,
-                                                                     int64_t n, float* __restrict__ d_tables) {
-    __shared__ float acc[2 * kOwnerSlots];
-    for (int task = blockIdx.x; task < plan.n_tasks; task += gridDim.x) {
+                                                                     int64_t n, const uint32_t* __restrict__ keys,
+                                                                     int* __restrict__ counter,
+                                                                     float* __restrict__ d_tables) {
+    __shared__ OwnerSmem sm;
+    float* acc = sm.acc;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // Keyed tasks are assigned statically so that all ranges of one level run on ONE XCD at the
+    // same time (workgroup b sits on XCD b % 8): the 32 workgroups walk the same points in the
+    // same order, and what one of them pulls into that XCD's L2 the others find there.
+    // Afterwards the small dense tasks are handed out through the counter.
+    const int xcd = blockIdx.x % kXcd, seat = blockIdx.x / kXcd, seats = gridDim.x / kXcd;
+    const bool has_seat = seats > 0 && (int)blockIdx.x < seats * kXcd;
+    const int dynamic_base = seats > 0 ? plan.first_task[plan.n_keyed] : 0;
+    int static_e = xcd, static_r = seat;
+    for (;;) {
+        int task = -1;
+        if (has_seat) {
+            while (static_e < plan.n_keyed) {
+                if (static_r < plan.ranges[static_e]) {
+                    task = plan.first_task[static_e] + static_r;
+                    static_r += seats;
+                    break;
+                }
+                static_r = seat;
+                static_e += kXcd;
+            }
+        }
+        if (task < 0) {
+            if (threadIdx.x == 0) sm.task = dynamic_base + atomicAdd(counter, 1);
+            __syncthreads();
+            task = sm.task;
+            if (task >= plan.n_tasks) break;         // uniform: every thread reads the same value
+        }
         int e = 0;
         while (e + 1 < plan.n_entries && task >= plan.first_task[e + 1]) ++e;
         const int local = task - plan.first_task[e];
@@ -302,31 +418,90 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         for (int k = threadIdx.x; k < 2 * kOwnerSlots; k += kOwnerThreads) acc[k] = 0.f;
         __syncthreads();
 
-        const float fres = (float)g.res[level];
-        for (int64_t i = begin + threadIdx.x; i < end; i += kOwnerThreads) {
-            const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
-            uint32_t match = 0;
+        if (e < plan.n_keyed) {
+            const uint32_t* kl = keys + (int64_t)e * n;
+            const uint32_t rpat = range * 0x01010101u;
+            uint32_t* qp = sm.q_point[wave];
+            uint32_t* qr = sm.q_rows[wave];
+            int qn = 0;                               // wave-uniform
+            // four keys per thread in flight, and the next four are requested before these are used
+            constexpr int kAhead = 4;
+            uint32_t cur[kAhead], nxt[kAhead];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) match |= ((c.slot[k] >> kOwnerSlotBits) == range ? 1u : 0u) << k;
-            if (match) {
-                const int64_t o = (int64_t)level * n + i;
-                const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-                const float2 qq = reinterpret_cast<const float2*>(q)[o];
-                const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+            for (int k = 0; k < kAhead; ++k) {
+                const int64_t i = begin + k * kOwnerThreads + threadIdx.x;
+                cur[k] = i < end ? kl[i] : ~rpat;     // ~rpat: no byte matches
+            }
+            for (int64_t base = begin; base < end; base += kAhead * kOwnerThreads) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if ((match >> k) & 1u) {
-                        const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
-                        const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
-                        const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
-                        const float sx = (k & 1) ? 1.f : -1.f;
-                        const float sy = (k & 2) ? 1.f : -1.f;
-                        const float sz = (k & 4) ? 1.f : -1.f;
-                        const float wk = fx * fy * fz;
-                        const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
-                        float* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
-                        atomicAdd(a + 0, wk * de.x + qq.x * dn);
-                        atomicAdd(a + 1, wk * de.y + qq.y * dn);
+                for (int k = 0; k < kAhead; ++k) {
+                    const int64_t i = base + (kAhead + k) * kOwnerThreads + threadIdx.x;
+                    nxt[k] = i < end ? kl[i] : ~rpat;
+                }
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) {
+                    const int64_t i = base + k * kOwnerThreads + threadIdx.x;
+                    const uint32_t z = cur[k] ^ rpat;
+                    // bit 7 of a byte of nzb is set iff that byte of z is non-zero (no carries cross bytes)
+                    const uint32_t nzb = ((z & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | z;
+                    const uint32_t rows = ~nzb & 0x80808080u;
+                    const unsigned long long ball = __ballot(rows != 0);
+                    if (ball == 0) continue;          // wave-uniform
+                    if (rows) {
+                        const int my = __builtin_amdgcn_mbcnt_hi((uint32_t)(ball >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ball, 0));
+                        qp[qn + my] = (uint32_t)(i - begin);
+                        qr[qn + my] = rows;
+                    }
+                    qn += __popcll(ball);
+                    if (qn >= 64) {
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        const uint32_t pi = qp[lane], pr = qr[lane];
+                        const uint32_t mi = qp[64 + lane], mr = qr[64 + lane];
+                        __builtin_amdgcn_wave_barrier();
+                        owner_accumulate(g, level, begin + pi, n, pr, pos, q, d_enc, d_normal, acc);
+                        qn -= 64;
+                        if (lane < qn) { qp[lane] = mi; qr[lane] = mr; }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) cur[k] = nxt[k];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < qn) owner_accumulate(g, level, begin + qp[lane], n, qr[lane], pos, q, d_enc, d_normal, acc);
+        } else {
+            const float fres = (float)g.res[level];
+            const bool dense = (g.dense_bits >> level) & 1u;
+            for (int64_t i = begin + threadIdx.x; i < end; i += kOwnerThreads) {
+                const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
+                // on a dense level the eight slots lie in [slot[0], slot[7]]
+                if (dense && ((c.slot[7] >> kOwnerSlotBits) < range || (c.slot[0] >> kOwnerSlotBits) > range)) continue;
+                uint32_t match = 0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) match |= ((c.slot[k] >> kOwnerSlotBits) == range ? 1u : 0u) << k;
+                if (match) {
+                    const int64_t o = (int64_t)level * n + i;
+                    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+                    const float2 qq = reinterpret_cast<const float2*>(q)[o];
+                    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        if ((match >> k) & 1u) {
+                            const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
+                            const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
+                            const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
+                            const float sx = (k & 1) ? 1.f : -1.f;
+                            const float sy = (k & 2) ? 1.f : -1.f;
+                            const float sz = (k & 4) ? 1.f : -1.f;
+                            const float wk = fx * fy * fz;
+                            const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
+                            float* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
+                            atomicAdd(a + 0, wk * de.x + qq.x * dn);
+                            atomicAdd(a + 1, wk * de.y + qq.y * dn);
+                        }
                     }
                 }
             }
@@ -343,25 +518,34 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                 else atomicAdd(dst + k, v);
             }
         }
-        __syncthreads();
+        __syncthreads();                              // also protects sm.task before the next fetch
     }
 }
 
-// Which levels get how many ranges and point chunks.  Returns the cost in "all points of one
-// level" units so that the caller can compare with the atomic kernel.
-OwnerPlan make_owner_plan(const neus2_config* cfg, int workgroups) {
+// Which levels get how many ranges and point chunks; keyed (hashed, several ranges) levels
+// first because their tasks are the heaviest.  ok = false if the configuration does not fit
+// the scheme (then the atomic kernel is used).
+OwnerPlan make_owner_plan(const neus2_config* cfg, bool& ok) {
     OwnerPlan p;
     memset(&p, 0, sizeof(p));
+    ok = true;
     const int64_t T = (int64_t)1 << cfg->log2_table_size;
+    p.range_bits = cfg->log2_table_size > kOwnerSlotBits ? cfg->log2_table_size - kOwnerSlotBits : 0;
+    if (p.range_bits > 8) ok = false;                 // a key byte holds one range number
     int e = 0, tasks = 0;
-    for (int pass = 0; pass < 2; ++pass) {           // hashed (heavy, one chunk) first, then dense
+    for (int pass = 0; pass < 2; ++pass) {
         for (int l = 0; l < cfg->active_levels; ++l) {
-            if ((cfg->dense[l] != 0) != (pass == 1)) continue;
+            const bool keyed = !cfg->dense[l] && p.range_bits > 0;
+            if (keyed != (pass == 0)) continue;
+            if (keyed && cfg->res[l] >= kOwnerSlots) ok = false;   // x must not reach the range bits
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
             const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
             const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
             int chunks = 1;
-            if (ranges * 2 <= workgroups / 8) chunks = workgroups / 8 / ranges;   // spread small levels over an eighth of the chip
+            if (!keyed) {                              // small tasks: at most an eighth of the points each
+                chunks = 32 / ranges;
+                if (chunks < 8) chunks = 8;
+            }
             p.level[e] = (short)l;
             p.ranges[e] = (short)ranges;
             p.chunks[e] = (short)chunks;
@@ -369,6 +553,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int workgroups) {
             tasks += ranges * chunks;
             ++e;
         }
+        if (pass == 0) p.n_keyed = e;
     }
     p.first_task[e] = tasks;
     p.n_entries = e;
@@ -398,19 +583,40 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     return check_launch("hash encode");
 }
 
+int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
+    if (n < kOwnerMinPoints) return 0;
+    bool ok = false;
+    const OwnerPlan plan = make_owner_plan(cfg, ok);
+    if (!ok) return 0;
+    return (kWorkspaceHeader + (int64_t)plan.n_keyed * n * 4 + 255) / 256 * 256;
+}
+
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, hipStream_t st) {
+                   float* d_pos, void* workspace, int64_t workspace_bytes, hipStream_t st) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
-    // Large batches: LDS-owner kernel (needs no global atomics on the big levels).  It does not
-    // produce the position gradient, and below ~2^16 points the atomic kernel is cheaper.
-    if (!d_pos && n >= kOwnerMinPoints && cfg->log2_table_size <= 15 + kOwnerSlotBits) {
-        const int wgs = compute_units();
-        const OwnerPlan plan = make_owner_plan(cfg, wgs);
-        hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0, st,
-                           g, plan, pos, q, d_enc, d_normal, n, d_tables);
-        return check_launch("hash scatter (owner)");
+    // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels).
+    // It does not produce the position gradient, and below ~2^16 points the atomic kernel is
+    // cheaper.
+    if (!d_pos && n >= kOwnerMinPoints && workspace) {
+        bool ok = false;
+        const OwnerPlan plan = make_owner_plan(cfg, ok);
+        const int64_t need = kWorkspaceHeader + (int64_t)plan.n_keyed * n * 4;
+        if (ok && workspace_bytes >= need) {
+            int* counter = reinterpret_cast<int*>(workspace);
+            uint32_t* keys = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + kWorkspaceHeader);
+            const int kpbs = (int)((n + kBlock - 1) / kBlock);
+            if (plan.n_keyed > 0) {
+                hipLaunchKernelGGL(rowkey_kernel, dim3(kpbs * plan.n_keyed), dim3(kBlock), 0, st, g, plan, pos, n, kpbs, keys, counter);
+            } else {
+                NEUS2_TRY(launch_zero(reinterpret_cast<float*>(workspace), 1, st));
+            }
+            const int wgs = compute_units();
+            hipLaunchKernelGGL(scatter_owner_kernel, dim3(wgs), dim3(kOwnerThreads), 0, st,
+                               g, plan, pos, q, d_enc, d_normal, n, keys, counter, d_tables);
+            return check_launch("hash scatter (owner)");
+        }
     }
     const int pbs = (int)((n + kScatterPoints - 1) / kScatterPoints);
     const dim3 grid(grid_blocks(g.active_levels, pbs));

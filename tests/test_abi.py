@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     # 5 ints + 2*32 ints + (1+5) + (1+5) ints + 2 ints + 2 floats
     assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 2)
-    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 25
+    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 27
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])

@@ -421,7 +421,27 @@ def train_step(cfg, params, batch, fp32_product: bool = True, want_pos_grad: boo
             dH[l] += S_l.T @ t
             t = fw["masks"][l] * (t @ np.asarray(H[l], dtype=np.float64).T)
 
-    # tables: first-order term w_c * dL/de and Eq. 7's term (dd/de) * d(de/dx)/dOmega
+    dtables = table_gradient(cfg, pos, q, d_enc, d_normal, fp32_product)
+
+    out = dict(fw)
+    out.update({"d_y": d_y, "d_normal": d_normal, "d_enc": d_enc, "dH": dH, "dW": dW, "dtables": dtables})
+    if want_pos_grad:
+        hess = fw["he"]["hess"]
+        d_pos = np.einsum("nka,nk->na", jac, d_enc)
+        d_pos += np.einsum("na,nk,nkab->nb", d_normal, q, hess)
+        out["dpos"] = d_pos + d_pos_color
+    return out
+
+
+def table_gradient(cfg, pos, q, d_enc, d_normal, fp32_product: bool = True) -> np.ndarray:
+    """dL/dOmega [L,T,F]: the first-order term w_c * dL/de plus Eq. 7's term
+    (dd/de) * d(de/dx)/dOmega contracted with dL/dn, i.e. for corner c of the cell of point i
+    at level l:  dOmega[l, slot_c, f] += w_c * d_enc[i, lF+f] + q[i, lF+f] * res_l * sum_a d_normal[i,a] * d_a w_c.
+    Active levels only."""
+    L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
+    q = np.asarray(q, dtype=np.float64)
+    d_enc = np.asarray(d_enc, dtype=np.float64)
+    d_normal = np.asarray(d_normal, dtype=np.float64)
     dtables = np.zeros((L, T, F))
     for l in range(min(L, cfg.active_levels)):
         res = cfg.res[l]
@@ -435,15 +455,7 @@ def train_step(cfg, params, batch, fp32_product: bool = True, want_pos_grad: boo
                 k = l * F + f
                 coef = wc[c] * d_enc[:, k] + q[:, k] * dn_dw
                 dtables[l, :, f] += np.bincount(idx, weights=coef, minlength=T)
-
-    out = dict(fw)
-    out.update({"d_y": d_y, "d_normal": d_normal, "d_enc": d_enc, "dH": dH, "dW": dW, "dtables": dtables})
-    if want_pos_grad:
-        hess = fw["he"]["hess"]
-        d_pos = np.einsum("nka,nk->na", jac, d_enc)
-        d_pos += np.einsum("na,nk,nkab->nb", d_normal, q, hess)
-        out["dpos"] = d_pos + d_pos_color
-    return out
+    return dtables
 
 
 def rigid_backward(x, R, T, d_xc, scale: float = 1.0):

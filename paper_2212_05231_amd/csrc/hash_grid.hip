@@ -266,146 +266,145 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
 // Float atomics leave the L2 as one 32-byte read-modify-write per (instruction, line) and
 // the chip retires about 2e10 of them per second, which caps the kernel above at about four
 // requests per point and level.  For large batches the table gradient is therefore
-// accumulated in LDS instead: a level's T slots are cut into ranges of 16384 slots (128 KiB
-// of fp32 pairs, one workgroup's LDS), and the workgroup that owns a range walks over ALL
-// points of the level, keeps only the corners whose slot falls into its range, adds them
-// with LDS atomics, and finally adds its LDS image to the global gradient with plain
-// coalesced loads and stores (nobody else writes that range).
+// accumulated in LDS instead: a level's T slots are cut into ranges of 8192 slots (128 KiB
+// of fp64 pairs, one workgroup's LDS); the workgroup that owns a range adds everything that
+// falls into it with LDS atomics and finally adds its LDS image to the global gradient with
+// plain coalesced loads and stores (nobody else writes that range).  The accumulators are
+// DOUBLES on purpose: measured on this chip, ds_add_f64 retires a lane in 0.37 clocks and
+// ds_add_f32 in 3.2 (the LDS does float atomics one lane at a time), so fp64 is both the
+// faster and the more accurate choice.
 //
-// On a hashed level the range of a corner is the top bits of slot = x ^ y*P1 ^ z*P2; x is
-// smaller than 2^14, so the range depends on (dy, dz) only and both x corners of a row share
-// it.  A small kernel writes, once per point and level, the four range numbers as the four
-// bytes of a key; the owner workgroup's inner loop is then: load the key, xor with its own
-// range replicated into every byte, find zero bytes.  Points with a hit (one in eight on
-// average) are compacted into a per-wave LDS queue and only full batches of 64 run the
-// expensive part (locate the cell again, weights, four LDS atomics per row).
-// Dense levels need few ranges; they take the plain path (test all eight corners) on chunks
-// of the points and flush with coalesced atomics when several chunks share a range.
+// Hashed levels (two kernels).  On a hashed level the range of a corner is the top bits of
+// slot = x ^ y*P1 ^ z*P2; x is smaller than 2^13, so the range depends on (dy, dz) only and
+// both x corners of a row (y+dy, z+dz) share it.  `bin_rows_kernel` computes, per point and
+// level, the four row records {two local slots, four values} once and appends each to the
+// list of its range in the workspace (position = per-workgroup LDS rank + one global cursor
+// reservation per workgroup and range).  `scatter_owner_kernel` then streams the list of its
+// range, fully coalesced.  A list that overflows its capacity (only possible when a batch
+// concentrates on very few cells) sends the surplus records straight to global atomics, so
+// the result never depends on the capacity.
+// Dense levels need few ranges; they take the in-place path (test all eight corners) on
+// chunks of the points and flush with coalesced atomics when several chunks share a range.
 // Workgroups take tasks from a counter, heaviest tasks first.
 constexpr int kOwnerThreads = 1024;
-constexpr int kOwnerWaves = kOwnerThreads / 64;
 constexpr int64_t kOwnerMinPoints = 1 << 16;
-constexpr int kOwnerSlotBits = 14;
+constexpr int kOwnerSlotBits = 13;
 constexpr int kOwnerSlots = 1 << kOwnerSlotBits;
-constexpr int kWorkspaceHeader = 256;          // bytes in front of the keys (task counter)
+constexpr int kMaxRanges = 256;
+constexpr int kCursorOffset = 256;                                  // bytes: [0,4) task counter
+constexpr int kWorkspaceHeader = kCursorOffset + 4 * NEUS2_MAX_LEVELS * kMaxRanges;
 
 struct OwnerPlan {
     int n_entries;
     int n_tasks;
-    int n_keyed;                            // entries [0, n_keyed) are hashed levels with keys
+    int n_keyed;                            // entries [0, n_keyed) are hashed levels with record lists
     int range_bits;                         // log2(T) - 14 for keyed levels
+    int capacity;                           // records per (level, range) list
     int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries
     short level[NEUS2_MAX_LEVELS];
     short ranges[NEUS2_MAX_LEVELS];
     short chunks[NEUS2_MAX_LEVELS];
 };
 
-__global__ __launch_bounds__(kBlock) void rowkey_kernel(GridDesc g, OwnerPlan plan, const float* __restrict__ pos,
-                                                        int64_t n, int point_blocks, uint32_t* __restrict__ keys,
-                                                        int* __restrict__ counter) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0;
-    const int e = blockIdx.x / point_blocks;
-    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBlock + threadIdx.x;
-    if (i >= n) return;
-    const int level = plan.level[e];
-    const int res = g.res[level];
-    const float fres = (float)res;
-    const int cy = min((int)floorf(grid_coord(pos[3 * i + 1], fres)), res - 1);
-    const int cz = min((int)floorf(grid_coord(pos[3 * i + 2], fres)), res - 1);
-    const uint32_t rmask = (1u << plan.range_bits) - 1u;
-    const uint32_t a0 = (((uint32_t)cy * kPrimeY) >> kOwnerSlotBits) & rmask;
-    const uint32_t a1 = ((((uint32_t)cy + 1u) * kPrimeY) >> kOwnerSlotBits) & rmask;
-    const uint32_t b0 = (((uint32_t)cz * kPrimeZ) >> kOwnerSlotBits) & rmask;
-    const uint32_t b1 = ((((uint32_t)cz + 1u) * kPrimeZ) >> kOwnerSlotBits) & rmask;
-    // byte (dy + 2 dz) = range of the row (y + dy, z + dz)
-    keys[(int64_t)e * n + i] = (a0 ^ b0) | ((a1 ^ b0) << 8) | ((a0 ^ b1) << 16) | ((a1 ^ b1) << 24);
-}
-
-struct OwnerSmem {
-    float acc[2 * kOwnerSlots];
-    uint32_t q_point[kOwnerWaves][128];
-    uint32_t q_rows[kOwnerWaves][128];
-    int task;
+struct Records {
+    int* cursor;            // [n_keyed][kMaxRanges]
+    uint32_t* slots;        // [n_keyed][ranges][capacity]  local slot of x | local slot of x+1 << 16
+    float4* vals;           // [n_keyed][ranges][capacity]  {x f0, x f1, x+1 f0, x+1 f1}
 };
 
-// the expensive part for one queued point: rows = 0x80 in byte r for every row r that hits
-__device__ __forceinline__ void owner_accumulate(const GridDesc& g, int level, int64_t i, int64_t n, uint32_t rows,
-                                                 const float* __restrict__ pos, const float* __restrict__ q,
-                                                 const float* __restrict__ d_enc, const float* __restrict__ d_normal,
-                                                 float* acc) {
-    const int res = g.res[level];
-    const float fres = (float)res;
-    const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
-    const int cx = min((int)floorf(gx), res - 1);
-    const int cy = min((int)floorf(gy), res - 1);
-    const int cz = min((int)floorf(gz), res - 1);
-    const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
-    const int64_t o = (int64_t)level * n + i;
-    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-    const float2 qq = reinterpret_cast<const float2*>(q)[o];
-    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
-    const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
-    while (rows) {
-        const int row = (__ffs(rows) - 1) >> 3;
-        rows &= rows - 1;
-        const int dy = row & 1, dz = row >> 1;
-        const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
-        const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
-        const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
-        const float fyz = fy * fz;
-        const float dn_x = nx * fyz;                         // times sx below
-        const float dn_yz = ny * (sy * fz) + nz * (fy * sz); // times fx below
+__global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
+                                                                const float* __restrict__ pos,
+                                                                const float* __restrict__ q,
+                                                                const float* __restrict__ d_enc,
+                                                                const float* __restrict__ d_normal, int64_t n,
+                                                                int point_blocks, float* __restrict__ d_tables) {
+    __shared__ int cnt[kMaxRanges];
+    __shared__ int base[kMaxRanges];
+    const int e = blockIdx.x / point_blocks;
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kOwnerThreads + threadIdx.x;
+    const int level = plan.level[e];
+    const int n_ranges = plan.ranges[e];
+    for (int k = threadIdx.x; k < n_ranges; k += kOwnerThreads) cnt[k] = 0;
+    __syncthreads();
+
+    const bool valid = i < n;
+    uint32_t range[4], packed[4];
+    float4 val[4];
+    int rank[4];
+    if (valid) {
+        const int res = g.res[level];
+        const float fres = (float)res;
+        const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
+        const int cx = min((int)floorf(gx), res - 1);
+        const int cy = min((int)floorf(gy), res - 1);
+        const int cz = min((int)floorf(gz), res - 1);
+        const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
+        const int64_t o = (int64_t)level * n + i;
+        const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+        const float2 qq = reinterpret_cast<const float2*>(q)[o];
+        const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+        const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
 #pragma unroll
-        for (int dx = 0; dx < 2; ++dx) {
-            const float fx = dx ? w0 : 1.f - w0;
-            const float wk = fx * fyz;
-            const float dn = (dx ? dn_x : -dn_x) + fx * dn_yz;
-            const uint32_t slot = ((uint32_t)(cx + dx) ^ rh) & g.table_mask;
-            float* a = acc + 2 * (slot & (kOwnerSlots - 1));
-            atomicAdd(a + 0, wk * de.x + qq.x * dn);
-            atomicAdd(a + 1, wk * de.y + qq.y * dn);
+        for (int row = 0; row < 4; ++row) {
+            const int dy = row & 1, dz = row >> 1;
+            const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
+            const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
+            const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
+            const float fyz = fy * fz;
+            const float dn_x = nx * fyz;
+            const float dn_yz = ny * (sy * fz) + nz * (fy * sz);
+            const uint32_t s0 = ((uint32_t)cx ^ rh) & g.table_mask, s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
+            const float f0 = 1.f - w0, f1 = w0;
+            const float dn0 = -dn_x + f0 * dn_yz, dn1 = dn_x + f1 * dn_yz;
+            const float wk0 = f0 * fyz, wk1 = f1 * fyz;
+            val[row] = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
+            range[row] = s0 >> kOwnerSlotBits;                      // == s1 >> kOwnerSlotBits
+            packed[row] = (s0 & (kOwnerSlots - 1)) | ((s1 & (kOwnerSlots - 1)) << 16);
+            rank[row] = atomicAdd(&cnt[range[row]], 1);
+        }
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < n_ranges; k += kOwnerThreads)
+        base[k] = cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], cnt[k]) : 0;
+    __syncthreads();
+    if (valid) {
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const int p = base[range[row]] + rank[row];
+            if (p < plan.capacity) {
+                const size_t at = ((size_t)e * n_ranges + range[row]) * plan.capacity + p;
+                rec.slots[at] = packed[row];
+                rec.vals[at] = val[row];
+            } else {                                                 // list full: straight to the global gradient
+                float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)range[row] << kOwnerSlotBits)) * 2;
+                atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 0, val[row].x);
+                atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 1, val[row].y);
+                atomicAdd(gt + 2 * (packed[row] >> 16) + 0, val[row].z);
+                atomicAdd(gt + 2 * (packed[row] >> 16) + 1, val[row].w);
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan,
+struct OwnerSmem {
+    double acc[2 * kOwnerSlots];
+    int task;
+};
+
+__global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan, Records rec,
                                                                      const float* __restrict__ pos,
                                                                      const float* __restrict__ q,
                                                                      const float* __restrict__ d_enc,
                                                                      const float* __restrict__ d_normal,
-                                                                     int64_t n, const uint32_t* __restrict__ keys,
-                                                                     int* __restrict__ counter,
+                                                                     int64_t n, int* __restrict__ counter,
                                                                      float* __restrict__ d_tables) {
     __shared__ OwnerSmem sm;
-    float* acc = sm.acc;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // Keyed tasks are assigned statically so that all ranges of one level run on ONE XCD at the
-    // same time (workgroup b sits on XCD b % 8): the 32 workgroups walk the same points in the
-    // same order, and what one of them pulls into that XCD's L2 the others find there.
-    // Afterwards the small dense tasks are handed out through the counter.
-    const int xcd = blockIdx.x % kXcd, seat = blockIdx.x / kXcd, seats = gridDim.x / kXcd;
-    const bool has_seat = seats > 0 && (int)blockIdx.x < seats * kXcd;
-    const int dynamic_base = seats > 0 ? plan.first_task[plan.n_keyed] : 0;
-    int static_e = xcd, static_r = seat;
+    double* acc = sm.acc;
     for (;;) {
-        int task = -1;
-        if (has_seat) {
-            while (static_e < plan.n_keyed) {
-                if (static_r < plan.ranges[static_e]) {
-                    task = plan.first_task[static_e] + static_r;
-                    static_r += seats;
-                    break;
-                }
-                static_r = seat;
-                static_e += kXcd;
-            }
-        }
-        if (task < 0) {
-            if (threadIdx.x == 0) sm.task = dynamic_base + atomicAdd(counter, 1);
-            __syncthreads();
-            task = sm.task;
-            if (task >= plan.n_tasks) break;         // uniform: every thread reads the same value
-        }
+        if (threadIdx.x == 0) sm.task = atomicAdd(counter, 1);
+        __syncthreads();
+        const int task = sm.task;
+        if (task >= plan.n_tasks) break;             // uniform: every thread reads the same value
         int e = 0;
         while (e + 1 < plan.n_entries && task >= plan.first_task[e + 1]) ++e;
         const int local = task - plan.first_task[e];
@@ -414,64 +413,39 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         const uint32_t range = (uint32_t)(local % n_ranges);
         const int chunk = local / n_ranges;
         const int64_t begin = n * chunk / n_chunks, end = n * (chunk + 1) / n_chunks;
+        const uint32_t first_slot = range << kOwnerSlotBits;
+        const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
 
-        for (int k = threadIdx.x; k < 2 * kOwnerSlots; k += kOwnerThreads) acc[k] = 0.f;
+        for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) acc[k] = 0.0;
         __syncthreads();
 
         if (e < plan.n_keyed) {
-            const uint32_t* kl = keys + (int64_t)e * n;
-            const uint32_t rpat = range * 0x01010101u;
-            uint32_t* qp = sm.q_point[wave];
-            uint32_t* qr = sm.q_rows[wave];
-            int qn = 0;                               // wave-uniform
-            // four keys per thread in flight, and the next four are requested before these are used
+            const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity);
+            const size_t at = ((size_t)e * n_ranges + range) * plan.capacity;
+            const uint32_t* rs = rec.slots + at;
+            const float4* rv = rec.vals + at;
+            // four records per thread in flight: the list is streamed from HBM
             constexpr int kAhead = 4;
-            uint32_t cur[kAhead], nxt[kAhead];
-#pragma unroll
-            for (int k = 0; k < kAhead; ++k) {
-                const int64_t i = begin + k * kOwnerThreads + threadIdx.x;
-                cur[k] = i < end ? kl[i] : ~rpat;     // ~rpat: no byte matches
-            }
-            for (int64_t base = begin; base < end; base += kAhead * kOwnerThreads) {
+            for (int j0 = threadIdx.x; j0 < count; j0 += kAhead * kOwnerThreads) {
+                uint32_t sl[kAhead];
+                float4 v[kAhead];
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
-                    const int64_t i = base + (kAhead + k) * kOwnerThreads + threadIdx.x;
-                    nxt[k] = i < end ? kl[i] : ~rpat;
+                    const int j = j0 + k * kOwnerThreads;
+                    if (j < count) { sl[k] = rs[j]; v[k] = rv[j]; }
                 }
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
-                    const int64_t i = base + k * kOwnerThreads + threadIdx.x;
-                    const uint32_t z = cur[k] ^ rpat;
-                    // bit 7 of a byte of nzb is set iff that byte of z is non-zero (no carries cross bytes)
-                    const uint32_t nzb = ((z & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | z;
-                    const uint32_t rows = ~nzb & 0x80808080u;
-                    const unsigned long long ball = __ballot(rows != 0);
-                    if (ball == 0) continue;          // wave-uniform
-                    if (rows) {
-                        const int my = __builtin_amdgcn_mbcnt_hi((uint32_t)(ball >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ball, 0));
-                        qp[qn + my] = (uint32_t)(i - begin);
-                        qr[qn + my] = rows;
-                    }
-                    qn += __popcll(ball);
-                    if (qn >= 64) {
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        const uint32_t pi = qp[lane], pr = qr[lane];
-                        const uint32_t mi = qp[64 + lane], mr = qr[64 + lane];
-                        __builtin_amdgcn_wave_barrier();
-                        owner_accumulate(g, level, begin + pi, n, pr, pos, q, d_enc, d_normal, acc);
-                        qn -= 64;
-                        if (lane < qn) { qp[lane] = mi; qr[lane] = mr; }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
+                    if (j0 + k * kOwnerThreads < count) {
+                        double* a0 = acc + 2 * (sl[k] & 0xFFFFu);
+                        double* a1 = acc + 2 * (sl[k] >> 16);
+                        atomicAdd(a0 + 0, (double)v[k].x);
+                        atomicAdd(a0 + 1, (double)v[k].y);
+                        atomicAdd(a1 + 0, (double)v[k].z);
+                        atomicAdd(a1 + 1, (double)v[k].w);
                     }
                 }
-#pragma unroll
-                for (int k = 0; k < kAhead; ++k) cur[k] = nxt[k];
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            if (lane < qn) owner_accumulate(g, level, begin + qp[lane], n, qr[lane], pos, q, d_enc, d_normal, acc);
         } else {
             const float fres = (float)g.res[level];
             const bool dense = (g.dense_bits >> level) & 1u;
@@ -498,9 +472,9 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                             const float sz = (k & 4) ? 1.f : -1.f;
                             const float wk = fx * fy * fz;
                             const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
-                            float* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
-                            atomicAdd(a + 0, wk * de.x + qq.x * dn);
-                            atomicAdd(a + 1, wk * de.y + qq.y * dn);
+                            double* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
+                            atomicAdd(a + 0, (double)(wk * de.x + qq.x * dn));
+                            atomicAdd(a + 1, (double)(wk * de.y + qq.y * dn));
                         }
                     }
                 }
@@ -508,11 +482,9 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         }
         __syncthreads();
 
-        const uint32_t first_slot = range << kOwnerSlotBits;
-        const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
         float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
         for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) {
-            const float v = acc[k];
+            const float v = (float)acc[k];
             if (v != 0.f) {
                 if (n_chunks == 1) dst[k] += v;
                 else atomicAdd(dst + k, v);
@@ -525,13 +497,17 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
 // Which levels get how many ranges and point chunks; keyed (hashed, several ranges) levels
 // first because their tasks are the heaviest.  ok = false if the configuration does not fit
 // the scheme (then the atomic kernel is used).
-OwnerPlan make_owner_plan(const neus2_config* cfg, bool& ok) {
+OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     OwnerPlan p;
     memset(&p, 0, sizeof(p));
     ok = true;
     const int64_t T = (int64_t)1 << cfg->log2_table_size;
     p.range_bits = cfg->log2_table_size > kOwnerSlotBits ? cfg->log2_table_size - kOwnerSlotBits : 0;
-    if (p.range_bits > 8) ok = false;                 // a key byte holds one range number
+    if (p.range_bits > 8) ok = false;                 // at most kMaxRanges lists per level
+    // a list holds 1.5 times its expected share of the 4 n row records of a level
+    const int64_t cap = ((4 * n >> p.range_bits) * 3 / 2 + 1023) / 64 * 64;
+    if (cap > (1 << 30)) ok = false;
+    p.capacity = (int)cap;
     int e = 0, tasks = 0;
     for (int pass = 0; pass < 2; ++pass) {
         for (int l = 0; l < cfg->active_levels; ++l) {
@@ -583,12 +559,17 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     return check_launch("hash encode");
 }
 
+int64_t owner_workspace_need(const OwnerPlan& plan) {
+    const int64_t lists = (int64_t)plan.n_keyed << plan.range_bits;
+    return kWorkspaceHeader + lists * plan.capacity * 20 + 256;
+}
+
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
     if (n < kOwnerMinPoints) return 0;
     bool ok = false;
-    const OwnerPlan plan = make_owner_plan(cfg, ok);
+    const OwnerPlan plan = make_owner_plan(cfg, n, ok);
     if (!ok) return 0;
-    return (kWorkspaceHeader + (int64_t)plan.n_keyed * n * 4 + 255) / 256 * 256;
+    return (owner_workspace_need(plan) + 255) / 256 * 256;
 }
 
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
@@ -601,20 +582,24 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
     // cheaper.
     if (!d_pos && n >= kOwnerMinPoints && workspace) {
         bool ok = false;
-        const OwnerPlan plan = make_owner_plan(cfg, ok);
-        const int64_t need = kWorkspaceHeader + (int64_t)plan.n_keyed * n * 4;
-        if (ok && workspace_bytes >= need) {
-            int* counter = reinterpret_cast<int*>(workspace);
-            uint32_t* keys = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + kWorkspaceHeader);
-            const int kpbs = (int)((n + kBlock - 1) / kBlock);
+        const OwnerPlan plan = make_owner_plan(cfg, n, ok);
+        if (ok && workspace_bytes >= owner_workspace_need(plan)) {
+            char* ws = reinterpret_cast<char*>(workspace);
+            int* counter = reinterpret_cast<int*>(ws);
+            Records rec;
+            rec.cursor = reinterpret_cast<int*>(ws + kCursorOffset);
+            const int64_t lists = (int64_t)plan.n_keyed << plan.range_bits;
+            rec.vals = reinterpret_cast<float4*>(ws + kWorkspaceHeader);                         // 16-byte aligned
+            rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + lists * plan.capacity * 16);
+            NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));      // task counter and cursors
             if (plan.n_keyed > 0) {
-                hipLaunchKernelGGL(rowkey_kernel, dim3(kpbs * plan.n_keyed), dim3(kBlock), 0, st, g, plan, pos, n, kpbs, keys, counter);
-            } else {
-                NEUS2_TRY(launch_zero(reinterpret_cast<float*>(workspace), 1, st));
+                const int pbs = (int)((n + kOwnerThreads - 1) / kOwnerThreads);
+                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_keyed), dim3(kOwnerThreads), 0, st, g, plan, rec, pos, q,
+                                   d_enc, d_normal, n, pbs, d_tables);
             }
             const int wgs = compute_units();
-            hipLaunchKernelGGL(scatter_owner_kernel, dim3(wgs), dim3(kOwnerThreads), 0, st,
-                               g, plan, pos, q, d_enc, d_normal, n, keys, counter, d_tables);
+            hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0, st,
+                               g, plan, rec, pos, q, d_enc, d_normal, n, counter, d_tables);
             return check_launch("hash scatter (owner)");
         }
     }

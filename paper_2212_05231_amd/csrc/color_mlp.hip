@@ -133,7 +133,7 @@ __device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v
     matvec<1, 2, kLd64>(w.W3f, a2, u, j, h);
 }
 
-__global__ __launch_bounds__(kThreads) void color_fwd_kernel(ColorArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     __shared__ ColorWeights<false> w;
     load_weights<false>(w, a);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

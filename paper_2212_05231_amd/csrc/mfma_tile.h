@@ -45,20 +45,35 @@ __device__ __forceinline__ constexpr int neuron_of(int r, int h) { return 8 * (r
 // registers of the last input block are used (inputs narrower than a multiple of 32).
 template <int MB, int KB, int LD, int RLAST = 16>
 __device__ __forceinline__ void matvec(const float* __restrict__ W, const v16f* x, v16f* z, int j, int h) {
+    // The weights of the next group of four steps are requested from LDS before the four
+    // MFMAs of the current group are issued, and the scheduler is told not to move anything
+    // across group boundaries: left alone it hoists every LDS read of the kernel to the top
+    // and needs more than 256 registers for what is a 130-register computation.
+    constexpr int kGroupsLast = RLAST / 4;
+    constexpr int kGroupsPerMb = (KB - 1) * 4 + kGroupsLast;
+    constexpr int kTotal = MB * kGroupsPerMb;
+    const float* base = W + j * LD + 4 * h;
+    auto address = [&](int t) -> const float4* {
+        const int mb = t / kGroupsPerMb, u = t % kGroupsPerMb;
+        const int kb = u / 4, g = u % 4;
+        return reinterpret_cast<const float4*>(base + 32 * mb * LD + 32 * kb + 8 * g);
+    };
+    float4 cur = *address(0);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         v16f acc = zero16();
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const int groups = (kb == KB - 1 ? RLAST : 16) / 4;
-#pragma unroll
-            for (int g = 0; g < groups; ++g) {
-                const float4 a = *reinterpret_cast<const float4*>(&W[(32 * mb + j) * LD + 32 * kb + 8 * g + 4 * h]);
-                acc = mfma32(a.x, x[kb][4 * g + 0], acc);
-                acc = mfma32(a.y, x[kb][4 * g + 1], acc);
-                acc = mfma32(a.z, x[kb][4 * g + 2], acc);
-                acc = mfma32(a.w, x[kb][4 * g + 3], acc);
-            }
+        for (int u = 0; u < kGroupsPerMb; ++u) {
+            const int t = mb * kGroupsPerMb + u;
+            const int kb = u / 4, g = u % 4;
+            float4 nxt = cur;
+            if (t + 1 < kTotal) nxt = *address(t + 1);
+            acc = mfma32(cur.x, x[kb][4 * g + 0], acc);
+            acc = mfma32(cur.y, x[kb][4 * g + 1], acc);
+            acc = mfma32(cur.z, x[kb][4 * g + 2], acc);
+            acc = mfma32(cur.w, x[kb][4 * g + 3], acc);
+            cur = nxt;
+            __builtin_amdgcn_sched_barrier(0);
         }
         z[mb] = acc;
     }
@@ -111,17 +126,29 @@ __device__ __forceinline__ void wave_lds_fence() {
 template <int ZB, int XB, int LDZ, int LDX>
 __device__ __forceinline__ void outer_accumulate(v16f (*G)[XB], const float* __restrict__ Zt,
                                                  const float* __restrict__ Xt, int j, int h) {
+    // operands of step s+1 are read from LDS before the MFMAs of step s are issued
+    float a[ZB], b[XB], an[ZB], bn[XB];
+#pragma unroll
+    for (int mb = 0; mb < ZB; ++mb) a[mb] = Zt[h * LDZ + 32 * mb + j];
+#pragma unroll
+    for (int nb = 0; nb < XB; ++nb) b[nb] = Xt[h * LDX + 32 * nb + j];
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
-        float a[ZB], b[XB];
+        if (s + 1 < 16) {
 #pragma unroll
-        for (int mb = 0; mb < ZB; ++mb) a[mb] = Zt[(2 * s + h) * LDZ + 32 * mb + j];
+            for (int mb = 0; mb < ZB; ++mb) an[mb] = Zt[(2 * s + 2 + h) * LDZ + 32 * mb + j];
 #pragma unroll
-        for (int nb = 0; nb < XB; ++nb) b[nb] = Xt[(2 * s + h) * LDX + 32 * nb + j];
+            for (int nb = 0; nb < XB; ++nb) bn[nb] = Xt[(2 * s + 2 + h) * LDX + 32 * nb + j];
+        }
 #pragma unroll
         for (int mb = 0; mb < ZB; ++mb)
 #pragma unroll
             for (int nb = 0; nb < XB; ++nb) G[mb][nb] = mfma32(a[mb], b[nb], G[mb][nb]);
+#pragma unroll
+        for (int mb = 0; mb < ZB; ++mb) a[mb] = an[mb];
+#pragma unroll
+        for (int nb = 0; nb < XB; ++nb) b[nb] = bn[nb];
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 

@@ -178,7 +178,7 @@ __device__ __forceinline__ void store_rows16(float* __restrict__ dst, int64_t i,
 
 // ------------------------------------------------------------------------------------------
 template <int D, int K>
-__global__ __launch_bounds__(kThreads) void sdf_fwd_kernel(SdfArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
     __shared__ SdfWeights<D, K> w;
     load_weights<D, K>(w, a);
     constexpr int LDIN = SdfWeights<D, K>::LDIN;

@@ -134,37 +134,40 @@ __device__ __forceinline__ void block_add(float v, float* dst, float* red) {
     __syncthreads();
 }
 
+// Grid-stride: a few hundred workgroups, each ending in two atomics (thousands of workgroups
+// all adding to the same two floats would serialise on them).
 __global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
                                                    const float* __restrict__ normal, const float* __restrict__ y,
                                                    int64_t rays, int64_t n, float beta, float* __restrict__ loss,
                                                    float* __restrict__ dC, float* __restrict__ d_normal,
                                                    float* __restrict__ d_y) {
     __shared__ float red[4];
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const float inv_n = 1.f / (float)n;
     float first = 0.f, eik = 0.f;
-    if (i < n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
         const float nx = normal[3 * i], ny = normal[3 * i + 1], nz = normal[3 * i + 2];
         const float len = sqrtf(nx * nx + ny * ny + nz * nz);
         const float dev = len - 1.f;
-        eik = beta * dev * dev * inv_n;
+        eik += beta * dev * dev * inv_n;
         const float k = 2.f * beta * inv_n * dev / fmaxf(len, 1e-30f);
         d_normal[3 * i] = k * nx; d_normal[3 * i + 1] = k * ny; d_normal[3 * i + 2] = k * nz;
         if (kind == 0) {
             const float d = y[16 * i];
-            first = d * d * inv_n;
+            first += d * d * inv_n;
             float4* o = reinterpret_cast<float4*>(d_y + 16 * i);
             o[0] = make_float4(2.f * d * inv_n, 0.f, 0.f, 0.f);
             o[1] = o[2] = o[3] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-    if (kind == 1 && i < rays) {
+    if (kind == 1) {
         const float inv_r = 1.f / (float)rays;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < rays; i += (int64_t)gridDim.x * 256) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            const float diff = C[3 * i + c] - target[3 * i + c];
-            first += fabsf(diff) * inv_r;
-            dC[3 * i + c] = diff > 0.f ? inv_r : (diff < 0.f ? -inv_r : 0.f);
+            for (int c = 0; c < 3; ++c) {
+                const float diff = C[3 * i + c] - target[3 * i + c];
+                first += fabsf(diff) * inv_r;
+                dC[3 * i + c] = diff > 0.f ? inv_r : (diff < 0.f ? -inv_r : 0.f);
+            }
         }
     }
     block_add(first, loss + 0, red);
@@ -293,7 +296,9 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
         NEUS2_TRY(check_ptr(d_y, "d_y"));
     }
     if (n == 0) return NEUS2_OK;
-    hipLaunchKernelGGL(loss_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, cfg->loss_kind,
+    const int64_t want = (n + 255) / 256;
+    const int64_t cap = 2 * (int64_t)compute_units();
+    hipLaunchKernelGGL(loss_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, (hipStream_t)stream, cfg->loss_kind,
                        C, target, normal, y, cfg->loss_kind == 1 ? rays : 0, n, cfg->beta, loss, dC, d_normal, d_y);
     return check_launch("loss");
 }

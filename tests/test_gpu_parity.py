@@ -401,10 +401,13 @@ def test_empty_batch_is_a_no_op():
     assert float(step.d_tables.abs().sum()) == 0.0
 
 
-def test_full_size_config2_sampled_rays():
-    """At the benchmark's full size and launch configuration: per-ray outputs of a random
-    sample of rays against the oracle run on those rays alone; adjoints scale with 1/rays."""
-    w = wl.make_workload(2)
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_full_size_sampled_rays(k):
+    """At the workload's full size and launch configuration: per-ray outputs of a random
+    sample of rays against the oracle run on those rays alone; adjoints scale with 1/rays.
+    The table gradient is checked against the oracle's scatter of the adjoints the GPU produced
+    (for the two 2^19-entry workloads; at 2^21 entries only on properties)."""
+    w = wl.make_workload(k)
     cfg, params, batch = w["cfg"], w["params"], w["batch"]
     n = batch["pos"].shape[0]
     spr = cfg.samples_per_ray
@@ -428,10 +431,20 @@ def test_full_size_config2_sampled_rays():
     assert rel(step.d_y[ptsg].cpu().numpy(), ref["d_y"] * scale) <= GRAD_TOL
     assert rel(step.d_normal[ptsg].cpu().numpy(), ref["d_normal"] * scale) <= GRAD_TOL
     assert rel(from_level_major(step.d_enc[:, ptsg], len(pts)), ref["d_enc"] * scale) <= GRAD_TOL
-    # properties that hold at any size: gradients are finite, inactive/untouched entries are zero
+    # properties that hold at any size: gradients are finite, inactive levels are untouched
     for g in step.dH + step.dW:
         assert torch.isfinite(g).all() and float(g.abs().sum()) > 0
     assert torch.isfinite(step.d_tables).all()
+    assert float(step.d_tables[cfg.active_levels:].abs().sum()) == 0.0
+    # the sum over a level's table of feature f equals the sum over points of dL/de_f, because
+    # the interpolation weights of a point sum to one and their derivatives to zero
+    got = step.d_tables[:cfg.active_levels].double().sum(dim=1).cpu().numpy()          # [levels, 2]
+    want = step.d_enc[:cfg.active_levels].double().sum(dim=1).cpu().numpy()
+    assert np.max(np.abs(got - want)) <= 1e-5 * np.max(np.abs(want)) + 1e-9
+    if k != 4:
+        want_t = o.table_gradient(cfg, batch["pos"], from_level_major(step.q, n), from_level_major(step.d_enc, n),
+                                  step.d_normal.cpu().numpy())
+        assert rel(step.d_tables.cpu().numpy(), want_t) <= GRAD_TOL
 
 
 def test_full_size_config2_against_full_oracle():

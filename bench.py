@@ -32,9 +32,27 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 
-# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy
-# kernel of known size); see profiles/.  None = not measured for this build.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes that crossed the L2 <-> fabric boundary per call, from the two rocprofv3 --pmc runs
+# summarised in profiles/hbm_traffic_cfg2-static-4096x64.txt (FETCH_SIZE x 2.000 + WRITE_SIZE
+# x 1.000, the factors a 256 MiB device copy gives), in MiB {read, written}.  Only this
+# workload has been measured; other workloads report null.
+MEASURED_TRAFFIC_MIB = {
+    "cfg2-static-4096x64": {
+        "hash_encode": (71.1, 128.0), "sdf_fwd_grad": (128.4, 51.0), "color_fwd": (22.6, 3.0),
+        "render_rays": (19.0, 1.1), "loss": (3.1, 3.1), "render_rays_bwd": (19.2, 4.0),
+        "color_bwd": (30.1, 26.6), "sdf_mlp_bwd": (147.8, 39.0),
+        "hash_scatter_bwd": (82.2 + 351.7, 237.5 + 51.4),      # bin_rows_kernel + scatter_owner_kernel
+        "adam_tables": (256.0, 288.0),
+    },
+}
+
+# the HIP kernels behind each timed call (names as rocprofv3 prints them)
+KERNELS_OF_CALL = {
+    "hash_encode": "encode_kernel", "sdf_fwd_grad": "sdf_fwd_kernel", "sdf_mlp_bwd": "sdf_bwd_kernel",
+    "hash_scatter_bwd": "zero_kernel + bin_rows_kernel + scatter_owner_kernel (scatter_kernel below 2^16 points)",
+    "adam_tables": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
+    "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
+}
 
 
 def algorithmic_cost(cfg, n):
@@ -193,7 +211,10 @@ def main() -> int:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": kd["GBps"], "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": round(kd["GBps"] / HBM_PEAK_GBS, 4)}
         roofline["us_per_launch"] = kd["us"]
-        roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((dom, cfg.name))
+        roofline["hip_kernels"] = KERNELS_OF_CALL.get(dom)
+        roofline["algorithmic_bytes"] = kd["bytes"]
+        mt = MEASURED_TRAFFIC_MIB.get(cfg.name, {}).get(dom) if n == wl.default_rays(args.workload) * cfg.samples_per_ray else None
+        roofline["traffic"] = int((mt[0] + mt[1]) * 1048576) if mt else None
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample
     cpu = None

@@ -144,6 +144,59 @@ __device__ __forceinline__ v16f apply_jac(const float* __restrict__ jac, int64_t
     return t;
 }
 
+// The Jacobian rows of this lane's features, held in registers so that the loads can be issued
+// long before they are needed.
+template <int D>
+struct JacRegs {
+    float2 v[D / 4][3];        // per level of this lane: (J00,J01) (J02,J10) (J11,J12)
+};
+
+template <int D>
+__device__ __forceinline__ JacRegs<D> load_jac(const float* __restrict__ jac, int64_t n, int64_t i, bool valid,
+                                               int active, int h) {
+    JacRegs<D> J;
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int level = 4 * g + 2 * h + u;
+            const bool on = valid && level < active;
+            const float2* p = reinterpret_cast<const float2*>(jac) + ((int64_t)(on ? level : 0) * n + (on ? i : 0)) * 3;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) J.v[2 * g + u][c] = on ? p[c] : make_float2(0.f, 0.f);
+        }
+    return J;
+}
+
+template <int D>
+__device__ __forceinline__ void contract_jac_regs(const JacRegs<D>& J, const v16f& x, float out[3]) {
+    out[0] = out[1] = out[2] = 0.f;
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float2 a = J.v[2 * g + u][0], b = J.v[2 * g + u][1], c = J.v[2 * g + u][2];
+            const float x0 = x[4 * g + 2 * u], x1 = x[4 * g + 2 * u + 1];
+            out[0] += x0 * a.x + x1 * b.y;
+            out[1] += x0 * a.y + x1 * c.x;
+            out[2] += x0 * b.x + x1 * c.y;
+        }
+}
+
+template <int D>
+__device__ __forceinline__ v16f apply_jac_regs(const JacRegs<D>& J, const float v[3]) {
+    v16f t = zero16();
+#pragma unroll
+    for (int g = 0; g < D / 8; ++g)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float2 a = J.v[2 * g + u][0], b = J.v[2 * g + u][1], c = J.v[2 * g + u][2];
+            t[4 * g + 2 * u] = a.x * v[0] + a.y * v[1] + b.x * v[2];
+            t[4 * g + 2 * u + 1] = b.y * v[0] + c.x * v[1] + c.y * v[2];
+        }
+    return t;
+}
+
 // row 0 of the last matrix in register layout, masked: S_{K-1} of Definition 1 for output 0
 template <int D, int K>
 __device__ __forceinline__ void last_row_masked(const SdfWeights<D, K>& w, uint32_t m, int h, v16f* s) {
@@ -185,10 +238,20 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
     const int64_t tiles = (a.n + 31) / 32;
-    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+    const int64_t stride = (int64_t)gridDim.x * kWaves;
+    int64_t tile = (int64_t)blockIdx.x * kWaves + wave;
+    // the encoding of the NEXT tile and the Jacobian of THIS tile are requested before the
+    // matrix work of this tile starts, so that HBM latency hides behind it
+    v16f x_next = load_levels<D>(a.enc, a.n, tile * 32 + j, tile < tiles && tile * 32 + j < a.n, a.active_levels, h);
+    for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
-        v16f x0[1] = {load_levels<D>(a.enc, a.n, i, valid, a.active_levels, h)};
+        v16f x0[1] = {x_next};
+        const JacRegs<D> J = load_jac<D>(a.jac, a.n, i, valid, a.active_levels, h);
+        {
+            const int64_t in = (tile + stride) * 32 + j;
+            x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
+        }
         v16f a1[2];
         matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
         const uint32_t m1 = relu_mask<2>(a1);
@@ -216,7 +279,7 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
         matvec<1, 2, kLd64>(w.H1t, s1, qv, j, h);
         store_levels<D>(a.q, a.n, i, valid, qv[0], h);
         float nrm[3];
-        contract_jac<D>(a.jac, a.n, i, valid, a.active_levels, h, qv[0], nrm);
+        contract_jac_regs<D>(J, qv[0], nrm);
 #pragma unroll
         for (int c = 0; c < 3; ++c) nrm[c] += __shfl_xor(nrm[c], 32);
         if (valid && h == 0) {
@@ -267,11 +330,24 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     }
 
     const int64_t tiles = (a.n + 31) / 32;
-    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+    const int64_t stride = (int64_t)gridDim.x * kWaves;
+    int64_t tile = (int64_t)blockIdx.x * kWaves + wave;
+    // every global input of a tile is requested at its top (the next tile's encoding as well),
+    // so that HBM latency hides behind the matrix work
+    v16f x_next = load_levels<D>(a.enc, a.n, tile * 32 + j, tile < tiles && tile * 32 + j < a.n, a.active_levels, h);
+    for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
+        v16f x0[1] = {x_next};
+        v16f dK[1] = {load_rows16(a.d_y, i, valid, h)};
+        float nb3[3] = {0.f, 0.f, 0.f};
+        if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }
+        const JacRegs<D> J = load_jac<D>(a.jac, a.n, i, valid, a.active_levels, h);
+        {
+            const int64_t in = (tile + stride) * 32 + j;
+            x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
+        }
         // ---- forward recompute
-        v16f x0[1] = {load_levels<D>(a.enc, a.n, i, valid, a.active_levels, h)};
         v16f a1[2], a2[2];
         matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
         const uint32_t m1 = relu_mask<2>(a1);
@@ -280,8 +356,9 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             matvec<2, 2, kLd64>(w.H2f, a1, a2, j, h);
             m_last = relu_mask<2>(a2);
         }
+        // t_0 = (de/dx) dL/dn, computed now so that the Jacobian's registers are free again
+        v16f t0[1] = {apply_jac_regs<D>(J, nb3)};
         // ---- first-order chain delta_K .. delta_1, weight gradients as they appear
-        v16f dK[1] = {load_rows16(a.d_y, i, valid, h)};
         v16f d2[2], d1[2];
         stage<1, kLd64>(Zt, dK, j, h);
         stage<2, kLd64>(Xt, K == 3 ? a2 : a1, j, h);
@@ -318,9 +395,6 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             }
         }
         // ---- second order: S sweep (reverse) and t sweep (forward mode), Theorem 1
-        float nb3[3] = {0.f, 0.f, 0.f};
-        if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }
-        v16f t0[1] = {apply_jac<D>(a.jac, a.n, i, valid, a.active_levels, h, nb3)};
         v16f s2[2], s1[2];
         last_row_masked<D, K>(w, m_last, h, s2);
         if (K == 3) {

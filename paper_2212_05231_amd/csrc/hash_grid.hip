@@ -297,19 +297,19 @@ constexpr int kWorkspaceHeader = kCursorOffset + 4 * NEUS2_MAX_LEVELS * kMaxRang
 struct OwnerPlan {
     int n_entries;
     int n_tasks;
-    int n_keyed;                            // entries [0, n_keyed) are hashed levels with record lists
-    int range_bits;                         // log2(T) - 14 for keyed levels
-    int capacity;                           // records per (level, range) list
+    int n_listed;                           // entries [0, n_listed) are levels with record lists
     int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries
+    int capacity[NEUS2_MAX_LEVELS];         // records per list of a listed entry
+    int64_t list_base[NEUS2_MAX_LEVELS + 1];// first record of the entry's lists; [n_listed] = total
     short level[NEUS2_MAX_LEVELS];
     short ranges[NEUS2_MAX_LEVELS];
     short chunks[NEUS2_MAX_LEVELS];
 };
 
 struct Records {
-    int* cursor;            // [n_keyed][kMaxRanges]
-    uint32_t* slots;        // [n_keyed][ranges][capacity]  local slot of x | local slot of x+1 << 16
-    float4* vals;           // [n_keyed][ranges][capacity]  {x f0, x f1, x+1 f0, x+1 f1}
+    int* cursor;            // [n_listed][kMaxRanges]
+    uint32_t* slots;        // per entry [ranges][capacity]: local slot of x | local slot of x+1 << 16
+    float4* vals;           // per entry [ranges][capacity]: {x f0, x f1, x+1 f0, x+1 f1}
 };
 
 __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
@@ -344,6 +344,8 @@ __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, Own
         const float2 qq = reinterpret_cast<const float2*>(q)[o];
         const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
         const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
+        const bool dense = (g.dense_bits >> level) & 1u;
+        const uint32_t stride = (uint32_t)res + 1u;
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
             const int dy = row & 1, dz = row >> 1;
@@ -353,12 +355,28 @@ __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, Own
             const float fyz = fy * fz;
             const float dn_x = nx * fyz;
             const float dn_yz = ny * (sy * fz) + nz * (fy * sz);
-            const uint32_t s0 = ((uint32_t)cx ^ rh) & g.table_mask, s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
+            uint32_t s0, s1;
+            if (dense) {
+                s0 = (uint32_t)cx + ((uint32_t)(cy + dy) + (uint32_t)(cz + dz) * stride) * stride;
+                s1 = s0 + 1u;
+            } else {
+                s0 = ((uint32_t)cx ^ rh) & g.table_mask;
+                s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
+            }
             const float f0 = 1.f - w0, f1 = w0;
             const float dn0 = -dn_x + f0 * dn_yz, dn1 = dn_x + f1 * dn_yz;
             const float wk0 = f0 * fyz, wk1 = f1 * fyz;
             val[row] = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
-            range[row] = s0 >> kOwnerSlotBits;                      // == s1 >> kOwnerSlotBits
+            range[row] = s0 >> kOwnerSlotBits;
+            // On a hashed level both corners share the range.  On a dense level the x+1 corner can be
+            // the first slot of the next range (1 row in 8192): it then goes straight to the gradient.
+            if ((s1 >> kOwnerSlotBits) != range[row]) {
+                float* gt = d_tables + ((size_t)level * g.table_size + s1) * 2;
+                atomicAdd(gt + 0, val[row].z);
+                atomicAdd(gt + 1, val[row].w);
+                val[row].z = 0.f; val[row].w = 0.f;
+                s1 = s0;
+            }
             packed[row] = (s0 & (kOwnerSlots - 1)) | ((s1 & (kOwnerSlots - 1)) << 16);
             rank[row] = atomicAdd(&cnt[range[row]], 1);
         }
@@ -371,8 +389,8 @@ __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, Own
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
             const int p = base[range[row]] + rank[row];
-            if (p < plan.capacity) {
-                const size_t at = ((size_t)e * n_ranges + range[row]) * plan.capacity + p;
+            if (p < plan.capacity[e]) {
+                const size_t at = (size_t)plan.list_base[e] + (size_t)range[row] * plan.capacity[e] + p;
                 rec.slots[at] = packed[row];
                 rec.vals[at] = val[row];
             } else {                                                 // list full: straight to the global gradient
@@ -419,9 +437,9 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) acc[k] = 0.0;
         __syncthreads();
 
-        if (e < plan.n_keyed) {
-            const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity);
-            const size_t at = ((size_t)e * n_ranges + range) * plan.capacity;
+        if (e < plan.n_listed) {
+            const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity[e]);
+            const size_t at = (size_t)plan.list_base[e] + (size_t)range * plan.capacity[e];
             const uint32_t* rs = rec.slots + at;
             const float4* rv = rec.vals + at;
             // four records per thread in flight: the list is streamed from HBM
@@ -447,35 +465,46 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                 }
             }
         } else {
+            // In-place path (levels with at most kInPlaceRanges ranges: nearly every point hits):
+            // four points per thread, all their loads issued before the first use.
             const float fres = (float)g.res[level];
-            const bool dense = (g.dense_bits >> level) & 1u;
-            for (int64_t i = begin + threadIdx.x; i < end; i += kOwnerThreads) {
-                const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
-                // on a dense level the eight slots lie in [slot[0], slot[7]]
-                if (dense && ((c.slot[7] >> kOwnerSlotBits) < range || (c.slot[0] >> kOwnerSlotBits) > range)) continue;
-                uint32_t match = 0;
+            const bool dense_level = (g.dense_bits >> level) & 1u;
+            constexpr int kAhead = 4;
+            for (int64_t i0 = begin + threadIdx.x; i0 < end; i0 += kAhead * kOwnerThreads) {
+                float px[kAhead], py[kAhead], pz[kAhead], nx[kAhead], ny[kAhead], nz[kAhead];
+                float2 de[kAhead], qq[kAhead];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) match |= ((c.slot[k] >> kOwnerSlotBits) == range ? 1u : 0u) << k;
-                if (match) {
-                    const int64_t o = (int64_t)level * n + i;
-                    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-                    const float2 qq = reinterpret_cast<const float2*>(q)[o];
-                    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+                for (int k = 0; k < kAhead; ++k) {
+                    const int64_t i = i0 + k * kOwnerThreads;
+                    if (i < end) {
+                        const int64_t o = (int64_t)level * n + i;
+                        px[k] = pos[3 * i + 0]; py[k] = pos[3 * i + 1]; pz[k] = pos[3 * i + 2];
+                        nx[k] = d_normal[3 * i + 0]; ny[k] = d_normal[3 * i + 1]; nz[k] = d_normal[3 * i + 2];
+                        de[k] = reinterpret_cast<const float2*>(d_enc)[o];
+                        qq[k] = reinterpret_cast<const float2*>(q)[o];
+                    }
+                }
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        if ((match >> k) & 1u) {
-                            const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
-                            const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
-                            const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
-                            const float sx = (k & 1) ? 1.f : -1.f;
-                            const float sy = (k & 2) ? 1.f : -1.f;
-                            const float sz = (k & 4) ? 1.f : -1.f;
-                            const float wk = fx * fy * fz;
-                            const float dn = nx * (sx * fy * fz) + ny * (fx * sy * fz) + nz * (fx * fy * sz);
-                            double* a = acc + 2 * (c.slot[k] & (kOwnerSlots - 1));
-                            atomicAdd(a + 0, (double)(wk * de.x + qq.x * dn));
-                            atomicAdd(a + 1, (double)(wk * de.y + qq.y * dn));
-                        }
+                for (int k = 0; k < kAhead; ++k) {
+                    if (i0 + k * kOwnerThreads >= end) continue;
+                    const Cell c = locate(g, level, px[k], py[k], pz[k]);
+                    // on a dense level the eight slots lie in [slot[0], slot[7]]
+                    if (dense_level && ((c.slot[7] >> kOwnerSlotBits) < range || (c.slot[0] >> kOwnerSlotBits) > range)) continue;
+                    const float ax = nx[k] * fres, ay = ny[k] * fres, az = nz[k] * fres;
+#pragma unroll
+                    for (int cr = 0; cr < 8; ++cr) {
+                        if ((c.slot[cr] >> kOwnerSlotBits) != range) continue;
+                        const float fx = (cr & 1) ? c.w[0] : 1.f - c.w[0];
+                        const float fy = (cr & 2) ? c.w[1] : 1.f - c.w[1];
+                        const float fz = (cr & 4) ? c.w[2] : 1.f - c.w[2];
+                        const float sx = (cr & 1) ? 1.f : -1.f;
+                        const float sy = (cr & 2) ? 1.f : -1.f;
+                        const float sz = (cr & 4) ? 1.f : -1.f;
+                        const float wk = fx * fy * fz;
+                        const float dn = ax * (sx * fy * fz) + ay * (fx * sy * fz) + az * (fx * fy * sz);
+                        double* a = acc + 2 * (c.slot[cr] & (kOwnerSlots - 1));
+                        atomicAdd(a + 0, (double)(wk * de[k].x + qq[k].x * dn));
+                        atomicAdd(a + 1, (double)(wk * de[k].y + qq[k].y * dn));
                     }
                 }
             }
@@ -494,31 +523,38 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
     }
 }
 
-// Which levels get how many ranges and point chunks; keyed (hashed, several ranges) levels
-// first because their tasks are the heaviest.  ok = false if the configuration does not fit
-// the scheme (then the atomic kernel is used).
+// Which levels get record lists, how many ranges and point chunks.  Listed levels (hashed
+// levels with several ranges, dense levels with more than kInPlaceRanges ranges) come first
+// because their tasks are the heaviest.  ok = false if the configuration does not fit the
+// scheme (then the atomic kernel is used).
+constexpr int kInPlaceRanges = 64;
+
 OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     OwnerPlan p;
     memset(&p, 0, sizeof(p));
     ok = true;
     const int64_t T = (int64_t)1 << cfg->log2_table_size;
-    p.range_bits = cfg->log2_table_size > kOwnerSlotBits ? cfg->log2_table_size - kOwnerSlotBits : 0;
-    if (p.range_bits > 8) ok = false;                 // at most kMaxRanges lists per level
-    // a list holds 1.5 times its expected share of the 4 n row records of a level
-    const int64_t cap = ((4 * n >> p.range_bits) * 3 / 2 + 1023) / 64 * 64;
-    if (cap > (1 << 30)) ok = false;
-    p.capacity = (int)cap;
+    if (T > (int64_t)kMaxRanges * kOwnerSlots) ok = false;          // at most kMaxRanges lists per level
     int e = 0, tasks = 0;
+    int64_t records = 0;
     for (int pass = 0; pass < 2; ++pass) {
         for (int l = 0; l < cfg->active_levels; ++l) {
-            const bool keyed = !cfg->dense[l] && p.range_bits > 0;
-            if (keyed != (pass == 0)) continue;
-            if (keyed && cfg->res[l] >= kOwnerSlots) ok = false;   // x must not reach the range bits
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
             const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
             const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
+            const bool listed = ranges > (cfg->dense[l] ? kInPlaceRanges : 1);
+            if (listed != (pass == 0)) continue;
+            if (listed && !cfg->dense[l] && cfg->res[l] >= kOwnerSlots) ok = false;   // x must not reach the range bits
             int chunks = 1;
-            if (!keyed) {                              // small tasks: at most an eighth of the points each
+            if (listed) {
+                // a list holds 1.5 times its expected share of the 4 n row records of the level;
+                // 3 times on a dense level, where the share of a slab of the grid follows the batch
+                const int64_t cap = ((4 * n / ranges) * (cfg->dense[l] ? 6 : 3) / 2 + 1023) / 64 * 64;
+                if (cap > (1 << 30)) ok = false;
+                p.capacity[e] = (int)cap;
+                p.list_base[e] = records;
+                records += cap * ranges;
+            } else {                                   // small tasks: at most an eighth of the points each
                 chunks = 32 / ranges;
                 if (chunks < 8) chunks = 8;
             }
@@ -529,7 +565,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
             tasks += ranges * chunks;
             ++e;
         }
-        if (pass == 0) p.n_keyed = e;
+        if (pass == 0) { p.n_listed = e; p.list_base[e] = records; }
     }
     p.first_task[e] = tasks;
     p.n_entries = e;
@@ -560,8 +596,7 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
 }
 
 int64_t owner_workspace_need(const OwnerPlan& plan) {
-    const int64_t lists = (int64_t)plan.n_keyed << plan.range_bits;
-    return kWorkspaceHeader + lists * plan.capacity * 20 + 256;
+    return kWorkspaceHeader + plan.list_base[plan.n_listed] * 20 + 256;
 }
 
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
@@ -588,13 +623,12 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             int* counter = reinterpret_cast<int*>(ws);
             Records rec;
             rec.cursor = reinterpret_cast<int*>(ws + kCursorOffset);
-            const int64_t lists = (int64_t)plan.n_keyed << plan.range_bits;
             rec.vals = reinterpret_cast<float4*>(ws + kWorkspaceHeader);                         // 16-byte aligned
-            rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + lists * plan.capacity * 16);
+            rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 16);
             NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));      // task counter and cursors
-            if (plan.n_keyed > 0) {
+            if (plan.n_listed > 0) {
                 const int pbs = (int)((n + kOwnerThreads - 1) / kOwnerThreads);
-                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_keyed), dim3(kOwnerThreads), 0, st, g, plan, rec, pos, q,
+                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_listed), dim3(kOwnerThreads), 0, st, g, plan, rec, pos, q,
                                    d_enc, d_normal, n, pbs, d_tables);
             }
             const int wgs = compute_units();

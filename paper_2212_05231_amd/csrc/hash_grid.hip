@@ -84,6 +84,68 @@ __device__ __forceinline__ float2 load_entry<__half>(const __half* t, uint32_t s
     return __half22float2(reinterpret_cast<const __half2*>(t)[slot]);
 }
 
+// The eight corner entries of a cell, as floats.  The coalescing unit in front of the L1
+// handles about one cache line per clock, so a gather instruction whose 64 lanes touch 64
+// lines costs 64 clocks whatever it returns; the two x corners of a row are therefore fetched
+// with ONE load where their slots allow it.
+template <typename T>
+__device__ __forceinline__ void gather_corners(const GridDesc& g, int level, const T* tab, const Cell& c, float2* v) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = load_entry<T>(tab, c.slot[k]);
+}
+
+struct __attribute__((packed, aligned(4))) EntryPair {
+    uint32_t a, b;
+};
+
+__device__ __forceinline__ float2 entry_to_float2(uint32_t e) {
+    return __half22float2(*reinterpret_cast<const __half2*>(&e));
+}
+
+// fp16 tables: an entry is one dword.  Dense level: slot(x+1) = slot(x) + 1, one 8-byte load.
+// Hashed level: slot = x ^ (y*P1 ^ z*P2), so slot(x) and slot(x+1) lie in the same aligned
+// group of four entries unless x % 4 == 3: one aligned 16-byte load, plus a single-entry load
+// for that quarter of the lanes.
+__device__ __forceinline__ uint32_t pick4(const uint4& q, uint32_t i) {
+    const uint32_t lo = (i & 1u) ? q.y : q.x, hi = (i & 1u) ? q.w : q.z;
+    return (i & 2u) ? hi : lo;
+}
+
+template <>
+__device__ __forceinline__ void gather_corners<__half>(const GridDesc& g, int level, const __half* tab, const Cell& c, float2* v) {
+    const uint32_t* t32 = reinterpret_cast<const uint32_t*>(tab);
+    if ((g.dense_bits >> level) & 1u) {                       // uniform over the workgroup
+        EntryPair p[4];
+#pragma unroll
+        for (int row = 0; row < 4; ++row) p[row] = *reinterpret_cast<const EntryPair*>(t32 + c.slot[2 * row]);
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            v[2 * row] = entry_to_float2(p[row].a);
+            v[2 * row + 1] = entry_to_float2(p[row].b);
+        }
+    } else {
+        // all loads are issued before any of them is used
+        uint4 grp[4];
+        uint32_t far[4];
+#pragma unroll
+        for (int row = 0; row < 4; ++row) grp[row] = *reinterpret_cast<const uint4*>(t32 + (c.slot[2 * row] & ~3u));
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            far[row] = 0u;
+            if ((c.slot[2 * row] ^ c.slot[2 * row + 1]) >= 4u) far[row] = t32[c.slot[2 * row + 1]];
+        }
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t s0 = c.slot[2 * row], s1 = c.slot[2 * row + 1];
+            const uint32_t e0 = pick4(grp[row], s0 & 3u);
+            const uint32_t near = pick4(grp[row], s1 & 3u);
+            const uint32_t e1 = (s0 ^ s1) < 4u ? near : far[row];
+            v[2 * row] = entry_to_float2(e0);
+            v[2 * row + 1] = entry_to_float2(e1);
+        }
+    }
+}
+
 // block index -> (level, point block); returns false for padding blocks
 __device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int& level, int& pb) {
     const int bid = blockIdx.x;
@@ -115,8 +177,7 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, const float*
     if (level < g.active_levels) {
         const T* tab = tables + (size_t)level * g.table_size * 2;
         float2 v[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = load_entry<T>(tab, c.slot[k]);
+        gather_corners<T>(g, level, tab, c, v);
         const float fres = (float)g.res[level];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {

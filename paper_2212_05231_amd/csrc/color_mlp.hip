@@ -96,29 +96,50 @@ __device__ __forceinline__ void sh16(float x, float y, float z, float* sh) {
     sh[15] = 0.5900435899266435f * x * (xx - 3.f * yy);
 }
 
-// Gather one point's input into the register layout: block 0 = [(d,g), SH16], block 1 = [x, n].
-__device__ __forceinline__ void load_input(const ColorArgs& a, int64_t i, bool valid, int h, v16f* cin) {
+// One point's inputs as they sit in memory; loaded one tile ahead so that HBM latency hides
+// behind the matrix work of the current tile.
+struct ColorRaw {
+    float4 ya, yb;
+    float dir[3], p[3], nr[3];
+    float d_rgb[3], d_sdf;
+};
+
+template <bool BWD>
+__device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool valid, int h) {
+    ColorRaw r = {};
+    if (!valid) return r;
+    r.ya = *reinterpret_cast<const float4*>(a.y + i * 16 + 4 * h);
+    r.yb = *reinterpret_cast<const float4*>(a.y + i * 16 + 8 + 4 * h);
+    const int64_t ray = i / a.spr;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        r.dir[c] = a.dirs[3 * ray + c];
+        r.p[c] = a.pos[3 * i + c];
+        r.nr[c] = a.normal[3 * i + c];
+        if (BWD) r.d_rgb[c] = a.d_rgb[3 * i + c];
+    }
+    if (BWD && a.d_sdf) r.d_sdf = a.d_sdf[i];
+    return r;
+}
+
+// Build the register layout from the raw inputs: block 0 = [(d,g), SH16], block 1 = [x, n].
+__device__ __forceinline__ void build_input(const ColorRaw& r, bool valid, int h, v16f* cin) {
     cin[0] = zero16();
     cin[1] = zero16();
     if (!valid) return;
-    const float4 ya = *reinterpret_cast<const float4*>(a.y + i * 16 + 4 * h);
-    const float4 yb = *reinterpret_cast<const float4*>(a.y + i * 16 + 8 + 4 * h);
-    cin[0][0] = ya.x; cin[0][1] = ya.y; cin[0][2] = ya.z; cin[0][3] = ya.w;
-    cin[0][4] = yb.x; cin[0][5] = yb.y; cin[0][6] = yb.z; cin[0][7] = yb.w;
-    const int64_t ray = i / a.spr;
+    cin[0][0] = r.ya.x; cin[0][1] = r.ya.y; cin[0][2] = r.ya.z; cin[0][3] = r.ya.w;
+    cin[0][4] = r.yb.x; cin[0][5] = r.yb.y; cin[0][6] = r.yb.z; cin[0][7] = r.yb.w;
     float sh[16];
-    sh16(a.dirs[3 * ray], a.dirs[3 * ray + 1], a.dirs[3 * ray + 2], sh);
+    sh16(r.dir[0], r.dir[1], r.dir[2], sh);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         cin[0][8 + k] = h ? sh[4 + k] : sh[k];
         cin[0][12 + k] = h ? sh[12 + k] : sh[8 + k];
     }
-    const float p0 = a.pos[3 * i], p1 = a.pos[3 * i + 1], p2 = a.pos[3 * i + 2];
-    const float n0 = a.normal[3 * i], n1 = a.normal[3 * i + 1], n2 = a.normal[3 * i + 2];
-    cin[1][0] = h ? n1 : p0;
-    cin[1][1] = h ? n2 : p1;
-    cin[1][2] = h ? 0.f : p2;
-    cin[1][3] = h ? 0.f : n0;
+    cin[1][0] = h ? r.nr[1] : r.p[0];
+    cin[1][1] = h ? r.nr[2] : r.p[1];
+    cin[1][2] = h ? 0.f : r.p[2];
+    cin[1][3] = h ? 0.f : r.nr[0];
 }
 
 __device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-u)); }
@@ -139,12 +160,19 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
     const int64_t tiles = (a.n + 31) / 32;
-    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+    const int64_t stride = (int64_t)gridDim.x * kWaves;
+    int64_t tile = (int64_t)blockIdx.x * kWaves + wave;
+    ColorRaw next = load_raw<false>(a, tile * 32 + j, tile < tiles && tile * 32 + j < a.n, h);
+    for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
         v16f cin[2], a1[2], a2[2], u[1];
         uint32_t m1, m2;
-        load_input(a, i, valid, h, cin);
+        build_input(next, valid, h, cin);
+        {
+            const int64_t in = (tile + stride) * 32 + j;
+            next = load_raw<false>(a, in, tile + stride < tiles && in < a.n, h);
+        }
         forward_tile<false>(w, cin, a1, a2, m1, m2, u, j, h);
         if (valid && h == 0) {
             a.rgb[3 * i + 0] = sigmoid(u[0][0]);
@@ -174,12 +202,20 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         for (int nb = 0; nb < 2; ++nb) { G1[mb][nb] = zero16(); G2[mb][nb] = zero16(); G3[0][nb] = zero16(); }
 
     const int64_t tiles = (a.n + 31) / 32;
-    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+    const int64_t stride = (int64_t)gridDim.x * kWaves;
+    int64_t tile = (int64_t)blockIdx.x * kWaves + wave;
+    ColorRaw next = load_raw<true>(a, tile * 32 + j, tile < tiles && tile * 32 + j < a.n, h);
+    for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
         v16f cin[2], a1[2], a2[2], u[1];
         uint32_t m1, m2;
-        load_input(a, i, valid, h, cin);
+        const ColorRaw cur = next;
+        build_input(cur, valid, h, cin);
+        {
+            const int64_t in = (tile + stride) * 32 + j;
+            next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
+        }
         forward_tile<true>(w, cin, a1, a2, m1, m2, u, j, h);
         // adjoint of the pre-sigmoid output
         v16f d3[1] = {zero16()};
@@ -187,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 const float s = sigmoid(u[0][c]);
-                d3[0][c] = a.d_rgb[3 * i + c] * s * (1.f - s);
+                d3[0][c] = cur.d_rgb[c] * s * (1.f - s);
             }
         }
         stage<1, kLd64>(Zt, d3, j, h);
@@ -215,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             // block 0, registers 0..7: dL/d(d,g) columns 4h..4h+3 and 8+4h..8+4h+3
             float4 lo = make_float4(dcin[0][0], dcin[0][1], dcin[0][2], dcin[0][3]);
             const float4 hi = make_float4(dcin[0][4], dcin[0][5], dcin[0][6], dcin[0][7]);
-            if (h == 0 && a.d_sdf) lo.x += a.d_sdf[i];
+            if (h == 0) lo.x += cur.d_sdf;
             *reinterpret_cast<float4*>(a.d_y + i * 16 + 4 * h) = lo;
             *reinterpret_cast<float4*>(a.d_y + i * 16 + 8 + 4 * h) = hi;
             // block 1: h = 0 -> x0 x1 x2 n0 ; h = 1 -> n1 n2

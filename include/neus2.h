@@ -60,9 +60,12 @@ typedef struct neus2_config {
     int32_t n_color_mats;      /* 0 (no colour network) or 3 */
     int32_t color_dims[NEUS2_MAX_MATS + 1]; /* {38, 64, 64, 3} */
     int32_t samples_per_ray;   /* 1..64 */
-    int32_t loss_kind;         /* 0: mean(d^2) + beta*eikonal; 1: L1 colour + beta*eikonal */
-    float s;                   /* slope of the logistic CDF Phi_s (held fixed) */
+    int32_t loss_kind;         /* 0: mean(d^2) + beta*eikonal; 1: L1 colour + beta*eikonal;
+                                  2: Huber colour (Eq. 4) + beta*eikonal */
+    float s;                   /* slope of the logistic CDF Phi_s; calls that take s_dev read it
+                                  from device memory instead when s_dev is not NULL */
     float beta;                /* weight of the eikonal term in Eq. 4 */
+    float huber_delta;         /* loss_kind 2: |r| <= delta is quadratic, beyond it linear */
 } neus2_config;
 
 const char* neus2_last_error(void);
@@ -117,21 +120,26 @@ int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* norm
 /* NeuS compositing (supplement Sec. E.3): alpha_i = max((Phi(d_i)-Phi(d_{i+1}))/Phi(d_i), 0),
  * alpha of the last sample is 0, T_i = prod_{j<i}(1-alpha_j), C = sum T_i alpha_i c_i.
  *   sdf [device]: d of sample i at sdf[i*sdf_stride];  rgb [device, n*3];
+ *   s_dev [device, 1 float] or NULL: the slope s when it is a trained parameter that lives
+ *   on the device (the paper keeps s learnable); NULL means cfg->s;
  *   C [device, rays*3];  weights [device, n] = T_i alpha_i. */
 int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_stride,
-                      const float* rgb, int64_t rays, float* C, float* weights, void* stream);
+                      const float* rgb, const float* s_dev, int64_t rays, float* C,
+                      float* weights, void* stream);
 
 /* Backward of neus2_render_rays: dC [device, rays*3] -> d_sdf [device, n], d_rgb [device, n*3]
- * (both overwritten). */
+ * (both overwritten);  d_s [device, 1 float] or NULL: dL/ds is ADDED into it. */
 int neus2_render_rays_bwd(const neus2_config* cfg, const float* sdf, int64_t sdf_stride,
-                          const float* rgb, const float* dC, int64_t rays, float* d_sdf,
-                          float* d_rgb, void* stream);
+                          const float* rgb, const float* dC, const float* s_dev, int64_t rays,
+                          float* d_sdf, float* d_rgb, float* d_s, void* stream);
 
 /* Loss of Eq. 4 and its first adjoints.
  *   loss_kind 1: loss = sum|C - target| / rays + beta * mean((|n|-1)^2); C, target
  *     [device, rays*3]; dC [device, rays*3] = sign(C-target)/rays.
+ *   loss_kind 2: as 1 with the Huber function of huber_delta in place of |.|;
+ *     dC = clamp(C-target, -delta, delta)/rays.
  *   loss_kind 0: loss = mean(d^2) + beta * mean((|n|-1)^2); C, target, dC are NULL and
- *     d_y [device, n*16] is overwritten with (2 d / n) e_0.  For loss_kind 1 d_y may be NULL.
+ *     d_y [device, n*16] is overwritten with (2 d / n) e_0.  For loss_kind 1, 2 d_y may be NULL.
  *   d_normal [device, n*3] is overwritten with the eikonal part (2 beta / n)(|n|-1) n/|n|.
  *   loss [device, 2 floats]: {first term, beta * eikonal term}; ADDED into (zero it first). */
 int neus2_loss(const neus2_config* cfg, const float* C, const float* target, const float* normal,
@@ -200,6 +208,8 @@ typedef struct neus2_step_buffers {
     float* const* dH; float* const* dW; float* d_tables;
     void* workspace;           /* optional scratch, see neus2_workspace_bytes */
     int64_t workspace_bytes;
+    const float* s_dev;        /* optional, see neus2_render_rays */
+    float* d_s;                /* optional, see neus2_render_rays_bwd (ADDED into) */
 } neus2_step_buffers;
 
 /* One forward + backward pass (everything above except Adam and the rigid transform), in the

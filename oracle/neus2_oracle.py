@@ -255,8 +255,10 @@ def render_rays(sdf: np.ndarray, rgb: np.ndarray, s: float):
     return C, wgt, alpha, trans
 
 
-def render_rays_backward(sdf, rgb, s, dC):
-    """Gradient of sum(dC * C) wrt sdf [R,n] and rgb [R,n,3], straight from the definitions.
+def render_rays_backward(sdf, rgb, s, dC, want_ds: bool = False):
+    """Gradient of sum(dC * C) wrt sdf [R,n] and rgb [R,n,3], straight from the definitions;
+    with `want_ds` also wrt the slope s of Phi_s (the paper keeps s learnable, supplement
+    Sec. E.3), returned as a third value.
 
     dC/dalpha_i is written out with the explicit product over the other factors
     (no division by 1-alpha_i).
@@ -282,6 +284,11 @@ def render_rays_backward(sdf, rgb, s, dC):
     # alpha_i = 1 - Phi_{i+1}/Phi_i
     d_sdf[:, :-1] += np.where(live, d_alpha[:, :-1] * phi[:, 1:] * dphi[:, :-1] / phi[:, :-1] ** 2, 0.0)
     d_sdf[:, 1:] += np.where(live, -d_alpha[:, :-1] * dphi[:, 1:] / phi[:, :-1], 0.0)
+    if want_ds:
+        # dPhi_s(x)/ds = x Phi (1 - Phi);  alpha_i = 1 - Phi_{i+1}/Phi_i
+        ps = sdf * phi * (1.0 - phi)
+        da_ds = -(ps[:, 1:] * phi[:, :-1] - phi[:, 1:] * ps[:, :-1]) / phi[:, :-1] ** 2
+        return d_sdf, d_rgb, float(np.sum(np.where(live, d_alpha[:, :-1] * da_ds, 0.0)))
     return d_sdf, d_rgb
 
 
@@ -318,7 +325,8 @@ def accumulate_transform(Rc_prev, Tc_prev, R, T):
 def forward(cfg, params, batch, fp32_product: bool = True, want_hess: bool = False) -> Dict[str, object]:
     """Everything the loss needs, from the definitions.
 
-    batch: pos [N,3] (unit-cube coordinates); for loss_kind 1 also dirs [R,3], target [R,3].
+    batch: pos [N,3] (unit-cube coordinates); for loss_kind 1 (L1 colour term) and 2 (Huber colour
+    term, Eq. 4) also dirs [R,3], target [R,3].
     """
     pos = batch["pos"]
     N = pos.shape[0]
@@ -343,8 +351,22 @@ def forward(cfg, params, batch, fp32_product: bool = True, want_hess: bool = Fal
     diff = C - np.asarray(batch["target"], dtype=np.float64)
     out.update({"cin": cin, "rgb": rgb, "cacts": cacts, "cmasks": cmasks, "C": C, "weights": wgt,
                 "alpha": alpha, "trans": trans, "diff": diff})
-    out["loss"] = np.sum(np.abs(diff)) / R + cfg.beta * eik
+    if cfg.loss_kind == 2:
+        out["loss"] = np.sum(huber(diff, cfg.huber_delta)) / R + cfg.beta * eik
+    else:
+        out["loss"] = np.sum(np.abs(diff)) / R + cfg.beta * eik
     return out
+
+
+def huber(r: np.ndarray, delta: float) -> np.ndarray:
+    """Huber loss of a residual: r^2/2 for |r| <= delta, delta (|r| - delta/2) beyond (Eq. 4 names
+    it for the colour term; delta is not given in the paper and is a configuration value)."""
+    a = np.abs(r)
+    return np.where(a <= delta, 0.5 * r * r, delta * (a - 0.5 * delta))
+
+
+def huber_derivative(r: np.ndarray, delta: float) -> np.ndarray:
+    return np.clip(r, -delta, delta)
 
 
 def loss_value(cfg, params, batch, fp32_product: bool = True) -> float:
@@ -394,8 +416,12 @@ def train_step(cfg, params, batch, fp32_product: bool = True, want_pos_grad: boo
     else:
         n = cfg.samples_per_ray
         R = N // n
-        dC = np.sign(fw["diff"]) / R
-        d_sdf, d_rgb = render_rays_backward(y[:, 0].reshape(R, n), fw["rgb"].reshape(R, n, 3), cfg.s, dC)
+        if cfg.loss_kind == 2:
+            dC = huber_derivative(fw["diff"], cfg.huber_delta) / R
+        else:
+            dC = np.sign(fw["diff"]) / R
+        d_sdf, d_rgb, d_s = render_rays_backward(y[:, 0].reshape(R, n), fw["rgb"].reshape(R, n, 3), cfg.s, dC, want_ds=True)
+        fw["d_s"] = d_s
         rgb = fw["rgb"]
         d_u = d_rgb.reshape(N, 3) * rgb * (1.0 - rgb)
         dW, d_cin, _ = mlp_backward(params["W"], fw["cacts"], fw["cmasks"], d_u)

@@ -27,7 +27,7 @@ class Neus2Config(C.Structure):
         ("n_sdf_mats", C.c_int32), ("sdf_dims", C.c_int32 * (MAX_MATS + 1)),
         ("n_color_mats", C.c_int32), ("color_dims", C.c_int32 * (MAX_MATS + 1)),
         ("samples_per_ray", C.c_int32), ("loss_kind", C.c_int32),
-        ("s", C.c_float), ("beta", C.c_float),
+        ("s", C.c_float), ("beta", C.c_float), ("huber_delta", C.c_float),
     ]
 
 
@@ -39,7 +39,7 @@ class Neus2StepBuffers(C.Structure):
         "pos", "dirs", "target", "tables", "H", "W",
         "enc", "jac", "y", "q", "normal", "rgb", "C", "weights", "loss",
         "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables", "workspace")] + [
-        ("workspace_bytes", C.c_int64)]
+        ("workspace_bytes", C.c_int64), ("s_dev", _P), ("d_s", _P)]
 
 
 class Neus2Error(RuntimeError):
@@ -59,8 +59,8 @@ _SIGNATURES = {
     "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
     "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
-    "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, C.c_int64, _P, _P, _P]),
-    "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
+    "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
+    "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P,
                                     C.c_int64, _P]),
@@ -112,6 +112,7 @@ def make_config(cfg) -> Neus2Config:
     for i, d in enumerate(cfg.color_dims):
         c.color_dims[i] = d
     c.samples_per_ray, c.loss_kind, c.s, c.beta = cfg.samples_per_ray, cfg.loss_kind, cfg.s, cfg.beta
+    c.huber_delta = getattr(cfg, "huber_delta", 0.0)
     return c
 
 
@@ -160,14 +161,14 @@ def color_bwd(c, pos, normal, dirs, y, W, d_rgb, d_sdf, n, dW, d_y, d_normal, d_
                                  _ptr(d_pos), _stream()))
 
 
-def render_rays(c, sdf, sdf_stride, rgb, rays, Cout, weights):
-    _check(lib().neus2_render_rays(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), rays, _ptr(Cout), _ptr(weights),
-                                   _stream()))
+def render_rays(c, sdf, sdf_stride, rgb, rays, Cout, weights, s_dev=None):
+    _check(lib().neus2_render_rays(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), _ptr(s_dev), rays, _ptr(Cout),
+                                   _ptr(weights), _stream()))
 
 
-def render_rays_bwd(c, sdf, sdf_stride, rgb, dC, rays, d_sdf, d_rgb):
-    _check(lib().neus2_render_rays_bwd(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), _ptr(dC), rays, _ptr(d_sdf),
-                                       _ptr(d_rgb), _stream()))
+def render_rays_bwd(c, sdf, sdf_stride, rgb, dC, rays, d_sdf, d_rgb, s_dev=None, d_s=None):
+    _check(lib().neus2_render_rays_bwd(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), _ptr(dC), _ptr(s_dev), rays,
+                                       _ptr(d_sdf), _ptr(d_rgb), _ptr(d_s), _stream()))
 
 
 def loss(c, Cimg, target, normal, y, rays, n, loss_out, dC, d_normal, d_y):
@@ -219,7 +220,7 @@ class Step:
     `neus2_step_buffers` struct that `train_step` hands to the library."""
 
     def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda",
-                 use_workspace: bool = True):
+                 use_workspace: bool = True, learn_s: bool = False):
         import torch
         self.cfg, self.c, self.n = cfg, make_config(cfg), n
         L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
@@ -234,8 +235,15 @@ class Step:
         for m in mats:
             offs.append(total)
             total += (m.numel() + 3) // 4 * 4
+        # a trained slope s of Phi_s sits behind the matrices: Adam updates it in the same launch
+        s_off = total
+        total += 4 if learn_s else 0
         self.small = torch.zeros(max(total, 4), **f32)
         self.d_small = torch.zeros_like(self.small)
+        self.s_dev = self.small[s_off:s_off + 1] if learn_s else None
+        self.d_s = self.d_small[s_off:s_off + 1] if learn_s else None
+        if learn_s:
+            self.s_dev.fill_(cfg.s)
         views = [self.small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
         gviews = [self.d_small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
         for v, m in zip(views, mats):
@@ -263,7 +271,8 @@ class Step:
         self._dH, self._dW = _ptr_array(self.dH), _ptr_array(self.dW)
         b = Neus2StepBuffers()
         for name in ("pos", "dirs", "target", "tables", "enc", "jac", "y", "q", "normal", "rgb", "C", "weights",
-                     "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables", "workspace"):
+                     "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables", "workspace",
+                     "s_dev", "d_s"):
             setattr(b, name, _ptr(getattr(self, name)))
         b.H, b.W = C.cast(self._H, _P), C.cast(self._W, _P)
         b.dH, b.dW = C.cast(self._dH, _P), C.cast(self._dW, _P)

@@ -94,7 +94,8 @@ int check_config(const neus2_config* c) {
     }
     if (c->samples_per_ray < 1 || c->samples_per_ray > 64)
         return fail(NEUS2_ERR_CONFIG, "samples_per_ray = %d, must be 1..64", c->samples_per_ray);
-    if (c->loss_kind != 0 && c->loss_kind != 1) return fail(NEUS2_ERR_CONFIG, "loss_kind = %d, must be 0 or 1", c->loss_kind);
+    if (c->loss_kind < 0 || c->loss_kind > 2) return fail(NEUS2_ERR_CONFIG, "loss_kind = %d, must be 0, 1 or 2", c->loss_kind);
+    if (c->loss_kind == 2 && !(c->huber_delta > 0.f)) return fail(NEUS2_ERR_CONFIG, "huber_delta must be positive for loss_kind 2");
     if (!(c->s > 0.f)) return fail(NEUS2_ERR_CONFIG, "s must be positive");
     if (!(c->beta >= 0.f)) return fail(NEUS2_ERR_CONFIG, "beta must be non-negative");
     return NEUS2_OK;
@@ -234,8 +235,8 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     if (!b) return fail(NEUS2_ERR_NULL, "buf is NULL");
     if (n < 0 || n % cfg->samples_per_ray != 0)
         return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
-    if (cfg->loss_kind == 1 && cfg->n_color_mats != 3)
-        return fail(NEUS2_ERR_CONFIG, "loss_kind 1 needs the colour network");
+    if (cfg->loss_kind != 0 && cfg->n_color_mats != 3)
+        return fail(NEUS2_ERR_CONFIG, "loss_kind %d needs the colour network", cfg->loss_kind);
     NEUS2_TRY(check_ptr(b->loss, "loss"));
     hipStream_t st = (hipStream_t)stream;
     const int64_t rays = n / cfg->samples_per_ray;
@@ -243,11 +244,12 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     if (n == 0) return NEUS2_OK;   // an empty batch has no buffers to look at
     NEUS2_TRY(neus2_hash_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, stream));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
-    if (cfg->loss_kind == 1) {
+    if (cfg->loss_kind != 0) {
         NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, n, b->rgb, stream));
-        NEUS2_TRY(neus2_render_rays(cfg, b->y, 16, b->rgb, rays, b->C, b->weights, stream));
+        NEUS2_TRY(neus2_render_rays(cfg, b->y, 16, b->rgb, b->s_dev, rays, b->C, b->weights, stream));
         NEUS2_TRY(neus2_loss(cfg, b->C, b->target, b->normal, b->y, rays, n, b->loss, b->dC, b->d_normal, nullptr, stream));
-        NEUS2_TRY(neus2_render_rays_bwd(cfg, b->y, 16, b->rgb, b->dC, rays, b->d_sdf, b->d_rgb, stream));
+        NEUS2_TRY(neus2_render_rays_bwd(cfg, b->y, 16, b->rgb, b->dC, b->s_dev, rays, b->d_sdf, b->d_rgb, b->d_s,
+                                        stream));
         NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
                                   b->d_normal, b->d_pos, stream));
     } else {

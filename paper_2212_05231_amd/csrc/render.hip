@@ -72,11 +72,12 @@ __device__ __forceinline__ RayLane ray_lane(float d, int lane, int spr, float s)
 
 __global__ __launch_bounds__(kRayThreads) void render_fwd_kernel(const float* __restrict__ sdf, int64_t stride,
                                                                 const float* __restrict__ rgb, int64_t rays, int spr,
-                                                                float s, float* __restrict__ C,
-                                                                float* __restrict__ weights) {
+                                                                float s, const float* __restrict__ s_dev,
+                                                                float* __restrict__ C, float* __restrict__ weights) {
     const int lane = threadIdx.x & 63;
     const int64_t ray = (int64_t)blockIdx.x * (kRayThreads / 64) + (threadIdx.x >> 6);
     if (ray >= rays) return;
+    if (s_dev) s = *s_dev;
     const bool live = lane < spr;
     const int64_t i = ray * spr + (live ? lane : 0);
     const float d = live ? sdf[i * stride] : 0.f;
@@ -92,14 +93,18 @@ __global__ __launch_bounds__(kRayThreads) void render_fwd_kernel(const float* __
 }
 
 // dC/dalpha_i = T_i (dC.c_i) - (sum_{j>i} T_j alpha_j (dC.c_j)) / (1 - alpha_i)
+// The slope s (learnable, supplement Sec. E.3) enters alpha only through the products s d_i, so
+// dL/ds = (1/s) sum_i d_i dL/dd_i: one wave sum on top of the SDF gradient.
 __global__ __launch_bounds__(kRayThreads) void render_bwd_kernel(const float* __restrict__ sdf, int64_t stride,
                                                                 const float* __restrict__ rgb,
                                                                 const float* __restrict__ dC, int64_t rays, int spr,
-                                                                float s, float* __restrict__ d_sdf,
-                                                                float* __restrict__ d_rgb) {
+                                                                float s, const float* __restrict__ s_dev,
+                                                                float* __restrict__ d_sdf,
+                                                                float* __restrict__ d_rgb, float* __restrict__ d_s) {
     const int lane = threadIdx.x & 63;
     const int64_t ray = (int64_t)blockIdx.x * (kRayThreads / 64) + (threadIdx.x >> 6);
     if (ray >= rays) return;
+    if (s_dev) s = *s_dev;
     const bool live = lane < spr;
     const int64_t i = ray * spr + (live ? lane : 0);
     const float d = live ? sdf[i * stride] : 0.f;
@@ -118,6 +123,10 @@ __global__ __launch_bounds__(kRayThreads) void render_bwd_kernel(const float* __
     float ds = d_alpha * r.dalpha_di;
     if (lane > 0) ds += from_prev;
     if (live) d_sdf[i] = ds;
+    if (d_s) {
+        const float t = wave_sum(live ? ds * d : 0.f);
+        if (lane == 0) atomicAdd(d_s, t / s);
+    }
 }
 
 // ---- loss ---------------------------------------------------------------------------------
@@ -138,7 +147,8 @@ __device__ __forceinline__ void block_add(float v, float* dst, float* red) {
 // all adding to the same two floats would serialise on them).
 __global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
                                                    const float* __restrict__ normal, const float* __restrict__ y,
-                                                   int64_t rays, int64_t n, float beta, float* __restrict__ loss,
+                                                   int64_t rays, int64_t n, float beta, float huber_delta,
+                                                   float* __restrict__ loss,
                                                    float* __restrict__ dC, float* __restrict__ d_normal,
                                                    float* __restrict__ d_y) {
     __shared__ float red[4];
@@ -159,14 +169,20 @@ __global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __rest
             o[1] = o[2] = o[3] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
-    if (kind == 1) {
+    if (kind != 0) {
         const float inv_r = 1.f / (float)rays;
         for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < rays; i += (int64_t)gridDim.x * 256) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 const float diff = C[3 * i + c] - target[3 * i + c];
-                first += fabsf(diff) * inv_r;
-                dC[3 * i + c] = diff > 0.f ? inv_r : (diff < 0.f ? -inv_r : 0.f);
+                const float a = fabsf(diff);
+                if (kind == 1) {
+                    first += a * inv_r;
+                    dC[3 * i + c] = diff > 0.f ? inv_r : (diff < 0.f ? -inv_r : 0.f);
+                } else {   // Huber: quadratic up to delta, linear beyond
+                    first += (a <= huber_delta ? 0.5f * diff * diff : huber_delta * (a - 0.5f * huber_delta)) * inv_r;
+                    dC[3 * i + c] = fminf(fmaxf(diff, -huber_delta), huber_delta) * inv_r;
+                }
             }
         }
     }
@@ -244,8 +260,8 @@ using namespace neus2;
 
 extern "C" {
 
-int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_stride, const float* rgb, int64_t rays,
-                      float* C, float* weights, void* stream) {
+int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_stride, const float* rgb,
+                      const float* s_dev, int64_t rays, float* C, float* weights, void* stream) {
     NEUS2_TRY(check_config(cfg));
     if (rays < 0 || rays > ((int64_t)1 << 28) / cfg->samples_per_ray) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
     if (sdf_stride < 1) return fail(NEUS2_ERR_SHAPE, "sdf_stride = %lld, must be >= 1", (long long)sdf_stride);
@@ -253,15 +269,17 @@ int neus2_render_rays(const neus2_config* cfg, const float* sdf, int64_t sdf_str
     NEUS2_TRY(check_ptr(rgb, "rgb"));
     NEUS2_TRY(check_ptr(C, "C"));
     NEUS2_TRY(check_ptr(weights, "weights"));
+    NEUS2_TRY(check_ptr(s_dev, "s_dev", false));
     if (rays == 0) return NEUS2_OK;
     const int per = kRayThreads / 64;
     hipLaunchKernelGGL(render_fwd_kernel, dim3((unsigned)((rays + per - 1) / per)), dim3(kRayThreads), 0,
-                       (hipStream_t)stream, sdf, sdf_stride, rgb, rays, cfg->samples_per_ray, cfg->s, C, weights);
+                       (hipStream_t)stream, sdf, sdf_stride, rgb, rays, cfg->samples_per_ray, cfg->s, s_dev, C, weights);
     return check_launch("render rays");
 }
 
 int neus2_render_rays_bwd(const neus2_config* cfg, const float* sdf, int64_t sdf_stride, const float* rgb,
-                          const float* dC, int64_t rays, float* d_sdf, float* d_rgb, void* stream) {
+                          const float* dC, const float* s_dev, int64_t rays, float* d_sdf, float* d_rgb, float* d_s,
+                          void* stream) {
     NEUS2_TRY(check_config(cfg));
     if (rays < 0 || rays > ((int64_t)1 << 28) / cfg->samples_per_ray) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
     if (sdf_stride < 1) return fail(NEUS2_ERR_SHAPE, "sdf_stride = %lld, must be >= 1", (long long)sdf_stride);
@@ -270,10 +288,12 @@ int neus2_render_rays_bwd(const neus2_config* cfg, const float* sdf, int64_t sdf
     NEUS2_TRY(check_ptr(dC, "dC"));
     NEUS2_TRY(check_ptr(d_sdf, "d_sdf"));
     NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
+    NEUS2_TRY(check_ptr(s_dev, "s_dev", false));
+    NEUS2_TRY(check_ptr(d_s, "d_s", false));
     if (rays == 0) return NEUS2_OK;
     const int per = kRayThreads / 64;
     hipLaunchKernelGGL(render_bwd_kernel, dim3((unsigned)((rays + per - 1) / per)), dim3(kRayThreads), 0,
-                       (hipStream_t)stream, sdf, sdf_stride, rgb, dC, rays, cfg->samples_per_ray, cfg->s, d_sdf, d_rgb);
+                       (hipStream_t)stream, sdf, sdf_stride, rgb, dC, rays, cfg->samples_per_ray, cfg->s, s_dev, d_sdf, d_rgb, d_s);
     return check_launch("render rays backward");
 }
 
@@ -284,7 +304,7 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
     NEUS2_TRY(check_ptr(normal, "normal"));
     NEUS2_TRY(check_ptr(loss, "loss"));
     NEUS2_TRY(check_ptr(d_normal, "d_normal"));
-    if (cfg->loss_kind == 1) {
+    if (cfg->loss_kind != 0) {
         if (rays < 0 || rays * cfg->samples_per_ray != n)
             return fail(NEUS2_ERR_SHAPE, "rays * samples_per_ray = %lld differs from n = %lld",
                         (long long)(rays * cfg->samples_per_ray), (long long)n);
@@ -299,7 +319,8 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
     const int64_t want = (n + 255) / 256;
     const int64_t cap = 2 * (int64_t)compute_units();
     hipLaunchKernelGGL(loss_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, (hipStream_t)stream, cfg->loss_kind,
-                       C, target, normal, y, cfg->loss_kind == 1 ? rays : 0, n, cfg->beta, loss, dC, d_normal, d_y);
+                       C, target, normal, y, cfg->loss_kind != 0 ? rays : 0, n, cfg->beta, cfg->huber_delta, loss, dC, d_normal,
+                       d_y);
     return check_launch("loss");
 }
 

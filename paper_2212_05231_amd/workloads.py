@@ -36,10 +36,11 @@ class Config:
     sdf_dims: List[int]              # e.g. [32, 64, 64, 16]
     color_dims: List[int]            # e.g. [38, 64, 64, 3] or [] when there is no colour net
     samples_per_ray: int
-    loss_kind: int                   # 0: mean(d^2) + beta*eikonal ; 1: L1 colour + beta*eikonal
+    loss_kind: int                   # 0: mean(d^2) + beta*eikonal ; 1: L1 colour + beta*eikonal ; 2: Huber colour
     s: float
     beta: float
     name: str = ""
+    huber_delta: float = 0.1
 
     @property
     def table_size(self) -> int:

@@ -30,8 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     # 5 ints + 2*32 ints + (1+5) + (1+5) ints + 2 ints + 2 floats
-    assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 2)
-    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 27
+    assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 3)
+    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 29
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
@@ -49,7 +49,7 @@ def test_bad_descriptors_are_rejected_with_a_message():
     cases = [
         (broken(n_levels=0), -3), (broken(n_levels=33), -3), (broken(n_features=4), -5),
         (broken(log2_table_size=30), -3), (broken(active_levels=17), -3), (broken(table_dtype=2), -3),
-        (broken(n_sdf_mats=5), -5), (broken(samples_per_ray=65), -3), (broken(loss_kind=3), -3),
+        (broken(n_sdf_mats=5), -5), (broken(samples_per_ray=65), -3), (broken(loss_kind=3), -3), (broken(loss_kind=2, huber_delta=0.0), -3),
         (broken(s=0.0), -3), (broken(beta=-1.0), -3),
     ]
     c = broken()
@@ -76,7 +76,7 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, ok, None, 64, ok, None) == -1
     arr = (C.c_void_p * 3)(ok, ok, ok)
     assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, ok, arr, 63, ok, None) == -2     # not a multiple of 64
-    assert L.neus2_render_rays(C.byref(c), ok, 0, ok, 4, ok, ok, None) == -2
+    assert L.neus2_render_rays(C.byref(c), ok, 0, ok, None, 4, ok, ok, None) == -2
     assert L.neus2_loss(C.byref(c), ok, ok, ok, ok, 3, 100, ok, ok, ok, ok, None) == -2
     assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 1, 0.01, 0.9, 0.99, 1e-15, 1, 1, None) == -1   # fp16 needs master
     assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 0, 0.01, 0.9, 0.99, 1e-15, 0, 1, None) == -3   # t starts at 1

@@ -87,7 +87,7 @@ def check_step(cfg, step, ref, n, want_pos=False):
     errs["normal"] = rel(step.normal.cpu().numpy(), ref["normal"])
     loss = step.loss.cpu().numpy()
     errs["loss"] = abs(float(loss[0] + loss[1]) - ref["loss"]) / abs(ref["loss"])
-    if cfg.loss_kind == 1:
+    if cfg.loss_kind != 0:
         errs["rgb"] = rel(step.rgb.cpu().numpy(), ref["rgb"])
         errs["C"] = rel(step.C.cpu().numpy(), ref["C"])
         errs["weights"] = rel(step.weights.cpu().numpy().reshape(ref["weights"].shape), ref["weights"])
@@ -214,6 +214,20 @@ def test_render_forward_backward_alone():
             assert torch.all(ds == 0)
         if spr == 64:
             assert np.all(wg.cpu().numpy().reshape(rays, spr)[1] == 0)
+        # the slope read from device memory (a trained parameter) and its gradient, added into d_s
+        s_dev = cuda(np.array([33.0], dtype=np.float32))
+        d_s = cuda(np.array([0.5], dtype=np.float32))
+        nb.render_rays(c, yg, 16, cuda(rgb.reshape(n, 3)), rays, Cg, wg, s_dev=s_dev)
+        nb.render_rays_bwd(c, yg, 16, cuda(rgb.reshape(n, 3)), cuda(dC), rays, ds, dr, s_dev=s_dev, d_s=d_s)
+        torch.cuda.synchronize()
+        Cr, wr, _, _ = o.render_rays(sdf.astype(np.float64), rgb.astype(np.float64), 33.0)
+        d_sdf, d_rgb, ref_ds = o.render_rays_backward(sdf.astype(np.float64), rgb.astype(np.float64), 33.0,
+                                                      dC.astype(np.float64), want_ds=True)
+        assert rel(Cg.cpu().numpy(), Cr) <= FWD_TOL
+        assert rel(ds.cpu().numpy().reshape(rays, spr), d_sdf) <= GRAD_TOL
+        # dL/ds is a sum of terms of both signs: measure the error against their magnitude
+        scale = float(np.sum(np.abs(d_sdf * sdf))) / 33.0
+        assert abs(float(d_s.cpu()[0]) - 0.5 - ref_ds) <= GRAD_TOL * max(scale, 1e-30) + 1e-7
 
 
 def test_color_forward_backward_alone():
@@ -332,6 +346,39 @@ def test_step_config2_with_order_one_tables_and_position_gradient():
     cfg, step, ref, n = run_step(2, 64, want_pos=True, scale_tables=2000.0)
     assert np.any(ref["alpha"] > 0.05)
     print(check_step(cfg, step, ref, n, want_pos=True))
+
+
+def test_step_huber_loss_and_trained_slope():
+    """Eq. 4's Huber colour term, and s of Phi_s as a parameter on the device that Adam updates
+    together with the matrices (supplement Sec. E.3)."""
+    w = wl.make_workload(2, n_rays=64)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    cfg.loss_kind, cfg.huber_delta = 2, 0.25
+    params["tables"] = (params["tables"].astype(np.float64) * 2000.0).astype(params["tables"].dtype)
+    n = batch["pos"].shape[0]
+    step = nb.Step(cfg, params, n, learn_s=True)
+    cfg_s = cfg.s
+    step.s_dev.fill_(cfg_s * 1.5)          # the device value wins over the descriptor's
+    cfg.s = cfg_s * 1.5                    # (the oracle reads cfg.s)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.train_step()
+    torch.cuda.synchronize()
+    ref = o.train_step(cfg, params, batch)
+    r = np.abs(ref["diff"])
+    assert np.any(r <= cfg.huber_delta) and np.any(r > cfg.huber_delta)
+    print(check_step(cfg, step, ref, n))
+    d_sdf = step.d_sdf.cpu().numpy().astype(np.float64)
+    scale = float(np.sum(np.abs(d_sdf * ref["y"][:, 0]))) / cfg.s
+    got = float(step.d_s.cpu()[0])
+    assert abs(got - ref["d_s"]) <= GRAD_TOL * scale, (got, ref["d_s"], scale)
+    assert abs(ref["d_s"]) > 1e-3 * scale          # not a vacuous comparison
+    step.init_optimizer()
+    step.adam()
+    torch.cuda.synchronize()
+    s_new, _, _ = o.adam_step(np.array([cfg.s]), np.array([got]), np.zeros(1), np.zeros(1), 1, 1e-2, 0.9, 0.99, 1e-15)
+    assert abs(float(step.s_dev.cpu()[0]) - s_new[0]) <= 1e-6 * cfg.s
+    assert float(step.d_s.cpu()[0]) == 0.0
 
 
 def test_step_config5_frames_with_transform_gradient():

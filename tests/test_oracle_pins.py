@@ -21,7 +21,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 def tiny_cfg(L=3, log2T=8, active=None, loss_kind=1, spr=8, sdf=(6, 8, 8, 16), res=(4, 7, 13)):
     dense = wl.dense_flags(list(res), 1 << log2T)
-    color = [38, 8, 8, 3] if loss_kind == 1 else []
+    color = [38, 8, 8, 3] if loss_kind >= 1 else []
     return wl.Config(L, 2, log2T, L if active is None else active, "f32", list(res), dense,
                      list(sdf), color, spr, loss_kind, 20.0, 0.1, "tiny")
 
@@ -32,7 +32,7 @@ def tiny_problem(seed=0, rays=5, **kw):
     tables = rng.uniform(-0.5, 0.5, size=(cfg.n_levels, cfg.table_size, 2))
     H = [rng.uniform(-1, 1, size=(cfg.sdf_dims[i + 1], cfg.sdf_dims[i])) * 0.6 for i in range(len(cfg.sdf_dims) - 1)]
     W = [rng.uniform(-1, 1, size=(cfg.color_dims[i + 1], cfg.color_dims[i])) * 0.5 for i in range(len(cfg.color_dims) - 1)]
-    if cfg.loss_kind == 1:
+    if cfg.loss_kind >= 1:
         batch = wl.make_rays(rays, cfg.samples_per_ray, seed + 7)
         batch = {k: v.astype(np.float64) for k, v in batch.items()}
     else:
@@ -375,6 +375,29 @@ def test_render_backward_by_finite_differences():
                 assert abs((f(sdf, rgb + e3) - f(sdf, rgb - e3)) / (2 * h) - d_rgb[r, i, ch]) < 1e-8
 
 
+def test_slope_gradient_by_finite_differences():
+    """s of Phi_s is a learnable parameter in the paper (supplement Sec. E.3)."""
+    rng = np.random.default_rng(8)
+    R, n, s = 4, 9, 20.0
+    sdf = rng.normal(size=(R, n)) * 0.05
+    rgb = rng.uniform(size=(R, n, 3))
+    dC = rng.normal(size=(R, 3))
+    _, _, d_s = o.render_rays_backward(sdf, rgb, s, dC, want_ds=True)
+    f = lambda ss: float(np.sum(o.render_rays(sdf, rgb, ss)[0] * dC))
+    h = 1e-5
+    assert abs((f(s + h) - f(s - h)) / (2 * h) - d_s) < 1e-8 * max(1.0, abs(d_s))
+    assert abs(d_s) > 1e-6
+
+
+def test_huber_closed_forms():
+    """Eq. 4 names the Huber loss for the colour term."""
+    r = np.array([-0.5, -0.1, -0.03, 0.0, 0.02, 0.1, 0.7])
+    d = 0.1
+    np.testing.assert_allclose(o.huber(r, d), [0.1 * 0.45, 0.005, 0.00045, 0.0, 0.0002, 0.005, 0.1 * 0.65], atol=1e-15)
+    h = 1e-7
+    np.testing.assert_allclose(o.huber_derivative(r, d), (o.huber(r + h, d) - o.huber(r - h, d)) / (2 * h), atol=1e-6)
+
+
 # ------------------------------------------------------------------ spherical harmonics
 
 def test_sh16_addition_theorem_and_orthonormality():
@@ -404,9 +427,11 @@ def _fd_param(cfg, params, batch, getter, index, h=1e-6):
     fp = o.forward(cfg, pp, batch, fp32_product=False)
     fm = o.forward(cfg, pm, batch, fp32_product=False)
     same = all(np.array_equal(a, b) for a, b in zip(fp["masks"], fm["masks"]))
-    if cfg.loss_kind == 1:
+    if cfg.loss_kind >= 1:
         same = same and all(np.array_equal(a, b) for a, b in zip(fp["cmasks"], fm["cmasks"]))
         same = same and np.array_equal(np.sign(fp["diff"]), np.sign(fm["diff"]))
+        if cfg.loss_kind == 2:
+            same = same and np.array_equal(np.abs(fp["diff"]) <= cfg.huber_delta, np.abs(fm["diff"]) <= cfg.huber_delta)
         same = same and np.array_equal(fp["alpha"] > 0, fm["alpha"] > 0)
     return (fp["loss"] - fm["loss"]) / (2 * h), same
 
@@ -442,7 +467,8 @@ def _check_all_grads(cfg, params, batch, out, rng, n_table=60, n_weight=40, tol=
     return checked
 
 
-@pytest.mark.parametrize("loss_kind,sdf", [(0, (6, 8, 16)), (0, (6, 8, 8, 16)), (1, (6, 8, 16)), (1, (6, 8, 8, 16))])
+@pytest.mark.parametrize("loss_kind,sdf", [(0, (6, 8, 16)), (0, (6, 8, 8, 16)), (1, (6, 8, 16)), (1, (6, 8, 8, 16)),
+                                           (2, (6, 8, 8, 16))])
 def test_whole_step_gradients_by_finite_differences(loss_kind, sdf):
     """Eq. 4 loss; Eqs. 5-8 gradients.  Central differences of the scalar loss in float64 wrt
     weights of both networks and touched table entries."""
@@ -450,8 +476,18 @@ def test_whole_step_gradients_by_finite_differences(loss_kind, sdf):
     out = o.train_step(cfg, params, batch, fp32_product=False)
     rng = np.random.default_rng(9)
     assert _check_all_grads(cfg, params, batch, out, rng) > 100
-    if loss_kind == 1:
+    if loss_kind >= 1:
         assert np.any(out["alpha"] > 0.01)           # the render path is really exercised
+        # dL/ds against a central difference of the loss in s
+        import copy as _copy
+        cp, cm = _copy.deepcopy(cfg), _copy.deepcopy(cfg)
+        cp.s += 1e-5
+        cm.s -= 1e-5
+        fd = (o.loss_value(cp, params, batch, False) - o.loss_value(cm, params, batch, False)) / 2e-5
+        assert abs(fd - out["d_s"]) < 1e-7 * max(1.0, abs(fd))
+    if loss_kind == 2:
+        d = np.abs(out["diff"])
+        assert np.any(d <= cfg.huber_delta) and np.any(d > cfg.huber_delta)   # both branches of Huber
 
 
 def test_second_order_terms_alone_and_negative_controls(monkeypatch):

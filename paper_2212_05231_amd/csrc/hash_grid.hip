@@ -11,6 +11,8 @@
 // time and that level's table (2 MiB in fp16 at T = 2^19) stays in its private 4 MiB L2.
 #include <cstring>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace neus2 {
@@ -359,7 +361,8 @@ struct OwnerPlan {
     int n_entries;
     int n_tasks;
     int n_listed;                           // entries [0, n_listed) are levels with record lists
-    int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries
+    int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries, in the order `order`
+    short order[NEUS2_MAX_LEVELS];          // entries by falling time of one task
     int capacity[NEUS2_MAX_LEVELS];         // records per list of a listed entry
     int64_t list_base[NEUS2_MAX_LEVELS + 1];// first record of the entry's lists; [n_listed] = total
     short level[NEUS2_MAX_LEVELS];
@@ -479,14 +482,24 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                                                                      float* __restrict__ d_tables) {
     __shared__ OwnerSmem sm;
     double* acc = sm.acc;
+    constexpr int kPerThread = 2 * kOwnerSlots / kOwnerThreads;      // accumulators per thread
+    // The next task number is requested while the current task runs: its round trip to the
+    // counter is hidden.
+    int next_task = 0;
+    if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
     for (;;) {
-        if (threadIdx.x == 0) sm.task = atomicAdd(counter, 1);
+        if (threadIdx.x == 0) sm.task = next_task;
         __syncthreads();
         const int task = sm.task;
         if (task >= plan.n_tasks) break;             // uniform: every thread reads the same value
-        int e = 0;
-        while (e + 1 < plan.n_entries && task >= plan.first_task[e + 1]) ++e;
-        const int local = task - plan.first_task[e];
+        if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
+        // entry of the task: all prefix sums are compared at once (independent scalar loads with
+        // constant offsets, not a dependent chain of them; the index must stay uniform)
+        int at_order = 0;
+#pragma unroll
+        for (int k = 1; k < NEUS2_MAX_LEVELS; ++k) at_order += (k < plan.n_entries && task >= plan.first_task[k]) ? 1 : 0;
+        const int e = plan.order[at_order];
+        const int local = task - plan.first_task[at_order];
         const int level = plan.level[e];
         const int n_ranges = plan.ranges[e], n_chunks = plan.chunks[e];
         const uint32_t range = (uint32_t)(local % n_ranges);
@@ -494,8 +507,10 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         const int64_t begin = n * chunk / n_chunks, end = n * (chunk + 1) / n_chunks;
         const uint32_t first_slot = range << kOwnerSlotBits;
         const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
+        float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
 
-        for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) acc[k] = 0.0;
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) acc[threadIdx.x + u * kOwnerThreads] = 0.0;
         __syncthreads();
 
         if (e < plan.n_listed) {
@@ -572,12 +587,27 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         }
         __syncthreads();
 
-        float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
-        for (uint32_t k = threadIdx.x; k < 2 * slots_here; k += kOwnerThreads) {
-            const float v = (float)acc[k];
-            if (v != 0.f) {
-                if (n_chunks == 1) dst[k] += v;
-                else atomicAdd(dst + k, v);
+        if (n_chunks == 1) {
+            // the task owns its range alone: plain loads and stores, all loads issued before the first use
+            float old[kPerThread];
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                old[u] = k < 2 * slots_here ? dst[k] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                const float v = (float)acc[k];
+                if (k < 2 * slots_here && v != 0.f) dst[k] = old[u] + v;
+            }
+        } else {
+            // several chunks of the points share the range: coalesced atomics
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                const float v = (float)acc[k];
+                if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
             }
         }
         __syncthreads();                              // also protects sm.task before the next fetch
@@ -598,6 +628,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     if (T > (int64_t)kMaxRanges * kOwnerSlots) ok = false;          // at most kMaxRanges lists per level
     int e = 0, tasks = 0;
     int64_t records = 0;
+    double cost[NEUS2_MAX_LEVELS];
     for (int pass = 0; pass < 2; ++pass) {
         for (int l = 0; l < cfg->active_levels; ++l) {
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
@@ -607,6 +638,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
             if (listed != (pass == 0)) continue;
             if (listed && !cfg->dense[l] && cfg->res[l] >= kOwnerSlots) ok = false;   // x must not reach the range bits
             int chunks = 1;
+            double task_ns = 4000.0 + 1.25 * (4.0 * (double)n / ranges);   // a list: 1.25 ns per record
             if (listed) {
                 // a list holds 1.5 times its expected share of the 4 n row records of the level;
                 // 3 times on a dense level, where the share of a slab of the grid follows the batch
@@ -615,21 +647,36 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
                 p.capacity[e] = (int)cap;
                 p.list_base[e] = records;
                 records += cap * ranges;
-            } else {                                   // small tasks: at most an eighth of the points each
-                chunks = 32 / ranges;
+            } else {
+                // Every task tests n / chunks points (0.9 ns each; the corner code runs for a whole
+                // wavefront as soon as one lane is in the range) and adds those in its range
+                // (about 1.5 ranges per point on a dense level, 7 ns each).  Times measured on
+                // this kernel; tasks of about 30 us.
+                const double hit = ranges > 1 ? 1.5 / ranges : 1.0;
+                const double level_ns = (double)n * ranges * (0.9 + 7.0 * (hit < 1.0 ? hit : 1.0));
+                chunks = (int)(level_ns / ranges / 30000.0) + 1;
                 if (chunks < 8) chunks = 8;
+                if (chunks > 128) chunks = 128;
+                task_ns = 4000.0 + level_ns / ranges / chunks;
             }
             p.level[e] = (short)l;
             p.ranges[e] = (short)ranges;
             p.chunks[e] = (short)chunks;
-            p.first_task[e] = tasks;
-            tasks += ranges * chunks;
+            cost[e] = task_ns;
             ++e;
         }
         if (pass == 0) { p.n_listed = e; p.list_base[e] = records; }
     }
-    p.first_task[e] = tasks;
     p.n_entries = e;
+    // Workgroups take tasks in this order: the longest first, so that the kernel does not end
+    // on a few workgroups that drew a long task late.
+    for (int k = 0; k < e; ++k) p.order[k] = (short)k;
+    std::stable_sort(p.order, p.order + e, [&](short a, short b) { return cost[a] > cost[b]; });
+    for (int k = 0; k < e; ++k) {
+        p.first_task[k] = tasks;
+        tasks += p.ranges[p.order[k]] * p.chunks[p.order[k]];
+    }
+    p.first_task[e] = tasks;
     p.n_tasks = tasks;
     return p;
 }

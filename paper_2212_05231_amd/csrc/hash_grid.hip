@@ -376,19 +376,36 @@ struct Records {
     float4* vals;           // per entry [ranges][capacity]: {x f0, x f1, x+1 f0, x+1 f1}
 };
 
-__global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
-                                                                const float* __restrict__ pos,
-                                                                const float* __restrict__ q,
-                                                                const float* __restrict__ d_enc,
-                                                                const float* __restrict__ d_normal, int64_t n,
-                                                                int point_blocks, float* __restrict__ d_tables) {
-    __shared__ int cnt[kMaxRanges];
-    __shared__ int base[kMaxRanges];
+// Records of one workgroup are first put in LDS in list order (range by range), then written
+// out by consecutive threads: runs of records of one list leave as whole cache lines instead
+// of one 16-byte piece per lane.
+constexpr int kBinThreads = 512;
+constexpr int kBinRecords = 4 * kBinThreads;
+constexpr uint32_t kNoRecord = 0xFFFFFFFFu;
+
+struct BinSmem {
+    float4 vals[kBinRecords];
+    uint32_t slots[kBinRecords];
+    uint32_t dest[kBinRecords];          // record index within the entry's lists, kNoRecord if it went elsewhere
+    int cnt[kMaxRanges];                 // records of this workgroup per range
+    int base[kMaxRanges];                // first position of this workgroup in the list of the range
+    int first[kMaxRanges];               // first staged position of the range
+    int total;
+};
+
+__global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
+                                                              const float* __restrict__ pos,
+                                                              const float* __restrict__ q,
+                                                              const float* __restrict__ d_enc,
+                                                              const float* __restrict__ d_normal, int64_t n,
+                                                              int point_blocks, float* __restrict__ d_tables) {
+    __shared__ BinSmem sm;
     const int e = blockIdx.x / point_blocks;
-    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kOwnerThreads + threadIdx.x;
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
     const int level = plan.level[e];
     const int n_ranges = plan.ranges[e];
-    for (int k = threadIdx.x; k < n_ranges; k += kOwnerThreads) cnt[k] = 0;
+    const int capacity = plan.capacity[e];
+    for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) sm.cnt[k] = 0;
     __syncthreads();
 
     const bool valid = i < n;
@@ -442,23 +459,44 @@ __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, Own
                 s1 = s0;
             }
             packed[row] = (s0 & (kOwnerSlots - 1)) | ((s1 & (kOwnerSlots - 1)) << 16);
-            rank[row] = atomicAdd(&cnt[range[row]], 1);
+            rank[row] = atomicAdd(&sm.cnt[range[row]], 1);
         }
     }
     __syncthreads();
-    for (int k = threadIdx.x; k < n_ranges; k += kOwnerThreads)
-        base[k] = cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], cnt[k]) : 0;
+    // one reservation per range in the global list, and the staged order: ranges one after another
+    for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
+        sm.base[k] = sm.cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], sm.cnt[k]) : 0;
+    if (threadIdx.x >= kBinThreads - 64) {               // the last wavefront: exclusive prefix sums of cnt
+        const int lane = threadIdx.x & 63;
+        constexpr int kPer = kMaxRanges / 64;
+        int c[kPer], sum = 0;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) { c[j] = sm.cnt[kPer * lane + j]; sum += c[j]; }
+        int incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d);
+            if (lane >= d) incl += o;
+        }
+        int at = incl - sum;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) { sm.first[kPer * lane + j] = at; at += c[j]; }
+        if (lane == 63) sm.total = incl;
+    }
     __syncthreads();
     if (valid) {
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
-            const int p = base[range[row]] + rank[row];
-            if (p < plan.capacity[e]) {
-                const size_t at = (size_t)plan.list_base[e] + (size_t)range[row] * plan.capacity[e] + p;
-                rec.slots[at] = packed[row];
-                rec.vals[at] = val[row];
+            const int r = (int)range[row];
+            const int in_list = sm.base[r] + rank[row];
+            const int at = sm.first[r] + rank[row];
+            sm.vals[at] = val[row];
+            sm.slots[at] = packed[row];
+            if (in_list < capacity) {
+                sm.dest[at] = (uint32_t)r * (uint32_t)capacity + (uint32_t)in_list;
             } else {                                                 // list full: straight to the global gradient
-                float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)range[row] << kOwnerSlotBits)) * 2;
+                sm.dest[at] = kNoRecord;
+                float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)r << kOwnerSlotBits)) * 2;
                 atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 0, val[row].x);
                 atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 1, val[row].y);
                 atomicAdd(gt + 2 * (packed[row] >> 16) + 0, val[row].z);
@@ -466,10 +504,25 @@ __global__ __launch_bounds__(kOwnerThreads) void bin_rows_kernel(GridDesc g, Own
             }
         }
     }
+    __syncthreads();
+    const int total = sm.total;
+    uint32_t* out_slots = rec.slots + plan.list_base[e];
+    float4* out_vals = rec.vals + plan.list_base[e];
+    for (int at = threadIdx.x; at < total; at += kBinThreads) {
+        const uint32_t d = sm.dest[at];
+        if (d != kNoRecord) {
+            out_slots[d] = sm.slots[at];
+            out_vals[d] = sm.vals[at];
+        }
+    }
 }
+
+constexpr int kQueue = 5 * kOwnerThreads;     // fewer than kOwnerThreads queued before a round adds at most 4 kOwnerThreads
 
 struct OwnerSmem {
     double acc[2 * kOwnerSlots];
+    uint32_t queue[kQueue];    // in-place path: points of the chunk that touch the range
+    int queued;
     int task;
 };
 
@@ -483,16 +536,19 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
     __shared__ OwnerSmem sm;
     double* acc = sm.acc;
     constexpr int kPerThread = 2 * kOwnerSlots / kOwnerThreads;      // accumulators per thread
-    // The next task number is requested while the current task runs: its round trip to the
-    // counter is hidden.
+    // The two features of a slot lie side by side.  Even lanes add feature 0 first, odd lanes
+    // feature 1: one instruction then spreads over all LDS banks instead of every other pair.
+    const int odd = threadIdx.x & 1;
+    // The next task number is requested while the current task runs (after the barrier that
+    // follows the clearing of the accumulators: a barrier waits for everything requested before
+    // it), so its round trip to the counter is hidden.
     int next_task = 0;
     if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
     for (;;) {
-        if (threadIdx.x == 0) sm.task = next_task;
+        if (threadIdx.x == 0) { sm.task = next_task; sm.queued = 0; }
         __syncthreads();
         const int task = sm.task;
         if (task >= plan.n_tasks) break;             // uniform: every thread reads the same value
-        if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
         // entry of the task: all prefix sums are compared at once (independent scalar loads with
         // constant offsets, not a dependent chain of them; the index must stay uniform)
         int at_order = 0;
@@ -512,8 +568,17 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
 #pragma unroll
         for (int u = 0; u < kPerThread; ++u) acc[threadIdx.x + u * kOwnerThreads] = 0.0;
         __syncthreads();
+        if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
 
         if (e < plan.n_listed) {
+            // A listed task owns its range alone and adds to the gradient with plain loads and
+            // stores.  The loads are requested here and arrive while the records are streamed.
+            float old[kPerThread];
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                old[u] = k < 2 * slots_here ? dst[k] : 0.f;
+            }
             const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity[e]);
             const size_t at = (size_t)plan.list_base[e] + (size_t)range * plan.capacity[e];
             const uint32_t* rs = rec.slots + at;
@@ -533,40 +598,70 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                     if (j0 + k * kOwnerThreads < count) {
                         double* a0 = acc + 2 * (sl[k] & 0xFFFFu);
                         double* a1 = acc + 2 * (sl[k] >> 16);
-                        atomicAdd(a0 + 0, (double)v[k].x);
-                        atomicAdd(a0 + 1, (double)v[k].y);
-                        atomicAdd(a1 + 0, (double)v[k].z);
-                        atomicAdd(a1 + 1, (double)v[k].w);
+                        atomicAdd(a0 + odd, (double)(odd ? v[k].y : v[k].x));
+                        atomicAdd(a0 + (odd ^ 1), (double)(odd ? v[k].x : v[k].y));
+                        atomicAdd(a1 + odd, (double)(odd ? v[k].w : v[k].z));
+                        atomicAdd(a1 + (odd ^ 1), (double)(odd ? v[k].z : v[k].w));
                     }
                 }
             }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                const float v = (float)acc[k];
+                if (k < 2 * slots_here && v != 0.f) dst[k] = old[u] + v;
+            }
         } else {
-            // In-place path (levels with at most kInPlaceRanges ranges: nearly every point hits):
-            // four points per thread, all their loads issued before the first use.
+            // In-place path.  A task tests its chunk of the points against its range and adds the
+            // corners that fall into it.  On a dense level with several ranges most points of a
+            // wavefront miss, so the test (position only) and the work are separated: points that
+            // hit are queued in LDS, and the queue is worked off with every lane busy.
             const float fres = (float)g.res[level];
-            const bool dense_level = (g.dense_bits >> level) & 1u;
-            constexpr int kAhead = 4;
-            for (int64_t i0 = begin + threadIdx.x; i0 < end; i0 += kAhead * kOwnerThreads) {
-                float px[kAhead], py[kAhead], pz[kAhead], nx[kAhead], ny[kAhead], nz[kAhead];
-                float2 de[kAhead], qq[kAhead];
+            const bool filter = n_ranges > 1;              // only dense levels have several ranges here
+            constexpr int kFilter = 4;                     // points per thread and filter round
+            int64_t next = begin;
+            for (;;) {
+                for (;;) {                                 // fill until every thread has work, or the chunk ends
+                    float px[kFilter], py[kFilter], pz[kFilter];
 #pragma unroll
-                for (int k = 0; k < kAhead; ++k) {
-                    const int64_t i = i0 + k * kOwnerThreads;
-                    if (i < end) {
-                        const int64_t o = (int64_t)level * n + i;
-                        px[k] = pos[3 * i + 0]; py[k] = pos[3 * i + 1]; pz[k] = pos[3 * i + 2];
-                        nx[k] = d_normal[3 * i + 0]; ny[k] = d_normal[3 * i + 1]; nz[k] = d_normal[3 * i + 2];
-                        de[k] = reinterpret_cast<const float2*>(d_enc)[o];
-                        qq[k] = reinterpret_cast<const float2*>(q)[o];
+                    for (int k = 0; k < kFilter; ++k) {
+                        const int64_t i = next + threadIdx.x + k * kOwnerThreads;
+                        if (filter && i < end) { px[k] = pos[3 * i + 0]; py[k] = pos[3 * i + 1]; pz[k] = pos[3 * i + 2]; }
                     }
-                }
 #pragma unroll
-                for (int k = 0; k < kAhead; ++k) {
-                    if (i0 + k * kOwnerThreads >= end) continue;
-                    const Cell c = locate(g, level, px[k], py[k], pz[k]);
-                    // on a dense level the eight slots lie in [slot[0], slot[7]]
-                    if (dense_level && ((c.slot[7] >> kOwnerSlotBits) < range || (c.slot[0] >> kOwnerSlotBits) > range)) continue;
-                    const float ax = nx[k] * fres, ay = ny[k] * fres, az = nz[k] * fres;
+                    for (int k = 0; k < kFilter; ++k) {
+                        const int64_t i = next + threadIdx.x + k * kOwnerThreads;
+                        bool hit = i < end;
+                        if (hit && filter) {
+                            // on a dense level the eight slots lie in [slot[0], slot[7]]
+                            const Cell c = locate(g, level, px[k], py[k], pz[k]);
+                            hit = (c.slot[7] >> kOwnerSlotBits) >= range && (c.slot[0] >> kOwnerSlotBits) <= range;
+                        }
+                        const unsigned long long m = __ballot(hit);
+                        if (m) {                            // one reservation per wavefront
+                            const int lane = threadIdx.x & 63;
+                            const int leader = __ffsll((long long)m) - 1;
+                            int at = 0;
+                            if (lane == leader) at = atomicAdd(&sm.queued, __popcll(m));
+                            at = __shfl(at, leader);
+                            if (hit) sm.queue[at + __popcll(m & ((1ull << lane) - 1ull))] = (uint32_t)(i - begin);
+                        }
+                    }
+                    next += (int64_t)kFilter * kOwnerThreads;
+                    __syncthreads();
+                    const int queued = sm.queued;
+                    __syncthreads();                        // nobody adds to the counter before all have read it
+                    if (queued >= kOwnerThreads || next >= end) break;
+                }
+                const int queued = sm.queued;
+                for (int j = threadIdx.x; j < queued; j += kOwnerThreads) {
+                    const int64_t i = begin + sm.queue[j];
+                    const int64_t o = (int64_t)level * n + i;
+                    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+                    const float2 qq = reinterpret_cast<const float2*>(q)[o];
+                    const float ax = d_normal[3 * i + 0] * fres, ay = d_normal[3 * i + 1] * fres, az = d_normal[3 * i + 2] * fres;
+                    const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
 #pragma unroll
                     for (int cr = 0; cr < 8; ++cr) {
                         if ((c.slot[cr] >> kOwnerSlotBits) != range) continue;
@@ -579,30 +674,18 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                         const float wk = fx * fy * fz;
                         const float dn = ax * (sx * fy * fz) + ay * (fx * sy * fz) + az * (fx * fy * sz);
                         double* a = acc + 2 * (c.slot[cr] & (kOwnerSlots - 1));
-                        atomicAdd(a + 0, (double)(wk * de[k].x + qq[k].x * dn));
-                        atomicAdd(a + 1, (double)(wk * de[k].y + qq[k].y * dn));
+                        const float v0 = wk * de.x + qq.x * dn, v1 = wk * de.y + qq.y * dn;
+                        atomicAdd(a + odd, (double)(odd ? v1 : v0));
+                        atomicAdd(a + (odd ^ 1), (double)(odd ? v0 : v1));
                     }
                 }
+                __syncthreads();
+                if (threadIdx.x == 0) sm.queued = 0;
+                __syncthreads();
+                if (next >= end) break;
             }
-        }
-        __syncthreads();
-
-        if (n_chunks == 1) {
-            // the task owns its range alone: plain loads and stores, all loads issued before the first use
-            float old[kPerThread];
-#pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const uint32_t k = threadIdx.x + u * kOwnerThreads;
-                old[u] = k < 2 * slots_here ? dst[k] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const uint32_t k = threadIdx.x + u * kOwnerThreads;
-                const float v = (float)acc[k];
-                if (k < 2 * slots_here && v != 0.f) dst[k] = old[u] + v;
-            }
-        } else {
             // several chunks of the points share the range: coalesced atomics
+            __syncthreads();
 #pragma unroll
             for (int u = 0; u < kPerThread; ++u) {
                 const uint32_t k = threadIdx.x + u * kOwnerThreads;
@@ -643,7 +726,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
                 // a list holds 1.5 times its expected share of the 4 n row records of the level;
                 // 3 times on a dense level, where the share of a slab of the grid follows the batch
                 const int64_t cap = ((4 * n / ranges) * (cfg->dense[l] ? 6 : 3) / 2 + 1023) / 64 * 64;
-                if (cap > (1 << 30)) ok = false;
+                if (cap * ranges >= ((int64_t)1 << 32) - 1) ok = false;     // record positions are 32 bits
                 p.capacity[e] = (int)cap;
                 p.list_base[e] = records;
                 records += cap * ranges;
@@ -735,8 +818,8 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 16);
             NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));      // task counter and cursors
             if (plan.n_listed > 0) {
-                const int pbs = (int)((n + kOwnerThreads - 1) / kOwnerThreads);
-                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_listed), dim3(kOwnerThreads), 0, st, g, plan, rec, pos, q,
+                const int pbs = (int)((n + kBinThreads - 1) / kBinThreads);
+                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_listed), dim3(kBinThreads), 0, st, g, plan, rec, pos, q,
                                    d_enc, d_normal, n, pbs, d_tables);
             }
             const int wgs = compute_units();

@@ -143,18 +143,21 @@ __device__ __forceinline__ void block_add(float v, float* dst, float* red) {
     __syncthreads();
 }
 
-// Grid-stride: a few hundred workgroups, each ending in two atomics (thousands of workgroups
-// all adding to the same two floats would serialise on them).
-__global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
+// Grid-stride with few, large workgroups: every workgroup ends in two atomics on the same cache
+// line, and those are applied one after the other by the memory side (about 12 ns each, which
+// is what this kernel's time was made of with a thousand of them).
+constexpr int kLossThreads = 1024;
+
+__global__ __launch_bounds__(kLossThreads) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
                                                    const float* __restrict__ normal, const float* __restrict__ y,
                                                    int64_t rays, int64_t n, float beta, float huber_delta,
                                                    float* __restrict__ loss,
                                                    float* __restrict__ dC, float* __restrict__ d_normal,
                                                    float* __restrict__ d_y) {
-    __shared__ float red[4];
+    __shared__ float red[kLossThreads / 64];
     const float inv_n = 1.f / (float)n;
     float first = 0.f, eik = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)blockIdx.x * kLossThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kLossThreads) {
         const float nx = normal[3 * i], ny = normal[3 * i + 1], nz = normal[3 * i + 2];
         const float len = sqrtf(nx * nx + ny * ny + nz * nz);
         const float dev = len - 1.f;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(256) void loss_kernel(int kind, const float* __rest
     }
     if (kind != 0) {
         const float inv_r = 1.f / (float)rays;
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < rays; i += (int64_t)gridDim.x * 256) {
+        for (int64_t i = (int64_t)blockIdx.x * kLossThreads + threadIdx.x; i < rays; i += (int64_t)gridDim.x * kLossThreads) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 const float diff = C[3 * i + c] - target[3 * i + c];
@@ -316,9 +319,9 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
         NEUS2_TRY(check_ptr(d_y, "d_y"));
     }
     if (n == 0) return NEUS2_OK;
-    const int64_t want = (n + 255) / 256;
-    const int64_t cap = 2 * (int64_t)compute_units();
-    hipLaunchKernelGGL(loss_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(256), 0, (hipStream_t)stream, cfg->loss_kind,
+    const int64_t want = (n + kLossThreads - 1) / kLossThreads;
+    const int64_t cap = (int64_t)compute_units() / 2;
+    hipLaunchKernelGGL(loss_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(kLossThreads), 0, (hipStream_t)stream, cfg->loss_kind,
                        C, target, normal, y, cfg->loss_kind != 0 ? rays : 0, n, cfg->beta, cfg->huber_delta, loss, dC, d_normal,
                        d_y);
     return check_launch("loss");

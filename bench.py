@@ -83,7 +83,7 @@ def algorithmic_cost(cfg, n):
         col_w = sum(cd[i] * cd[i + 1] for i in range(3))
         cost.update({
             "color_fwd": {"bytes": 12 + 12 + 64 + 12, "flops": 2 * col_w},
-            "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 4 + 64 + 24, "flops": 2 * col_w + 4 * col_w},
+            "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 12 + 4 + 64 + 24, "flops": 2 * col_w + 4 * col_w},
             "render_rays": {"bytes": 4 + 12 + 4, "flops": 0},
             "render_rays_bwd": {"bytes": 4 + 12 + 4 + 12, "flops": 0},
             "loss": {"bytes": 12 + 12, "flops": 0},
@@ -177,7 +177,7 @@ def main() -> int:
                 "render_rays": lambda: nb.render_rays(c, s.y, 16, s.rgb, rays, s.C, s.weights),
                 "loss": lambda: nb.loss(c, s.C, s.target, s.normal, s.y, rays, n, s.loss, s.dC, s.d_normal, None),
                 "render_rays_bwd": lambda: nb.render_rays_bwd(c, s.y, 16, s.rgb, s.dC, rays, s.d_sdf, s.d_rgb),
-                "color_bwd": lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.d_rgb, s.d_sdf, n, s.dW, s.d_y,
+                "color_bwd": lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW, s.d_y,
                                                   torch.zeros_like(s.d_normal)),
             })
         else:

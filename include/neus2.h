@@ -107,13 +107,15 @@ int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* norm
 
 /* First-order backward of the colour network (the paper needs no second-order term for
  * Upsilon, text after Eq. 6).
+ *   rgb [device, n*3] in: the colours neus2_color_fwd wrote for the same inputs (the
+ *   sigmoid's derivative is taken from them);
  *   d_rgb [device, n*3] in;  d_sdf [device, n] in or NULL (render's dL/dd, added to d_y[.,0]);
  *   dW [host array of 3 device pointers]: gradients are ADDED into them;
  *   d_y [device, n*16] is OVERWRITTEN with the colour network's dL/d(d,g) (+ d_sdf);
  *   d_normal [device, n*3] is ADDED into (it already holds the eikonal part);
  *   d_pos [device, n*3] or NULL is OVERWRITTEN with the colour network's dL/dx. */
 int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal,
-                    const float* dirs, const float* y, const float* const* W,
+                    const float* dirs, const float* y, const float* const* W, const float* rgb,
                     const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
                     float* d_y, float* d_normal, float* d_pos, void* stream);
 

@@ -58,7 +58,7 @@ _SIGNATURES = {
     "neus2_hash_encode": (C.c_int, [C.POINTER(Neus2Config), _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
-    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
@@ -155,9 +155,9 @@ def color_fwd(c, pos, normal, dirs, y, W, n, rgb):
                                  _ptr(rgb), _stream()))
 
 
-def color_bwd(c, pos, normal, dirs, y, W, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None):
+def color_bwd(c, pos, normal, dirs, y, W, rgb, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None):
     _check(lib().neus2_color_bwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(y), _ptr_array(W),
-                                 _ptr(d_rgb), _ptr(d_sdf), n, _ptr_array(dW), _ptr(d_y), _ptr(d_normal),
+                                 _ptr(rgb), _ptr(d_rgb), _ptr(d_sdf), n, _ptr_array(dW), _ptr(d_y), _ptr(d_normal),
                                  _ptr(d_pos), _stream()))
 
 

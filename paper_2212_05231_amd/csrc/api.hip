@@ -250,7 +250,7 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
         NEUS2_TRY(neus2_loss(cfg, b->C, b->target, b->normal, b->y, rays, n, b->loss, b->dC, b->d_normal, nullptr, stream));
         NEUS2_TRY(neus2_render_rays_bwd(cfg, b->y, 16, b->rgb, b->dC, b->s_dev, rays, b->d_sdf, b->d_rgb, b->d_s,
                                         stream));
-        NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
+        NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->rgb, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
                                   b->d_normal, b->d_pos, stream));
     } else {
         NEUS2_TRY(neus2_loss(cfg, nullptr, nullptr, b->normal, b->y, 0, n, b->loss, nullptr, b->d_normal, b->d_y, stream));

@@ -4,9 +4,11 @@
 // and its adjoint dL/dn is handed on to the SDF backward.
 //
 // Input, as the caller sees it: [x(3), n(3), SH16(v)(16), (d,g)(16)] = 38 columns of W_1.
-// Inside the kernel the columns are walked in the order [(d,g), SH16, x, n, 0, 0] so that
-// each lane's registers map to contiguous loads; W_1 is permuted to match when it is copied
-// into LDS.
+// Inside the kernel the columns are walked in the order [(d,g), x, n, 0, 0, SH16]: each lane's
+// registers map to contiguous loads, and every column whose adjoint is wanted ((d,g), x, n;
+// the view direction is not trained) lies in the first block of 32, so the backward pass
+// computes only that block of dL/d(input).  W_1 is permuted to match when it is copied into
+// LDS.
 #include "common.h"
 #include "mfma_tile.h"
 
@@ -21,7 +23,7 @@ constexpr int kLdOutT = 12;    // row stride of W_3^T in LDS (3 used columns)
 
 struct ColorArgs {
     const float* pos; const float* normal; const float* dirs; const float* y; const float* W[3];
-    const float* d_rgb; const float* d_sdf;
+    const float* d_rgb; const float* d_sdf; const float* rgb_in;
     float* rgb; float* dW[3]; float* d_y; float* d_normal; float* d_pos;
     int64_t n; int spr;
 };
@@ -29,9 +31,9 @@ struct ColorArgs {
 // caller's column of W_1 for internal column c (or -1 for padding)
 __device__ __forceinline__ int external_column(int c) {
     if (c < 16) return 22 + c;          // (d, g)
-    if (c < 32) return 6 + (c - 16);    // SH16
-    if (c < 38) return c - 32;          // x (0..2), n (3..5)
-    return -1;
+    if (c < 22) return c - 16;          // x (0..2), n (3..5)
+    if (c < 24) return -1;
+    return 6 + (c - 24);                // SH16
 }
 
 template <bool BWD>
@@ -39,7 +41,7 @@ struct ColorWeights {
     float W1f[64 * kLdIn];
     float W2f[64 * kLd64];
     float W3f[32 * kLd64];                       // rows >= 3 zero
-    float W1t[BWD ? 64 * kLd64 : 4];             // [40 -> 64 rows][64], rows >= 38 zero
+    float W1t[BWD ? 32 * kLd64 : 4];             // [first 32 input columns][64]
     float W2t[BWD ? 64 * kLd64 : 4];
     float W3t[BWD ? 64 * kLdOutT : 4];           // [64][3 -> 8], columns >= 3 zero
 };
@@ -49,7 +51,7 @@ __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
     const int tid = threadIdx.x;
     for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W3f[idx] = 0.f;
     if (BWD) {
-        for (int idx = tid; idx < 64 * kLd64; idx += kThreads) w.W1t[idx] = 0.f;
+        for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W1t[idx] = 0.f;
         for (int idx = tid; idx < 64 * kLdOutT; idx += kThreads) w.W3t[idx] = 0.f;
     }
     __syncthreads();
@@ -58,7 +60,7 @@ __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
         const int e = external_column(c);
         const float v = e >= 0 ? a.W[0][o * 38 + e] : 0.f;
         w.W1f[o * kLdIn + c] = v;
-        if (BWD) w.W1t[c * kLd64 + o] = v;
+        if (BWD && c < 32) w.W1t[c * kLd64 + o] = v;
     }
     for (int idx = tid; idx < 64 * 64; idx += kThreads) {
         const int o = idx / 64, i = idx % 64;
@@ -101,7 +103,7 @@ __device__ __forceinline__ void sh16(float x, float y, float z, float* sh) {
 struct ColorRaw {
     float4 ya, yb;
     float dir[3], p[3], nr[3];
-    float d_rgb[3], d_sdf;
+    float d_rgb[3], rgb[3], d_sdf;
 };
 
 template <bool BWD>
@@ -116,13 +118,14 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
         r.dir[c] = a.dirs[3 * ray + c];
         r.p[c] = a.pos[3 * i + c];
         r.nr[c] = a.normal[3 * i + c];
-        if (BWD) r.d_rgb[c] = a.d_rgb[3 * i + c];
+        if (BWD) { r.d_rgb[c] = a.d_rgb[3 * i + c]; r.rgb[c] = a.rgb_in[3 * i + c]; }
     }
     if (BWD && a.d_sdf) r.d_sdf = a.d_sdf[i];
     return r;
 }
 
-// Build the register layout from the raw inputs: block 0 = [(d,g), SH16], block 1 = [x, n].
+// Build the register layout from the raw inputs: block 0 = [(d,g), x, n, 0, 0, SH 0..7],
+// block 1 = [SH 8..15].
 __device__ __forceinline__ void build_input(const ColorRaw& r, bool valid, int h, v16f* cin) {
     cin[0] = zero16();
     cin[1] = zero16();
@@ -131,15 +134,15 @@ __device__ __forceinline__ void build_input(const ColorRaw& r, bool valid, int h
     cin[0][4] = r.yb.x; cin[0][5] = r.yb.y; cin[0][6] = r.yb.z; cin[0][7] = r.yb.w;
     float sh[16];
     sh16(r.dir[0], r.dir[1], r.dir[2], sh);
+    cin[0][8] = h ? r.nr[1] : r.p[0];
+    cin[0][9] = h ? r.nr[2] : r.p[1];
+    cin[0][10] = h ? 0.f : r.p[2];
+    cin[0][11] = h ? 0.f : r.nr[0];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        cin[0][8 + k] = h ? sh[4 + k] : sh[k];
-        cin[0][12 + k] = h ? sh[12 + k] : sh[8 + k];
+        cin[0][12 + k] = h ? sh[4 + k] : sh[k];
+        cin[1][k] = h ? sh[12 + k] : sh[8 + k];
     }
-    cin[1][0] = h ? r.nr[1] : r.p[0];
-    cin[1][1] = h ? r.nr[2] : r.p[1];
-    cin[1][2] = h ? 0.f : r.p[2];
-    cin[1][3] = h ? 0.f : r.nr[0];
 }
 
 __device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-u)); }
@@ -151,7 +154,7 @@ __device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v
     m1 = relu_mask<2>(a1);
     matvec<2, 2, kLd64>(w.W2f, a1, a2, j, h);
     m2 = relu_mask<2>(a2);
-    matvec<1, 2, kLd64>(w.W3f, a2, u, j, h);
+    if (!BWD) matvec<1, 2, kLd64>(w.W3f, a2, u, j, h);    // the backward pass reads rgb instead
 }
 
 __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
@@ -217,20 +220,17 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
         }
         forward_tile<true>(w, cin, a1, a2, m1, m2, u, j, h);
-        // adjoint of the pre-sigmoid output
+        // adjoint of the pre-sigmoid output, from the colour the forward pass stored
         v16f d3[1] = {zero16()};
         if (valid && h == 0) {
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const float s = sigmoid(u[0][c]);
-                d3[0][c] = cur.d_rgb[c] * s * (1.f - s);
-            }
+            for (int c = 0; c < 3; ++c) d3[0][c] = cur.d_rgb[c] * cur.rgb[c] * (1.f - cur.rgb[c]);
         }
         stage<1, kLd64>(Zt, d3, j, h);
         stage<2, kLd64>(Xt, a2, j, h);
         wave_lds_fence();
         outer_accumulate<1, 2, kLd64, kLd64>(G3, Zt, Xt, j, h);
-        v16f d2[2], d1[2], dcin[2];
+        v16f d2[2], d1[2], dcin[1];
         matvec<2, 1, kLdOutT, 4>(w.W3t, d3, d2, j, h);
         apply_mask<2>(d2, m2);
         wave_lds_fence();
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         stage<2, kLd64>(Xt, cin, j, h);
         wave_lds_fence();
         outer_accumulate<2, 2, kLd64, kLd64>(G1, Zt, Xt, j, h);
-        matvec<2, 2, kLd64>(w.W1t, d1, dcin, j, h);
+        matvec<1, 2, kLd64>(w.W1t, d1, dcin, j, h);
         wave_lds_fence();
         if (valid) {
             // block 0, registers 0..7: dL/d(d,g) columns 4h..4h+3 and 8+4h..8+4h+3
@@ -254,13 +254,13 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             if (h == 0) lo.x += cur.d_sdf;
             *reinterpret_cast<float4*>(a.d_y + i * 16 + 4 * h) = lo;
             *reinterpret_cast<float4*>(a.d_y + i * 16 + 8 + 4 * h) = hi;
-            // block 1: h = 0 -> x0 x1 x2 n0 ; h = 1 -> n1 n2
+            // registers 8..11: h = 0 -> x0 x1 x2 n0 ; h = 1 -> n1 n2
             if (h == 0) {
-                if (a.d_pos) { a.d_pos[3 * i] = dcin[1][0]; a.d_pos[3 * i + 1] = dcin[1][1]; a.d_pos[3 * i + 2] = dcin[1][2]; }
-                a.d_normal[3 * i] += dcin[1][3];
+                if (a.d_pos) { a.d_pos[3 * i] = dcin[0][8]; a.d_pos[3 * i + 1] = dcin[0][9]; a.d_pos[3 * i + 2] = dcin[0][10]; }
+                a.d_normal[3 * i] += dcin[0][11];
             } else {
-                a.d_normal[3 * i + 1] += dcin[1][0];
-                a.d_normal[3 * i + 2] += dcin[1][1];
+                a.d_normal[3 * i + 1] += dcin[0][8];
+                a.d_normal[3 * i + 2] += dcin[0][9];
             }
         }
     }
@@ -335,9 +335,10 @@ int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* norm
 }
 
 int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
-                    const float* const* W, const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
-                    float* d_y, float* d_normal, float* d_pos, void* stream) {
+                    const float* const* W, const float* rgb, const float* d_rgb, const float* d_sdf, int64_t n,
+                    float* const* dW, float* d_y, float* d_normal, float* d_pos, void* stream) {
     NEUS2_TRY(check_common(cfg, pos, normal, dirs, y, W, n));
+    NEUS2_TRY(check_ptr(rgb, "rgb"));
     NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
     NEUS2_TRY(check_ptr(d_sdf, "d_sdf", false));
     if (!dW) return fail(NEUS2_ERR_NULL, "dW is NULL");
@@ -348,7 +349,7 @@ int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* norm
     if (n == 0) return NEUS2_OK;
     ColorArgs a = {};
     a.pos = pos; a.normal = normal; a.dirs = dirs; a.y = y; a.n = n; a.spr = cfg->samples_per_ray;
-    a.d_rgb = d_rgb; a.d_sdf = d_sdf; a.d_y = d_y; a.d_normal = d_normal; a.d_pos = d_pos;
+    a.rgb_in = rgb; a.d_rgb = d_rgb; a.d_sdf = d_sdf; a.d_y = d_y; a.d_normal = d_normal; a.d_pos = d_pos;
     for (int l = 0; l < 3; ++l) { a.W[l] = W[l]; a.dW[l] = dW[l]; }
     const int blocks = persistent_blocks((const void*)color_bwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
     hipLaunchKernelGGL(color_bwd_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);

@@ -253,7 +253,7 @@ def test_color_forward_backward_alone():
     d_y = torch.empty(n, 16, device="cuda")
     d_normal = cuda(dn0)
     d_pos = torch.empty(n, 3, device="cuda")
-    nb.color_bwd(c, *args, Wg, cuda(d_rgb), cuda(d_sdf), n, dW, d_y, d_normal, d_pos)
+    nb.color_bwd(c, *args, Wg, rgb, cuda(d_rgb), cuda(d_sdf), n, dW, d_y, d_normal, d_pos)
     torch.cuda.synchronize()
     cin = o.color_input(pos, nrm.astype(np.float64), dirs, y.astype(np.float64), spr)
     rgb_r, acts, masks = o.color_forward(W, cin)

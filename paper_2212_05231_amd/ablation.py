@@ -1,0 +1,116 @@
+"""Second-order backward of the SDF network: this library against torch.autograd's double
+backward (the comparison of the paper's Fig. 7, "speed-up of our 2nd-order derivative over
+PyTorch across MLP layer numbers and batch sizes").
+
+    python -m paper_2212_05231_amd.ablation [--log2-min 14] [--log2-max 20] [--reps 20]
+
+Both sides compute, for a batch of encodings e [n, 32] with Jacobians J = de/dx [n, 32, 3]:
+    (d, g) = f(e),  q = dd/de,  normal = q J,
+    loss = mean(d^2) + beta * mean((|normal| - 1)^2),
+and the gradient of the loss with respect to every matrix of f (which needs the second-order
+term of Theorem 1 because the loss depends on normal) and with respect to e.
+The library runs neus2_sdf_fwd_grad + neus2_loss + neus2_sdf_mlp_bwd; PyTorch runs the same
+network with autograd.grad(create_graph=True) for q and .backward() for the rest.  Depths are
+the ones the kernels are built for (1 and 2 hidden layers of 64).  Prints one line per case and
+a JSON summary; the gradients of the two sides are compared as a sanity check (the parity
+tests proper are against the float64 oracle).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+
+import numpy as np
+
+
+def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
+    import torch
+    from . import binding as nb, workloads as wl
+    dev = "cuda"
+    out = []
+    for hidden in (1, 2):
+        cfg = wl.make_config(1)
+        cfg.sdf_dims = [32] + [64] * hidden + [16]
+        cfg.n_levels, cfg.active_levels = 16, 16
+        cfg.res, cfg.dense = wl.make_config(2).res, wl.make_config(2).dense
+        cfg.log2_table_size = wl.make_config(2).log2_table_size
+        cfg.loss_kind, cfg.beta = 0, beta
+        c = nb.make_config(cfg)
+        g = torch.Generator(device="cpu").manual_seed(7 + hidden)
+        Hs = [(torch.randn(cfg.sdf_dims[i + 1], cfg.sdf_dims[i], generator=g) * (2.0 / cfg.sdf_dims[i]) ** 0.5).to(dev)
+              for i in range(hidden + 1)]
+        for lg in range(log2_min, log2_max + 1):
+            n = 1 << lg
+            e = torch.randn(n, 32, generator=g).to(dev)
+            J = (torch.randn(n, 32, 3, generator=g) * 0.3).to(dev)
+            # library layout: level-major [L][n][F] and [L][n][F][3]
+            enc = e.view(n, 16, 2).permute(1, 0, 2).contiguous()
+            jac = J.view(n, 16, 2, 3).permute(1, 0, 2, 3).contiguous()
+            y = torch.empty(n, 16, device=dev); q = torch.empty(16, n, 2, device=dev); normal = torch.empty(n, 3, device=dev)
+            loss = torch.zeros(4, device=dev); d_y = torch.empty(n, 16, device=dev); d_normal = torch.empty(n, 3, device=dev)
+            d_enc = torch.empty(16, n, 2, device=dev)
+            dH = [torch.zeros_like(h) for h in Hs]
+
+            def ours():
+                nb.sdf_fwd_grad(c, enc, jac, Hs, n, y, q, normal)
+                nb.loss(c, None, None, normal, y, 0, n, loss, None, d_normal, d_y)
+                nb.sdf_mlp_bwd(c, enc, jac, Hs, d_y, d_normal, n, dH, d_enc)
+
+            params = [h.clone().requires_grad_(True) for h in Hs]
+
+            def theirs():
+                for p in params:
+                    p.grad = None
+                x = e.detach().requires_grad_(True)
+                a = x
+                for l, h in enumerate(params):
+                    a = a @ h.t()
+                    if l < len(params) - 1:
+                        a = torch.relu(a)
+                d = a[:, 0]
+                (qq,) = torch.autograd.grad(d.sum(), x, create_graph=True)
+                nrm = torch.einsum("nk,nkc->nc", qq, J)
+                ls = (d * d).mean() + beta * ((nrm.norm(dim=1) - 1.0) ** 2).mean()
+                ls.backward()
+                return x.grad
+
+            def timed(fn):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0.record()
+                for _ in range(reps):
+                    fn()
+                t1.record()
+                torch.cuda.synchronize()
+                return t0.elapsed_time(t1) / reps
+
+            for h in dH:
+                h.zero_()
+            ours()
+            gx = theirs()
+            torch.cuda.synchronize()
+            err = max(float((a - p.grad).norm() / p.grad.norm()) for a, p in zip(dH, params))
+            err_x = float((d_enc.permute(1, 0, 2).reshape(n, 32) - gx).norm() / gx.norm())
+            t_ours, t_torch = timed(ours), timed(theirs)
+            row = {"hidden_layers": hidden, "batch": n, "ours_ms": round(t_ours, 4), "autograd_ms": round(t_torch, 4),
+                   "speedup": round(t_torch / t_ours, 2), "grad_rel_diff": err, "input_grad_rel_diff": err_x}
+            print(f"hidden {hidden}  batch 2^{lg:<2d}  ours {t_ours:8.3f} ms   autograd {t_torch:8.3f} ms   speed-up {t_torch / t_ours:6.2f}x   "
+                  f"grad diff {err:.1e} / {err_x:.1e}", flush=True)
+            out.append(row)
+    return out
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--log2-min", type=int, default=14)
+    ap.add_argument("--log2-max", type=int, default=20)
+    ap.add_argument("--reps", type=int, default=20)
+    a = ap.parse_args()
+    rows = run(a.log2_min, a.log2_max, a.reps)
+    print(json.dumps({"ablation": "second-order backward vs torch.autograd double backward", "rows": rows}))
+
+
+if __name__ == "__main__":
+    main()

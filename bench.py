@@ -38,10 +38,10 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 # workload has been measured; other workloads report null.
 MEASURED_TRAFFIC_MIB = {
     "cfg2-static-4096x64": {
-        "hash_encode": (71.1, 128.0), "sdf_fwd_grad": (128.4, 51.0), "color_fwd": (22.6, 3.0),
-        "render_rays": (19.0, 1.1), "loss": (3.1, 3.1), "render_rays_bwd": (19.2, 4.0),
-        "color_bwd": (30.1, 26.6), "sdf_mlp_bwd": (147.8, 39.0),
-        "hash_scatter_bwd": (82.2 + 351.7, 237.5 + 51.4),      # bin_rows_kernel + scatter_owner_kernel
+        "hash_encode": (71.3, 128.0), "sdf_fwd_grad": (128.4, 51.0), "color_fwd": (22.6, 3.0),
+        "render_rays": (19.0, 1.1), "loss": (3.2, 3.1), "render_rays_bwd": (19.2, 4.0),
+        "color_bwd": (33.0, 28.2), "sdf_mlp_bwd": (148.8, 44.0),
+        "hash_scatter_bwd": (83.8 + 349.0, 232.8 + 61.2),      # bin_rows_kernel + scatter_owner_kernel
         "adam_tables": (256.0, 288.0),
     },
 }
@@ -156,47 +156,58 @@ def main() -> int:
     value = n * args.steps / dt
     loss_now = [float(x) for x in step.loss.cpu().numpy()[:2]]
 
-    # ---- per-kernel durations, each call alone, events on the stream the kernels run on
+    # ---- per-call durations: the same step, driven call by call through the C-ABI in the order
+    # neus2_train_step uses, with an event on the kernels' stream between calls, so that every
+    # kernel sees the cache state it has inside a step (a call timed alone in a loop runs up to
+    # 15 % faster than in the step and would not agree with a rocprofv3 trace of this command)
     kernels = {}
     roofline = None
     if not args.no_kernel_timing:
         c, s = step.c, step
         rays = s.rays
-        calls = {
-            "hash_encode": lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac),
-            "sdf_fwd_grad": lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal),
-            "sdf_mlp_bwd": lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc),
-            "hash_scatter_bwd": lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
-                                                              workspace=s.workspace),
-            "adam_tables": lambda: nb.adam_step(s.tables, s.opt["master"], s.d_tables, s.opt["m_t"], s.opt["v_t"],
-                                                1 if cfg.table_dtype == "f16" else 0, 0.0, 0.9, 0.99, 1e-15, 1, True),
-        }
-        if cfg.loss_kind == 1:
-            calls.update({
-                "color_fwd": lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb),
-                "render_rays": lambda: nb.render_rays(c, s.y, 16, s.rgb, rays, s.C, s.weights),
-                "loss": lambda: nb.loss(c, s.C, s.target, s.normal, s.y, rays, n, s.loss, s.dC, s.d_normal, None),
-                "render_rays_bwd": lambda: nb.render_rays_bwd(c, s.y, 16, s.rgb, s.dC, rays, s.d_sdf, s.d_rgb),
-                "color_bwd": lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW, s.d_y,
-                                                  torch.zeros_like(s.d_normal)),
-            })
+        o = s.opt
+        half = 1 if cfg.table_dtype == "f16" else 0
+        seq = [("hash_encode", lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac)),
+               ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal))]
+        if cfg.loss_kind != 0:
+            seq += [
+                ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb)),
+                ("render_rays", lambda: nb.render_rays(c, s.y, 16, s.rgb, rays, s.C, s.weights)),
+                ("loss", lambda: nb.loss(c, s.C, s.target, s.normal, s.y, rays, n, s.loss, s.dC, s.d_normal, None)),
+                ("render_rays_bwd", lambda: nb.render_rays_bwd(c, s.y, 16, s.rgb, s.dC, rays, s.d_sdf, s.d_rgb)),
+                ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
+                                                   s.d_y, s.d_normal)),
+            ]
         else:
-            calls["loss"] = lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y)
-        # bring every buffer to the state it has inside a step
-        step.train_step()
-        torch.cuda.synchronize()
+            seq += [("loss", lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y))]
+        seq += [
+            ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
+            ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
+                                                             workspace=s.workspace)),
+            ("adam_tables", lambda: nb.adam_step(s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"], half,
+                                                 o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
+            ("adam_matrices", lambda: nb.adam_step(s.small, None, s.d_small, o["m_s"], o["v_s"], 0,
+                                                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
+        ]
         cost = algorithmic_cost(cfg, n)
-        reps = max(5, min(args.steps, 50))
-        for name, fn in calls.items():
-            fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
+        cost["adam_matrices"] = {"bytes": 34 * int(s.small.numel()), "flops": 0}
+        reps = max(5, min(args.steps, 100))
+        total = {name: 0.0 for name, _ in seq}
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(seq) + 1)] for _ in range(reps)]
+        one_step()                                       # the state a step starts from
+        for r in range(reps):
+            o["t"] += 1
+            s.loss.zero_()
+            for k, (name, fn) in enumerate(seq):
+                events[r][k].record()
                 fn()
-            e1.record()
-            torch.cuda.synchronize()
-            us = 1e3 * e0.elapsed_time(e1) / reps
+            events[r][len(seq)].record()
+        torch.cuda.synchronize()
+        for r in range(reps):
+            for k, (name, _) in enumerate(seq):
+                total[name] += events[r][k].elapsed_time(events[r][k + 1])
+        for name, _ in seq:
+            us = 1e3 * total[name] / reps
             k = {"us": round(us, 2), "bytes": cost[name]["bytes"], "flops": cost[name]["flops"],
                  "GBps": round(cost[name]["bytes"] / us * 1e-3, 1)}
             if cost[name]["flops"]:

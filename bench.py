@@ -50,7 +50,7 @@ MEASURED_TRAFFIC_MIB = {
 KERNELS_OF_CALL = {
     "hash_encode": "encode_kernel", "sdf_fwd_grad": "sdf_fwd_kernel", "sdf_mlp_bwd": "sdf_bwd_kernel",
     "hash_scatter_bwd": "zero_kernel + bin_rows_kernel + scatter_owner_kernel (scatter_kernel below 2^16 points)",
-    "adam_tables": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
+    "adam_tables": "adam_tables_kernel", "adam_matrices": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
     "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
 }
 
@@ -91,7 +91,8 @@ def algorithmic_cost(cfg, n):
     else:
         cost["loss"] = {"bytes": 12 + 12 + 4 + 64, "flops": 0}
     out = {k: {"bytes": v["bytes"] * n, "flops": v["flops"] * n} for k, v in cost.items()}
-    n_tab = cfg.n_levels * cfg.table_size * F
+    # parameters a point can address: a dense level uses (res+1)^3 of its T slots
+    n_tab = sum(((r + 1) ** 3 if d else cfg.table_size) for r, d in zip(cfg.res, cfg.dense)) * F
     # read grad, m, v, fp32 value; write m, v, fp32 value, cleared grad (+ the fp16 copy)
     per_param = 16 + 16 + (2 if cfg.table_dtype == "f16" else 0)
     out["adam_tables"] = {"bytes": n_tab * per_param, "flops": 0}
@@ -184,8 +185,8 @@ def main() -> int:
             ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
             ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
                                                              workspace=s.workspace)),
-            ("adam_tables", lambda: nb.adam_step(s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"], half,
-                                                 o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
+            ("adam_tables", lambda: nb.adam_tables(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"],
+                                                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
             ("adam_matrices", lambda: nb.adam_step(s.small, None, s.d_small, o["m_s"], o["v_s"], 0,
                                                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
         ]

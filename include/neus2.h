@@ -187,6 +187,14 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
                     int dtype, float lr, float beta1, float beta2, float eps, int t,
                     int zero_grad, void* stream);
 
+/* The same update over the hash tables [L][T][F] of a descriptor (fp16 tables with their fp32
+ * master copy, or fp32 tables and master NULL), skipping the slots no point can address: a
+ * dense level uses (res+1)^3 of its T slots; the rest never receive a gradient and the update
+ * would leave them unchanged.  Same result as neus2_adam_step over L*T*F parameters. */
+int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m,
+                      float* v, float lr, float beta1, float beta2, float eps, int t,
+                      int zero_grad, void* stream);
+
 /* Global rigid transform of Eq. 9, x_c = R (x + T), then the affine map scale*x_c + offset
  * that takes world coordinates to the unit cube.  R [host, 9 row-major], T [host, 3]. */
 int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset,

@@ -68,6 +68,8 @@ _SIGNATURES = {
     "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
                                   C.c_float, C.c_int, C.c_int, _P]),
+    "neus2_adam_tables": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float,
+                                    C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
     "neus2_rigid_bwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
     "neus2_train_step": (C.c_int, [C.POINTER(Neus2Config), C.POINTER(Neus2StepBuffers), C.c_int64, _P]),
@@ -204,6 +206,11 @@ def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_g
                                  lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
 
 
+def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_grad=True):
+    _check(lib().neus2_adam_tables(C.byref(c), _ptr(tables), _ptr(master), _ptr(grad), _ptr(m), _ptr(v),
+                                   lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
+
+
 def rigid_fwd(pos, R, T, scale, offset, out):
     Ra = (C.c_float * 9)(*[float(x) for x in R])
     Ta = (C.c_float * 3)(*[float(x) for x in T])
@@ -302,9 +309,8 @@ class Step:
         """One Adam step on every parameter; the gradient buffers are cleared in the same pass."""
         o = self.opt
         o["t"] += 1
-        half = self.tables.dtype != self.d_tables.dtype
-        adam_step(self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"], 1 if half else 0,
-                  o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
+        adam_tables(self.c, self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"],
+                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
         adam_step(self.small, None, self.d_small, o["m_s"], o["v_s"], 0,
                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
 

@@ -9,6 +9,8 @@
 // which has no cancellation when both SDF values are close to zero (fp32).
 //
 // One ray = one wavefront, one sample = one lane (at most 64 samples per ray).
+#include <cstring>
+
 #include "common.h"
 
 namespace neus2 {
@@ -221,6 +223,34 @@ __global__ __launch_bounds__(256) void adam_kernel(void* __restrict__ param, flo
     if (zero_grad) grad[i] = 0.f;
 }
 
+// The same update over the hash tables [L][T][F], restricted to the slots a level can address:
+// a dense level uses (res+1)^3 of its T slots, the others never receive a gradient, keep zero
+// moments and would be left unchanged by the update, so skipping them changes nothing.
+struct TableLevels {
+    uint32_t used[NEUS2_MAX_LEVELS];     // parameters (slots * F) of each level that can be addressed
+};
+
+template <bool HALF>
+__global__ __launch_bounds__(256) void adam_tables_kernel(void* __restrict__ param, float* __restrict__ master,
+                                                          float* __restrict__ grad, float* __restrict__ m,
+                                                          float* __restrict__ v, TableLevels lv, uint32_t per_level,
+                                                          AdamArgs a, int zero_grad) {
+    const int level = blockIdx.y;
+    const uint32_t k = blockIdx.x * 256u + threadIdx.x;
+    if (k >= lv.used[level]) return;
+    const int64_t i = (int64_t)level * per_level + k;
+    const float g = grad[i];
+    const float mi = a.b1 * m[i] + (1.f - a.b1) * g;
+    const float vi = a.b2 * v[i] + (1.f - a.b2) * g * g;
+    m[i] = mi;
+    v[i] = vi;
+    float* full = HALF ? master : reinterpret_cast<float*>(param);
+    const float p = full[i] - a.lr * (mi * a.inv_c1) / (sqrtf(vi * a.inv_c2) + a.eps);
+    full[i] = p;
+    if (HALF) reinterpret_cast<__half*>(param)[i] = __float2half_rn(p);
+    if (zero_grad) grad[i] = 0.f;
+}
+
 // ---- rigid transform (Eq. 9) ---------------------------------------------------------------
 struct Rigid {
     float R[9], T[3], scale, offset;
@@ -349,6 +379,41 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
     else
         hipLaunchKernelGGL(adam_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, zero_grad);
     return check_launch("adam");
+}
+
+int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
+                      float beta1, float beta2, float eps, int t, int zero_grad, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return fail(NEUS2_ERR_CONFIG, "beta1, beta2 must be in [0,1)");
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(grad, "grad"));
+    NEUS2_TRY(check_ptr(m, "m"));
+    NEUS2_TRY(check_ptr(v, "v"));
+    if (cfg->table_dtype == 1) NEUS2_TRY(check_ptr(master, "master"));
+    AdamArgs a;
+    a.lr = lr; a.b1 = beta1; a.b2 = beta2; a.eps = eps;
+    a.inv_c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
+    a.inv_c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+    const int64_t T = (int64_t)1 << cfg->log2_table_size;
+    const int F = cfg->n_features;
+    TableLevels lv;
+    memset(&lv, 0, sizeof(lv));
+    uint32_t most = 0;
+    for (int l = 0; l < cfg->n_levels; ++l) {
+        const int64_t r1 = (int64_t)cfg->res[l] + 1;
+        const int64_t slots = cfg->dense[l] ? r1 * r1 * r1 : T;     // check_config: a dense level fits T
+        lv.used[l] = (uint32_t)(slots * F);
+        if (lv.used[l] > most) most = lv.used[l];
+    }
+    const dim3 grid((most + 255u) / 256u, (unsigned)cfg->n_levels);
+    if (cfg->table_dtype == 1)
+        hipLaunchKernelGGL(adam_tables_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
+                           (uint32_t)(T * F), a, zero_grad);
+    else
+        hipLaunchKernelGGL(adam_tables_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
+                           (uint32_t)(T * F), a, zero_grad);
+    return check_launch("adam (tables)");
 }
 
 int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset, int64_t n, float* out,

@@ -302,6 +302,45 @@ def test_adam_fp32_and_fp16():
                 assert torch.equal(half, pg.to(torch.float16))
 
 
+def test_adam_tables_skips_only_unaddressable_slots():
+    """The table update leaves out the slots of dense levels no point can reach; the result must
+    be the dense update of every parameter (their gradient and moments are zero)."""
+    for k in (2, 4):
+        cfg = wl.make_config(k)
+        cfg.log2_table_size, cfg.n_levels, cfg.active_levels = 14, 8, 8      # small tables, dense and hashed levels
+        cfg.res = cfg.res[:8]
+        cfg.dense = [1 if (r + 1) ** 3 <= cfg.table_size else 0 for r in cfg.res]
+        cfg.sdf_dims = [16] + cfg.sdf_dims[1:]
+        assert 0 < sum(cfg.dense) < 8
+        c = nb.make_config(cfg)
+        rng = np.random.default_rng(30 + k)
+        L, T = cfg.n_levels, cfg.table_size
+        p = (rng.normal(size=(L, T, 2)) * 1e-3).astype(np.float32)
+        g = np.zeros((L, T, 2), dtype=np.float32)
+        m = np.zeros_like(g)
+        v = np.zeros_like(g)
+        for l in range(L):
+            used = (cfg.res[l] + 1) ** 3 if cfg.dense[l] else T
+            g[l, :used] = rng.normal(size=(used, 2)) * 1e-4
+            m[l, :used] = rng.normal(size=(used, 2)) * 1e-5
+            v[l, :used] = np.abs(rng.normal(size=(used, 2))) * 1e-9
+        half = cfg.table_dtype == "f16"
+        tab = cuda(p, torch.float16) if half else cuda(p)
+        master = cuda(p) if half else None
+        gg, mg, vg = cuda(g), cuda(m), cuda(v)
+        nb.adam_tables(c, tab, master, gg, mg, vg, 1e-2, 0.9, 0.99, 1e-15, 5)
+        torch.cuda.synchronize()
+        pr, mr, vr = o.adam_step(p, g, m, v, 5, 1e-2, 0.9, 0.99, 1e-15)
+        full = master if half else tab
+        for got, want in ((full, pr), (mg, mr), (vg, vr)):
+            got = got.cpu().numpy().astype(np.float64)
+            assert rel(got, want) <= 1e-6
+            assert np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+        assert torch.all(gg == 0)
+        if half:
+            assert torch.equal(tab, master.to(torch.float16))
+
+
 def test_rigid_forward_backward():
     rng = np.random.default_rng(4)
     n = 5000

@@ -51,7 +51,7 @@ KERNELS_OF_CALL = {
     "hash_encode": "encode_kernel", "sdf_fwd_grad": "sdf_fwd_kernel", "sdf_mlp_bwd": "sdf_bwd_kernel",
     "hash_scatter_bwd": "zero_kernel + bin_rows_kernel + scatter_owner_kernel (scatter_kernel below 2^16 points)",
     "adam_tables": "adam_tables_kernel", "adam_matrices": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
-    "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
+    "render_loss_bwd": "render_loss_kernel", "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
 }
 
 
@@ -85,6 +85,7 @@ def algorithmic_cost(cfg, n):
             "color_fwd": {"bytes": 12 + 12 + 64 + 12, "flops": 2 * col_w},
             "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 12 + 4 + 64 + 24, "flops": 2 * col_w + 4 * col_w},
             "render_rays": {"bytes": 4 + 12 + 4, "flops": 0},
+            "render_loss_bwd": {"bytes": 4 + 12 + 12 + 4 + 4 + 12 + 12, "flops": 0},
             "render_rays_bwd": {"bytes": 4 + 12 + 4 + 12, "flops": 0},
             "loss": {"bytes": 12 + 12, "flops": 0},
         })
@@ -173,9 +174,8 @@ def main() -> int:
         if cfg.loss_kind != 0:
             seq += [
                 ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb)),
-                ("render_rays", lambda: nb.render_rays(c, s.y, 16, s.rgb, rays, s.C, s.weights)),
-                ("loss", lambda: nb.loss(c, s.C, s.target, s.normal, s.y, rays, n, s.loss, s.dC, s.d_normal, None)),
-                ("render_rays_bwd", lambda: nb.render_rays_bwd(c, s.y, 16, s.rgb, s.dC, rays, s.d_sdf, s.d_rgb)),
+                ("render_loss_bwd", lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
+                                                                s.dC, s.d_sdf, s.d_rgb, s.d_normal)),
                 ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
                                                    s.d_y, s.d_normal)),
             ]

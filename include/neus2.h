@@ -179,6 +179,14 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
                            float* d_tables, float* d_pos, void* workspace, int64_t workspace_bytes,
                            void* stream);
 
+/* neus2_render_rays, neus2_loss (loss_kind 1 or 2) and neus2_render_rays_bwd in one launch,
+ * same arguments and results (sdf is column 0 of y [device, n*16]); neus2_train_step uses
+ * it.  A ray's samples stay in registers between the three stages. */
+int neus2_render_loss_bwd(const neus2_config* cfg, const float* y, const float* rgb,
+                          const float* normal, const float* target, const float* s_dev,
+                          int64_t rays, float* C, float* weights, float* loss, float* dC,
+                          float* d_sdf, float* d_rgb, float* d_normal, float* d_s, void* stream);
+
 /* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
  *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
  *   the full-precision copy, is updated, and param receives its round-to-nearest-even.

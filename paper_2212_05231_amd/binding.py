@@ -61,6 +61,7 @@ _SIGNATURES = {
     "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
+    "neus2_render_loss_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P,
                                     C.c_int64, _P]),
@@ -171,6 +172,12 @@ def render_rays(c, sdf, sdf_stride, rgb, rays, Cout, weights, s_dev=None):
 def render_rays_bwd(c, sdf, sdf_stride, rgb, dC, rays, d_sdf, d_rgb, s_dev=None, d_s=None):
     _check(lib().neus2_render_rays_bwd(C.byref(c), _ptr(sdf), sdf_stride, _ptr(rgb), _ptr(dC), _ptr(s_dev), rays,
                                        _ptr(d_sdf), _ptr(d_rgb), _ptr(d_s), _stream()))
+
+
+def render_loss_bwd(c, y, rgb, normal, target, rays, Cout, weights, loss_out, dC, d_sdf, d_rgb, d_normal, s_dev=None, d_s=None):
+    _check(lib().neus2_render_loss_bwd(C.byref(c), _ptr(y), _ptr(rgb), _ptr(normal), _ptr(target), _ptr(s_dev), rays,
+                                       _ptr(Cout), _ptr(weights), _ptr(loss_out), _ptr(dC), _ptr(d_sdf), _ptr(d_rgb),
+                                       _ptr(d_normal), _ptr(d_s), _stream()))
 
 
 def loss(c, Cimg, target, normal, y, rays, n, loss_out, dC, d_normal, d_y):

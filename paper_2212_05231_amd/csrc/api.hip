@@ -246,10 +246,8 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
     if (cfg->loss_kind != 0) {
         NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, n, b->rgb, stream));
-        NEUS2_TRY(neus2_render_rays(cfg, b->y, 16, b->rgb, b->s_dev, rays, b->C, b->weights, stream));
-        NEUS2_TRY(neus2_loss(cfg, b->C, b->target, b->normal, b->y, rays, n, b->loss, b->dC, b->d_normal, nullptr, stream));
-        NEUS2_TRY(neus2_render_rays_bwd(cfg, b->y, 16, b->rgb, b->dC, b->s_dev, rays, b->d_sdf, b->d_rgb, b->d_s,
-                                        stream));
+        NEUS2_TRY(neus2_render_loss_bwd(cfg, b->y, b->rgb, b->normal, b->target, b->s_dev, rays, b->C, b->weights, b->loss,
+                                        b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s, stream));
         NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->rgb, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
                                   b->d_normal, b->d_pos, stream));
     } else {

@@ -195,6 +195,103 @@ __global__ __launch_bounds__(kLossThreads) void loss_kernel(int kind, const floa
     block_add(eik, loss + 1, red);
 }
 
+// ---- compositing, loss and the backward of both for one ray per wavefront, in one kernel ----
+// What render_fwd_kernel, loss_kernel and render_bwd_kernel do one after the other; a ray's
+// samples stay in registers in between.  Wavefronts walk the rays with a grid stride and keep
+// their share of the two loss terms in registers, so a workgroup ends in two atomics.
+constexpr int kFusedThreads = 1024;
+
+__global__ __launch_bounds__(kFusedThreads) void render_loss_kernel(int kind, const float* __restrict__ y,
+                                                                   const float* __restrict__ rgb,
+                                                                   const float* __restrict__ normal,
+                                                                   const float* __restrict__ target, int64_t rays, int spr,
+                                                                   float s, const float* __restrict__ s_dev, float beta,
+                                                                   float huber_delta, float* __restrict__ C,
+                                                                   float* __restrict__ weights, float* __restrict__ loss,
+                                                                   float* __restrict__ dC, float* __restrict__ d_sdf,
+                                                                   float* __restrict__ d_rgb, float* __restrict__ d_normal,
+                                                                   float* __restrict__ d_s) {
+    __shared__ float red[kFusedThreads / 64];
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = (int64_t)gridDim.x * (kFusedThreads / 64);
+    if (s_dev) s = *s_dev;
+    const float inv_r = 1.f / (float)rays;
+    const float inv_n = 1.f / ((float)rays * (float)spr);
+    const bool live = lane < spr;
+    float first = 0.f, eik = 0.f, ds_total = 0.f;
+    // the inputs of a wavefront's next ray are requested before the current one is worked on
+    struct In { float d, c0, c1, c2, nx, ny, nz, t0, t1, t2; };
+    auto load = [&](int64_t ray) {
+        In in = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (ray < rays) {
+            const int64_t i = ray * spr + (live ? lane : 0);
+            if (live) {
+                in.d = y[16 * i];
+                in.c0 = rgb[3 * i]; in.c1 = rgb[3 * i + 1]; in.c2 = rgb[3 * i + 2];
+                in.nx = normal[3 * i]; in.ny = normal[3 * i + 1]; in.nz = normal[3 * i + 2];
+            }
+            in.t0 = target[3 * ray]; in.t1 = target[3 * ray + 1]; in.t2 = target[3 * ray + 2];
+        }
+        return in;
+    };
+    int64_t ray = (int64_t)blockIdx.x * (kFusedThreads / 64) + (threadIdx.x >> 6);
+    In next = load(ray);
+    for (; ray < rays; ray += waves) {
+        const int64_t i = ray * spr + (live ? lane : 0);
+        const In cur = next;
+        next = load(ray + waves);
+        const float d = cur.d, c0 = cur.c0, c1 = cur.c1, c2 = cur.c2, nx = cur.nx, ny = cur.ny, nz = cur.nz;
+        const float t0 = cur.t0, t1 = cur.t1, t2 = cur.t2;
+        // eikonal term and its adjoint
+        if (live) {
+            const float len = sqrtf(nx * nx + ny * ny + nz * nz);
+            const float dev = len - 1.f;
+            eik += beta * dev * dev * inv_n;
+            const float k = 2.f * beta * inv_n * dev / fmaxf(len, 1e-30f);
+            d_normal[3 * i] = k * nx; d_normal[3 * i + 1] = k * ny; d_normal[3 * i + 2] = k * nz;
+        }
+        // compositing
+        const RayLane r = ray_lane(d, lane, spr, s);
+        const float w = live ? r.trans * r.alpha : 0.f;
+        const float C0 = wave_sum(w * c0), C1 = wave_sum(w * c1), C2 = wave_sum(w * c2);
+        if (live) weights[i] = w;
+        // colour term and dL/dC
+        float g[3];
+        const float diff[3] = {C0 - t0, C1 - t1, C2 - t2};
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float a = fabsf(diff[c]);
+            if (kind == 1) {
+                if (lane == 0) first += a * inv_r;
+                g[c] = diff[c] > 0.f ? inv_r : (diff[c] < 0.f ? -inv_r : 0.f);
+            } else {
+                if (lane == 0) first += (a <= huber_delta ? 0.5f * diff[c] * diff[c] : huber_delta * (a - 0.5f * huber_delta)) * inv_r;
+                g[c] = fminf(fmaxf(diff[c], -huber_delta), huber_delta) * inv_r;
+            }
+        }
+        if (lane == 0) {
+            C[3 * ray] = C0; C[3 * ray + 1] = C1; C[3 * ray + 2] = C2;
+            dC[3 * ray] = g[0]; dC[3 * ray + 1] = g[1]; dC[3 * ray + 2] = g[2];
+        }
+        // backward of the compositing
+        float cb = 0.f;
+        if (live) {
+            cb = g[0] * c0 + g[1] * c1 + g[2] * c2;
+            d_rgb[3 * i] = w * g[0]; d_rgb[3 * i + 1] = w * g[1]; d_rgb[3 * i + 2] = w * g[2];
+        }
+        const float wc = w * cb;
+        const float after = wave_suffix_sum(wc, lane) - wc;
+        const float d_alpha = r.trans * cb - after / (1.f - r.alpha);
+        const float from_prev = __shfl_up(d_alpha * r.dalpha_dnext, 1);
+        float ds = d_alpha * r.dalpha_di;
+        if (lane > 0) ds += from_prev;
+        if (live) { d_sdf[i] = ds; ds_total += ds * d; }
+    }
+    block_add(first, loss + 0, red);
+    block_add(eik, loss + 1, red);
+    if (d_s) block_add(ds_total / s, d_s, red);
+}
+
 __global__ void zero_kernel(float* p, int64_t count) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0.f;
@@ -355,6 +452,35 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
                        C, target, normal, y, cfg->loss_kind != 0 ? rays : 0, n, cfg->beta, cfg->huber_delta, loss, dC, d_normal,
                        d_y);
     return check_launch("loss");
+}
+
+int neus2_render_loss_bwd(const neus2_config* cfg, const float* y, const float* rgb, const float* normal,
+                          const float* target, const float* s_dev, int64_t rays, float* C, float* weights, float* loss,
+                          float* dC, float* d_sdf, float* d_rgb, float* d_normal, float* d_s, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (cfg->loss_kind == 0) return fail(NEUS2_ERR_CONFIG, "loss_kind 0 has no colour term to composite for");
+    if (rays < 0 || rays > ((int64_t)1 << 28) / cfg->samples_per_ray) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
+    NEUS2_TRY(check_ptr(y, "y"));
+    NEUS2_TRY(check_ptr(rgb, "rgb"));
+    NEUS2_TRY(check_ptr(normal, "normal"));
+    NEUS2_TRY(check_ptr(target, "target"));
+    NEUS2_TRY(check_ptr(s_dev, "s_dev", false));
+    NEUS2_TRY(check_ptr(C, "C"));
+    NEUS2_TRY(check_ptr(weights, "weights"));
+    NEUS2_TRY(check_ptr(loss, "loss"));
+    NEUS2_TRY(check_ptr(dC, "dC"));
+    NEUS2_TRY(check_ptr(d_sdf, "d_sdf"));
+    NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_ptr(d_s, "d_s", false));
+    if (rays == 0) return NEUS2_OK;
+    const int per = kFusedThreads / 64;
+    const int64_t want = (rays + per - 1) / per;
+    const int64_t cap = (int64_t)compute_units() / 2;
+    hipLaunchKernelGGL(render_loss_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(kFusedThreads), 0,
+                       (hipStream_t)stream, cfg->loss_kind, y, rgb, normal, target, rays, cfg->samples_per_ray, cfg->s, s_dev,
+                       cfg->beta, cfg->huber_delta, C, weights, loss, dC, d_sdf, d_rgb, d_normal, d_s);
+    return check_launch("render + loss + backward");
 }
 
 int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count, int dtype, float lr,

@@ -230,6 +230,54 @@ def test_render_forward_backward_alone():
         assert abs(float(d_s.cpu()[0]) - 0.5 - ref_ds) <= GRAD_TOL * max(scale, 1e-30) + 1e-7
 
 
+@pytest.mark.parametrize("loss_kind", [1, 2])
+def test_fused_render_loss_backward_against_oracle(loss_kind):
+    """neus2_render_loss_bwd = render + loss + render backward in one launch."""
+    rng = np.random.default_rng(40 + loss_kind)
+    for spr, rays in ((64, 1500), (17, 9), (1, 5)):
+        cfg = wl.make_config(2)
+        cfg.samples_per_ray, cfg.loss_kind, cfg.huber_delta = spr, loss_kind, 0.05
+        c = nb.make_config(cfg)
+        n = rays * spr
+        sdf = (rng.normal(size=(rays, spr)) * 0.05)
+        sdf[0] = np.linspace(0.3, -0.3, spr)
+        sdf = sdf.astype(np.float32)
+        rgb = rng.uniform(size=(rays, spr, 3)).astype(np.float32)
+        normal = (rng.normal(size=(n, 3)) * 0.7).astype(np.float32)
+        target = rng.uniform(size=(rays, 3)).astype(np.float32)
+        y = np.zeros((n, 16), dtype=np.float32)
+        y[:, 0] = sdf.reshape(-1)
+        z = lambda *sh: torch.zeros(*sh, device="cuda")
+        Cg, wg, loss, dC, ds, dr, dn, d_s = z(rays, 3), z(n), z(2), z(rays, 3), z(n), z(n, 3), z(n, 3), z(1)
+        nb.render_loss_bwd(c, cuda(y), cuda(rgb.reshape(n, 3)), cuda(normal), cuda(target), rays, Cg, wg, loss, dC, ds, dr, dn,
+                           d_s=d_s)
+        torch.cuda.synchronize()
+        s64, r64 = sdf.astype(np.float64), rgb.astype(np.float64)
+        Cr, wr, _, _ = o.render_rays(s64, r64, cfg.s)
+        diff = Cr - target
+        if loss_kind == 1:
+            first, g = np.sum(np.abs(diff)) / rays, np.sign(diff) / rays
+        else:
+            first, g = np.sum(o.huber(diff, cfg.huber_delta)) / rays, o.huber_derivative(diff, cfg.huber_delta) / rays
+        ln = np.linalg.norm(normal.astype(np.float64), axis=1)
+        eik = cfg.beta * np.mean((ln - 1.0) ** 2)
+        d_normal = (2.0 * cfg.beta / n) * ((ln - 1.0) / ln)[:, None] * normal
+        d_sdf, d_rgb, ref_ds = o.render_rays_backward(s64, r64, cfg.s, g, want_ds=True)
+        got_loss = loss.cpu().numpy()
+        assert abs(got_loss[0] - first) <= FWD_TOL * first and abs(got_loss[1] - eik) <= FWD_TOL * eik
+        assert rel(Cg.cpu().numpy(), Cr) <= FWD_TOL
+        assert rel(wg.cpu().numpy().reshape(rays, spr), wr) <= FWD_TOL
+        # a colour within rounding of its target may take the other branch of |.|' in fp32: compare where it is clear
+        clear = np.abs(diff) > 1e-6
+        assert np.array_equal(dC.cpu().numpy()[clear] > 0, g[clear] > 0)
+        assert rel(dn.cpu().numpy(), d_normal) <= GRAD_TOL
+        assert rel(dr.cpu().numpy().reshape(rays, spr, 3), d_rgb) <= GRAD_TOL
+        if spr > 1:
+            assert rel(ds.cpu().numpy().reshape(rays, spr), d_sdf) <= GRAD_TOL
+            scale = float(np.sum(np.abs(d_sdf * s64))) / cfg.s
+            assert abs(float(d_s.cpu()[0]) - ref_ds) <= GRAD_TOL * scale + 1e-9
+
+
 def test_color_forward_backward_alone():
     rng = np.random.default_rng(2)
     cfg = wl.make_config(2)

@@ -217,8 +217,9 @@ def sh16(dirs: np.ndarray) -> np.ndarray:
     return out
 
 
-def color_input(pos, normal, dirs, y, samples_per_ray: int) -> np.ndarray:
-    """[x(3), n(3), SH16(v)(16), (d,g)(16)] per sample; v is the sample's ray direction."""
+def color_input(pos, normal, dirs, y, samples_per_ray) -> np.ndarray:
+    """[x(3), n(3), SH16(v)(16), (d,g)(16)] per sample; v is the sample's ray direction.
+    `samples_per_ray` is one count for all rays or an array with one count per ray."""
     sh = np.repeat(sh16(dirs), samples_per_ray, axis=0)
     return np.concatenate([np.asarray(pos, dtype=np.float64), normal, sh, y], axis=1)
 
@@ -343,11 +344,19 @@ def forward(cfg, params, batch, fp32_product: bool = True, want_hess: bool = Fal
     if cfg.loss_kind == 0:
         out["loss"] = np.mean(y[:, 0] ** 2) + cfg.beta * eik
         return out
-    n = cfg.samples_per_ray
-    R = N // n
-    cin = color_input(pos, normal, batch["dirs"], y, n)
-    rgb, cacts, cmasks = color_forward(params["W"], cin)
-    C, wgt, alpha, trans = render_rays(y[:, 0].reshape(R, n), rgb.reshape(R, n, 3), cfg.s)
+    if "ray_offsets" in batch:                       # rays with their own sample counts
+        offsets = np.asarray(batch["ray_offsets"], dtype=np.int64)
+        R = len(offsets) - 1
+        cin = color_input(pos, normal, batch["dirs"], y, np.diff(offsets))
+        rgb, cacts, cmasks = color_forward(params["W"], cin)
+        C, wgt, alpha = render_rays_ragged(y[:, 0], rgb, offsets, cfg.s)
+        trans = None
+    else:
+        n = cfg.samples_per_ray
+        R = N // n
+        cin = color_input(pos, normal, batch["dirs"], y, n)
+        rgb, cacts, cmasks = color_forward(params["W"], cin)
+        C, wgt, alpha, trans = render_rays(y[:, 0].reshape(R, n), rgb.reshape(R, n, 3), cfg.s)
     diff = C - np.asarray(batch["target"], dtype=np.float64)
     out.update({"cin": cin, "rgb": rgb, "cacts": cacts, "cmasks": cmasks, "C": C, "weights": wgt,
                 "alpha": alpha, "trans": trans, "diff": diff})
@@ -356,6 +365,36 @@ def forward(cfg, params, batch, fp32_product: bool = True, want_hess: bool = Fal
     else:
         out["loss"] = np.sum(np.abs(diff)) / R + cfg.beta * eik
     return out
+
+
+def render_rays_ragged(sdf, rgb, offsets, s: float):
+    """Rays with their own sample counts, as an occupancy-grid ray marcher produces them
+    (supplement Sec. E.3, "Ray Marching Strategy"): ray r owns samples offsets[r]..offsets[r+1]-1
+    of the flat arrays sdf [N], rgb [N,3].  Every ray is composited by `render_rays` on its own
+    slice; a ray without samples has colour 0.  -> (C [R,3], weights [N], alpha [N])."""
+    R = len(offsets) - 1
+    C = np.zeros((R, 3))
+    wgt = np.zeros(sdf.shape[0])
+    alpha = np.zeros(sdf.shape[0])
+    for r in range(R):
+        a, b = int(offsets[r]), int(offsets[r + 1])
+        if b > a:
+            Cr, wr, ar, _ = render_rays(sdf[a:b][None, :], rgb[a:b][None, :, :], s)
+            C[r], wgt[a:b], alpha[a:b] = Cr[0], wr[0], ar[0]
+    return C, wgt, alpha
+
+
+def render_rays_ragged_backward(sdf, rgb, offsets, s: float, dC):
+    """Backward of `render_rays_ragged`, ray by ray -> (d_sdf [N], d_rgb [N,3], d_s)."""
+    d_sdf = np.zeros(sdf.shape[0])
+    d_rgb = np.zeros((sdf.shape[0], 3))
+    d_s = 0.0
+    for r in range(len(offsets) - 1):
+        a, b = int(offsets[r]), int(offsets[r + 1])
+        if b > a:
+            ds, dr, dss = render_rays_backward(sdf[a:b][None, :], rgb[a:b][None, :, :], s, dC[r][None, :], want_ds=True)
+            d_sdf[a:b], d_rgb[a:b], d_s = ds[0], dr[0], d_s + dss
+    return d_sdf, d_rgb, d_s
 
 
 def huber(r: np.ndarray, delta: float) -> np.ndarray:
@@ -414,13 +453,18 @@ def train_step(cfg, params, batch, fp32_product: bool = True, want_pos_grad: boo
     if cfg.loss_kind == 0:
         d_y[:, 0] += 2.0 * y[:, 0] / N
     else:
+        ragged = "ray_offsets" in batch
         n = cfg.samples_per_ray
-        R = N // n
+        R = len(batch["ray_offsets"]) - 1 if ragged else N // n
         if cfg.loss_kind == 2:
             dC = huber_derivative(fw["diff"], cfg.huber_delta) / R
         else:
             dC = np.sign(fw["diff"]) / R
-        d_sdf, d_rgb, d_s = render_rays_backward(y[:, 0].reshape(R, n), fw["rgb"].reshape(R, n, 3), cfg.s, dC, want_ds=True)
+        if ragged:
+            d_sdf, d_rgb, d_s = render_rays_ragged_backward(y[:, 0], fw["rgb"], np.asarray(batch["ray_offsets"], dtype=np.int64),
+                                                            cfg.s, dC)
+        else:
+            d_sdf, d_rgb, d_s = render_rays_backward(y[:, 0].reshape(R, n), fw["rgb"].reshape(R, n, 3), cfg.s, dC, want_ds=True)
         fw["d_s"] = d_s
         rgb = fw["rgb"]
         d_u = d_rgb.reshape(N, 3) * rgb * (1.0 - rgb)

@@ -143,6 +143,44 @@ def make_rays(n_rays: int, samples_per_ray: int, seed: int, to_cube: bool = True
             "target": rgb.astype(np.float32)}
 
 
+def make_ragged_rays(n_rays: int, seed: int, max_len: int = 200) -> Dict[str, np.ndarray]:
+    """Rays with their own sample counts, the shape an occupancy-grid ray marcher hands to the
+    step: a fixed marching step dt = 2/128 along the chord through the unit sphere, samples only
+    on one occupied interval per ray.  Length mix: 10 % of the rays have no sample (they miss
+    the occupied cells), 75 % have 4..64, 15 % have 65..max_len (longer than one wavefront).
+
+    Returns pos [N,3] (unit cube), dirs [R,3], target [R,3] (fp32), ray_offsets [R+1] and
+    sample_ray [N] (int32).
+    """
+    rng = np.random.default_rng(seed)
+    u = rng.normal(size=(n_rays, 3))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    o = 3.0 * u
+    tgt = rng.uniform(-0.3, 0.3, size=(n_rays, 3))
+    v = tgt - o
+    v /= np.linalg.norm(v, axis=1, keepdims=True)
+    b = np.sum(o * v, axis=1)
+    root = np.sqrt(b * b - (np.sum(o * o, axis=1) - 1.0))
+    near, far = -b - root, -b + root
+    dt = 2.0 / 128.0
+    kind = rng.uniform(size=n_rays)
+    count = np.where(kind < 0.10, 0, np.where(kind < 0.85, rng.integers(min(4, max_len), min(64, max_len) + 1, size=n_rays),
+                                              rng.integers(min(65, max_len), max_len + 1, size=n_rays)))
+    count = np.minimum(count, np.floor((far - near) / dt).astype(np.int64))
+    offsets = np.zeros(n_rays + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(count)
+    N = int(offsets[-1])
+    sample_ray = np.repeat(np.arange(n_rays), count)
+    k = np.arange(N) - offsets[sample_ray]
+    t0 = near + rng.uniform(size=n_rays) * np.maximum(far - near - count * dt, 0.0)
+    t = t0[sample_ray] + (k + rng.uniform(size=N)) * dt
+    p = o[sample_ray] + t[:, None] * v[sample_ray]
+    p = np.clip((p + 1.0) * 0.5, 0.0, 1.0 - 2.0 ** -24)
+    rgb = rng.uniform(0.0, 1.0, size=(n_rays, 3))
+    return {"pos": p.astype(np.float32), "dirs": v.astype(np.float32), "target": rgb.astype(np.float32),
+            "ray_offsets": offsets.astype(np.int32), "sample_ray": sample_ray.astype(np.int32)}
+
+
 def make_rigid(seed: int, max_angle_deg: float = 5.0, max_shift: float = 0.05) -> Dict[str, np.ndarray]:
     """Workload 5: a small axis-angle vector omega and a translation, float64."""
     rng = np.random.default_rng(seed)

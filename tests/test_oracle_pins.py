@@ -389,6 +389,40 @@ def test_slope_gradient_by_finite_differences():
     assert abs(d_s) > 1e-6
 
 
+def test_ragged_rays_reduce_to_rows_and_to_finite_differences():
+    """Rays with their own sample counts (supplement Sec. E.3, ray marching): with equal counts the
+    ragged compositing is the fixed one; its gradient matches central differences; a ray without
+    samples renders black and has no gradient."""
+    rng = np.random.default_rng(12)
+    R, n, s = 5, 7, 20.0
+    sdf = rng.normal(size=(R, n)) * 0.05
+    rgb = rng.uniform(size=(R, n, 3))
+    off = np.arange(R + 1) * n
+    C, w, a = o.render_rays_ragged(sdf.reshape(-1), rgb.reshape(-1, 3), off, s)
+    Cf, wf, af, _ = o.render_rays(sdf, rgb, s)
+    assert np.array_equal(C, Cf) and np.array_equal(w, wf.reshape(-1)) and np.array_equal(a, af.reshape(-1))
+    off = np.array([0, 3, 3, 11, 12, 35])              # lengths 3, 0, 8, 1, 23
+    N = off[-1]
+    sdf = rng.normal(size=N) * 0.05
+    sdf[12:35] = np.linspace(0.2, -0.2, 23)            # a ray that crosses the surface
+    rgb = rng.uniform(size=(N, 3))
+    dC = rng.normal(size=(5, 3))
+    C, w, a = o.render_rays_ragged(sdf, rgb, off, s)
+    assert np.all(C[1] == 0) and a[2] == 0 and a[10] == 0 and a[11] == 0 and a[34] == 0    # last samples, empty ray
+    assert np.sum(w[12:35]) > 0.9
+    d_sdf, d_rgb, d_s = o.render_rays_ragged_backward(sdf, rgb, off, s, dC)
+    f = lambda sd, c, ss: float(np.sum(o.render_rays_ragged(sd, c, off, ss)[0] * dC))
+    h = 1e-6
+    for i in range(N):
+        e = np.zeros(N); e[i] = h
+        assert abs((f(sdf + e, rgb, s) - f(sdf - e, rgb, s)) / (2 * h) - d_sdf[i]) < 1e-7
+    for i in (0, 5, 20):
+        e = np.zeros((N, 3)); e[i, 1] = h
+        assert abs((f(sdf, rgb + e, s) - f(sdf, rgb - e, s)) / (2 * h) - d_rgb[i, 1]) < 1e-8
+    assert abs((f(sdf, rgb, s + 1e-5) - f(sdf, rgb, s - 1e-5)) / 2e-5 - d_s) < 1e-8
+    assert d_sdf[11] == 0                              # a single sample has alpha 0: no gradient
+
+
 def test_huber_closed_forms():
     """Eq. 4 names the Huber loss for the colour term."""
     r = np.array([-0.5, -0.1, -0.03, 0.0, 0.02, 0.1, 0.7])
@@ -488,6 +522,19 @@ def test_whole_step_gradients_by_finite_differences(loss_kind, sdf):
     if loss_kind == 2:
         d = np.abs(out["diff"])
         assert np.any(d <= cfg.huber_delta) and np.any(d > cfg.huber_delta)   # both branches of Huber
+
+
+def test_whole_step_gradients_with_ragged_rays():
+    """The same finite-difference check with rays of different lengths (0, 1, short, long)."""
+    cfg, params, _ = tiny_problem(seed=27, rays=5, loss_kind=1, sdf=(6, 8, 8, 16))
+    batch = wl.make_ragged_rays(14, seed=5, max_len=40)
+    batch = {k: (v.astype(np.float64) if v.dtype == np.float32 else v) for k, v in batch.items()}
+    lengths = np.diff(batch["ray_offsets"])
+    assert np.any(lengths == 0) and np.any(lengths > 20)
+    out = o.train_step(cfg, params, batch, fp32_product=False)
+    rng = np.random.default_rng(10)
+    assert _check_all_grads(cfg, params, batch, out, rng) > 100
+    assert np.any(out["alpha"] > 0.01)
 
 
 def test_second_order_terms_alone_and_negative_controls(monkeypatch):

@@ -107,6 +107,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=2, help="1..4 (benchmark configuration number)")
     ap.add_argument("--rays", type=int, default=None, help="override the number of rays (points for workload 1)")
+    ap.add_argument("--ragged", action="store_true",
+                    help="rays with their own sample counts (the length mix of a ray marcher) instead of a fixed count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -129,8 +131,15 @@ def main() -> int:
     torch.cuda.set_device(0)
     w = wl.make_workload(args.workload, n_rays=args.rays)
     cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    if args.ragged:
+        if cfg.loss_kind == 0:
+            print("bench.py: --ragged needs a workload with rays (2..4)", file=sys.stderr)
+            return 2
+        # about as many samples as the fixed workload: the mix averages 43 samples per ray
+        batch = wl.make_ragged_rays(args.rays or (wl.default_rays(args.workload) * cfg.samples_per_ray) // 43, seed=2000 + args.workload)
+        cfg.name = f"cfg{args.workload}-ragged-{batch['dirs'].shape[0]}rays"
     n = batch["pos"].shape[0]
-    step = nb.Step(cfg, params, n)
+    step = nb.Step(cfg, params, n, n_rays=batch["dirs"].shape[0] if args.ragged else None)
     step.set_batch(batch)
     step.zero_grads()
     step.init_optimizer()
@@ -173,11 +182,14 @@ def main() -> int:
                ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal))]
         if cfg.loss_kind != 0:
             seq += [
-                ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb)),
-                ("render_loss_bwd", lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
-                                                                s.dC, s.d_sdf, s.d_rgb, s.d_normal)),
+                ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb, sample_ray=s.sample_ray)),
+                ("render_loss_bwd", (lambda: nb.render_loss_bwd_ragged(c, s.y, s.rgb, s.normal, s.target, s.ray_offsets, rays, n,
+                                                                       s.C, s.weights, s.loss, s.dC, s.d_sdf, s.d_rgb, s.d_normal))
+                 if args.ragged else
+                 (lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
+                                             s.dC, s.d_sdf, s.d_rgb, s.d_normal))),
                 ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
-                                                   s.d_y, s.d_normal)),
+                                                   s.d_y, s.d_normal, sample_ray=s.sample_ray)),
             ]
         else:
             seq += [("loss", lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y))]
@@ -233,8 +245,10 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_limits
         from oracle import neus2_oracle as o
-        sample_rays = min(512, n // cfg.samples_per_ray)
+        sample_rays = min(128 if args.ragged else 512, step.rays)
         ws = wl.make_workload(args.workload, n_rays=sample_rays)
+        if args.ragged:
+            ws["batch"] = wl.make_ragged_rays(sample_rays, seed=2000 + args.workload)
         with threadpool_limits(limits=1):
             t0 = time.perf_counter()
             reps = 0
@@ -246,16 +260,16 @@ def main() -> int:
                     break
         ns = ws["batch"]["pos"].shape[0]
         cpu = {"value": round(ns * reps / el, 1), "unit": "ray-samples/s", "cores": 1, "kind": "oracle",
-               "sample": f"{reps} forward+backward steps of the float64 numpy oracle on {sample_rays} rays x "
-                         f"{cfg.samples_per_ray} samples of the same workload (no Adam), {el:.1f} s, BLAS limited to 1 thread"}
+               "sample": f"{reps} forward+backward steps of the float64 numpy oracle on {sample_rays} rays "
+                         f"({ns} samples) of the same workload (no Adam), {el:.1f} s, BLAS limited to 1 thread"}
 
     line = {
         "metric": "ray-samples/sec per training step (fwd+2nd-order bwd)",
         "value": round(value, 1), "unit": "ray-samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "points_per_step": n, "rays": n // cfg.samples_per_ray,
-                   "samples_per_ray": cfg.samples_per_ray, "levels": cfg.n_levels, "active_levels": cfg.active_levels,
+        "config": {"workload": cfg.name, "points_per_step": n, "rays": step.rays,
+                   "samples_per_ray": "0..128 per ray (ray marcher's mix)" if args.ragged else cfg.samples_per_ray, "levels": cfg.n_levels, "active_levels": cfg.active_levels,
                    "log2_table_size": cfg.log2_table_size, "table_dtype": cfg.table_dtype,
                    "sdf_mlp": cfg.sdf_dims, "color_mlp": cfg.color_dims, "includes_adam": True},
         "loss": loss_now,

@@ -100,10 +100,11 @@ int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* j
 
 /* Colour network forward (Eq. 3): rgb = sigmoid(W_3 relu(W_2 relu(W_1 cin))),
  * cin = [pos(3), normal(3), SH16(dir)(16), y(16)]; dirs [device, rays*3] are unit vectors,
- * sample i uses ray i / samples_per_ray.  rgb [device, n*3]. */
+ * sample i uses ray sample_ray[i] (sample_ray [device, n int32], rays with their own sample
+ * counts) or, with sample_ray NULL, ray i / samples_per_ray.  rgb [device, n*3]. */
 int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal,
-                    const float* dirs, const float* y, const float* const* W, int64_t n,
-                    float* rgb, void* stream);
+                    const float* dirs, const int32_t* sample_ray, const float* y,
+                    const float* const* W, int64_t n, float* rgb, void* stream);
 
 /* First-order backward of the colour network (the paper needs no second-order term for
  * Upsilon, text after Eq. 6).
@@ -115,7 +116,8 @@ int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* norm
  *   d_normal [device, n*3] is ADDED into (it already holds the eikonal part);
  *   d_pos [device, n*3] or NULL is OVERWRITTEN with the colour network's dL/dx. */
 int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal,
-                    const float* dirs, const float* y, const float* const* W, const float* rgb,
+                    const float* dirs, const int32_t* sample_ray, const float* y,
+                    const float* const* W, const float* rgb,
                     const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
                     float* d_y, float* d_normal, float* d_pos, void* stream);
 
@@ -187,6 +189,18 @@ int neus2_render_loss_bwd(const neus2_config* cfg, const float* y, const float* 
                           int64_t rays, float* C, float* weights, float* loss, float* dC,
                           float* d_sdf, float* d_rgb, float* d_normal, float* d_s, void* stream);
 
+/* The same for rays with their own sample counts (an occupancy-grid ray marcher, supplement
+ * Sec. E.3): ray r owns samples ray_offsets[r] .. ray_offsets[r+1]-1 of the n samples
+ * (ray_offsets [device, rays+1 int32], non-decreasing, first 0, last n); any count, also 0
+ * (such a ray renders black and still enters the colour term).  The last sample of a ray has
+ * alpha 0.  The colour term is averaged over rays, the eikonal term over the n samples. */
+int neus2_render_loss_bwd_ragged(const neus2_config* cfg, const float* y, const float* rgb,
+                                 const float* normal, const float* target,
+                                 const int32_t* ray_offsets, const float* s_dev, int64_t rays,
+                                 int64_t n, float* C, float* weights, float* loss, float* dC,
+                                 float* d_sdf, float* d_rgb, float* d_normal, float* d_s,
+                                 void* stream);
+
 /* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
  *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
  *   the full-precision copy, is updated, and param receives its round-to-nearest-even.
@@ -215,7 +229,7 @@ int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float 
 
 /* All buffers of one training step, for neus2_train_step.  Every pointer is [device] except
  * H, W, dH, dW, which are [host] arrays of device pointers.  Sizes as in the calls above;
- * rays * samples_per_ray = n. */
+ * rays * samples_per_ray = n, unless ray_offsets / sample_ray describe the rays. */
 typedef struct neus2_step_buffers {
     const float* pos; const float* dirs; const float* target; const void* tables;
     const float* const* H; const float* const* W;
@@ -228,6 +242,9 @@ typedef struct neus2_step_buffers {
     int64_t workspace_bytes;
     const float* s_dev;        /* optional, see neus2_render_rays */
     float* d_s;                /* optional, see neus2_render_rays_bwd (ADDED into) */
+    const int32_t* ray_offsets;/* optional: rays with their own sample counts, see          */
+    const int32_t* sample_ray; /*   neus2_render_loss_bwd_ragged and neus2_color_fwd; both or */
+    int64_t n_rays;            /*   neither; n_rays is read only when they are given         */
 } neus2_step_buffers;
 
 /* One forward + backward pass (everything above except Adam and the rigid transform), in the

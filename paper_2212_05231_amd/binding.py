@@ -39,7 +39,8 @@ class Neus2StepBuffers(C.Structure):
         "pos", "dirs", "target", "tables", "H", "W",
         "enc", "jac", "y", "q", "normal", "rgb", "C", "weights", "loss",
         "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables", "workspace")] + [
-        ("workspace_bytes", C.c_int64), ("s_dev", _P), ("d_s", _P)]
+        ("workspace_bytes", C.c_int64), ("s_dev", _P), ("d_s", _P), ("ray_offsets", _P), ("sample_ray", _P),
+        ("n_rays", C.c_int64)]
 
 
 class Neus2Error(RuntimeError):
@@ -57,8 +58,10 @@ _SIGNATURES = {
     "neus2_workspace_bytes": (C.c_int64, [C.POINTER(Neus2Config), C.c_int64]),
     "neus2_hash_encode": (C.c_int, [C.POINTER(Neus2Config), _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
-    "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
-    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
+    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_render_loss_bwd_ragged": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P,
+                                               _P, _P, _P, _P, _P, _P]),
     "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
     "neus2_render_rays_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
     "neus2_render_loss_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
@@ -153,13 +156,13 @@ def sdf_fwd_grad(c, enc, jac, H, n, y, q, normal):
                                     _ptr(normal), _stream()))
 
 
-def color_fwd(c, pos, normal, dirs, y, W, n, rgb):
-    _check(lib().neus2_color_fwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(y), _ptr_array(W), n,
+def color_fwd(c, pos, normal, dirs, y, W, n, rgb, sample_ray=None):
+    _check(lib().neus2_color_fwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(sample_ray), _ptr(y), _ptr_array(W), n,
                                  _ptr(rgb), _stream()))
 
 
-def color_bwd(c, pos, normal, dirs, y, W, rgb, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None):
-    _check(lib().neus2_color_bwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(y), _ptr_array(W),
+def color_bwd(c, pos, normal, dirs, y, W, rgb, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None, sample_ray=None):
+    _check(lib().neus2_color_bwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(sample_ray), _ptr(y), _ptr_array(W),
                                  _ptr(rgb), _ptr(d_rgb), _ptr(d_sdf), n, _ptr_array(dW), _ptr(d_y), _ptr(d_normal),
                                  _ptr(d_pos), _stream()))
 
@@ -178,6 +181,13 @@ def render_loss_bwd(c, y, rgb, normal, target, rays, Cout, weights, loss_out, dC
     _check(lib().neus2_render_loss_bwd(C.byref(c), _ptr(y), _ptr(rgb), _ptr(normal), _ptr(target), _ptr(s_dev), rays,
                                        _ptr(Cout), _ptr(weights), _ptr(loss_out), _ptr(dC), _ptr(d_sdf), _ptr(d_rgb),
                                        _ptr(d_normal), _ptr(d_s), _stream()))
+
+
+def render_loss_bwd_ragged(c, y, rgb, normal, target, ray_offsets, rays, n, Cout, weights, loss_out, dC, d_sdf, d_rgb,
+                           d_normal, s_dev=None, d_s=None):
+    _check(lib().neus2_render_loss_bwd_ragged(C.byref(c), _ptr(y), _ptr(rgb), _ptr(normal), _ptr(target), _ptr(ray_offsets),
+                                              _ptr(s_dev), rays, n, _ptr(Cout), _ptr(weights), _ptr(loss_out), _ptr(dC),
+                                              _ptr(d_sdf), _ptr(d_rgb), _ptr(d_normal), _ptr(d_s), _stream()))
 
 
 def loss(c, Cimg, target, normal, y, rays, n, loss_out, dC, d_normal, d_y):
@@ -234,11 +244,14 @@ class Step:
     `neus2_step_buffers` struct that `train_step` hands to the library."""
 
     def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda",
-                 use_workspace: bool = True, learn_s: bool = False):
+                 use_workspace: bool = True, learn_s: bool = False, n_rays: Optional[int] = None):
+        """`n_rays` given: rays have their own sample counts (set_batch then wants "ray_offsets"
+        and "sample_ray"); otherwise n / samples_per_ray rays of equal length."""
         import torch
         self.cfg, self.c, self.n = cfg, make_config(cfg), n
         L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
-        self.rays = n // cfg.samples_per_ray
+        self.ragged = n_rays is not None
+        self.rays = n_rays if self.ragged else n // cfg.samples_per_ray
         f32 = dict(dtype=torch.float32, device=device)
         tdt = torch.float16 if cfg.table_dtype == "f16" else torch.float32
         self.tables = torch.as_tensor(params["tables"]).to(device=device, dtype=tdt).contiguous()
@@ -275,6 +288,8 @@ class Step:
         self.C, self.dC = z(max(self.rays, 1), 3), z(max(self.rays, 1), 3)
         self.weights, self.d_sdf = z(n), z(n)
         self.loss = z(4)
+        self.ray_offsets = torch.zeros(self.rays + 1, dtype=torch.int32, device=device) if self.ragged else None
+        self.sample_ray = torch.zeros(max(n, 1), dtype=torch.int32, device=device) if self.ragged else None
         self.d_pos = z(n, 3) if want_pos_grad else None
         self.dH, self.dW = gviews[:nH], gviews[nH:]
         self.opt = None
@@ -286,11 +301,12 @@ class Step:
         b = Neus2StepBuffers()
         for name in ("pos", "dirs", "target", "tables", "enc", "jac", "y", "q", "normal", "rgb", "C", "weights",
                      "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables", "workspace",
-                     "s_dev", "d_s"):
+                     "s_dev", "d_s", "ray_offsets", "sample_ray"):
             setattr(b, name, _ptr(getattr(self, name)))
         b.H, b.W = C.cast(self._H, _P), C.cast(self._W, _P)
         b.dH, b.dW = C.cast(self._dH, _P), C.cast(self._dW, _P)
         b.workspace_bytes = ws if self.workspace is not None else 0
+        b.n_rays = self.rays
         self.buffers = b
 
     def set_batch(self, batch: Dict[str, object]) -> None:
@@ -299,6 +315,10 @@ class Step:
         if "dirs" in batch:
             self.dirs.copy_(torch.as_tensor(batch["dirs"], dtype=torch.float32))
             self.target.copy_(torch.as_tensor(batch["target"], dtype=torch.float32))
+        if self.ragged:
+            self.ray_offsets.copy_(torch.as_tensor(batch["ray_offsets"], dtype=torch.int32))
+            if self.n > 0:
+                self.sample_ray.copy_(torch.as_tensor(batch["sample_ray"], dtype=torch.int32))
 
     def zero_grads(self) -> None:
         self.d_small.zero_()

@@ -233,22 +233,36 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
 extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* b, int64_t n, void* stream) {
     NEUS2_TRY(check_config(cfg));
     if (!b) return fail(NEUS2_ERR_NULL, "buf is NULL");
-    if (n < 0 || n % cfg->samples_per_ray != 0)
+    const bool ragged = b->ray_offsets != nullptr;
+    if (ragged != (b->sample_ray != nullptr)) return fail(NEUS2_ERR_NULL, "ray_offsets and sample_ray go together");
+    if (ragged && cfg->loss_kind == 0) return fail(NEUS2_ERR_CONFIG, "loss_kind 0 has no rays");
+    if (n < 0 || (!ragged && n % cfg->samples_per_ray != 0))
         return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
+    if (ragged && b->n_rays < 0) return fail(NEUS2_ERR_SHAPE, "n_rays = %lld is negative", (long long)b->n_rays);
     if (cfg->loss_kind != 0 && cfg->n_color_mats != 3)
         return fail(NEUS2_ERR_CONFIG, "loss_kind %d needs the colour network", cfg->loss_kind);
     NEUS2_TRY(check_ptr(b->loss, "loss"));
     hipStream_t st = (hipStream_t)stream;
-    const int64_t rays = n / cfg->samples_per_ray;
+    const int64_t rays = ragged ? b->n_rays : n / cfg->samples_per_ray;
     NEUS2_TRY(launch_zero(b->loss, 2, st));
-    if (n == 0) return NEUS2_OK;   // an empty batch has no buffers to look at
+    if (n == 0) {                  // an empty batch has no sample buffers to look at
+        if (ragged && rays > 0)    // rays without samples still enter the colour term
+            return neus2_render_loss_bwd_ragged(cfg, nullptr, nullptr, nullptr, b->target, b->ray_offsets, b->s_dev, rays, 0,
+                                                b->C, nullptr, b->loss, b->dC, nullptr, nullptr, nullptr, b->d_s, stream);
+        return NEUS2_OK;
+    }
     NEUS2_TRY(neus2_hash_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, stream));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
     if (cfg->loss_kind != 0) {
-        NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, n, b->rgb, stream));
-        NEUS2_TRY(neus2_render_loss_bwd(cfg, b->y, b->rgb, b->normal, b->target, b->s_dev, rays, b->C, b->weights, b->loss,
-                                        b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s, stream));
-        NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->y, b->W, b->rgb, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
+        NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, stream));
+        if (ragged)
+            NEUS2_TRY(neus2_render_loss_bwd_ragged(cfg, b->y, b->rgb, b->normal, b->target, b->ray_offsets, b->s_dev, rays, n,
+                                                   b->C, b->weights, b->loss, b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s,
+                                                   stream));
+        else
+            NEUS2_TRY(neus2_render_loss_bwd(cfg, b->y, b->rgb, b->normal, b->target, b->s_dev, rays, b->C, b->weights, b->loss,
+                                            b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s, stream));
+        NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, b->rgb, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
                                   b->d_normal, b->d_pos, stream));
     } else {
         NEUS2_TRY(neus2_loss(cfg, nullptr, nullptr, b->normal, b->y, 0, n, b->loss, nullptr, b->d_normal, b->d_y, stream));

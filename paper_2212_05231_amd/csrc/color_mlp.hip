@@ -22,7 +22,7 @@ constexpr int kLdIn = 44;      // row stride of W_1 in LDS (40 used columns)
 constexpr int kLdOutT = 12;    // row stride of W_3^T in LDS (3 used columns)
 
 struct ColorArgs {
-    const float* pos; const float* normal; const float* dirs; const float* y; const float* W[3];
+    const float* pos; const float* normal; const float* dirs; const int32_t* sample_ray; const float* y; const float* W[3];
     const float* d_rgb; const float* d_sdf; const float* rgb_in;
     float* rgb; float* dW[3]; float* d_y; float* d_normal; float* d_pos;
     int64_t n; int spr;
@@ -112,7 +112,7 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
     if (!valid) return r;
     r.ya = *reinterpret_cast<const float4*>(a.y + i * 16 + 4 * h);
     r.yb = *reinterpret_cast<const float4*>(a.y + i * 16 + 8 + 4 * h);
-    const int64_t ray = i / a.spr;
+    const int64_t ray = a.sample_ray ? (int64_t)a.sample_ray[i] : i / a.spr;
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
         r.dir[c] = a.dirs[3 * ray + c];
@@ -297,12 +297,12 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     }
 }
 
-int check_common(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
-                 const float* const* W, int64_t n) {
+int check_common(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs,
+                 const int32_t* sample_ray, const float* y, const float* const* W, int64_t n) {
     NEUS2_TRY(check_config(cfg));
     if (cfg->n_color_mats != 3) return fail(NEUS2_ERR_CONFIG, "the descriptor has no colour network");
     if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
-    if (n % cfg->samples_per_ray != 0)
+    if (!sample_ray && n % cfg->samples_per_ray != 0)
         return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
     NEUS2_TRY(check_ptr(pos, "pos"));
     NEUS2_TRY(check_ptr(normal, "normal"));
@@ -321,23 +321,24 @@ using namespace neus2;
 
 extern "C" {
 
-int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
-                    const float* const* W, int64_t n, float* rgb, void* stream) {
-    NEUS2_TRY(check_common(cfg, pos, normal, dirs, y, W, n));
+int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs,
+                    const int32_t* sample_ray, const float* y, const float* const* W, int64_t n, float* rgb, void* stream) {
+    NEUS2_TRY(check_common(cfg, pos, normal, dirs, sample_ray, y, W, n));
     NEUS2_TRY(check_ptr(rgb, "rgb"));
     if (n == 0) return NEUS2_OK;
     ColorArgs a = {};
-    a.pos = pos; a.normal = normal; a.dirs = dirs; a.y = y; a.rgb = rgb; a.n = n; a.spr = cfg->samples_per_ray;
+    a.pos = pos; a.normal = normal; a.dirs = dirs; a.sample_ray = sample_ray; a.y = y; a.rgb = rgb; a.n = n;
+    a.spr = cfg->samples_per_ray;
     for (int l = 0; l < 3; ++l) a.W[l] = W[l];
     const int blocks = persistent_blocks((const void*)color_fwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
     hipLaunchKernelGGL(color_fwd_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
     return check_launch("colour forward");
 }
 
-int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs, const float* y,
-                    const float* const* W, const float* rgb, const float* d_rgb, const float* d_sdf, int64_t n,
+int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs,
+                    const int32_t* sample_ray, const float* y, const float* const* W, const float* rgb, const float* d_rgb, const float* d_sdf, int64_t n,
                     float* const* dW, float* d_y, float* d_normal, float* d_pos, void* stream) {
-    NEUS2_TRY(check_common(cfg, pos, normal, dirs, y, W, n));
+    NEUS2_TRY(check_common(cfg, pos, normal, dirs, sample_ray, y, W, n));
     NEUS2_TRY(check_ptr(rgb, "rgb"));
     NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
     NEUS2_TRY(check_ptr(d_sdf, "d_sdf", false));
@@ -348,7 +349,7 @@ int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* norm
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
     if (n == 0) return NEUS2_OK;
     ColorArgs a = {};
-    a.pos = pos; a.normal = normal; a.dirs = dirs; a.y = y; a.n = n; a.spr = cfg->samples_per_ray;
+    a.pos = pos; a.normal = normal; a.dirs = dirs; a.sample_ray = sample_ray; a.y = y; a.n = n; a.spr = cfg->samples_per_ray;
     a.rgb_in = rgb; a.d_rgb = d_rgb; a.d_sdf = d_sdf; a.d_y = d_y; a.d_normal = d_normal; a.d_pos = d_pos;
     for (int l = 0; l < 3; ++l) { a.W[l] = W[l]; a.dW[l] = dW[l]; }
     const int blocks = persistent_blocks((const void*)color_bwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);

@@ -292,6 +292,144 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_kernel(int kind, co
     if (d_s) block_add(ds_total / s, d_s, red);
 }
 
+// ---- the same for rays with their own sample counts ------------------------------------------
+// Ray r owns samples offsets[r] .. offsets[r+1]-1 (what an occupancy-grid ray marcher produces,
+// supplement Sec. E.3).  One wavefront per ray walks the ray in chunks of 64 samples: forwards
+// for T, C and the loss (the transmittance at the start of chunk k is kept in lane k of one
+// register), then backwards for the adjoints, carrying the sum over later samples.
+struct AlphaTerms {
+    float alpha, dalpha_di, dalpha_dnext;
+};
+
+__device__ __forceinline__ AlphaTerms alpha_terms(float d, float dn, bool has_next, float s) {
+    AlphaTerms r = {0.f, 0.f, 0.f};
+    const float delta = d - dn;
+    if (has_next && delta > 0.f) {
+        const float one_minus_phi_n = 1.f / (1.f + __expf(s * dn));
+        const float phi_n = 1.f - one_minus_phi_n;
+        const float em = -expm1f(-s * delta);
+        const float e = 1.f - em;
+        r.alpha = one_minus_phi_n * em;
+        r.dalpha_di = one_minus_phi_n * s * e;
+        r.dalpha_dnext = -s * phi_n * one_minus_phi_n * em - r.dalpha_di;
+    }
+    return r;
+}
+
+// product of (1 - alpha) over the 64 samples from `first` (samples at or beyond `end` count as 1)
+__device__ __forceinline__ float chunk_transmittance(const float* __restrict__ y, int64_t first, int64_t end, int lane, float s) {
+    const int64_t i = first + lane;
+    float one_minus = 1.f;
+    if (i + 1 < end) one_minus = 1.f - alpha_terms(y[16 * i], y[16 * (i + 1)], true, s).alpha;
+    return __shfl(wave_scan_mul(one_minus, lane), 63);
+}
+
+__global__ __launch_bounds__(kFusedThreads) void render_loss_ragged_kernel(
+    int kind, const float* __restrict__ y, const float* __restrict__ rgb, const float* __restrict__ normal,
+    const float* __restrict__ target, const int32_t* __restrict__ offsets, int64_t rays, int64_t n, float s,
+    const float* __restrict__ s_dev, float beta, float huber_delta, float* __restrict__ C, float* __restrict__ weights,
+    float* __restrict__ loss, float* __restrict__ dC, float* __restrict__ d_sdf, float* __restrict__ d_rgb,
+    float* __restrict__ d_normal, float* __restrict__ d_s) {
+    __shared__ float red[kFusedThreads / 64];
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = (int64_t)gridDim.x * (kFusedThreads / 64);
+    if (s_dev) s = *s_dev;
+    const float inv_r = 1.f / (float)rays;
+    const float inv_n = 1.f / (float)n;
+    float first = 0.f, eik = 0.f, ds_total = 0.f;
+    for (int64_t ray = (int64_t)blockIdx.x * (kFusedThreads / 64) + (threadIdx.x >> 6); ray < rays; ray += waves) {
+        const int64_t begin = offsets[ray], end = offsets[ray + 1];
+        const int64_t chunks = (end - begin + 63) / 64;
+        // ---- forwards
+        float t_carry = 1.f, t_start = 1.f, C0 = 0.f, C1 = 0.f, C2 = 0.f;
+        for (int64_t c = 0; c < chunks; ++c) {
+            const int64_t i = begin + 64 * c + lane;
+            const bool live = i < end, has_next = i + 1 < end;
+            float d = 0.f, dn = 0.f, c0 = 0.f, c1 = 0.f, c2 = 0.f;
+            if (live) {
+                d = y[16 * i];
+                c0 = rgb[3 * i]; c1 = rgb[3 * i + 1]; c2 = rgb[3 * i + 2];
+                const float nx = normal[3 * i], ny = normal[3 * i + 1], nz = normal[3 * i + 2];
+                const float len = sqrtf(nx * nx + ny * ny + nz * nz);
+                const float dev = len - 1.f;
+                eik += beta * dev * dev * inv_n;
+                const float k = 2.f * beta * inv_n * dev / fmaxf(len, 1e-30f);
+                d_normal[3 * i] = k * nx; d_normal[3 * i + 1] = k * ny; d_normal[3 * i + 2] = k * nz;
+            }
+            if (has_next) dn = y[16 * (i + 1)];
+            const AlphaTerms a = alpha_terms(d, dn, has_next, s);
+            if (c < 64 && lane == (int)c) t_start = t_carry;
+            const float incl = wave_scan_mul(1.f - a.alpha, lane);
+            const float excl = __shfl_up(incl, 1);
+            const float trans = t_carry * (lane == 0 ? 1.f : excl);
+            const float w = live ? trans * a.alpha : 0.f;
+            if (live) weights[i] = w;
+            C0 += wave_sum(w * c0); C1 += wave_sum(w * c1); C2 += wave_sum(w * c2);
+            t_carry *= __shfl(incl, 63);
+        }
+        // ---- colour term and dL/dC
+        float g[3];
+        const float diff[3] = {C0 - target[3 * ray], C1 - target[3 * ray + 1], C2 - target[3 * ray + 2]};
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float a = fabsf(diff[c]);
+            if (kind == 1) {
+                if (lane == 0) first += a * inv_r;
+                g[c] = diff[c] > 0.f ? inv_r : (diff[c] < 0.f ? -inv_r : 0.f);
+            } else {
+                if (lane == 0) first += (a <= huber_delta ? 0.5f * diff[c] * diff[c] : huber_delta * (a - 0.5f * huber_delta)) * inv_r;
+                g[c] = fminf(fmaxf(diff[c], -huber_delta), huber_delta) * inv_r;
+            }
+        }
+        if (lane == 0) {
+            C[3 * ray] = C0; C[3 * ray + 1] = C1; C[3 * ray + 2] = C2;
+            dC[3 * ray] = g[0]; dC[3 * ray + 1] = g[1]; dC[3 * ray + 2] = g[2];
+        }
+        // ---- backwards
+        float after_carry = 0.f, pending = 0.f;          // pending: dL/dd of the first sample of the chunk after this one,
+        for (int64_t c = chunks - 1; c >= 0; --c) {      // still without the term from this chunk's last sample
+            const int64_t base = begin + 64 * c;
+            const int64_t i = base + lane;
+            const bool live = i < end, has_next = i + 1 < end;
+            float d = 0.f, dn = 0.f, c0 = 0.f, c1 = 0.f, c2 = 0.f;
+            if (live) { d = y[16 * i]; c0 = rgb[3 * i]; c1 = rgb[3 * i + 1]; c2 = rgb[3 * i + 2]; }
+            if (has_next) dn = y[16 * (i + 1)];
+            const AlphaTerms a = alpha_terms(d, dn, has_next, s);
+            float t_chunk;
+            if (c < 64) {
+                t_chunk = __shfl(t_start, (int)c);
+            } else {                                     // rays beyond 4096 samples: walk on from chunk 63
+                t_chunk = __shfl(t_start, 63);
+                for (int64_t k = 63; k < c; ++k) t_chunk *= chunk_transmittance(y, begin + 64 * k, end, lane, s);
+            }
+            const float incl = wave_scan_mul(1.f - a.alpha, lane);
+            const float excl = __shfl_up(incl, 1);
+            const float trans = t_chunk * (lane == 0 ? 1.f : excl);
+            const float w = live ? trans * a.alpha : 0.f;
+            float cb = 0.f;
+            if (live) {
+                cb = g[0] * c0 + g[1] * c1 + g[2] * c2;
+                d_rgb[3 * i] = w * g[0]; d_rgb[3 * i + 1] = w * g[1]; d_rgb[3 * i + 2] = w * g[2];
+            }
+            const float wc = w * cb;
+            const float after = wave_suffix_sum(wc, lane) - wc + after_carry;
+            const float d_alpha = trans * cb - after / (1.f - a.alpha);
+            const float to_next = d_alpha * a.dalpha_dnext;
+            float ds = d_alpha * a.dalpha_di;
+            const float from_prev = __shfl_up(to_next, 1);
+            if (lane > 0) ds += from_prev;
+            ds_total += d_alpha * (a.dalpha_di * d + a.dalpha_dnext * dn);
+            if (c + 1 < chunks && lane == 63) d_sdf[base + 64] = pending + to_next;
+            pending = __shfl(ds, 0);
+            if (live && (lane > 0 || c == 0)) d_sdf[i] = ds;
+            after_carry += wave_sum(wc);
+        }
+    }
+    block_add(first, loss + 0, red);
+    block_add(eik, loss + 1, red);
+    if (d_s) block_add(ds_total / s, d_s, red);
+}
+
 __global__ void zero_kernel(float* p, int64_t count) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0.f;
@@ -481,6 +619,40 @@ int neus2_render_loss_bwd(const neus2_config* cfg, const float* y, const float* 
                        (hipStream_t)stream, cfg->loss_kind, y, rgb, normal, target, rays, cfg->samples_per_ray, cfg->s, s_dev,
                        cfg->beta, cfg->huber_delta, C, weights, loss, dC, d_sdf, d_rgb, d_normal, d_s);
     return check_launch("render + loss + backward");
+}
+
+int neus2_render_loss_bwd_ragged(const neus2_config* cfg, const float* y, const float* rgb, const float* normal,
+                                 const float* target, const int32_t* ray_offsets, const float* s_dev, int64_t rays,
+                                 int64_t n, float* C, float* weights, float* loss, float* dC, float* d_sdf, float* d_rgb,
+                                 float* d_normal, float* d_s, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    if (cfg->loss_kind == 0) return fail(NEUS2_ERR_CONFIG, "loss_kind 0 has no colour term to composite for");
+    if (rays < 0 || rays > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "rays = %lld out of range", (long long)rays);
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    if (!ray_offsets) return fail(NEUS2_ERR_NULL, "ray_offsets is NULL");
+    NEUS2_TRY(check_ptr(target, "target"));
+    NEUS2_TRY(check_ptr(s_dev, "s_dev", false));
+    NEUS2_TRY(check_ptr(C, "C"));
+    NEUS2_TRY(check_ptr(loss, "loss"));
+    NEUS2_TRY(check_ptr(dC, "dC"));
+    NEUS2_TRY(check_ptr(d_s, "d_s", false));
+    if (n > 0) {
+        NEUS2_TRY(check_ptr(y, "y"));
+        NEUS2_TRY(check_ptr(rgb, "rgb"));
+        NEUS2_TRY(check_ptr(normal, "normal"));
+        NEUS2_TRY(check_ptr(weights, "weights"));
+        NEUS2_TRY(check_ptr(d_sdf, "d_sdf"));
+        NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
+        NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    }
+    if (rays == 0) return NEUS2_OK;
+    const int per = kFusedThreads / 64;
+    const int64_t want = (rays + per - 1) / per;
+    const int64_t cap = (int64_t)compute_units() / 2;
+    hipLaunchKernelGGL(render_loss_ragged_kernel, dim3((unsigned)(want < cap ? want : cap)), dim3(kFusedThreads), 0,
+                       (hipStream_t)stream, cfg->loss_kind, y, rgb, normal, target, ray_offsets, rays, n > 0 ? n : 1, cfg->s,
+                       s_dev, cfg->beta, cfg->huber_delta, C, weights, loss, dC, d_sdf, d_rgb, d_normal, d_s);
+    return check_launch("render + loss + backward (ragged rays)");
 }
 
 int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count, int dtype, float lr,

@@ -278,6 +278,75 @@ def test_fused_render_loss_backward_against_oracle(loss_kind):
             assert abs(float(d_s.cpu()[0]) - ref_ds) <= GRAD_TOL * scale + 1e-9
 
 
+@pytest.mark.parametrize("loss_kind", [1, 2])
+def test_ragged_render_loss_backward_against_oracle(loss_kind):
+    """Rays with their own sample counts: none, one, short, longer than one and than three wavefronts."""
+    rng = np.random.default_rng(50 + loss_kind)
+    cfg = wl.make_config(2)
+    cfg.loss_kind, cfg.huber_delta = loss_kind, 0.05
+    c = nb.make_config(cfg)
+    lengths = np.array([3, 0, 64, 1, 65, 128, 200, 0, 17, 63, 129, 2] + list(rng.integers(0, 90, size=300)))
+    off = np.zeros(len(lengths) + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lengths)
+    rays, n = len(lengths), int(off[-1])
+    sdf = (rng.normal(size=n) * 0.05)
+    sdf[off[6]:off[7]] = np.linspace(0.4, -0.4, 200)          # a long ray that crosses the surface in its third chunk
+    sdf = sdf.astype(np.float32)
+    rgb = rng.uniform(size=(n, 3)).astype(np.float32)
+    normal = (rng.normal(size=(n, 3)) * 0.7).astype(np.float32)
+    target = rng.uniform(size=(rays, 3)).astype(np.float32)
+    y = np.zeros((n, 16), dtype=np.float32)
+    y[:, 0] = sdf
+    z = lambda *sh: torch.zeros(*sh, device="cuda")
+    Cg, wg, loss, dC, ds, dr, dn, d_s = z(rays, 3), z(n), z(2), z(rays, 3), z(n), z(n, 3), z(n, 3), z(1)
+    nb.render_loss_bwd_ragged(c, cuda(y), cuda(rgb), cuda(normal), cuda(target), cuda(off, torch.int32), rays, n, Cg, wg, loss,
+                              dC, ds, dr, dn, d_s=d_s)
+    torch.cuda.synchronize()
+    s64, r64 = sdf.astype(np.float64), rgb.astype(np.float64)
+    Cr, wr, _ = o.render_rays_ragged(s64, r64, off, cfg.s)
+    diff = Cr - target
+    if loss_kind == 1:
+        first, g = np.sum(np.abs(diff)) / rays, np.sign(diff) / rays
+    else:
+        first, g = np.sum(o.huber(diff, cfg.huber_delta)) / rays, o.huber_derivative(diff, cfg.huber_delta) / rays
+    ln = np.linalg.norm(normal.astype(np.float64), axis=1)
+    eik = cfg.beta * np.mean((ln - 1.0) ** 2)
+    d_normal = (2.0 * cfg.beta / n) * ((ln - 1.0) / ln)[:, None] * normal
+    d_sdf, d_rgb, ref_ds = o.render_rays_ragged_backward(s64, r64, off, cfg.s, g)
+    got_loss = loss.cpu().numpy()
+    assert abs(got_loss[0] - first) <= FWD_TOL * first and abs(got_loss[1] - eik) <= FWD_TOL * eik
+    assert rel(Cg.cpu().numpy(), Cr) <= FWD_TOL
+    assert np.all(Cg.cpu().numpy()[[1, 7]] == 0)                 # rays without samples
+    assert rel(wg.cpu().numpy(), wr) <= FWD_TOL
+    assert rel(dn.cpu().numpy(), d_normal) <= GRAD_TOL
+    assert rel(dr.cpu().numpy(), d_rgb) <= GRAD_TOL
+    assert rel(ds.cpu().numpy(), d_sdf) <= GRAD_TOL
+    long_ray = slice(off[6], off[7])
+    assert rel(ds.cpu().numpy()[long_ray], d_sdf[long_ray]) <= GRAD_TOL and np.linalg.norm(d_sdf[long_ray]) > 0
+    scale = float(np.sum(np.abs(d_sdf * s64))) / cfg.s
+    assert abs(float(d_s.cpu()[0]) - ref_ds) <= GRAD_TOL * scale
+
+
+def test_step_with_ragged_rays():
+    """A whole step on rays of different lengths (the colour network looks its direction up by
+    the sample's ray), against the oracle."""
+    w = wl.make_workload(2, n_rays=8)
+    cfg, params = w["cfg"], w["params"]
+    params["tables"] = (params["tables"].astype(np.float64) * 2000.0).astype(params["tables"].dtype)
+    batch = wl.make_ragged_rays(150, seed=77)
+    n, rays = batch["pos"].shape[0], batch["dirs"].shape[0]
+    lengths = np.diff(batch["ray_offsets"])
+    assert np.any(lengths == 0) and np.any(lengths > 64) and n % cfg.samples_per_ray != 0
+    step = nb.Step(cfg, params, n, n_rays=rays)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.train_step()
+    torch.cuda.synchronize()
+    ref = o.train_step(cfg, params, batch)
+    assert np.any(ref["alpha"] > 0.05)
+    print(check_step(cfg, step, ref, n))
+
+
 def test_color_forward_backward_alone():
     rng = np.random.default_rng(2)
     cfg = wl.make_config(2)

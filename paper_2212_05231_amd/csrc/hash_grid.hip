@@ -368,6 +368,7 @@ struct OwnerPlan {
     short level[NEUS2_MAX_LEVELS];
     short ranges[NEUS2_MAX_LEVELS];
     short chunks[NEUS2_MAX_LEVELS];
+    int chunk_points[NEUS2_MAX_LEVELS];     // points per chunk (the last chunk may hold fewer)
 };
 
 struct Records {
@@ -523,7 +524,7 @@ struct OwnerSmem {
     double acc[2 * kOwnerSlots];
     uint32_t queue[kQueue];    // in-place path: points of the chunk that touch the range
     int queued;
-    int task;
+    int task[2];               // mailbox for the task numbers, see the kernel
 };
 
 __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan, Records rec,
@@ -539,16 +540,18 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
     // The two features of a slot lie side by side.  Even lanes add feature 0 first, odd lanes
     // feature 1: one instruction then spreads over all LDS banks instead of every other pair.
     const int odd = threadIdx.x & 1;
-    // The next task number is requested while the current task runs (after the barrier that
-    // follows the clearing of the accumulators: a barrier waits for everything requested before
-    // it), so its round trip to the counter is hidden.
+    // The accumulators are cleared once here and then by every flush as it reads them, and the
+    // next task number is requested while the current task runs and handed over through a
+    // two-entry mailbox: one barrier separates two tasks.
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) acc[threadIdx.x + u * kOwnerThreads] = 0.0;
     int next_task = 0;
-    if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
-    for (;;) {
-        if (threadIdx.x == 0) { sm.task = next_task; sm.queued = 0; }
-        __syncthreads();
-        const int task = sm.task;
+    if (threadIdx.x == 0) { sm.task[0] = atomicAdd(counter, 1); sm.queued = 0; }
+    __syncthreads();
+    for (int turn = 0;; turn ^= 1) {
+        const int task = sm.task[turn];
         if (task >= plan.n_tasks) break;             // uniform: every thread reads the same value
+        if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
         // entry of the task: all prefix sums are compared at once (independent scalar loads with
         // constant offsets, not a dependent chain of them; the index must stay uniform)
         int at_order = 0;
@@ -560,15 +563,11 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         const int n_ranges = plan.ranges[e], n_chunks = plan.chunks[e];
         const uint32_t range = (uint32_t)(local % n_ranges);
         const int chunk = local / n_ranges;
-        const int64_t begin = n * chunk / n_chunks, end = n * (chunk + 1) / n_chunks;
+        const int64_t begin = (int64_t)chunk * plan.chunk_points[e];
+        const int64_t end = min(begin + plan.chunk_points[e], n);
         const uint32_t first_slot = range << kOwnerSlotBits;
         const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
         float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
-
-#pragma unroll
-        for (int u = 0; u < kPerThread; ++u) acc[threadIdx.x + u * kOwnerThreads] = 0.0;
-        __syncthreads();
-        if (threadIdx.x == 0) next_task = atomicAdd(counter, 1);
 
         if (e < plan.n_listed) {
             // A listed task owns its range alone and adds to the gradient with plain loads and
@@ -610,6 +609,7 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             for (int u = 0; u < kPerThread; ++u) {
                 const uint32_t k = threadIdx.x + u * kOwnerThreads;
                 const float v = (float)acc[k];
+                acc[k] = 0.0;
                 if (k < 2 * slots_here && v != 0.f) dst[k] = old[u] + v;
             }
         } else {
@@ -690,10 +690,12 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             for (int u = 0; u < kPerThread; ++u) {
                 const uint32_t k = threadIdx.x + u * kOwnerThreads;
                 const float v = (float)acc[k];
+                acc[k] = 0.0;
                 if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
             }
         }
-        __syncthreads();                              // also protects sm.task before the next fetch
+        if (threadIdx.x == 0) sm.task[turn ^ 1] = next_task;
+        __syncthreads();
     }
 }
 
@@ -745,6 +747,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
             p.level[e] = (short)l;
             p.ranges[e] = (short)ranges;
             p.chunks[e] = (short)chunks;
+            p.chunk_points[e] = (int)((n + chunks - 1) / chunks);
             cost[e] = task_ns;
             ++e;
         }

@@ -104,6 +104,7 @@ struct ColorRaw {
     float4 ya, yb;
     float dir[3], p[3], nr[3];
     float d_rgb[3], rgb[3], d_sdf;
+    float dn[2];               // backward: this lane's part of d_normal as it comes in (h = 0: n0; h = 1: n1, n2)
 };
 
 template <bool BWD>
@@ -112,7 +113,8 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
     if (!valid) return r;
     r.ya = *reinterpret_cast<const float4*>(a.y + i * 16 + 4 * h);
     r.yb = *reinterpret_cast<const float4*>(a.y + i * 16 + 8 + 4 * h);
-    const int64_t ray = a.sample_ray ? (int64_t)a.sample_ray[i] : i / a.spr;
+    // n is at most 2^28: a 32-bit division (the 64-bit one costs over a hundred instructions)
+    const int64_t ray = a.sample_ray ? (int64_t)a.sample_ray[i] : (int64_t)((uint32_t)i / (uint32_t)a.spr);
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
         r.dir[c] = a.dirs[3 * ray + c];
@@ -121,6 +123,10 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
         if (BWD) { r.d_rgb[c] = a.d_rgb[3 * i + c]; r.rgb[c] = a.rgb_in[3 * i + c]; }
     }
     if (BWD && a.d_sdf) r.d_sdf = a.d_sdf[i];
+    if (BWD) {
+        r.dn[0] = a.d_normal[3 * i + (h ? 1 : 0)];
+        if (h) r.dn[1] = a.d_normal[3 * i + 2];
+    }
     return r;
 }
 
@@ -257,10 +263,10 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             // registers 8..11: h = 0 -> x0 x1 x2 n0 ; h = 1 -> n1 n2
             if (h == 0) {
                 if (a.d_pos) { a.d_pos[3 * i] = dcin[0][8]; a.d_pos[3 * i + 1] = dcin[0][9]; a.d_pos[3 * i + 2] = dcin[0][10]; }
-                a.d_normal[3 * i] += dcin[0][11];
+                a.d_normal[3 * i] = cur.dn[0] + dcin[0][11];
             } else {
-                a.d_normal[3 * i + 1] += dcin[0][8];
-                a.d_normal[3 * i + 2] += dcin[0][9];
+                a.d_normal[3 * i + 1] = cur.dn[0] + dcin[0][8];
+                a.d_normal[3 * i + 2] = cur.dn[1] + dcin[0][9];
             }
         }
     }

@@ -105,7 +105,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=2, help="1..4 (benchmark configuration number)")
+    ap.add_argument("--workload", type=int, default=2, help="1..5 (benchmark configuration number; 5 = one frame of the dynamic scene: rigid "
+                         "transform in front of the step, its gradient behind it)")
     ap.add_argument("--rays", type=int, default=None, help="override the number of rays (points for workload 1)")
     ap.add_argument("--ragged", action="store_true",
                     help="rays with their own sample counts (the length mix of a ray marcher) instead of a fixed count")
@@ -139,13 +140,27 @@ def main() -> int:
         batch = wl.make_ragged_rays(args.rays or (wl.default_rays(args.workload) * cfg.samples_per_ray) // 43, seed=2000 + args.workload)
         cfg.name = f"cfg{args.workload}-ragged-{batch['dirs'].shape[0]}rays"
     n = batch["pos"].shape[0]
-    step = nb.Step(cfg, params, n, n_rays=batch["dirs"].shape[0] if args.ragged else None)
+    dynamic = "omega" in batch
+    step = nb.Step(cfg, params, n, n_rays=batch["dirs"].shape[0] if args.ragged else None, want_pos_grad=dynamic)
     step.set_batch(batch)
     step.zero_grads()
     step.init_optimizer()
+    if dynamic:
+        # Eq. 9: the frame's points go through x_c = R (x + T) and the map to the unit cube; the
+        # gradient with respect to (R, T) is reduced on the device to M (3x3) and b (3)
+        from paper_2212_05231_amd import rigid
+        rot = rigid.rotation(batch["omega"]).astype(np.float32).reshape(-1)
+        shift = batch["shift"].astype(np.float32)
+        world = torch.as_tensor(batch["pos"]).cuda()
+        Mb = torch.zeros(12, device="cuda")
 
     def one_step():
+        if dynamic:
+            nb.rigid_fwd(world, rot, shift, 0.5, 0.5, step.pos)
         step.train_step()
+        if dynamic:
+            Mb.zero_()
+            nb.rigid_bwd(world, shift, step.d_pos, 0.5, Mb)
         step.adam()
 
     if args.copy_calibration:
@@ -178,7 +193,10 @@ def main() -> int:
         rays = s.rays
         o = s.opt
         half = 1 if cfg.table_dtype == "f16" else 0
-        seq = [("hash_encode", lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac)),
+        seq = []
+        if dynamic:
+            seq += [("rigid_fwd", lambda: nb.rigid_fwd(world, rot, shift, 0.5, 0.5, s.pos))]
+        seq += [("hash_encode", lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac)),
                ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal))]
         if cfg.loss_kind != 0:
             seq += [
@@ -189,14 +207,15 @@ def main() -> int:
                  (lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
                                              s.dC, s.d_sdf, s.d_rgb, s.d_normal))),
                 ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
-                                                   s.d_y, s.d_normal, sample_ray=s.sample_ray)),
+                                                   s.d_y, s.d_normal, s.d_pos, sample_ray=s.sample_ray)),
             ]
         else:
             seq += [("loss", lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y))]
         seq += [
-            ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
+            ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc, s.d_pos)),
             ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
-                                                             workspace=s.workspace)),
+                                                             s.d_pos, workspace=s.workspace)),
+        ] + ([("rigid_bwd", lambda: nb.rigid_bwd(world, shift, s.d_pos, 0.5, Mb))] if dynamic else []) + [
             ("adam_tables", lambda: nb.adam_tables(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"],
                                                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
             ("adam_matrices", lambda: nb.adam_step(s.small, None, s.d_small, o["m_s"], o["v_s"], 0,
@@ -204,6 +223,8 @@ def main() -> int:
         ]
         cost = algorithmic_cost(cfg, n)
         cost["adam_matrices"] = {"bytes": 34 * int(s.small.numel()), "flops": 0}
+        cost["rigid_fwd"] = {"bytes": 24 * n, "flops": 0}
+        cost["rigid_bwd"] = {"bytes": 24 * n, "flops": 0}
         reps = max(5, min(args.steps, 100))
         total = {name: 0.0 for name, _ in seq}
         events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(seq) + 1)] for _ in range(reps)]

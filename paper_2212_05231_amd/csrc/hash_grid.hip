@@ -324,6 +324,54 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
     }
 }
 
+// The position-gradient part of the backward pass on its own, for the path below that does
+// not touch the tables' values: per point and level, the mixed second derivative of the
+// interpolation contracted with q and dL/dn (three numbers), written to part[level][i][3];
+// `sum_levels_kernel` adds the levels into d_pos.  Same gather as the encoder, same
+// workgroup -> level mapping (a level's table stays in the L2 of the XCDs that work on it).
+template <typename T>
+__global__ __launch_bounds__(kBlock) void pos_hessian_kernel(GridDesc g, const float* __restrict__ pos,
+                                                             const T* __restrict__ tables,
+                                                             const float* __restrict__ q,
+                                                             const float* __restrict__ d_normal, int64_t n,
+                                                             int point_blocks, float* __restrict__ part) {
+    int level, pb;
+    if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
+    const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
+    const int64_t o = (int64_t)level * n + i;
+    const float2 qq = reinterpret_cast<const float2*>(q)[o];
+    const float fres = (float)g.res[level];
+    const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
+    float2 v[8];
+    gather_corners<T>(g, level, tables + (size_t)level * g.table_size * 2, c, v);
+    float hp[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float fx = (k & 1) ? c.w[0] : 1.f - c.w[0];
+        const float fy = (k & 2) ? c.w[1] : 1.f - c.w[1];
+        const float fz = (k & 4) ? c.w[2] : 1.f - c.w[2];
+        const float sx = (k & 1) ? 1.f : -1.f;
+        const float sy = (k & 2) ? 1.f : -1.f;
+        const float sz = (k & 4) ? 1.f : -1.f;
+        const float qv = (qq.x * v[k].x + qq.y * v[k].y) * fres;
+        hp[0] += qv * (ny * (sx * sy * fz) + nz * (sx * fy * sz));
+        hp[1] += qv * (nx * (sx * sy * fz) + nz * (fx * sy * sz));
+        hp[2] += qv * (nx * (sx * fy * sz) + ny * (fx * sy * sz));
+    }
+    part[3 * o + 0] = hp[0]; part[3 * o + 1] = hp[1]; part[3 * o + 2] = hp[2];
+}
+
+__global__ __launch_bounds__(kBlock) void sum_levels_kernel(const float* __restrict__ part, int levels, int64_t n,
+                                                            float* __restrict__ d_pos) {
+    const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;      // over the 3 n numbers of d_pos
+    if (k >= 3 * n) return;
+    float acc = d_pos[k];
+    for (int l = 0; l < levels; ++l) acc += part[(int64_t)l * 3 * n + k];
+    d_pos[k] = acc;
+}
+
 // ---- scatter-add without global atomics: LDS-resident slot ranges ---------------------------
 //
 // Float atomics leave the L2 as one 32-byte read-modify-write per (instruction, line) and
@@ -793,12 +841,15 @@ int64_t owner_workspace_need(const OwnerPlan& plan) {
     return kWorkspaceHeader + plan.list_base[plan.n_listed] * 20 + 256;
 }
 
+// scratch of the position-gradient path: part[active levels][n][3], behind the records
+int64_t pos_scratch_bytes(const neus2_config* cfg, int64_t n) { return (int64_t)cfg->active_levels * n * 12; }
+
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
     if (n < kOwnerMinPoints) return 0;
     bool ok = false;
     const OwnerPlan plan = make_owner_plan(cfg, n, ok);
     if (!ok) return 0;
-    return (owner_workspace_need(plan) + 255) / 256 * 256;
+    return (owner_workspace_need(plan) + 255) / 256 * 256 + (int64_t)cfg->n_levels * n * 12;
 }
 
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
@@ -806,13 +857,14 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
                    float* d_pos, void* workspace, int64_t workspace_bytes, hipStream_t st) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
-    // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels).
-    // It does not produce the position gradient, and below ~2^16 points the atomic kernel is
-    // cheaper.
-    if (!d_pos && n >= kOwnerMinPoints && workspace) {
+    // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels);
+    // the position gradient, if wanted, comes from a gather pass of its own.  Below ~2^16
+    // points the atomic kernel is cheaper.
+    if (n >= kOwnerMinPoints && workspace) {
         bool ok = false;
         const OwnerPlan plan = make_owner_plan(cfg, n, ok);
-        if (ok && workspace_bytes >= owner_workspace_need(plan)) {
+        const int64_t records_end = (owner_workspace_need(plan) + 255) / 256 * 256;
+        if (ok && workspace_bytes >= (d_pos ? records_end + pos_scratch_bytes(cfg, n) : owner_workspace_need(plan))) {
             char* ws = reinterpret_cast<char*>(workspace);
             int* counter = reinterpret_cast<int*>(ws);
             Records rec;
@@ -828,6 +880,19 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             const int wgs = compute_units();
             hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0, st,
                                g, plan, rec, pos, q, d_enc, d_normal, n, counter, d_tables);
+            if (d_pos) {
+                float* part = reinterpret_cast<float*>(ws + records_end);
+                const int pbs = (int)((n + kBlock - 1) / kBlock);
+                const dim3 grid(grid_blocks(g.active_levels, pbs));
+                if (cfg->table_dtype == 1)
+                    hipLaunchKernelGGL(pos_hessian_kernel<__half>, grid, dim3(kBlock), 0, st, g, pos, (const __half*)tables, q,
+                                       d_normal, n, pbs, part);
+                else
+                    hipLaunchKernelGGL(pos_hessian_kernel<float>, grid, dim3(kBlock), 0, st, g, pos, (const float*)tables, q,
+                                       d_normal, n, pbs, part);
+                hipLaunchKernelGGL(sum_levels_kernel, dim3((unsigned)((3 * n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, part,
+                                   g.active_levels, n, d_pos);
+            }
             return check_launch("hash scatter (owner)");
         }
     }

@@ -145,9 +145,30 @@ __device__ __forceinline__ void block_add(float v, float* dst, float* red) {
     __syncthreads();
 }
 
-// Grid-stride with few, large workgroups: every workgroup ends in two atomics on the same cache
-// line, and those are applied one after the other by the memory side (about 12 ns each, which
-// is what this kernel's time was made of with a thousand of them).
+// N sums per workgroup, added to N neighbouring floats by N lanes of ONE atomic instruction: the
+// memory side merges lanes that fall into the same cache line into one request, and requests
+// to one line are applied one after the other (about 12 ns each), so this costs a workgroup
+// one request where one call of block_add per value costs N.
+template <int N>
+__device__ __forceinline__ void block_add_n(const float (&v)[N], float* dst, float* red) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float t = wave_sum(v[k]);
+        if (lane == 0) red[wave * N + k] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x < N) {
+        float t = 0.f;
+        for (int w = 0; w < waves; ++w) t += red[w * N + threadIdx.x];
+        atomicAdd(dst + threadIdx.x, t);
+    }
+    __syncthreads();
+}
+
+// Grid-stride with few, large workgroups: every workgroup ends in an atomic on one cache line,
+// and those are applied one after the other by the memory side (about 12 ns each, which is
+// what this kernel's time was made of with a thousand workgroups).
 constexpr int kLossThreads = 1024;
 
 __global__ __launch_bounds__(kLossThreads) void loss_kernel(int kind, const float* __restrict__ C, const float* __restrict__ target,
@@ -156,7 +177,7 @@ __global__ __launch_bounds__(kLossThreads) void loss_kernel(int kind, const floa
                                                    float* __restrict__ loss,
                                                    float* __restrict__ dC, float* __restrict__ d_normal,
                                                    float* __restrict__ d_y) {
-    __shared__ float red[kLossThreads / 64];
+    __shared__ float red[2 * kLossThreads / 64];
     const float inv_n = 1.f / (float)n;
     float first = 0.f, eik = 0.f;
     for (int64_t i = (int64_t)blockIdx.x * kLossThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kLossThreads) {
@@ -191,8 +212,8 @@ __global__ __launch_bounds__(kLossThreads) void loss_kernel(int kind, const floa
             }
         }
     }
-    block_add(first, loss + 0, red);
-    block_add(eik, loss + 1, red);
+    const float both[2] = {first, eik};
+    block_add_n<2>(both, loss, red);
 }
 
 // ---- compositing, loss and the backward of both for one ray per wavefront, in one kernel ----
@@ -211,7 +232,7 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_kernel(int kind, co
                                                                    float* __restrict__ dC, float* __restrict__ d_sdf,
                                                                    float* __restrict__ d_rgb, float* __restrict__ d_normal,
                                                                    float* __restrict__ d_s) {
-    __shared__ float red[kFusedThreads / 64];
+    __shared__ float red[2 * kFusedThreads / 64];
     const int lane = threadIdx.x & 63;
     const int64_t waves = (int64_t)gridDim.x * (kFusedThreads / 64);
     if (s_dev) s = *s_dev;
@@ -287,8 +308,8 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_kernel(int kind, co
         if (lane > 0) ds += from_prev;
         if (live) { d_sdf[i] = ds; ds_total += ds * d; }
     }
-    block_add(first, loss + 0, red);
-    block_add(eik, loss + 1, red);
+    const float both[2] = {first, eik};
+    block_add_n<2>(both, loss, red);
     if (d_s) block_add(ds_total / s, d_s, red);
 }
 
@@ -330,7 +351,7 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_ragged_kernel(
     const float* __restrict__ s_dev, float beta, float huber_delta, float* __restrict__ C, float* __restrict__ weights,
     float* __restrict__ loss, float* __restrict__ dC, float* __restrict__ d_sdf, float* __restrict__ d_rgb,
     float* __restrict__ d_normal, float* __restrict__ d_s) {
-    __shared__ float red[kFusedThreads / 64];
+    __shared__ float red[2 * kFusedThreads / 64];
     const int lane = threadIdx.x & 63;
     const int64_t waves = (int64_t)gridDim.x * (kFusedThreads / 64);
     if (s_dev) s = *s_dev;
@@ -425,8 +446,8 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_ragged_kernel(
             after_carry += wave_sum(wc);
         }
     }
-    block_add(first, loss + 0, red);
-    block_add(eik, loss + 1, red);
+    const float both[2] = {first, eik};
+    block_add_n<2>(both, loss, red);
     if (d_s) block_add(ds_total / s, d_s, red);
 }
 
@@ -500,14 +521,16 @@ __global__ __launch_bounds__(256) void rigid_fwd_kernel(const float* __restrict_
     for (int r = 0; r < 3; ++r) out[3 * i + r] = t.scale * (t.R[3 * r] * x + t.R[3 * r + 1] * y + t.R[3 * r + 2] * z) + t.offset;
 }
 
-__global__ __launch_bounds__(256) void rigid_bwd_kernel(const float* __restrict__ pos, Rigid t,
-                                                        const float* __restrict__ d_out, int64_t n,
-                                                        float* __restrict__ Mb) {
-    __shared__ float red[4];
+constexpr int kRigidThreads = 1024;
+
+__global__ __launch_bounds__(kRigidThreads) void rigid_bwd_kernel(const float* __restrict__ pos, Rigid t,
+                                                                 const float* __restrict__ d_out, int64_t n,
+                                                                 float* __restrict__ Mb) {
+    __shared__ float red[12 * kRigidThreads / 64];
     float acc[12];
 #pragma unroll
     for (int k = 0; k < 12; ++k) acc[k] = 0.f;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)blockIdx.x * kRigidThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kRigidThreads) {
         const float x[3] = {pos[3 * i] + t.T[0], pos[3 * i + 1] + t.T[1], pos[3 * i + 2] + t.T[2]};
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
@@ -516,8 +539,7 @@ __global__ __launch_bounds__(256) void rigid_bwd_kernel(const float* __restrict_
             acc[9 + r] += g;
         }
     }
-#pragma unroll
-    for (int k = 0; k < 12; ++k) block_add(acc[k], Mb + k, red);
+    block_add_n<12>(acc, Mb, red);
 }
 
 }  // namespace
@@ -739,9 +761,9 @@ int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float 
     Rigid t = {};
     for (int k = 0; k < 3; ++k) t.T[k] = T[k];
     t.scale = scale;
-    int64_t blocks = (n + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(rigid_bwd_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, pos, t, d_out, n, Mb);
+    int64_t blocks = (n + kRigidThreads - 1) / kRigidThreads;
+    if (blocks > compute_units()) blocks = compute_units();
+    hipLaunchKernelGGL(rigid_bwd_kernel, dim3((unsigned)blocks), dim3(kRigidThreads), 0, (hipStream_t)stream, pos, t, d_out, n, Mb);
     return check_launch("rigid transform backward");
 }
 

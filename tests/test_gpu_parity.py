@@ -661,6 +661,35 @@ def test_full_size_sampled_rays(k):
         assert rel(step.d_tables.cpu().numpy(), want_t) <= GRAD_TOL
 
 
+def test_large_batch_position_gradient():
+    """Batches of 2^16 points and more take the path that keeps the table gradient in LDS; the
+    position gradient then comes from a gather pass of its own.  Against the oracle on a sample
+    of rays (adjoints scale with 1/rays), and against the atomic path on all points."""
+    w = wl.make_workload(2, n_rays=1024 + 3)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    params["tables"] = (params["tables"].astype(np.float64) * 2000.0).astype(params["tables"].dtype)
+    n = batch["pos"].shape[0]
+    spr = cfg.samples_per_ray
+    R = n // spr
+    assert n >= 1 << 16
+    outs = []
+    for use_ws in (True, False):
+        step = nb.Step(cfg, params, n, want_pos_grad=True, use_workspace=use_ws)
+        step.set_batch(batch)
+        step.zero_grads()
+        step.train_step()
+        torch.cuda.synchronize()
+        outs.append((step.d_pos.cpu().numpy().astype(np.float64), step.d_tables.cpu().numpy().astype(np.float64)))
+    assert rel(outs[0][0], outs[1][0]) <= 1e-5 and rel(outs[0][1], outs[1][1]) <= 1e-5
+    rng = np.random.default_rng(1)
+    pick = np.sort(rng.choice(R, size=40, replace=False))
+    pts = (pick[:, None] * spr + np.arange(spr)[None, :]).reshape(-1)
+    sub = {"pos": batch["pos"][pts], "dirs": batch["dirs"][pick], "target": batch["target"][pick]}
+    ref = o.train_step(cfg, params, sub, want_pos_grad=True)
+    assert np.linalg.norm(ref["dpos"]) > 0
+    assert rel(outs[0][0][pts], ref["dpos"] * (len(pick) / R)) <= GRAD_TOL
+
+
 def test_full_size_config2_against_full_oracle():
     """The whole benchmark step, all gradients, against the oracle at full size (about a minute of CPU)."""
     cfg, step, ref, n = run_step(2, None)

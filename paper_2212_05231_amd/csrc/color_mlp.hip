@@ -46,33 +46,46 @@ struct ColorWeights {
     float W3t[BWD ? 64 * kLdOutT : 4];           // [64][3 -> 8], columns >= 3 zero
 };
 
+// All elements a thread copies are requested from global memory first (fixed trip counts, so
+// the loads are in flight together) and written to LDS afterwards.
 template <bool BWD>
 __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
     const int tid = threadIdx.x;
+    constexpr int N1 = 64 * 40 / kThreads, N2 = 64 * 64 / kThreads;
+    float v1[N1], v2[N2], v3 = 0.f;
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
+        const int e = external_column(idx % 40);
+        v1[k] = e >= 0 ? a.W[0][(idx / 40) * 38 + e] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < N2; ++k) v2[k] = a.W[1][tid + k * kThreads];
+    if (tid < 3 * 64) v3 = a.W[2][tid];
     for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W3f[idx] = 0.f;
     if (BWD) {
         for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W1t[idx] = 0.f;
         for (int idx = tid; idx < 64 * kLdOutT; idx += kThreads) w.W3t[idx] = 0.f;
     }
     __syncthreads();
-    for (int idx = tid; idx < 64 * 40; idx += kThreads) {
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
         const int o = idx / 40, c = idx % 40;
-        const int e = external_column(c);
-        const float v = e >= 0 ? a.W[0][o * 38 + e] : 0.f;
-        w.W1f[o * kLdIn + c] = v;
-        if (BWD && c < 32) w.W1t[c * kLd64 + o] = v;
+        w.W1f[o * kLdIn + c] = v1[k];
+        if (BWD && c < 32) w.W1t[c * kLd64 + o] = v1[k];
     }
-    for (int idx = tid; idx < 64 * 64; idx += kThreads) {
+#pragma unroll
+    for (int k = 0; k < N2; ++k) {
+        const int idx = tid + k * kThreads;
         const int o = idx / 64, i = idx % 64;
-        const float v = a.W[1][idx];
-        w.W2f[o * kLd64 + i] = v;
-        if (BWD) w.W2t[i * kLd64 + o] = v;
+        w.W2f[o * kLd64 + i] = v2[k];
+        if (BWD) w.W2t[i * kLd64 + o] = v2[k];
     }
-    for (int idx = tid; idx < 3 * 64; idx += kThreads) {
-        const int o = idx / 64, i = idx % 64;
-        const float v = a.W[2][idx];
-        w.W3f[o * kLd64 + i] = v;
-        if (BWD) w.W3t[i * kLdOutT + o] = v;
+    if (tid < 3 * 64) {
+        const int o = tid / 64, i = tid % 64;
+        w.W3f[o * kLd64 + i] = v3;
+        if (BWD) w.W3t[i * kLdOutT + o] = v3;
     }
     __syncthreads();
 }
@@ -272,16 +285,10 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     }
     __syncthreads();
     float* scratch = &sm.tiles[0][0][0];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            G1[mb][nb] = block_sum<kWaves>(scratch, G1[mb][nb], wave, lane);
-            G2[mb][nb] = block_sum<kWaves>(scratch, G2[mb][nb], wave, lane);
-        }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) G3[0][nb] = block_sum<kWaves>(scratch, G3[0][nb], wave, lane);
-    if (wave == kWaves - 1) {
+    v16f* all[10] = {&G1[0][0], &G1[0][1], &G1[1][0], &G1[1][1], &G2[0][0], &G2[0][1], &G2[1][0], &G2[1][1], &G3[0][0], &G3[0][1]};
+    static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 5 * 1024 * sizeof(float), "scratch for the block sum");
+    block_sum_all<kWaves, 10>(scratch, all, wave, lane);
+    if (wave == 0) {
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll

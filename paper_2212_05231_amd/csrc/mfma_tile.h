@@ -171,4 +171,38 @@ __device__ __forceinline__ v16f block_sum(float* __restrict__ scratch, v16f v, i
     return v;
 }
 
+// Sum V register vectors over the block's WAVES waves; the result is valid in wave 0.  The
+// other waves park their vectors in LDS, HALF = ceil(V/2) at a time (scratch holds
+// (WAVES-1) * HALF * 1024 floats), and wave 0 adds them: four barriers for any V instead of
+// WAVES per vector.  Every thread of the block must call it.
+template <int WAVES, int V>
+__device__ __forceinline__ void block_sum_all(float* __restrict__ scratch, v16f* (&vec)[V], int wave, int lane) {
+    constexpr int HALF = (V + 1) / 2;
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        if (wave > 0) {
+#pragma unroll
+            for (int k = 0; k < HALF; ++k)
+                if (round * HALF + k < V) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        scratch[((wave - 1) * HALF + k) * 1024 + r * 64 + lane] = (*vec[round * HALF + k])[r];
+                }
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int k = 0; k < HALF; ++k)
+                if (round * HALF + k < V) {
+#pragma unroll
+                    for (int wv = 0; wv < WAVES - 1; ++wv)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            (*vec[round * HALF + k])[r] += scratch[(wv * HALF + k) * 1024 + r * 64 + lane];
+                }
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace neus2

@@ -42,30 +42,43 @@ struct SdfWeights {
     float HLt[64 * 20];             // its transpose [64][16]
 };
 
+// All elements a thread copies are requested from global memory first (fixed trip counts, so
+// the loads are independent and in flight together) and written to LDS afterwards: a loop of
+// load-then-store waits for one memory round trip per iteration, some 30 of them per kernel.
 template <int D, int K>
 __device__ void load_weights(SdfWeights<D, K>& w, const SdfArgs& a) {
     const int tid = threadIdx.x;
+    constexpr int N1 = 64 * D / kThreads, N2 = K == 3 ? 64 * 64 / kThreads : 0, NL = 16 * 64 / kThreads;
+    static_assert(64 * D % kThreads == 0, "whole passes over the first matrix");
+    float v1[N1], v2[N2 > 0 ? N2 : 1], vl[NL];
+#pragma unroll
+    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * kThreads];
+#pragma unroll
+    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * kThreads];
+#pragma unroll
+    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * kThreads];
     for (int idx = tid; idx < 32 * kLd64; idx += kThreads) { w.H1t[idx] = 0.f; w.HLf[idx] = 0.f; }
     __syncthreads();
-    for (int idx = tid; idx < 64 * D; idx += kThreads) {
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
         const int o = idx / D, i = idx % D;
-        const float v = a.H[0][idx];
-        w.H1f[o * SdfWeights<D, K>::LDIN + i] = v;
-        w.H1t[i * kLd64 + o] = v;
+        w.H1f[o * SdfWeights<D, K>::LDIN + i] = v1[k];
+        w.H1t[i * kLd64 + o] = v1[k];
     }
-    if (K == 3) {
-        for (int idx = tid; idx < 64 * 64; idx += kThreads) {
-            const int o = idx / 64, i = idx % 64;
-            const float v = a.H[1][idx];
-            w.H2f[o * kLd64 + i] = v;
-            w.H2t[i * kLd64 + o] = v;
-        }
-    }
-    for (int idx = tid; idx < 16 * 64; idx += kThreads) {
+#pragma unroll
+    for (int k = 0; k < N2; ++k) {
+        const int idx = tid + k * kThreads;
         const int o = idx / 64, i = idx % 64;
-        const float v = a.H[K - 1][idx];
-        w.HLf[o * kLd64 + i] = v;
-        w.HLt[i * 20 + o] = v;
+        w.H2f[o * kLd64 + i] = v2[k];
+        w.H2t[i * kLd64 + o] = v2[k];
+    }
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / 64, i = idx % 64;
+        w.HLf[o * kLd64 + i] = vl[k];
+        w.HLt[i * 20 + o] = vl[k];
     }
     __syncthreads();
 }
@@ -439,6 +452,7 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     __syncthreads();
     // ---- reduce over the block's waves, then one atomic add per element and block
     float* scratch = &sm.tiles[0][0][0];
+    static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 4 * 1024 * sizeof(float), "scratch for the block sum");
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
         G1[mb][0] = block_sum<kWaves>(scratch, G1[mb][0], wave, lane);

@@ -48,6 +48,7 @@ MEASURED_TRAFFIC_MIB = {
 # the HIP kernels behind each timed call (names as rocprofv3 prints them)
 KERNELS_OF_CALL = {
     "hash_encode": "encode_kernel", "sdf_fwd_grad": "sdf_fwd_kernel", "sdf_mlp_bwd": "sdf_bwd_kernel",
+    "sdf_bwd_2nd": "sdf_bwd_kernel + zero_kernel + bin_rows_kernel + scatter_owner_kernel + pos_hessian_kernel + sum_levels_kernel",
     "hash_scatter_bwd": "zero_kernel + bin_rows_kernel + scatter_owner_kernel (scatter_kernel below 2^16 points)",
     "adam_tables": "adam_tables_kernel", "adam_matrices": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
     "render_loss_bwd": "render_loss_kernel", "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
@@ -115,7 +116,7 @@ def main() -> int:
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures ONE GPU; no multi-GPU path exists (see DESIGN.md, 'How it would shard').",
+        print("bench.py: this build measures ONE GPU; no multi-GPU path exists; every ray is independent, so the step would shard over rays with one gradient sum per step.",
               file=sys.stderr)
         return 2
 
@@ -210,11 +211,20 @@ def main() -> int:
             ]
         else:
             seq += [("loss", lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y))]
+        if dynamic:
+            # with the position gradient the two halves share work (the scatter's gather pass adds the
+            # first-order part): timed as the one call the step makes
+            seq += [("sdf_bwd_2nd", lambda: nb.sdf_bwd_2nd(c, s.pos, s.tables, s.enc, s.jac, s.H, s.q, s.d_y, s.d_normal, n,
+                                                           s.dH, s.d_tables, s.d_enc, s.d_pos, workspace=s.workspace))]
+        else:
+            seq += [
+                ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
+                ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
+                                                                 workspace=s.workspace)),
+            ]
+        if dynamic:
+            seq += [("rigid_bwd", lambda: nb.rigid_bwd(world, shift, s.d_pos, 0.5, Mb))]
         seq += [
-            ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc, s.d_pos)),
-            ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
-                                                             s.d_pos, workspace=s.workspace)),
-        ] + ([("rigid_bwd", lambda: nb.rigid_bwd(world, shift, s.d_pos, 0.5, Mb))] if dynamic else []) + [
             ("adam_tables", lambda: nb.adam_tables(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"],
                                                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
             ("adam_matrices", lambda: nb.adam_step(s.small, None, s.d_small, o["m_s"], o["v_s"], 0,
@@ -222,6 +232,8 @@ def main() -> int:
         ]
         cost = algorithmic_cost(cfg, n)
         cost["adam_matrices"] = {"bytes": 34 * int(s.small.numel()), "flops": 0}
+        cost["sdf_bwd_2nd"] = {"bytes": cost["sdf_mlp_bwd"]["bytes"] + cost["hash_scatter_bwd"]["bytes"] + 24 * n,
+                               "flops": cost["sdf_mlp_bwd"]["flops"]}
         cost["rigid_fwd"] = {"bytes": 24 * n, "flops": 0}
         cost["rigid_bwd"] = {"bytes": 24 * n, "flops": 0}
         reps = max(5, min(args.steps, 100))

@@ -200,7 +200,7 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
     NEUS2_TRY(check_ptr(d_tables, "d_tables"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
     NEUS2_TRY(check_ptr(workspace, "workspace", false));
-    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes,
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, false,
                           (hipStream_t)stream);
 }
 
@@ -224,8 +224,12 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
     NEUS2_TRY(check_ptr(d_enc, "d_enc"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
     hipStream_t st = (hipStream_t)stream;
-    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, st));
-    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, st);
+    // With a large batch and a workspace the scatter's gather pass has the corners of every level
+    // in registers and adds (de/dx)^T dL/de to d_pos on the way; otherwise the network kernel
+    // does it from the stored Jacobian.
+    const bool gather = d_pos && scatter_gathers_position(cfg, n, workspace, workspace_bytes);
+    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, st));
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, gather, st);
 }
 
 }  // extern "C"

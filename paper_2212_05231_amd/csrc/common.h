@@ -45,9 +45,12 @@ int launch_zero(float* p, int64_t count, hipStream_t st);
 // internal launchers (each validates nothing; the extern "C" wrappers do)
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
                   float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st);
+// first_order_pos: d_pos also gets J^T d_enc (the part the SDF backward kernel adds when it is
+// handed d_pos); only honoured on the path scatter_gathers_position() reports.
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, void* workspace, int64_t workspace_bytes, hipStream_t st);
+                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st);
+bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes);
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
                    const float* const* H, int64_t n, float* y, float* q, float* normal, hipStream_t st);

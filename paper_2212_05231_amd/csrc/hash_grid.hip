@@ -333,7 +333,8 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void pos_hessian_kernel(GridDesc g, const float* __restrict__ pos,
                                                              const T* __restrict__ tables,
                                                              const float* __restrict__ q,
-                                                             const float* __restrict__ d_normal, int64_t n,
+                                                             const float* __restrict__ d_normal,
+                                                             const float* __restrict__ d_enc, int64_t n,
                                                              int point_blocks, float* __restrict__ part) {
     int level, pb;
     if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
@@ -346,6 +347,10 @@ __global__ __launch_bounds__(kBlock) void pos_hessian_kernel(GridDesc g, const f
     const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
     float2 v[8];
     gather_corners<T>(g, level, tables + (size_t)level * g.table_size * 2, c, v);
+    // with d_enc: the first-order part (de/dx)^T dL/de of this level as well (the Jacobian is
+    // rebuilt from the corners that are here anyway)
+    float2 de = make_float2(0.f, 0.f);
+    if (d_enc) de = reinterpret_cast<const float2*>(d_enc)[o];
     float hp[3] = {0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -355,6 +360,10 @@ __global__ __launch_bounds__(kBlock) void pos_hessian_kernel(GridDesc g, const f
         const float sx = (k & 1) ? 1.f : -1.f;
         const float sy = (k & 2) ? 1.f : -1.f;
         const float sz = (k & 4) ? 1.f : -1.f;
+        const float ev = (de.x * v[k].x + de.y * v[k].y) * fres;
+        hp[0] += ev * (sx * fy * fz);
+        hp[1] += ev * (fx * sy * fz);
+        hp[2] += ev * (fx * fy * sz);
         const float qv = (qq.x * v[k].x + qq.y * v[k].y) * fres;
         hp[0] += qv * (ny * (sx * sy * fz) + nz * (sx * fy * sz));
         hp[1] += qv * (nx * (sx * sy * fz) + nz * (fx * sy * sz));
@@ -852,9 +861,16 @@ int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
     return (owner_workspace_need(plan) + 255) / 256 * 256 + (int64_t)cfg->n_levels * n * 12;
 }
 
+bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes) {
+    if (n < kOwnerMinPoints || !workspace || cfg->active_levels == 0) return false;
+    bool ok = false;
+    const OwnerPlan plan = make_owner_plan(cfg, n, ok);
+    return ok && workspace_bytes >= (owner_workspace_need(plan) + 255) / 256 * 256 + pos_scratch_bytes(cfg, n);
+}
+
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, void* workspace, int64_t workspace_bytes, hipStream_t st) {
+                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
     // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels);
@@ -886,10 +902,10 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
                 const dim3 grid(grid_blocks(g.active_levels, pbs));
                 if (cfg->table_dtype == 1)
                     hipLaunchKernelGGL(pos_hessian_kernel<__half>, grid, dim3(kBlock), 0, st, g, pos, (const __half*)tables, q,
-                                       d_normal, n, pbs, part);
+                                       d_normal, first_order_pos ? d_enc : nullptr, n, pbs, part);
                 else
                     hipLaunchKernelGGL(pos_hessian_kernel<float>, grid, dim3(kBlock), 0, st, g, pos, (const float*)tables, q,
-                                       d_normal, n, pbs, part);
+                                       d_normal, first_order_pos ? d_enc : nullptr, n, pbs, part);
                 hipLaunchKernelGGL(sum_levels_kernel, dim3((unsigned)((3 * n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, part,
                                    g.active_levels, n, d_pos);
             }

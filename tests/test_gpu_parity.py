@@ -690,6 +690,46 @@ def test_large_batch_position_gradient():
     assert rel(outs[0][0][pts], ref["dpos"] * (len(pick) / R)) <= GRAD_TOL
 
 
+def test_full_size_dynamic_frame_sampled_rays():
+    """Workload 5 at full size as bench.py runs it: rigid transform, step with the position
+    gradient (gather pass of the large-batch scatter), reduction to (M, b).  Sampled rays against
+    the oracle on those rays alone; the reduction against the oracle's applied to the GPU's
+    position gradient."""
+    w = wl.make_workload(5)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    params["tables"] = (params["tables"].astype(np.float64) * 2000).astype(np.float16)
+    world = batch["pos"]
+    n = world.shape[0]
+    spr = cfg.samples_per_ray
+    R = o.rotation_from_axis_angle(batch["omega"]).astype(np.float32)
+    T = batch["shift"].astype(np.float32)
+    step = nb.Step(cfg, params, n, want_pos_grad=True)
+    step.set_batch(batch)
+    wg = cuda(world)
+    nb.rigid_fwd(wg, R.reshape(-1), T, 0.5, 0.5, step.pos)
+    step.zero_grads()
+    step.train_step()
+    Mb = torch.zeros(12, device="cuda")
+    nb.rigid_bwd(wg, T, step.d_pos, 0.5, Mb)
+    torch.cuda.synchronize()
+    pos_gpu = step.pos.cpu().numpy()
+    rng = np.random.default_rng(2)
+    rays = n // spr
+    pick = np.sort(rng.choice(rays, size=40, replace=False))
+    pts = (pick[:, None] * spr + np.arange(spr)[None, :]).reshape(-1)
+    assert rel(pos_gpu[pts], o.rigid_forward(world[pts], R, T, 0.5, 0.5)) <= 1e-6
+    sub = {"pos": pos_gpu[pts], "dirs": batch["dirs"][pick], "target": batch["target"][pick]}
+    ref = o.train_step(cfg, params, sub, want_pos_grad=True)
+    scale = len(pick) / rays
+    d_pos = step.d_pos.cpu().numpy().astype(np.float64)
+    assert rel(step.y.cpu().numpy()[pts], ref["y"]) <= FWD_TOL
+    assert rel(step.C.cpu().numpy()[pick], ref["C"]) <= FWD_TOL
+    assert np.linalg.norm(ref["dpos"]) > 0 and rel(d_pos[pts], ref["dpos"] * scale) <= GRAD_TOL
+    M, dT, bsum = o.rigid_backward(world, R, T, d_pos, 0.5)
+    got = Mb.cpu().numpy()
+    assert rel(got[:9].reshape(3, 3), M) <= GRAD_TOL and rel(got[9:], bsum) <= GRAD_TOL
+
+
 def test_full_size_config2_against_full_oracle():
     """The whole benchmark step, all gradients, against the oracle at full size (about a minute of CPU)."""
     cfg, step, ref, n = run_step(2, None)

@@ -66,6 +66,12 @@ typedef struct neus2_config {
                                   from device memory instead when s_dev is not NULL */
     float beta;                /* weight of the eikonal term in Eq. 4 */
     float huber_delta;         /* loss_kind 2: |r| <= delta is quadratic, beyond it linear */
+    int32_t frozen_levels;     /* levels [0, frozen_levels) are inputs, not parameters: encoded and
+                                  differentiated with respect to the position like the others, but
+                                  they get no table gradient and no Adam update.  Filled with the
+                                  vertex coordinates (trilinear interpolation reproduces linear
+                                  functions exactly) they feed the position x itself to the SDF
+                                  network: Eq. 1's e = (x, h(x)) */
 } neus2_config;
 
 const char* neus2_last_error(void);

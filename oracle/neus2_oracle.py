@@ -492,6 +492,9 @@ def train_step(cfg, params, batch, fp32_product: bool = True, want_pos_grad: boo
             t = fw["masks"][l] * (t @ np.asarray(H[l], dtype=np.float64).T)
 
     dtables = table_gradient(cfg, pos, q, d_enc, d_normal, fp32_product)
+    # Levels below frozen_levels are inputs, not parameters (they carry the position x into the
+    # network, Eq. 1 feeds e = (x, h(x))): no gradient.
+    dtables[:getattr(cfg, "frozen_levels", 0)] = 0.0
 
     out = dict(fw)
     out.update({"d_y": d_y, "d_normal": d_normal, "d_enc": d_enc, "dH": dH, "dW": dW, "dtables": dtables})

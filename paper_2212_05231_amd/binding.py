@@ -28,6 +28,7 @@ class Neus2Config(C.Structure):
         ("n_color_mats", C.c_int32), ("color_dims", C.c_int32 * (MAX_MATS + 1)),
         ("samples_per_ray", C.c_int32), ("loss_kind", C.c_int32),
         ("s", C.c_float), ("beta", C.c_float), ("huber_delta", C.c_float),
+        ("frozen_levels", C.c_int32),
     ]
 
 
@@ -119,6 +120,7 @@ def make_config(cfg) -> Neus2Config:
         c.color_dims[i] = d
     c.samples_per_ray, c.loss_kind, c.s, c.beta = cfg.samples_per_ray, cfg.loss_kind, cfg.s, cfg.beta
     c.huber_delta = getattr(cfg, "huber_delta", 0.0)
+    c.frozen_levels = getattr(cfg, "frozen_levels", 0)
     return c
 
 

@@ -96,6 +96,8 @@ int check_config(const neus2_config* c) {
         return fail(NEUS2_ERR_CONFIG, "samples_per_ray = %d, must be 1..64", c->samples_per_ray);
     if (c->loss_kind < 0 || c->loss_kind > 2) return fail(NEUS2_ERR_CONFIG, "loss_kind = %d, must be 0, 1 or 2", c->loss_kind);
     if (c->loss_kind == 2 && !(c->huber_delta > 0.f)) return fail(NEUS2_ERR_CONFIG, "huber_delta must be positive for loss_kind 2");
+    if (c->frozen_levels < 0 || c->frozen_levels > c->n_levels)
+        return fail(NEUS2_ERR_CONFIG, "frozen_levels = %d outside 0..n_levels", c->frozen_levels);
     if (!(c->s > 0.f)) return fail(NEUS2_ERR_CONFIG, "s must be positive");
     if (!(c->beta >= 0.f)) return fail(NEUS2_ERR_CONFIG, "beta must be non-negative");
     return NEUS2_OK;
@@ -106,6 +108,7 @@ GridDesc make_grid_desc(const neus2_config* cfg) {
     memset(&g, 0, sizeof(g));
     g.n_levels = cfg->n_levels;
     g.active_levels = cfg->active_levels;
+    g.frozen_levels = cfg->frozen_levels;
     g.table_size = 1u << cfg->log2_table_size;
     g.table_mask = g.table_size - 1u;
     for (int l = 0; l < cfg->n_levels; ++l) {

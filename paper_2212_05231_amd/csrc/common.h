@@ -25,6 +25,7 @@ int check_launch(const char* what);                  // hipGetLastError -> NEUS2
 struct GridDesc {
     int n_levels;
     int active_levels;
+    int frozen_levels;         // levels below this get no table gradient
     uint32_t table_mask;       // T - 1
     uint32_t table_size;       // T
     uint32_t dense_bits;       // bit l set: level l is dense

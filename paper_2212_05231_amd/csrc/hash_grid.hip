@@ -230,6 +230,7 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
                                                          float* __restrict__ d_pos) {
     int level, pb;
     if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
+    if (level < g.frozen_levels && !WANT_POS) return;      // an input level: no table gradient
     const int sub = threadIdx.x & 3;
     const int dxb = sub >> 1, f = sub & 1;
     const int64_t i_raw = (int64_t)pb * kScatterPoints + (threadIdx.x >> 2);
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(GridDesc g, const float
         }
         issue = valid && tail;
     }
-    if (issue) {
+    if (issue && level >= g.frozen_levels) {
         float* gt = d_tables + (size_t)level * g.table_size * 2 + f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) atomicAdd(gt + 2 * (size_t)slot[k], val[k]);
@@ -772,7 +773,7 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     int64_t records = 0;
     double cost[NEUS2_MAX_LEVELS];
     for (int pass = 0; pass < 2; ++pass) {
-        for (int l = 0; l < cfg->active_levels; ++l) {
+        for (int l = cfg->frozen_levels; l < cfg->active_levels; ++l) {
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
             const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
             const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
@@ -862,7 +863,7 @@ int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
 }
 
 bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes) {
-    if (n < kOwnerMinPoints || !workspace || cfg->active_levels == 0) return false;
+    if (n < kOwnerMinPoints || !workspace || cfg->active_levels <= cfg->frozen_levels) return false;
     bool ok = false;
     const OwnerPlan plan = make_owner_plan(cfg, n, ok);
     return ok && workspace_bytes >= (owner_workspace_need(plan) + 255) / 256 * 256 + pos_scratch_bytes(cfg, n);
@@ -894,8 +895,9 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
                                    d_enc, d_normal, n, pbs, d_tables);
             }
             const int wgs = compute_units();
-            hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0, st,
-                               g, plan, rec, pos, q, d_enc, d_normal, n, counter, d_tables);
+            if (plan.n_tasks > 0)
+                hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0,
+                                   st, g, plan, rec, pos, q, d_enc, d_normal, n, counter, d_tables);
             if (d_pos) {
                 float* part = reinterpret_cast<float*>(ws + records_end);
                 const int pbs = (int)((n + kBlock - 1) / kBlock);

@@ -723,7 +723,7 @@ int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, floa
     for (int l = 0; l < cfg->n_levels; ++l) {
         const int64_t r1 = (int64_t)cfg->res[l] + 1;
         const int64_t slots = cfg->dense[l] ? r1 * r1 * r1 : T;     // check_config: a dense level fits T
-        lv.used[l] = (uint32_t)(slots * F);
+        lv.used[l] = l < cfg->frozen_levels ? 0u : (uint32_t)(slots * F);
         if (lv.used[l] > most) most = lv.used[l];
     }
     const dim3 grid((most + 255u) / 256u, (unsigned)cfg->n_levels);

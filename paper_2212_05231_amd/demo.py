@@ -44,10 +44,11 @@ def make_batch(rng, n_rays: int, spr: int):
 
 def geometric_init(cfg, params, rng, radius_cube: float) -> None:
     """Start the SDF network near d(x) = |x - centre| - r (the paper initialises geometrically,
-    Sec. 4.1, and feeds the position to the network for that).  Here the position reaches the
-    network through the encoding itself: trilinear interpolation reproduces linear functions
-    exactly, so the two coarsest (dense) levels are filled with the vertex coordinates
-    (x, y | z, 1) and the bias-free network gets the position and a constant.  The matrices
+    Sec. 4.1, and feeds the position to the network for that: e = (x, h(x)) in Eq. 1).  Here the
+    position reaches the network through the encoding itself: trilinear interpolation reproduces
+    linear functions exactly, so the two coarsest (dense) levels are filled with the vertex
+    coordinates (x, y | z, 1) and declared frozen (inputs, not parameters): the bias-free network
+    gets the position and a constant beside 14 trained levels.  The matrices
     follow the usual sphere initialisation of ReLU networks: Gaussian hidden weights of
     variance 2/width on the position channels, a constant sqrt(pi/width) last row, and -r
     carried by a hidden unit that passes the constant through."""
@@ -83,6 +84,7 @@ def run(steps: int, n_rays: int, seed: int = 0, log=print):
     cfg.dense = wl.dense_flags(cfg.res, cfg.table_size)
     params = wl.make_params(cfg, seed + 1)
     geometric_init(cfg, params, np.random.default_rng(seed + 2), radius_cube=0.5 * 0.6)
+    cfg.frozen_levels = 2          # the two coordinate levels stay what they are: e = (x, h(x))
     n = n_rays * cfg.samples_per_ray
     step = nb.Step(cfg, params, n)
     step.init_optimizer(lr=1e-2)

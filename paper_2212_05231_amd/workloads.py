@@ -41,6 +41,7 @@ class Config:
     beta: float
     name: str = ""
     huber_delta: float = 0.1
+    frozen_levels: int = 0           # levels [0, frozen) are inputs (they carry x), not parameters
 
     @property
     def table_size(self) -> int:

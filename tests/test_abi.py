@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     # 5 ints + 2*32 ints + (1+5) + (1+5) ints + 2 ints + 2 floats
-    assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 3)
+    assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 4)
     assert C.sizeof(nb.Neus2StepBuffers) == 8 * 32
 
 
@@ -50,7 +50,7 @@ def test_bad_descriptors_are_rejected_with_a_message():
         (broken(n_levels=0), -3), (broken(n_levels=33), -3), (broken(n_features=4), -5),
         (broken(log2_table_size=30), -3), (broken(active_levels=17), -3), (broken(table_dtype=2), -3),
         (broken(n_sdf_mats=5), -5), (broken(samples_per_ray=65), -3), (broken(loss_kind=3), -3), (broken(loss_kind=2, huber_delta=0.0), -3),
-        (broken(s=0.0), -3), (broken(beta=-1.0), -3),
+        (broken(s=0.0), -3), (broken(frozen_levels=17), -3), (broken(beta=-1.0), -3),
     ]
     c = broken()
     c.dense[15] = 1          # (2049)^3 vertices do not fit 2^19 slots

@@ -537,6 +537,54 @@ def test_step_huber_loss_and_trained_slope():
     assert float(step.d_s.cpu()[0]) == 0.0
 
 
+@pytest.mark.parametrize("n_rays", [48, 1024 + 5])
+def test_step_with_frozen_coordinate_levels(n_rays):
+    """Eq. 1 feeds e = (x, h(x)): the two coarsest levels hold the vertex coordinates and are frozen
+    (no table gradient, no Adam update); the position gradient still flows through them.  Small
+    batch (atomic scatter) and large batch (LDS scatter + gather pass)."""
+    w = wl.make_workload(2, n_rays=n_rays)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    tab = params["tables"].astype(np.float32) * 2000.0
+    for level, cols in enumerate(((0, 1), (2, None))):
+        r1 = cfg.res[level] + 1
+        idx = np.arange(r1 ** 3)
+        coords = [(idx % r1) / cfg.res[level] - 0.5, ((idx // r1) % r1) / cfg.res[level] - 0.5, (idx // (r1 * r1)) / cfg.res[level] - 0.5]
+        tab[level, :r1 ** 3, 0] = coords[cols[0]]
+        tab[level, :r1 ** 3, 1] = coords[cols[1]] if cols[1] is not None else 1.0
+    params["tables"] = tab.astype(np.float16)
+    cfg.frozen_levels = 2
+    n = batch["pos"].shape[0]
+    step = nb.Step(cfg, params, n, want_pos_grad=True)
+    step.set_batch(batch)
+    step.zero_grads()
+    step.train_step()
+    torch.cuda.synchronize()
+    # the encoding of the frozen levels IS the position (and a constant)
+    enc = from_level_major(step.enc, n)
+    assert np.max(np.abs(enc[:, 0:3] - (batch["pos"] - 0.5))) <= 1e-3 and np.max(np.abs(enc[:, 3] - 1.0)) <= 1e-6
+    if n_rays < 100:
+        ref = o.train_step(cfg, params, batch, want_pos_grad=True)
+        assert np.all(ref["dtables"][:2] == 0) and np.linalg.norm(ref["dtables"][2:]) > 0
+        check_step(cfg, step, ref, n, want_pos=True)
+    else:
+        pick = np.arange(0, n_rays, 40)
+        spr = cfg.samples_per_ray
+        pts = (pick[:, None] * spr + np.arange(spr)[None, :]).reshape(-1)
+        sub = {"pos": batch["pos"][pts], "dirs": batch["dirs"][pick], "target": batch["target"][pick]}
+        ref = o.train_step(cfg, params, sub, want_pos_grad=True)
+        assert rel(step.d_pos.cpu().numpy()[pts], ref["dpos"] * (len(pick) / n_rays)) <= GRAD_TOL
+        want_t = o.table_gradient(cfg, batch["pos"], from_level_major(step.q, n), from_level_major(step.d_enc, n),
+                                  step.d_normal.cpu().numpy())
+        want_t[:2] = 0.0
+        assert rel(step.d_tables.cpu().numpy(), want_t) <= GRAD_TOL
+    assert float(step.d_tables[:2].abs().sum()) == 0.0
+    before = step.tables[:2].clone()
+    step.init_optimizer()
+    step.adam()
+    torch.cuda.synchronize()
+    assert torch.equal(step.tables[:2], before) and not torch.equal(step.tables[2:4], cuda(params["tables"][2:4], torch.float16))
+
+
 def test_step_config5_frames_with_transform_gradient():
     w = wl.make_workload(5, n_rays=32, frame=1)
     cfg, params, batch = w["cfg"], w["params"], w["batch"]

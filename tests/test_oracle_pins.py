@@ -389,6 +389,32 @@ def test_slope_gradient_by_finite_differences():
     assert abs(d_s) > 1e-6
 
 
+def test_coordinate_levels_feed_the_position_itself():
+    """Eq. 1 feeds e = (x, h(x)).  Trilinear interpolation reproduces linear functions exactly, so a
+    dense level filled with the vertex coordinates encodes to the position, with the identity as
+    Jacobian; declared frozen, such a level gets no table gradient."""
+    cfg = tiny_cfg(L=3, log2T=10, res=(4, 7, 13), loss_kind=0)
+    rng = np.random.default_rng(3)
+    tables = rng.uniform(-0.5, 0.5, size=(3, cfg.table_size, 2))
+    for level, cols in enumerate(((0, 1), (2, None))):
+        assert cfg.dense[level]
+        r1 = cfg.res[level] + 1
+        idx = np.arange(r1 ** 3)
+        coords = [(idx % r1) / cfg.res[level], ((idx // r1) % r1) / cfg.res[level], (idx // (r1 * r1)) / cfg.res[level]]
+        tables[level, :r1 ** 3, 0] = coords[cols[0]]
+        tables[level, :r1 ** 3, 1] = coords[cols[1]] if cols[1] is not None else 1.0
+    pos = rng.uniform(0.02, 0.98, size=(50, 3))
+    he = o.hash_encode(cfg, tables, pos, fp32_product=False)
+    np.testing.assert_allclose(he["enc"][:, 0:3], pos, atol=1e-13)
+    np.testing.assert_allclose(he["enc"][:, 3], 1.0, atol=1e-13)
+    np.testing.assert_allclose(he["jac"][:, 0:3, :], np.broadcast_to(np.eye(3), (50, 3, 3)), atol=1e-11)
+    np.testing.assert_allclose(he["jac"][:, 3, :], 0.0, atol=1e-11)
+    cfg.frozen_levels = 2
+    H = [rng.uniform(-1, 1, size=(cfg.sdf_dims[i + 1], cfg.sdf_dims[i])) * 0.6 for i in range(len(cfg.sdf_dims) - 1)]
+    out = o.train_step(cfg, {"tables": tables, "H": H, "W": []}, {"pos": pos}, fp32_product=False)
+    assert np.all(out["dtables"][:2] == 0) and np.linalg.norm(out["dtables"][2]) > 0
+
+
 def test_ragged_rays_reduce_to_rows_and_to_finite_differences():
     """Rays with their own sample counts (supplement Sec. E.3, ray marching): with equal counts the
     ragged compositing is the fixed one; its gradient matches central differences; a ray without

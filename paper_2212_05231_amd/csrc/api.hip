@@ -3,6 +3,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
 
 #include "common.h"
 
@@ -46,10 +49,23 @@ int compute_units() {
 }
 
 int persistent_blocks(const void* kernel, int threads, int64_t want) {
-    int per_cu = 1;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) {
-        (void)hipGetLastError();
+    // the occupancy query costs several microseconds of host time; its answer never changes
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, int> cache;
+    int per_cu = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        auto it = cache.find({kernel, threads});
+        if (it != cache.end()) per_cu = it->second;
+    }
+    if (per_cu == 0) {
         per_cu = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) {
+            (void)hipGetLastError();
+            per_cu = 1;
+        }
+        std::lock_guard<std::mutex> lock(mu);
+        cache[{kernel, threads}] = per_cu;
     }
     const int64_t cap = (int64_t)per_cu * compute_units();
     const int64_t b = want < cap ? want : cap;

@@ -217,11 +217,14 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     const int j = lane & 31, h = lane >> 5;
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];
-    v16f G1[2][2], G2[2][2], G3[1][2];
+    v16f G1[2][2], G2[2][2];
+    v4f G3[4];                 // gradient of the last matrix (3 of 16 rows used): four blocks of 16 columns
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) { G1[mb][nb] = zero16(); G2[mb][nb] = zero16(); G3[0][nb] = zero16(); }
+        for (int nb = 0; nb < 2; ++nb) { G1[mb][nb] = zero16(); G2[mb][nb] = zero16(); }
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) G3[cb] = v4f{0.f, 0.f, 0.f, 0.f};
 
     const int64_t tiles = (a.n + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * kWaves;
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         stage<1, kLd64>(Zt, d3, j, h);
         stage<2, kLd64>(Xt, a2, j, h);
         wave_lds_fence();
-        outer_accumulate<1, 2, kLd64, kLd64>(G3, Zt, Xt, j, h);
+        outer_accumulate16<2, kLd64, kLd64>(G3, Zt, Xt, lane);
         v16f d2[2], d1[2], dcin[1];
         matvec<2, 1, kLdOutT, 4>(w.W3t, d3, d2, j, h);
         apply_mask<2>(d2, m2);
@@ -285,9 +288,14 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     }
     __syncthreads();
     float* scratch = &sm.tiles[0][0][0];
-    v16f* all[10] = {&G1[0][0], &G1[0][1], &G1[1][0], &G1[1][1], &G2[0][0], &G2[0][1], &G2[1][0], &G2[1][1], &G3[0][0], &G3[0][1]};
+    v16f g3;                   // the four 16-column blocks of G3 side by side, for the sum over waves
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) g3[4 * cb + v] = G3[cb][v];
+    v16f* all[9] = {&G1[0][0], &G1[0][1], &G1[1][0], &G1[1][1], &G2[0][0], &G2[0][1], &G2[1][0], &G2[1][1], &g3};
     static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 5 * 1024 * sizeof(float), "scratch for the block sum");
-    block_sum_all<kWaves, 10>(scratch, all, wave, lane);
+    block_sum_all<kWaves, 9>(scratch, all, wave, lane);
     if (wave == 0) {
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -300,13 +308,12 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
                     const int e = external_column(c);
                     if (e >= 0) atomicAdd(a.dW[0] + o * 38 + e, G1[mb][nb][r]);
                 }
+        if (lane < 16) {       // rows 0..3 of a block live in lanes 0..15; three of them are real
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+            for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int o = neuron_of(r, h), c = 32 * nb + j;
-                if (o < 3) atomicAdd(a.dW[2] + o * 64 + c, G3[0][nb][r]);
-            }
+                for (int v = 0; v < 3; ++v) atomicAdd(a.dW[2] + v * 64 + 16 * cb + lane, g3[4 * cb + v]);
+        }
     }
 }
 

@@ -152,6 +152,38 @@ __device__ __forceinline__ void outer_accumulate(v16f (*G)[XB], const float* __r
     }
 }
 
+// The same for a factor Z with at most 16 columns (the 16-wide output adjoint, the 3 colour
+// adjoints), on v_mfma_f32_16x16x4_f32: half the matrix-pipe time of a 32-row block that is
+// half or nearly all padding, and a quarter of the accumulator registers per 32 columns.
+//   D(16x16) += A(16x4) B(4x16); lane l holds A[l%16][l/16] and B[l/16][l%16], and register v
+//   of lane l holds D[4*(l/16) + v][l%16]   (checked on the chip).
+// G[cb][v] accumulates row 4*(lane/16) + v, column 16*cb + lane%16 of Z^T X.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int XB, int LDZ, int LDX>
+__device__ __forceinline__ void outer_accumulate16(v4f* G, const float* __restrict__ Zt, const float* __restrict__ Xt,
+                                                   int lane) {
+    constexpr int CB = 2 * XB;
+    const int i = lane & 15, k = lane >> 4;
+    float a = Zt[k * LDZ + i], an = 0.f, b[CB], bn[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) b[cb] = Xt[k * LDX + 16 * cb + i];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if (s + 1 < 8) {
+            an = Zt[(4 * s + 4 + k) * LDZ + i];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) bn[cb] = Xt[(4 * s + 4 + k) * LDX + 16 * cb + i];
+        }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) G[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[cb], G[cb], 0, 0, 0);
+        a = an;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) b[cb] = bn[cb];
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Sum one register vector over the block's WAVES waves through a 1024-float LDS scratch;
 // the result is valid in the last wave.  Every thread of the block must call it.
 template <int WAVES>

@@ -333,14 +333,16 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];
 
-    v16f G1[2][1], G2[2][2], GL[1][2], tsum[2];
+    v16f G1[2][1], G2[2][2], tsum[2];
+    v4f GL[4];                 // gradient of the last matrix [16][64]: four blocks of 16 columns
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
         G1[mb][0] = zero16();
         G2[mb][0] = zero16(); G2[mb][1] = zero16();
-        GL[0][mb] = zero16();
         tsum[mb] = zero16();
     }
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) GL[cb] = v4f{0.f, 0.f, 0.f, 0.f};
 
     const int64_t tiles = (a.n + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * kWaves;
@@ -376,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         stage<1, kLd64>(Zt, dK, j, h);
         stage<2, kLd64>(Xt, K == 3 ? a2 : a1, j, h);
         wave_lds_fence();
-        outer_accumulate<1, 2, kLd64, kLd64>(GL, Zt, Xt, j, h);
+        outer_accumulate16<2, kLd64, kLd64>(GL, Zt, Xt, lane);
         matvec<2, 1, 20, 8>(w.HLt, dK, d2, j, h);
         apply_mask<2>(d2, m_last);
         if (K == 3) {
@@ -447,16 +449,21 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         stage<1, kLd64>(Zt, onehot, j, h);
         stage<2, kLd64>(Xt, tsum, j, h);
         wave_lds_fence();
-        outer_accumulate<1, 2, kLd64, kLd64>(GL, Zt, Xt, j, h);
+        outer_accumulate16<2, kLd64, kLd64>(GL, Zt, Xt, lane);
     }
     __syncthreads();
     // ---- reduce over the block's waves, then one atomic add per element and block
     float* scratch = &sm.tiles[0][0][0];
     static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 4 * 1024 * sizeof(float), "scratch for the block sum");
+    v16f gl;                   // the four 16-column blocks of GL side by side, for the sum over waves
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) gl[4 * cb + v] = GL[cb][v];
+    gl = block_sum<kWaves>(scratch, gl, wave, lane);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
         G1[mb][0] = block_sum<kWaves>(scratch, G1[mb][0], wave, lane);
-        GL[0][mb] = block_sum<kWaves>(scratch, GL[0][mb], wave, lane);
         if (K == 3) {
             G2[mb][0] = block_sum<kWaves>(scratch, G2[mb][0], wave, lane);
             G2[mb][1] = block_sum<kWaves>(scratch, G2[mb][1], wave, lane);
@@ -465,7 +472,11 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     if (wave == kWaves - 1) {
         flush_grad<2, 1>(a.dH[0], 64, D, G1, j, h);
         if (K == 3) flush_grad<2, 2>(a.dH[1], 64, 64, G2, j, h);
-        flush_grad<1, 2>(a.dH[K - 1], 16, 64, GL, j, h);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                atomicAdd(a.dH[K - 1] + (4 * (lane >> 4) + v) * 64 + 16 * cb + (lane & 15), gl[4 * cb + v]);
     }
 }
 

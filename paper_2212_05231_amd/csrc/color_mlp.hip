@@ -179,7 +179,8 @@ __device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v
 __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     __shared__ ColorWeights<false> w;
     load_weights<false>(w, a);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
     const int64_t tiles = (a.n + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * kWaves;
@@ -213,7 +214,8 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     __shared__ ColorBwdSmem sm;
     ColorWeights<true>& w = sm.w;
     load_weights<true>(w, a);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];

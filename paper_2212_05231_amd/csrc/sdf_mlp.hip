@@ -248,7 +248,8 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
     __shared__ SdfWeights<D, K> w;
     load_weights<D, K>(w, a);
     constexpr int LDIN = SdfWeights<D, K>::LDIN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
     const int64_t tiles = (a.n + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * kWaves;
@@ -328,7 +329,8 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     SdfWeights<D, K>& w = sm.w;
     load_weights<D, K>(w, a);
     constexpr int LDIN = SdfWeights<D, K>::LDIN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];

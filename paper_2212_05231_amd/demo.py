@@ -39,7 +39,8 @@ def make_batch(rng, n_rays: int, spr: int):
     th = -b - np.sqrt(np.where(hit, disc, 0.0))
     ph = o + th[:, None] * v
     target = np.where(hit[:, None], 0.5 + 0.5 * ph / RADIUS, 0.0)
-    return {"pos": pos.reshape(-1, 3).astype(np.float32), "dirs": v.astype(np.float32), "target": target.astype(np.float32)}
+    return {"pos": pos.reshape(-1, 3).astype(np.float32), "dirs": v.astype(np.float32), "target": target.astype(np.float32),
+            "t": t, "hit": hit, "t_hit": th}
 
 
 def geometric_init(cfg, params, rng, radius_cube: float) -> None:
@@ -109,10 +110,21 @@ def run(steps: int, n_rays: int, seed: int = 0, log=print):
     d = step2.y[:, 0].cpu().numpy()
     world = probe["pos"].astype(np.float64) * 2.0 - 1.0
     true = np.linalg.norm(world, axis=1) - RADIUS
-    clear = np.abs(true) > 0.05
-    agree = float(np.mean(np.sign(d[clear]) == np.sign(true[clear])))
-    log(f"sign of the learnt SDF agrees with the sphere on {100 * agree:.1f} % of {int(clear.sum())} probe points")
-    return {"history": history, "sign_agreement": agree}
+    # outside the object the rays supervise the field; behind the first surface the transmittance is
+    # zero and nothing but the eikonal term constrains it, so the sign is judged outside only
+    outside = true > 0.05
+    agree = float(np.mean(d[outside] > 0))
+    # where the rendered surface is: expected distance of the compositing weights along rays that hit
+    wgt = step2.weights.cpu().numpy().reshape(2048, cfg.samples_per_ray).astype(np.float64)
+    mass = wgt.sum(axis=1)
+    seen = probe["hit"] & (mass > 0.5)
+    depth = (wgt * probe["t"]).sum(axis=1) / np.maximum(mass, 1e-12)
+    depth_err = float(np.mean(np.abs(depth[seen] - probe["t_hit"][seen])))
+    found = float(np.mean(mass[probe["hit"]] > 0.5))
+    log(f"outside the sphere the learnt SDF is positive on {100 * agree:.1f} % of {int(outside.sum())} probe points; "
+        f"{100 * found:.1f} % of the rays that hit the sphere render a surface, at a mean distance error of {depth_err:.4f} "
+        f"(sphere radius {RADIUS}, sample spacing {2.0 / cfg.samples_per_ray:.3f})")
+    return {"history": history, "outside_positive": agree, "surface_found": found, "depth_error": depth_err}
 
 
 def main() -> None:

@@ -645,13 +645,15 @@ def test_concentrated_batch_overflows_the_record_lists():
 
 def test_training_loop_on_an_analytic_scene_learns():
     """The step used as a training loop (new rays every iteration, progressive levels, Adam): on a
-    shaded sphere the colour loss falls and the learnt SDF separates inside from outside, starting
-    from a sphere of the wrong radius."""
+    shaded sphere the colour loss falls and the rays that hit the sphere render a surface at the
+    right distance, starting from a sphere of the wrong radius."""
     from paper_2212_05231_amd import demo
     out = demo.run(steps=200, n_rays=2048, log=lambda *_: None)
     first, last = out["history"][0][1], np.mean([h[1] for h in out["history"][-3:]])
     assert last < 0.3 * first, out["history"]
-    assert out["sign_agreement"] > 0.97, out["sign_agreement"]
+    # (the sign of the field in empty space is not asserted: without a mask term a black surface in
+    # front of the background fits the photometric loss as well as no surface does)
+    assert out["surface_found"] > 0.9 and out["depth_error"] < 0.06, out
 
 
 def test_empty_batch_is_a_no_op():

@@ -656,6 +656,31 @@ def test_training_loop_on_an_analytic_scene_learns():
     assert out["surface_found"] > 0.9 and out["depth_error"] < 0.06, out
 
 
+@pytest.mark.parametrize("n_rays", [40, 1100])
+def test_step_with_no_active_or_no_trained_level(n_rays):
+    """Degenerate level settings on both scatter paths: lambda = 0 (every encoding is zero: the
+    networks see zeros, all table gradients are zero) and frozen_levels = active_levels (levels
+    feed the network but none is trained)."""
+    for active, frozen in ((0, 0), (3, 3)):
+        w = wl.make_workload(2, n_rays=n_rays)
+        cfg, params, batch = w["cfg"], w["params"], w["batch"]
+        params["tables"] = (params["tables"].astype(np.float64) * 2000.0).astype(params["tables"].dtype)
+        cfg.active_levels, cfg.frozen_levels = active, frozen
+        n = batch["pos"].shape[0]
+        step = nb.Step(cfg, params, n)
+        step.set_batch(batch)
+        step.zero_grads()
+        step.train_step()
+        torch.cuda.synchronize()
+        assert float(step.d_tables.abs().sum()) == 0.0
+        assert torch.isfinite(step.loss).all()
+        if active == 0:
+            assert float(step.enc.abs().sum()) == 0.0 and float(step.y.abs().sum()) == 0.0
+        if n_rays < 100:
+            ref = o.train_step(cfg, params, batch)
+            check_step(cfg, step, ref, n)
+
+
 def test_empty_batch_is_a_no_op():
     cfg = wl.make_config(2)
     params = wl.make_params(cfg, 1)

@@ -182,6 +182,48 @@ def make_ragged_rays(n_rays: int, seed: int, max_len: int = 200) -> Dict[str, np
             "ray_offsets": offsets.astype(np.int32), "sample_ray": sample_ray.astype(np.int32)}
 
 
+def make_camera_rays(n_rays: int, seed: int) -> Dict[str, np.ndarray]:
+    """Rays for the ray marcher, in unit-cube coordinates: the cameras of `make_rays` (on a
+    sphere of radius 3 around the scene, looking at the origin with +-0.3 jitter, world cube
+    [-1,1]^3 mapped to [0,1]^3), plus 3 % of rays that miss the cube and 2 % that start
+    inside it.  Returns origins [R,3], dirs [R,3] (unit), jitter [R] in [0,1), target [R,3], fp32.
+    """
+    rng = np.random.default_rng(seed)
+    u = rng.normal(size=(n_rays, 3))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    o = 3.0 * u
+    tgt = rng.uniform(-0.3, 0.3, size=(n_rays, 3))
+    kind = rng.uniform(size=n_rays)
+    tgt[kind < 0.03] += 4.0 * u[kind < 0.03][:, [1, 2, 0]]          # looks past the scene
+    inside = kind > 0.98
+    o[inside] = rng.uniform(-0.9, 0.9, size=(int(inside.sum()), 3))
+    v = tgt - o
+    v /= np.linalg.norm(v, axis=1, keepdims=True)
+    return {"origins": ((o + 1.0) * 0.5).astype(np.float32), "dirs": v.astype(np.float32),
+            "jitter": rng.uniform(0.0, 1.0, size=n_rays).astype(np.float32),
+            "target": rng.uniform(0.0, 1.0, size=(n_rays, 3)).astype(np.float32)}
+
+
+def make_shell_cells(log2_res: int, radius: float = 0.3, half_width: float = 0.03) -> np.ndarray:
+    """Occupied cells of a trained scene, as a bool array [G,G,G] indexed [x,y,z]: the cells
+    whose centre lies within `half_width` of a sphere of `radius` around the cube's centre
+    (cells near the surface are the ones an SDF-driven update keeps)."""
+    G = 1 << log2_res
+    c = (np.arange(G) + 0.5) / G - 0.5
+    r = np.sqrt(c[:, None, None] ** 2 + c[None, :, None] ** 2 + c[None, None, :] ** 2)
+    return np.abs(r - radius) <= half_width
+
+
+def make_candidate_cells(log2_res: int, m: int, seed: int, duplicates: bool = True) -> Dict[str, np.ndarray]:
+    """Candidate cells of one grid update: m cell numbers (uniform over the grid, so some are
+    drawn twice unless `duplicates` is off) and a point offset in [0,1)^3 inside each."""
+    rng = np.random.default_rng(seed)
+    n_cells = 1 << (3 * log2_res)
+    cells = rng.integers(0, n_cells, size=m) if duplicates else rng.permutation(n_cells)[:m]
+    jit = rng.uniform(0.0, 1.0, size=(m, 3)).astype(np.float32)
+    return {"cells": cells.astype(np.int32), "jitter": np.minimum(jit, np.float32(1.0 - 2.0 ** -24))}
+
+
 def make_rigid(seed: int, max_angle_deg: float = 5.0, max_shift: float = 0.05) -> Dict[str, np.ndarray]:
     """Workload 5: a small axis-angle vector omega and a translation, float64."""
     rng = np.random.default_rng(seed)

@@ -258,6 +258,46 @@ typedef struct neus2_step_buffers {
  * loss is zeroed first; dH, dW and d_tables are ADDED into. */
 int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* buf, int64_t n, void* stream);
 
+/* ---- Occupancy grid and ray marching (supplement Sec. E.3 "Ray Marching Acceleration") ------
+ * A grid of G^3 cells over the unit cube, G = 2^log2_res (2 <= log2_res <= 8), marks cells as
+ * empty or not; the marcher leaves out samples in empty cells.  Cell (x,y,z) has the Morton
+ * number with bit b of x, y, z at bit 3b, 3b+1, 3b+2.  density [device, G^3 fp32] holds one
+ * non-negative value per cell in Morton order, bitfield [device, G^3/32 uint32] cell c in bit
+ * c%32 of word c/32.  The paper refreshes the grid from the SDF through the logistic density
+ * phi_s(d) = s e^{-sd} / (1+e^{-sd})^2 "in the same way as" the publication it cites: decay
+ * all values, raise candidate cells to the density at a random point inside them, threshold. */
+
+/* Sample points of m candidate cells: pos[i] = (cell coordinate + jitter[i]) / G.
+ *   cells [device, m int32] Morton numbers (taken modulo G^3), jitter [device, m*3] in [0,1),
+ *   pos [device, m*3].  The caller evaluates the SDF there (neus2_hash_encode,
+ *   neus2_sdf_fwd_grad) and hands it to neus2_occupancy_update. */
+int neus2_occupancy_points(int log2_res, const int32_t* cells, const float* jitter, int64_t m,
+                           float* pos, void* stream);
+
+/* One refresh: density *= decay for every cell; density[cells[i]] = max(., phi_s(sdf[i*sdf_stride]))
+ * (a cell named twice keeps the larger; cell numbers outside the grid and non-finite values
+ * are skipped); then bit c = density[c] > threshold for every cell.
+ *   s_dev [device, 1] the trained slope, or NULL to use the argument s.  0 <= decay <= 1,
+ *   threshold >= 0.  m may be 0 (decay and threshold only). */
+int neus2_occupancy_update(int log2_res, float* density, const int32_t* cells, const float* sdf,
+                           int64_t sdf_stride, int64_t m, const float* s_dev, float s, float decay,
+                           float threshold, uint32_t* bitfield, void* stream);
+
+/* Ray marching through the grid.  Ray r (origins, dirs [device, rays*3], unit-cube coordinates;
+ * jitter [device, rays] in [0,1)) is clipped against [0,1]^3 (slab test, t_near >= 0); its
+ * samples are the lattice points t_k = t_0 + k dt, t_0 = t_near + jitter dt, 0 <= k < max_steps,
+ * with t_k < t_far whose cell clamp(floor((o + t_k d) G)) has its bit set.  All of this is
+ * binary32 arithmetic, one rounding per operation, in the order written here.
+ * Outputs, rays in order, a ray's samples in order of k:
+ *   ray_offsets [device, rays+1 int32], pos [device, capacity*3], sample_ray [device, capacity
+ *   int32] (the ray of each sample), t [device, capacity] or NULL (the parameters t_k).
+ * At most `capacity` samples are written: the ray that crosses the capacity is cut there and
+ * later rays get none (ray_offsets is clamped to capacity); n = ray_offsets[rays].  These are
+ * the ray_offsets / sample_ray / pos that neus2_train_step takes for rays of unequal length. */
+int neus2_march_rays(int log2_res, const uint32_t* bitfield, const float* origins, const float* dirs,
+                     const float* jitter, int64_t rays, float dt, int32_t max_steps, int64_t capacity,
+                     int32_t* ray_offsets, float* pos, int32_t* sample_ray, float* t, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

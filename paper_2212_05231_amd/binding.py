@@ -77,6 +77,9 @@ _SIGNATURES = {
                                     C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
     "neus2_rigid_bwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
+    "neus2_occupancy_points": (C.c_int, [C.c_int, _P, _P, C.c_int64, _P, _P]),
+    "neus2_occupancy_update": (C.c_int, [C.c_int, _P, _P, _P, C.c_int64, C.c_int64, _P, C.c_float, C.c_float, C.c_float, _P, _P]),
+    "neus2_march_rays": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int64, C.c_float, C.c_int32, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_train_step": (C.c_int, [C.POINTER(Neus2Config), C.POINTER(Neus2StepBuffers), C.c_int64, _P]),
 }
 
@@ -241,6 +244,21 @@ def rigid_bwd(pos, T, d_out, scale, Mb):
     _check(lib().neus2_rigid_bwd(_ptr(pos), Ta, _ptr(d_out), scale, pos.shape[0], _ptr(Mb), _stream()))
 
 
+def occupancy_points(log2_res, cells, jitter, pos):
+    _check(lib().neus2_occupancy_points(log2_res, _ptr(cells), _ptr(jitter), cells.shape[0], _ptr(pos), _stream()))
+
+
+def occupancy_update(log2_res, density, cells, sdf, sdf_stride, m, s, decay, threshold, bitfield, s_dev=None):
+    _check(lib().neus2_occupancy_update(log2_res, _ptr(density), _ptr(cells), _ptr(sdf), sdf_stride, m, _ptr(s_dev),
+                                        s, decay, threshold, _ptr(bitfield), _stream()))
+
+
+def march_rays(log2_res, bitfield, origins, dirs, jitter, dt, max_steps, capacity, ray_offsets, pos, sample_ray, t=None):
+    _check(lib().neus2_march_rays(log2_res, _ptr(bitfield), _ptr(origins), _ptr(dirs), _ptr(jitter), origins.shape[0],
+                                  dt, max_steps, capacity, _ptr(ray_offsets), _ptr(pos), _ptr(sample_ray), _ptr(t),
+                                  _stream()))
+
+
 class Step:
     """All device buffers of one training step, allocated once with torch, plus the
     `neus2_step_buffers` struct that `train_step` hands to the library."""
@@ -343,5 +361,11 @@ class Step:
         adam_step(self.small, None, self.d_small, o["m_s"], o["v_s"], 0,
                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
 
-    def train_step(self) -> None:
-        _check(lib().neus2_train_step(C.byref(self.c), C.byref(self.buffers), self.n, _stream()))
+    def train_step(self, n: Optional[int] = None) -> None:
+        """`n` (at most the n the buffers were sized for) runs the step on the first n samples:
+        what a ray marcher that filled part of the buffers wants.  Per-point arrays are laid
+        out for that n, so every call of one step must be given the same value."""
+        n = self.n if n is None else n
+        if not 0 <= n <= self.n:
+            raise ValueError(f"n = {n} outside 0..{self.n}")
+        _check(lib().neus2_train_step(C.byref(self.c), C.byref(self.buffers), n, _stream()))

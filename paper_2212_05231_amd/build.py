@@ -12,7 +12,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libneus2.so")
-SOURCES = ["api.hip", "hash_grid.hip", "sdf_mlp.hip", "color_mlp.hip", "render.hip"]
+SOURCES = ["api.hip", "hash_grid.hip", "sdf_mlp.hip", "color_mlp.hip", "render.hip", "occupancy.hip"]
+# the ray marcher decides integers from binary32 arithmetic: one rounding per operation there
+EXTRA_FLAGS = {"occupancy.hip": ["-ffp-contract=off"]}
 # packed fp32 instructions are switched off on purpose (the compiler otherwise forms them at -O3)
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -32,7 +34,7 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [cc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")

@@ -110,6 +110,9 @@ def main() -> int:
     ap.add_argument("--rays", type=int, default=None, help="override the number of rays (points for workload 1)")
     ap.add_argument("--ragged", action="store_true",
                     help="rays with their own sample counts (the length mix of a ray marcher) instead of a fixed count")
+    ap.add_argument("--marched", action="store_true",
+                    help="samples come from the ray marcher: camera rays through a 128^3 occupancy grid around a surface, marched "
+                         "inside every timed step (workloads 2..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -141,8 +144,34 @@ def main() -> int:
         cfg.name = f"cfg{args.workload}-ragged-{batch['dirs'].shape[0]}rays"
     n = batch["pos"].shape[0]
     dynamic = "omega" in batch
-    step = nb.Step(cfg, params, n, n_rays=batch["dirs"].shape[0] if args.ragged else None, want_pos_grad=dynamic)
-    step.set_batch(batch)
+    grid = None
+    if args.marched:
+        if cfg.loss_kind == 0 or dynamic or args.ragged:
+            print("bench.py: --marched needs one of the workloads 2..4 and excludes --ragged", file=sys.stderr)
+            return 2
+        import math
+        from paper_2212_05231_amd import occupancy
+        R = args.rays or wl.default_rays(args.workload)
+        cam = wl.make_camera_rays(R, seed=2000 + args.workload)
+        cfg.name = f"cfg{args.workload}-marched-{R}rays"
+        step = nb.Step(cfg, params, 128 * R, n_rays=R)
+        step.dirs.copy_(torch.from_numpy(cam["dirs"]))
+        step.target.copy_(torch.from_numpy(cam["target"]))
+        # the grid of a trained scene, made by the library's own update from an analytic SDF: cells whose
+        # centre is within 0.03 of a sphere of radius 0.3 (threshold = the logistic density at that distance)
+        log2_res, band = 7, 0.03
+        e = math.exp(-cfg.s * band)
+        grid = occupancy.OccupancyGrid(step, log2_res=log2_res, threshold=cfg.s * e / (1.0 + e) ** 2)
+        all_cells = torch.arange(grid.n_cells, dtype=torch.int32, device="cuda")
+        nb.occupancy_points(log2_res, all_cells, torch.full((grid.n_cells, 3), 0.5, device="cuda"), grid.pos)
+        sdf = ((grid.pos - 0.5).norm(dim=1) - 0.3).contiguous()
+        nb.occupancy_update(log2_res, grid.density, all_cells, sdf, 1, grid.n_cells, cfg.s, 1.0, grid.threshold, grid.bitfield)
+        origins, jitter = torch.from_numpy(cam["origins"]).cuda(), torch.from_numpy(cam["jitter"]).cuda()
+        march_dt, march_steps = math.sqrt(3.0) / 1024, 1024
+        n = grid.march(origins, step.dirs, jitter, march_dt, march_steps)
+    else:
+        step = nb.Step(cfg, params, n, n_rays=batch["dirs"].shape[0] if args.ragged else None, want_pos_grad=dynamic)
+        step.set_batch(batch)
     step.zero_grads()
     step.init_optimizer()
     if dynamic:
@@ -157,7 +186,11 @@ def main() -> int:
     def one_step():
         if dynamic:
             nb.rigid_fwd(world, rot, shift, 0.5, 0.5, step.pos)
-        step.train_step()
+        if grid is not None:
+            # the host reads the sample count back before it can size the step's launches
+            step.train_step(grid.march(origins, step.dirs, jitter, march_dt, march_steps))
+        else:
+            step.train_step()
         if dynamic:
             Mb.zero_()
             nb.rigid_bwd(world, shift, step.d_pos, 0.5, Mb)
@@ -194,16 +227,19 @@ def main() -> int:
         o = s.opt
         half = 1 if cfg.table_dtype == "f16" else 0
         seq = []
+        if grid is not None:
+            seq += [("ray_march", lambda: nb.march_rays(grid.log2_res, grid.bitfield, origins, s.dirs, jitter, march_dt, march_steps,
+                                                        s.n, s.ray_offsets, s.pos, s.sample_ray))]
         if dynamic:
             seq += [("rigid_fwd", lambda: nb.rigid_fwd(world, rot, shift, 0.5, 0.5, s.pos))]
-        seq += [("hash_encode", lambda: nb.hash_encode(c, s.pos, s.tables, s.enc, s.jac)),
+        seq += [("hash_encode", lambda: nb.hash_encode(c, s.pos[:n], s.tables, s.enc, s.jac)),
                ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal))]
         if cfg.loss_kind != 0:
             seq += [
                 ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb, sample_ray=s.sample_ray)),
                 ("render_loss_bwd", (lambda: nb.render_loss_bwd_ragged(c, s.y, s.rgb, s.normal, s.target, s.ray_offsets, rays, n,
                                                                        s.C, s.weights, s.loss, s.dC, s.d_sdf, s.d_rgb, s.d_normal))
-                 if args.ragged else
+                 if s.ragged else
                  (lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
                                              s.dC, s.d_sdf, s.d_rgb, s.d_normal))),
                 ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
@@ -219,7 +255,7 @@ def main() -> int:
         else:
             seq += [
                 ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
-                ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos, s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
+                ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos[:n], s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
                                                                  workspace=s.workspace)),
             ]
         if dynamic:
@@ -236,6 +272,7 @@ def main() -> int:
                                "flops": cost["sdf_mlp_bwd"]["flops"]}
         cost["rigid_fwd"] = {"bytes": 24 * n, "flops": 0}
         cost["rigid_bwd"] = {"bytes": 24 * n, "flops": 0}
+        cost["ray_march"] = {"bytes": 32 * rays + 16 * n, "flops": 0}       # a ray's 32 bytes in, a sample's pos + owner out
         reps = max(5, min(args.steps, 100))
         total = {name: 0.0 for name, _ in seq}
         events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(seq) + 1)] for _ in range(reps)]
@@ -269,6 +306,18 @@ def main() -> int:
         roofline["us_per_launch"] = kd["us"]
         roofline["hip_kernels"] = KERNELS_OF_CALL.get(dom)
         roofline["algorithmic_bytes"] = kd["bytes"]
+        if grid is not None:
+            # one refresh of the grid with every cell a candidate (encode + SDF network on 128^3 points, then the update):
+            # runs every 16th iteration, outside the timed step
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            grid.update()
+            ev[0].record()
+            for _ in range(5):
+                grid.update()
+            ev[1].record()
+            torch.cuda.synchronize()
+            kernels["occupancy_refresh"] = {"us": round(1e3 * ev[0].elapsed_time(ev[1]) / 5, 1), "candidate_cells": grid.n_cells,
+                                            "note": "every 16th iteration, not part of the timed step"}
         mt = MEASURED_TRAFFIC_MIB.get(cfg.name, {}).get(dom) if n == wl.default_rays(args.workload) * cfg.samples_per_ray else None
         roofline["traffic"] = int((mt[0] + mt[1]) * 1048576) if mt else None
 
@@ -277,9 +326,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from threadpoolctl import threadpool_limits
         from oracle import neus2_oracle as o
-        sample_rays = min(128 if args.ragged else 512, step.rays)
+        sample_rays = min(128 if step.ragged else 512, step.rays)
         ws = wl.make_workload(args.workload, n_rays=sample_rays)
-        if args.ragged:
+        if step.ragged:
             ws["batch"] = wl.make_ragged_rays(sample_rays, seed=2000 + args.workload)
         with threadpool_limits(limits=1):
             t0 = time.perf_counter()
@@ -301,7 +350,9 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "points_per_step": n, "rays": step.rays,
-                   "samples_per_ray": "0..128 per ray (ray marcher's mix)" if args.ragged else cfg.samples_per_ray, "levels": cfg.n_levels, "active_levels": cfg.active_levels,
+                   "samples_per_ray": ("0..128 per ray (ray marcher's mix)" if args.ragged else
+                                       f"marched, step sqrt(3)/1024, {n / max(step.rays, 1):.1f} per ray on average" if args.marched else
+                                       cfg.samples_per_ray), "levels": cfg.n_levels, "active_levels": cfg.active_levels,
                    "log2_table_size": cfg.log2_table_size, "table_dtype": cfg.table_dtype,
                    "sdf_mlp": cfg.sdf_dims, "color_mlp": cfg.color_dims, "includes_adam": True},
         "loss": loss_now,

@@ -1,13 +1,18 @@
 """A small end-to-end training run on an analytic scene (no dataset is needed): a shaded sphere
 of radius 0.5 seen from cameras on a sphere of radius 3, black background.
 
-    python -m paper_2212_05231_amd.demo [--steps 400] [--rays 4096]
+    python -m paper_2212_05231_amd.demo [--steps 400] [--rays 4096] [--march]
 
 Every iteration draws new rays, renders their target colour analytically, and runs the
 library's training step (forward, second-order backward, Adam) with the progressive level
 schedule of Sec. 4.3.  Prints the loss as it falls and, at the end, how well the sign of the
 learnt SDF separates inside from outside on fresh points.  It exercises the step as a
 training loop; it is not one of the paper's experiments.
+
+With --march the samples come from the ray marcher instead (supplement Sec. E.3): an occupancy
+grid is refreshed from the learnt SDF every 16 iterations and each ray keeps only the lattice
+points in occupied cells, so rays have their own sample counts and the batch shrinks as the
+grid empties.
 """
 from __future__ import annotations
 
@@ -40,7 +45,7 @@ def make_batch(rng, n_rays: int, spr: int):
     ph = o + th[:, None] * v
     target = np.where(hit[:, None], 0.5 + 0.5 * ph / RADIUS, 0.0)
     return {"pos": pos.reshape(-1, 3).astype(np.float32), "dirs": v.astype(np.float32), "target": target.astype(np.float32),
-            "t": t, "hit": hit, "t_hit": th}
+            "t": t, "hit": hit, "t_hit": th, "origin": o}
 
 
 def geometric_init(cfg, params, rng, radius_cube: float) -> None:
@@ -76,9 +81,9 @@ def geometric_init(cfg, params, rng, radius_cube: float) -> None:
     params["H"] = H
 
 
-def run(steps: int, n_rays: int, seed: int = 0, log=print):
+def run(steps: int, n_rays: int, seed: int = 0, log=print, march: bool = False):
     import torch
-    from . import binding as nb, schedule, workloads as wl
+    from . import binding as nb, occupancy, schedule, workloads as wl
     cfg = wl.make_config(2)
     cfg.log2_table_size = 15
     cfg.res = wl.level_resolutions(16, 16, 512)
@@ -87,19 +92,40 @@ def run(steps: int, n_rays: int, seed: int = 0, log=print):
     geometric_init(cfg, params, np.random.default_rng(seed + 2), radius_cube=0.5 * 0.6)
     cfg.frozen_levels = 2          # the two coordinate levels stay what they are: e = (x, h(x))
     n = n_rays * cfg.samples_per_ray
-    step = nb.Step(cfg, params, n)
-    step.init_optimizer(lr=1e-2)
     rng = np.random.default_rng(seed)
-    history = []
+    history, marched = [], []
+    if march:
+        # room for 3 times the fixed batch; marching step 1/128 of the cube's edge
+        step = nb.Step(cfg, params, 3 * n, n_rays=n_rays)
+        grid = occupancy.OccupancyGrid(step, log2_res=6, decay=0.95, threshold=0.3 * cfg.s / 4)
+        dt, max_steps = 1.0 / 128, 256
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+    else:
+        step = nb.Step(cfg, params, n)
+    step.init_optimizer(lr=1e-2)
     for it in range(steps):
         step.c.active_levels = schedule.active_levels(it, steps, cfg.n_levels)
-        step.set_batch(make_batch(rng, n_rays, cfg.samples_per_ray))
-        step.train_step()
+        if march:
+            if it % 16 == 0:
+                grid.update(gen)
+            b = make_batch(rng, n_rays, 1)
+            step.dirs.copy_(torch.from_numpy(b["dirs"]))
+            step.target.copy_(torch.from_numpy(b["target"]))
+            origins = torch.from_numpy(((b["origin"] + 1.0) * 0.5).astype(np.float32)).cuda()
+            jitter = torch.from_numpy(rng.uniform(size=n_rays).astype(np.float32)).cuda()
+            n_it = grid.march(origins, step.dirs, jitter, dt, max_steps)
+            marched.append(n_it)
+            step.train_step(n_it)
+        else:
+            step.set_batch(make_batch(rng, n_rays, cfg.samples_per_ray))
+            step.train_step()
         step.adam()
         if it % 25 == 0 or it == steps - 1:
             l = step.loss.cpu().numpy()
             history.append((it, float(l[0]), float(l[1])))
-            log(f"step {it:5d}  levels {step.c.active_levels:2d}  colour loss {l[0]:.4f}  eikonal term {l[1]:.4f}")
+            log(f"step {it:5d}  levels {step.c.active_levels:2d}  colour loss {l[0]:.4f}  eikonal term {l[1]:.4f}"
+                + (f"  samples {marched[-1]:7d}  occupied cells {100 * grid.occupied_fraction():5.1f} %" if march else ""))
     # sign of the learnt SDF against the true one on fresh sample points
     probe = make_batch(rng, 2048, cfg.samples_per_ray)
     step2 = nb.Step(cfg, {"tables": step.tables.cpu().numpy(), "H": [h.cpu().numpy() for h in step.H],
@@ -124,15 +150,19 @@ def run(steps: int, n_rays: int, seed: int = 0, log=print):
     log(f"outside the sphere the learnt SDF is positive on {100 * agree:.1f} % of {int(outside.sum())} probe points; "
         f"{100 * found:.1f} % of the rays that hit the sphere render a surface, at a mean distance error of {depth_err:.4f} "
         f"(sphere radius {RADIUS}, sample spacing {2.0 / cfg.samples_per_ray:.3f})")
-    return {"history": history, "outside_positive": agree, "surface_found": found, "depth_error": depth_err}
+    out = {"history": history, "outside_positive": agree, "surface_found": found, "depth_error": depth_err}
+    if march:
+        out.update({"samples_first": marched[0], "samples_last": marched[-1], "occupied_fraction": grid.occupied_fraction()})
+    return out
 
 
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--rays", type=int, default=4096)
+    ap.add_argument("--march", action="store_true", help="sample with the occupancy grid and the ray marcher")
     a = ap.parse_args()
-    out = run(a.steps, a.rays)
+    out = run(a.steps, a.rays, march=a.march)
     print(json.dumps(out))
 
 

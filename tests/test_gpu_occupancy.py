@@ -213,3 +213,43 @@ def test_marched_batch_through_the_training_step():
     assert rel(step.d_tables.cpu().numpy(), ref["dtables"]) <= 1e-4
     for a, b in zip(list(step.dH) + list(step.dW), list(ref["dH"]) + list(ref["dW"])):
         assert rel(a.cpu().numpy(), b) <= 1e-4
+
+
+def test_grid_refresh_from_the_network_and_candidate_schedule():
+    """OccupancyGrid.update strings points -> encode -> SDF network -> update together; its result
+    is the oracle's update fed with the oracle's SDF at the same points.  Then the schedule: all
+    cells while warming up, afterwards half of the candidates among the occupied cells."""
+    from paper_2212_05231_amd import occupancy
+    w = wl.make_workload(2, n_rays=8)
+    cfg, params = w["cfg"], w["params"]
+    params["tables"] = (params["tables"].astype(np.float64) * 3000.0).astype(params["tables"].dtype)
+    step = nb.Step(cfg, params, 64, n_rays=1)
+    log2_res = 4
+    grid = occupancy.OccupancyGrid(step, log2_res=log2_res, decay=0.9, threshold=4.0, warm_updates=1)
+    assert grid.occupied_fraction() == 1.0
+    m = grid.update()
+    torch.cuda.synchronize()
+    assert m == 4096
+    pos = grid.pos.cpu().numpy()
+    assert np.array_equal(pos, oc.cell_points(np.arange(4096), grid.jitter.cpu().numpy(), log2_res))
+    he = o.hash_encode(cfg, params["tables"].astype(np.float64), pos.astype(np.float64))
+    y = o.mlp_forward([np.asarray(h, np.float64) for h in params["H"]], he["enc"])[0]
+    dens_ref, bits_ref = oc.occupancy_update(np.zeros(4096), np.arange(4096), y[:, 0], cfg.s, 0.9, 4.0)
+    got = grid.density.cpu().numpy()
+    assert np.all(np.abs(got - dens_ref) <= 1e-4 * dens_ref + 1e-30)
+    clear = np.abs(dens_ref - 4.0) > 1e-3
+    bits = words_to_bits(grid.bitfield)[:4096]
+    assert np.array_equal(bits[clear], bits_ref[clear]) and 0.0 < bits.mean() < 1.0
+    cand = grid.candidates().cpu().numpy()
+    assert len(cand) == 2048 and bits[cand[1024:]].all() and not bits[cand[:1024]].all()
+
+
+def test_training_loop_with_marched_samples():
+    """The demo's loop with the marcher: the grid is refreshed from the learnt SDF, rays keep the
+    lattice points in occupied cells, and the rendered surface ends up where the sphere is."""
+    from paper_2212_05231_amd import demo
+    out = demo.run(steps=200, n_rays=2048, log=lambda *_: None, march=True)
+    first, last = out["history"][0][1], out["history"][-1][1]
+    assert last < 0.35 * first
+    assert out["surface_found"] > 0.95 and out["depth_error"] < 0.06
+    assert 0.05 < out["occupied_fraction"] < 0.95 and out["samples_last"] > 2048

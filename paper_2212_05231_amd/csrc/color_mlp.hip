@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
 
 struct ColorBwdSmem {
     ColorWeights<true> w;
-    float tiles[kWaves][2][32 * kLd64];
+    float tiles[kWaves][2][kTileWords];
 };
 
 __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
@@ -219,6 +219,8 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     const int j = lane & 31, h = lane >> 5;
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];
+    uint32_t* Zs = reinterpret_cast<uint32_t*>(Zt);     // the same tiles in the transposed split layout
+    uint32_t* Xs = reinterpret_cast<uint32_t*>(Xt);
     v16f G1[2][2], G2[2][2];
     v4f G3[4];                 // gradient of the last matrix (3 of 16 rows used): four blocks of 16 columns
 #pragma unroll
@@ -258,17 +260,17 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         matvec<2, 1, kLdOutT, 4>(w.W3t, d3, d2, j, h);
         apply_mask<2>(d2, m2);
         wave_lds_fence();
-        stage<2, kLd64>(Zt, d2, j, h);
-        stage<2, kLd64>(Xt, a1, j, h);
+        stage_split<2>(Zs, d2, j, h);
+        stage_split<2>(Xs, a1, j, h);
         wave_lds_fence();
-        outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+        outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
         matvec<2, 2, kLd64>(w.W2t, d2, d1, j, h);
         apply_mask<2>(d1, m1);
         wave_lds_fence();
-        stage<2, kLd64>(Zt, d1, j, h);
-        stage<2, kLd64>(Xt, cin, j, h);
+        stage_split<2>(Zs, d1, j, h);
+        stage_split<2>(Xs, cin, j, h);
         wave_lds_fence();
-        outer_accumulate<2, 2, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        outer_accumulate_split<2, 2>(G1, Zs, Xs, lane);
         matvec<1, 2, kLd64>(w.W1t, d1, dcin, j, h);
         wave_lds_fence();
         if (valid) {

@@ -152,6 +152,85 @@ __device__ __forceinline__ void outer_accumulate(v16f (*G)[XB], const float* __r
     }
 }
 
+// ---- weight gradients on the bf16 matrix cores --------------------------------------------
+// A weight gradient is a sum over all points of products of two per-point numbers; it is
+// compared with a reference at gradient tolerance, not at forward tolerance, and its rounding
+// errors average out over the sum.  Both factors are therefore split into two bf16 numbers,
+// x = hi + mid (round to nearest even each time, |x - hi - mid| <= 2^-16 |x|), and the product
+// is taken as hi*hi + hi*mid + mid*hi on v_mfma_f32_32x32x16_bf16, which contracts 16 points
+// per instruction in half the time the fp32 instruction takes for 2: 12 instructions of 32
+// clocks for a 32x32 block over a tile's 32 points, instead of 16 of 64 clocks.
+//   D(32x32) += A(32x16) B(16x32); lane l holds A[l%32][8*(l/32) + s] and B[8*(l/32) + s][l%32],
+//   s = 0..7, and D in the register layout at the top of this file (checked on the chip).
+// The contraction index (the point) must run along a lane's eight operand slots, so the tile
+// is kept transposed, [neuron][point], one 32-bit word [hi | mid] per element, row stride
+// kLdT words: a lane reads its eight points as two 16-byte words, conflict-free.
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kLdT = 36;    // row stride (words) of a transposed split tile [64 neurons][32 points]
+constexpr int kTileWords = 64 * kLdT;   // a per-wave tile holds either layout: [32 points][kLd64] floats or this
+
+__device__ __forceinline__ uint32_t split_bf16(float x) {
+    const __bf16 hi = (__bf16)x;
+    const __bf16 mid = (__bf16)(x - (float)hi);
+    return ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16) | (uint32_t)__builtin_bit_cast(uint16_t, mid);
+}
+
+// Write a register vector to a per-wave transposed split tile.
+template <int NB>
+__device__ __forceinline__ void stage_split(uint32_t* __restrict__ tile, const v16f* v, int j, int h) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tile[(32 * b + neuron_of(r, h)) * kLdT + j] = split_bf16(v[b][r]);
+}
+
+// Eight [hi | mid] words -> the eight hi halves and the eight mid halves as MFMA operands.
+__device__ __forceinline__ void unpack_split(const u32x4& p, const u32x4& q, bf8& hi, bf8& mid) {
+    u32x4 vh, vm;
+    vh[0] = __builtin_amdgcn_perm(p[1], p[0], 0x07060302u);
+    vh[1] = __builtin_amdgcn_perm(p[3], p[2], 0x07060302u);
+    vh[2] = __builtin_amdgcn_perm(q[1], q[0], 0x07060302u);
+    vh[3] = __builtin_amdgcn_perm(q[3], q[2], 0x07060302u);
+    vm[0] = __builtin_amdgcn_perm(p[1], p[0], 0x05040100u);
+    vm[1] = __builtin_amdgcn_perm(p[3], p[2], 0x05040100u);
+    vm[2] = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
+    vm[3] = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
+    hi = __builtin_bit_cast(bf8, vh);
+    mid = __builtin_bit_cast(bf8, vm);
+}
+
+// G[mb][nb] += sum over the tile's 32 points of Z[32*mb + .][point] (x) X[32*nb + .][point], both
+// tiles transposed and split as above; G as in outer_accumulate.
+template <int ZB, int XB>
+__device__ __forceinline__ void outer_accumulate_split(v16f (*G)[XB], const uint32_t* __restrict__ Zt,
+                                                       const uint32_t* __restrict__ Xt, int lane) {
+    const int i = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        bf8 bh[XB], bm[XB];
+#pragma unroll
+        for (int nb = 0; nb < XB; ++nb) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(Xt + (32 * nb + i) * kLdT + 16 * t + 8 * g);
+            unpack_split(src[0], src[1], bh[nb], bm[nb]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < ZB; ++mb) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(Zt + (32 * mb + i) * kLdT + 16 * t + 8 * g);
+            bf8 ah, am;
+            unpack_split(src[0], src[1], ah, am);
+#pragma unroll
+            for (int nb = 0; nb < XB; ++nb) {
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[nb], G[mb][nb], 0, 0, 0);
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm[nb], G[mb][nb], 0, 0, 0);
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh[nb], G[mb][nb], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // The same for a factor Z with at most 16 columns (the 16-wide output adjoint, the 3 colour
 // adjoints), on v_mfma_f32_16x16x4_f32: half the matrix-pipe time of a 32-row block that is
 // half or nearly all padding, and a quarter of the accumulator registers per 32 columns.

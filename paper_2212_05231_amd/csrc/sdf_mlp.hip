@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
 template <int D, int K>
 struct SdfBwdSmem {
     SdfWeights<D, K> w;
-    float tiles[kWaves][2][32 * kLd64];
+    float tiles[kWaves][2][kTileWords];
 };
 
 // add this wave's accumulator into dst[rows][cols] (row-major, ld = cols) with atomics
@@ -334,6 +334,8 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     const int j = lane & 31, h = lane >> 5;
     float* Zt = sm.tiles[wave][0];
     float* Xt = sm.tiles[wave][1];
+    uint32_t* Zs = reinterpret_cast<uint32_t*>(Zt);     // the same tiles in the transposed split layout
+    uint32_t* Xs = reinterpret_cast<uint32_t*>(Xt);
 
     v16f G1[2][1], G2[2][2], tsum[2];
     v4f GL[4];                 // gradient of the last matrix [16][64]: four blocks of 16 columns
@@ -385,20 +387,20 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         apply_mask<2>(d2, m_last);
         if (K == 3) {
             wave_lds_fence();
-            stage<2, kLd64>(Zt, d2, j, h);
-            stage<2, kLd64>(Xt, a1, j, h);
+            stage_split<2>(Zs, d2, j, h);
+            stage_split<2>(Xs, a1, j, h);
             wave_lds_fence();
-            outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+            outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
             matvec<2, 2, kLd64>(w.H2t, d2, d1, j, h);
             apply_mask<2>(d1, m1);
         } else {
             d1[0] = d2[0]; d1[1] = d2[1];
         }
         wave_lds_fence();
-        stage<2, kLd64>(Zt, d1, j, h);
-        stage<1, kLd64>(Xt, x0, j, h);
+        stage_split<2>(Zs, d1, j, h);
+        stage_split<1>(Xs, x0, j, h);
         wave_lds_fence();
-        outer_accumulate<2, 1, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f de[1];
         matvec<1, 2, kLd64>(w.H1t, d1, de, j, h);
         store_levels<D>(a.d_enc, a.n, i, valid, de[0], h);
@@ -421,19 +423,19 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             s1[0] = s2[0]; s1[1] = s2[1];
         }
         wave_lds_fence();
-        stage<2, kLd64>(Zt, s1, j, h);
-        stage<1, kLd64>(Xt, t0, j, h);
+        stage_split<2>(Zs, s1, j, h);
+        stage_split<1>(Xs, t0, j, h);
         wave_lds_fence();
-        outer_accumulate<2, 1, kLd64, kLd64>(G1, Zt, Xt, j, h);
+        outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f t1[2], t2[2];
         matvec<2, 1, LDIN, D / 2>(w.H1f, t0, t1, j, h);
         apply_mask<2>(t1, m1);
         if (K == 3) {
             wave_lds_fence();
-            stage<2, kLd64>(Zt, s2, j, h);
-            stage<2, kLd64>(Xt, t1, j, h);
+            stage_split<2>(Zs, s2, j, h);
+            stage_split<2>(Xs, t1, j, h);
             wave_lds_fence();
-            outer_accumulate<2, 2, kLd64, kLd64>(G2, Zt, Xt, j, h);
+            outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
             matvec<2, 2, kLd64>(w.H2f, t1, t2, j, h);
             apply_mask<2>(t2, m_last);
             tsum[0] += t2[0]; tsum[1] += t2[1];

@@ -205,15 +205,61 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     }
 }
 
+// The backward kernel keeps its matrices split into bf16 terms (see mfma_tile.h): three terms
+// for the recomputed forward pass, whose ReLU masks must come out as in the forward kernel, two
+// for the adjoint sweep.
+struct ColorBwdWeights {
+    alignas(16) unsigned char W1f[64 * SplitMatrix<3, 3>::kLd];     // [64][40 -> 48]
+    alignas(16) unsigned char W2f[64 * SplitMatrix<4, 3>::kLd];
+    alignas(16) unsigned char W1t[32 * SplitMatrix<4, 2>::kLd];     // [first 32 input columns][64]
+    alignas(16) unsigned char W2t[64 * SplitMatrix<4, 2>::kLd];
+    alignas(16) unsigned char W3t[64 * SplitMatrix<1, 2>::kLd];     // [64][3 -> 16]
+};
+
+__device__ void load_weights_split(ColorBwdWeights& w, const ColorArgs& a) {
+    const int tid = threadIdx.x;
+    constexpr int N1 = 64 * 40 / kThreads, N2 = 64 * 64 / kThreads;
+    float v1[N1], v2[N2], v3 = 0.f;
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
+        const int e = external_column(idx % 40);
+        v1[k] = e >= 0 ? a.W[0][(idx / 40) * 38 + e] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < N2; ++k) v2[k] = a.W[1][tid + k * kThreads];
+    if (tid < 3 * 64) v3 = a.W[2][tid];
+    static_assert(sizeof(ColorBwdWeights) % 4 == 0, "cleared word by word");
+    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
+    for (int idx = tid; idx < (int)(sizeof(ColorBwdWeights) / 4); idx += kThreads) words[idx] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / 40, c = idx % 40;
+        SplitMatrix<3, 3>::store(w.W1f, o, c, v1[k]);
+        if (c < 32) SplitMatrix<4, 2>::store(w.W1t, c, o, v1[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < N2; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / 64, i = idx % 64;
+        SplitMatrix<4, 3>::store(w.W2f, o, i, v2[k]);
+        SplitMatrix<4, 2>::store(w.W2t, i, o, v2[k]);
+    }
+    if (tid < 3 * 64) SplitMatrix<1, 2>::store(w.W3t, tid % 64, tid / 64, v3);
+    __syncthreads();
+}
+
 struct ColorBwdSmem {
-    ColorWeights<true> w;
+    ColorBwdWeights w;
     float tiles[kWaves][2][kTileWords];
 };
 
 __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     __shared__ ColorBwdSmem sm;
-    ColorWeights<true>& w = sm.w;
-    load_weights<true>(w, a);
+    ColorBwdWeights& w = sm.w;
+    load_weights_split(w, a);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
@@ -237,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
-        v16f cin[2], a1[2], a2[2], u[1];
+        v16f cin[2], a1[2], a2[2];
         uint32_t m1, m2;
         const ColorRaw cur = next;
         build_input(cur, valid, h, cin);
@@ -245,7 +291,14 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        forward_tile<true>(w, cin, a1, a2, m1, m2, u, j, h);
+        // ---- forward pass again, six-product split arithmetic (masks as in the forward kernel)
+        uint32_t wc[2][16], lc[2][8], w1[2][16], l1[2][8];
+        split3<2>(cin, wc, lc);
+        matvec_split<2, 3, 3, 3>(w.W1f, wc, lc, a1, lane);
+        m1 = relu_mask<2>(a1);
+        split3<2>(a1, w1, l1);
+        matvec_split<2, 4, 3, 3>(w.W2f, w1, l1, a2, lane);
+        m2 = relu_mask<2>(a2);
         // adjoint of the pre-sigmoid output, from the colour the forward pass stored
         v16f d3[1] = {zero16()};
         if (valid && h == 0) {
@@ -256,22 +309,27 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         stage<2, kLd64>(Xt, a2, j, h);
         wave_lds_fence();
         outer_accumulate16<2, kLd64, kLd64>(G3, Zt, Xt, lane);
+        // ---- adjoint sweep, three-product split arithmetic
         v16f d2[2], d1[2], dcin[1];
-        matvec<2, 1, kLdOutT, 4>(w.W3t, d3, d2, j, h);
+        uint32_t wd[2][16];
+        split2<1>(d3, wd);
+        matvec_split<2, 1, 2, 2>(w.W3t, wd, nullptr, d2, lane);
         apply_mask<2>(d2, m2);
+        split2<2>(d2, wd);
         wave_lds_fence();
-        stage_split<2>(Zs, d2, j, h);
-        stage_split<2>(Xs, a1, j, h);
+        stage_words<2>(Zs, wd, j, h);
+        stage_words<2>(Xs, w1, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-        matvec<2, 2, kLd64>(w.W2t, d2, d1, j, h);
+        matvec_split<2, 4, 2, 2>(w.W2t, wd, nullptr, d1, lane);
         apply_mask<2>(d1, m1);
+        split2<2>(d1, wd);
         wave_lds_fence();
-        stage_split<2>(Zs, d1, j, h);
-        stage_split<2>(Xs, cin, j, h);
+        stage_words<2>(Zs, wd, j, h);
+        stage_words<2>(Xs, wc, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 2>(G1, Zs, Xs, lane);
-        matvec<1, 2, kLd64>(w.W1t, d1, dcin, j, h);
+        matvec_split<1, 4, 2, 2>(w.W1t, wd, nullptr, dcin, lane);
         wave_lds_fence();
         if (valid) {
             // block 0, registers 0..7: dL/d(d,g) columns 4h..4h+3 and 8+4h..8+4h+3

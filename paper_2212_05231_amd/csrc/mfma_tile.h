@@ -231,6 +231,144 @@ __device__ __forceinline__ void outer_accumulate_split(v16f (*G)[XB], const uint
     }
 }
 
+// ---- matrix-vector products on the bf16 matrix cores ---------------------------------------
+// The same splitting carries the products W x of the backward kernels.  With two terms per
+// factor and three products the relative error of a product is about 2^-16, which is enough
+// for quantities that are compared at gradient tolerance (the adjoint sweeps).  With three
+// terms, x = hi + mid + lo (|x - hi - mid - lo| <= 2^-24 |x|), and the six products hi*hi,
+// hi*mid, mid*hi, mid*mid, hi*lo, lo*hi the result is as accurate as an fp32 product: that is
+// used where a ReLU mask is decided from the result (the recomputed forward pass), in 6/16 of
+// the matrix-pipe time of the fp32 instruction.
+//
+// Register side: a vector in the layout at the top of this file is turned into one word
+// [hi | mid] per element (and, for three terms, one word per two elements holding both lo
+// parts).  Registers 8q..8q+7 of input block kb are the eight operand slots of k-step
+// u = 2 kb + q, so slot s of lane half g stands for input 32 kb + 16 q + 8 (s/4) + 4 g + s%4.
+// LDS side: a matrix is stored per output row as [k-step][lane half][plane][8 bf16], the slots in
+// the order just given, so that a lane reads each plane of its operand as one 16-byte word;
+// the row stride leaves 16 bytes of padding, which makes those reads conflict-free.
+template <int KSTEPS, int PS>
+struct SplitMatrix {
+    static constexpr int kLd = KSTEPS * 2 * PS * 16 + 16;     // bytes per output row
+    // byte offset of plane 0 of (output row o, input c)
+    __device__ static __forceinline__ int offset(int o, int c) {
+        const int u = c >> 4, rem = c & 15;
+        const int g = (rem >> 2) & 1, s = ((rem >> 3) << 2) | (rem & 3);
+        return o * kLd + (2 * u + g) * (PS * 16) + 2 * s;
+    }
+    // store one weight, split into PS bf16 terms
+    __device__ static __forceinline__ void store(unsigned char* __restrict__ W, int o, int c, float v) {
+        unsigned char* dst = W + offset(o, c);
+#pragma unroll
+        for (int p = 0; p < PS; ++p) {
+            const __bf16 t = (__bf16)v;
+            *reinterpret_cast<__bf16*>(dst + 16 * p) = t;
+            v -= (float)t;
+        }
+    }
+};
+
+// v -> words [hi | mid]
+template <int NB>
+__device__ __forceinline__ void split2(const v16f* v, uint32_t (*w)[16]) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) w[b][r] = split_bf16(v[b][r]);
+}
+
+// v -> words [hi | mid] and, per two elements, one word [lo(2p+1) | lo(2p)]
+template <int NB>
+__device__ __forceinline__ void split3(const v16f* v, uint32_t (*w)[16], uint32_t (*l)[8]) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            uint16_t lo[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float x = v[b][2 * p + e];
+                const __bf16 hi = (__bf16)x;
+                const float r1 = x - (float)hi;
+                const __bf16 mid = (__bf16)r1;
+                const __bf16 lw = (__bf16)(r1 - (float)mid);
+                w[b][2 * p + e] = ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16) | (uint32_t)__builtin_bit_cast(uint16_t, mid);
+                lo[e] = __builtin_bit_cast(uint16_t, lw);
+            }
+            l[b][p] = ((uint32_t)lo[1] << 16) | (uint32_t)lo[0];
+        }
+}
+
+// Write words [hi | mid] to a per-wave transposed split tile.
+template <int NB>
+__device__ __forceinline__ void stage_words(uint32_t* __restrict__ tile, const uint32_t (*w)[16], int j, int h) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tile[(32 * b + neuron_of(r, h)) * kLdT + j] = w[b][r];
+}
+
+// z[mb] = sum_c W[32 mb + .][c] x[c] for MB blocks of outputs and KSTEPS * 16 inputs; W is a
+// SplitMatrix<KSTEPS, PS>, x comes as the words of split2 / split3 (P = 2: three products,
+// P = 3: six; P <= PS).
+template <int MB, int KSTEPS, int PS, int P>
+__device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W, const uint32_t (*wx)[16],
+                                             const uint32_t (*lx)[8], v16f* z, int lane) {
+    static_assert(P == 2 || P == 3, "two or three terms");
+    static_assert(P <= PS, "the matrix holds fewer terms than asked for");
+    constexpr int kLd = SplitMatrix<KSTEPS, PS>::kLd;
+    constexpr int kTotal = KSTEPS * MB;
+    const int i = lane & 31, g = lane >> 5;
+    const unsigned char* base = W + i * kLd + g * (PS * 16);
+    auto address = [&](int t) -> const u32x4* {
+        const int u = t / MB, mb = t % MB;
+        return reinterpret_cast<const u32x4*>(base + 32 * mb * kLd + u * (2 * PS * 16));
+    };
+    u32x4 cur[P], nxt[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) cur[p] = address(0)[p];
+    v16f acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = zero16();
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) {
+        const uint32_t* s = &wx[u >> 1][8 * (u & 1)];
+        u32x4 vh, vm, vl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            vh[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x07060302u);
+            vm[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x05040100u);
+            vl[e] = P == 3 ? lx[u >> 1][4 * (u & 1) + e] : 0u;
+        }
+        const bf8 bh = __builtin_bit_cast(bf8, vh), bm = __builtin_bit_cast(bf8, vm), bl = __builtin_bit_cast(bf8, vl);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int t = u * MB + mb;
+#pragma unroll
+            for (int p = 0; p < P; ++p) nxt[p] = cur[p];
+            if (t + 1 < kTotal) {
+#pragma unroll
+                for (int p = 0; p < P; ++p) nxt[p] = address(t + 1)[p];
+            }
+            const bf8 ah = __builtin_bit_cast(bf8, cur[0]), am = __builtin_bit_cast(bf8, cur[1]);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc[mb], 0, 0, 0);
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc[mb], 0, 0, 0);
+            if (P == 3) {
+                const bf8 al = __builtin_bit_cast(bf8, cur[P - 1]);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[mb], 0, 0, 0);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[mb], 0, 0, 0);
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p) cur[p] = nxt[p];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) z[mb] = acc[mb];
+}
+
 // The same for a factor Z with at most 16 columns (the 16-wide output adjoint, the 3 colour
 // adjoints), on v_mfma_f32_16x16x4_f32: half the matrix-pipe time of a 32-row block that is
 // half or nearly all padding, and a quarter of the accumulator registers per 32 columns.

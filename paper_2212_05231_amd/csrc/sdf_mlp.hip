@@ -211,13 +211,12 @@ __device__ __forceinline__ v16f apply_jac_regs(const JacRegs<D>& J, const float 
 }
 
 // row 0 of the last matrix in register layout, masked: S_{K-1} of Definition 1 for output 0
-template <int D, int K>
-__device__ __forceinline__ void last_row_masked(const SdfWeights<D, K>& w, uint32_t m, int h, v16f* s) {
+__device__ __forceinline__ void last_row_masked(const float* __restrict__ row0, uint32_t m, int h, v16f* s) {
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const float4 v = *reinterpret_cast<const float4*>(&w.HLf[32 * b + 8 * g + 4 * h]);
+            const float4 v = *reinterpret_cast<const float4*>(&row0[32 * b + 8 * g + 4 * h]);
             s[b][4 * g + 0] = v.x; s[b][4 * g + 1] = v.y; s[b][4 * g + 2] = v.z; s[b][4 * g + 3] = v.w;
         }
     apply_mask<2>(s, m);
@@ -282,7 +281,7 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
         store_rows16(a.y, i, valid, h, yv[0]);
         // reverse sweep for dd/de
         v16f s[2], s1[2];
-        last_row_masked<D, K>(w, m_last, h, s);
+        last_row_masked(w.HLf, m_last, h, s);
         if (K == 3) {
             matvec<2, 2, kLd64>(w.H2t, s, s1, j, h);
             apply_mask<2>(s1, m1);
@@ -303,9 +302,69 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// The backward kernel keeps its matrices split into bf16 terms (see mfma_tile.h): three terms
+// where the forward pass is recomputed (its ReLU masks must come out as in the forward kernel),
+// two for the adjoint, S and t sweeps.
+template <int D, int K>
+struct SdfBwdWeights {
+    static constexpr int KS1 = D / 16;
+    typedef SplitMatrix<KS1, 3> M1f;
+    typedef SplitMatrix<4, 2> M1t;
+    typedef SplitMatrix<4, 3> M2f;
+    typedef SplitMatrix<4, 2> M2t;
+    typedef SplitMatrix<1, 2> MLt;
+    alignas(16) unsigned char H1f[64 * M1f::kLd];                 // [64][D]
+    alignas(16) unsigned char H1t[32 * M1t::kLd];                 // [D][64], rows >= D zero
+    alignas(16) unsigned char H2f[K == 3 ? 64 * M2f::kLd : 16];
+    alignas(16) unsigned char H2t[K == 3 ? 64 * M2t::kLd : 16];
+    alignas(16) unsigned char HLt[64 * MLt::kLd];                 // transpose of the last matrix, [64][16]
+    alignas(16) float HLrow0[64];                                 // its row 0 (the SDF output)
+};
+
+template <int D, int K>
+__device__ void load_weights_split(SdfBwdWeights<D, K>& w, const SdfArgs& a) {
+    typedef SdfBwdWeights<D, K> W;
+    const int tid = threadIdx.x;
+    constexpr int N1 = 64 * D / kThreads, N2 = K == 3 ? 64 * 64 / kThreads : 0, NL = 16 * 64 / kThreads;
+    static_assert(64 * D % kThreads == 0, "whole passes over the first matrix");
+    float v1[N1], v2[N2 > 0 ? N2 : 1], vl[NL];
+#pragma unroll
+    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * kThreads];
+#pragma unroll
+    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * kThreads];
+#pragma unroll
+    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * kThreads];
+    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
+    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
+    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += kThreads) words[idx] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / D, i = idx % D;
+        W::M1f::store(w.H1f, o, i, v1[k]);
+        W::M1t::store(w.H1t, i, o, v1[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < N2; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / 64, i = idx % 64;
+        W::M2f::store(w.H2f, o, i, v2[k]);
+        W::M2t::store(w.H2t, i, o, v2[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+        const int idx = tid + k * kThreads;
+        const int o = idx / 64, i = idx % 64;
+        W::MLt::store(w.HLt, i, o, vl[k]);
+        if (o == 0) w.HLrow0[i] = vl[k];
+    }
+    __syncthreads();
+}
+
 template <int D, int K>
 struct SdfBwdSmem {
-    SdfWeights<D, K> w;
+    SdfBwdWeights<D, K> w;
     float tiles[kWaves][2][kTileWords];
 };
 
@@ -326,9 +385,9 @@ __device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, in
 template <int D, int K>
 __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     __shared__ SdfBwdSmem<D, K> sm;
-    SdfWeights<D, K>& w = sm.w;
-    load_weights<D, K>(w, a);
-    constexpr int LDIN = SdfWeights<D, K>::LDIN;
+    SdfBwdWeights<D, K>& w = sm.w;
+    load_weights_split<D, K>(w, a);
+    constexpr int KS1 = SdfBwdWeights<D, K>::KS1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
@@ -366,43 +425,54 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
         }
-        // ---- forward recompute
+        // ---- forward pass again, six-product split arithmetic (masks as in the forward kernel)
         v16f a1[2], a2[2];
-        matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
+        uint32_t wx[1][16], lx[1][8], w1[2][16];
+        split3<1>(x0, wx, lx);
+        matvec_split<2, KS1, 3, 3>(w.H1f, wx, lx, a1, lane);
         const uint32_t m1 = relu_mask<2>(a1);
         uint32_t m_last = m1;
         if (K == 3) {
-            matvec<2, 2, kLd64>(w.H2f, a1, a2, j, h);
+            uint32_t l1[2][8];
+            split3<2>(a1, w1, l1);
+            matvec_split<2, 4, 3, 3>(w.H2f, w1, l1, a2, lane);
             m_last = relu_mask<2>(a2);
+        } else {
+            split2<2>(a1, w1);
         }
         // t_0 = (de/dx) dL/dn, computed now so that the Jacobian's registers are free again
         v16f t0[1] = {apply_jac_regs<D>(J, nb3)};
-        // ---- first-order chain delta_K .. delta_1, weight gradients as they appear
+        // ---- first-order chain delta_K .. delta_1 (three-product split arithmetic from here on),
+        // weight gradients as they appear
         v16f d2[2], d1[2];
+        uint32_t wd[2][16];
         stage<1, kLd64>(Zt, dK, j, h);
         stage<2, kLd64>(Xt, K == 3 ? a2 : a1, j, h);
         wave_lds_fence();
         outer_accumulate16<2, kLd64, kLd64>(GL, Zt, Xt, lane);
-        matvec<2, 1, 20, 8>(w.HLt, dK, d2, j, h);
+        split2<1>(dK, wd);
+        matvec_split<2, 1, 2, 2>(w.HLt, wd, nullptr, d2, lane);
         apply_mask<2>(d2, m_last);
         if (K == 3) {
+            split2<2>(d2, wd);
             wave_lds_fence();
-            stage_split<2>(Zs, d2, j, h);
-            stage_split<2>(Xs, a1, j, h);
+            stage_words<2>(Zs, wd, j, h);
+            stage_words<2>(Xs, w1, j, h);
             wave_lds_fence();
             outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-            matvec<2, 2, kLd64>(w.H2t, d2, d1, j, h);
+            matvec_split<2, 4, 2, 2>(w.H2t, wd, nullptr, d1, lane);
             apply_mask<2>(d1, m1);
         } else {
             d1[0] = d2[0]; d1[1] = d2[1];
         }
+        split2<2>(d1, wd);
         wave_lds_fence();
-        stage_split<2>(Zs, d1, j, h);
-        stage_split<1>(Xs, x0, j, h);
+        stage_words<2>(Zs, wd, j, h);
+        stage_words<1>(Xs, wx, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f de[1];
-        matvec<1, 2, kLd64>(w.H1t, d1, de, j, h);
+        matvec_split<1, 4, 2, 2>(w.H1t, wd, nullptr, de, lane);
         store_levels<D>(a.d_enc, a.n, i, valid, de[0], h);
         if (a.d_pos) {
             float dp[3];
@@ -415,28 +485,36 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         }
         // ---- second order: S sweep (reverse) and t sweep (forward mode), Theorem 1
         v16f s2[2], s1[2];
-        last_row_masked<D, K>(w, m_last, h, s2);
+        uint32_t ws2[2][16], wt[1][16];
+        last_row_masked(w.HLrow0, m_last, h, s2);
+        split2<2>(s2, ws2);
         if (K == 3) {
-            matvec<2, 2, kLd64>(w.H2t, s2, s1, j, h);
+            matvec_split<2, 4, 2, 2>(w.H2t, ws2, nullptr, s1, lane);
             apply_mask<2>(s1, m1);
+            split2<2>(s1, wd);
         } else {
-            s1[0] = s2[0]; s1[1] = s2[1];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) wd[b][r] = ws2[b][r];
         }
+        split2<1>(t0, wt);
         wave_lds_fence();
-        stage_split<2>(Zs, s1, j, h);
-        stage_split<1>(Xs, t0, j, h);
+        stage_words<2>(Zs, wd, j, h);
+        stage_words<1>(Xs, wt, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f t1[2], t2[2];
-        matvec<2, 1, LDIN, D / 2>(w.H1f, t0, t1, j, h);
+        matvec_split<2, KS1, 3, 2>(w.H1f, wt, nullptr, t1, lane);
         apply_mask<2>(t1, m1);
         if (K == 3) {
+            split2<2>(t1, wd);
             wave_lds_fence();
-            stage_split<2>(Zs, s2, j, h);
-            stage_split<2>(Xs, t1, j, h);
+            stage_words<2>(Zs, ws2, j, h);
+            stage_words<2>(Xs, wd, j, h);
             wave_lds_fence();
             outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-            matvec<2, 2, kLd64>(w.H2f, t1, t2, j, h);
+            matvec_split<2, 4, 3, 2>(w.H2f, wd, nullptr, t2, lane);
             apply_mask<2>(t2, m_last);
             tsum[0] += t2[0]; tsum[1] += t2[1];
         } else {

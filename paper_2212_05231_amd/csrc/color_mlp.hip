@@ -18,8 +18,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kLdIn = 44;      // row stride of W_1 in LDS (40 used columns)
-constexpr int kLdOutT = 12;    // row stride of W_3^T in LDS (3 used columns)
 
 struct ColorArgs {
     const float* pos; const float* normal; const float* dirs; const int32_t* sample_ray; const float* y; const float* W[3];
@@ -36,20 +34,31 @@ __device__ __forceinline__ int external_column(int c) {
     return 6 + (c - 24);                // SH16
 }
 
+// The matrices live in LDS split into bf16 terms (see mfma_tile.h).  The forward pass, in the
+// forward kernel and where the backward kernel recomputes it, uses three terms per factor and six
+// products: as accurate as fp32 arithmetic, and the same arithmetic in both kernels, so the ReLU
+// masks agree.  The adjoint sweep of the backward kernel uses two terms and three products.
 template <bool BWD>
 struct ColorWeights {
-    float W1f[64 * kLdIn];
-    float W2f[64 * kLd64];
-    float W3f[32 * kLd64];                       // rows >= 3 zero
-    float W1t[BWD ? 32 * kLd64 : 4];             // [first 32 input columns][64]
-    float W2t[BWD ? 64 * kLd64 : 4];
-    float W3t[BWD ? 64 * kLdOutT : 4];           // [64][3 -> 8], columns >= 3 zero
+    typedef SplitMatrix<3, 3> M1f;     // [64][40 -> 48]
+    typedef SplitMatrix<4, 3> M2f;     // [64][64]
+    typedef SplitMatrix<4, 3> M3f;     // [3 -> 32][64]
+    typedef SplitMatrix<4, 2> M1t;     // [first 32 input columns][64]
+    typedef SplitMatrix<4, 2> M2t;
+    typedef SplitMatrix<1, 2> M3t;     // [64][3 -> 16]
+    alignas(16) unsigned char W1f[64 * M1f::kLd];
+    alignas(16) unsigned char W2f[64 * M2f::kLd];
+    alignas(16) unsigned char W3f[BWD ? 16 : 32 * M3f::kLd];     // the backward pass reads rgb instead
+    alignas(16) unsigned char W1t[BWD ? 32 * M1t::kLd : 16];
+    alignas(16) unsigned char W2t[BWD ? 64 * M2t::kLd : 16];
+    alignas(16) unsigned char W3t[BWD ? 64 * M3t::kLd : 16];
 };
 
 // All elements a thread copies are requested from global memory first (fixed trip counts, so
 // the loads are in flight together) and written to LDS afterwards.
 template <bool BWD>
 __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
+    typedef ColorWeights<BWD> W;
     const int tid = threadIdx.x;
     constexpr int N1 = 64 * 40 / kThreads, N2 = 64 * 64 / kThreads;
     float v1[N1], v2[N2], v3 = 0.f;
@@ -62,30 +71,28 @@ __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
 #pragma unroll
     for (int k = 0; k < N2; ++k) v2[k] = a.W[1][tid + k * kThreads];
     if (tid < 3 * 64) v3 = a.W[2][tid];
-    for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W3f[idx] = 0.f;
-    if (BWD) {
-        for (int idx = tid; idx < 32 * kLd64; idx += kThreads) w.W1t[idx] = 0.f;
-        for (int idx = tid; idx < 64 * kLdOutT; idx += kThreads) w.W3t[idx] = 0.f;
-    }
+    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
+    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
+    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += kThreads) words[idx] = 0u;
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < N1; ++k) {
         const int idx = tid + k * kThreads;
         const int o = idx / 40, c = idx % 40;
-        w.W1f[o * kLdIn + c] = v1[k];
-        if (BWD && c < 32) w.W1t[c * kLd64 + o] = v1[k];
+        W::M1f::store(w.W1f, o, c, v1[k]);
+        if (BWD && c < 32) W::M1t::store(w.W1t, c, o, v1[k]);
     }
 #pragma unroll
     for (int k = 0; k < N2; ++k) {
         const int idx = tid + k * kThreads;
         const int o = idx / 64, i = idx % 64;
-        w.W2f[o * kLd64 + i] = v2[k];
-        if (BWD) w.W2t[i * kLd64 + o] = v2[k];
+        W::M2f::store(w.W2f, o, i, v2[k]);
+        if (BWD) W::M2t::store(w.W2t, i, o, v2[k]);
     }
     if (tid < 3 * 64) {
         const int o = tid / 64, i = tid % 64;
-        w.W3f[o * kLd64 + i] = v3;
-        if (BWD) w.W3t[i * kLdOutT + o] = v3;
+        if (BWD) W::M3t::store(w.W3t, i, o, v3);
+        else W::M3f::store(w.W3f, o, i, v3);
     }
     __syncthreads();
 }
@@ -166,14 +173,29 @@ __device__ __forceinline__ void build_input(const ColorRaw& r, bool valid, int h
 
 __device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-u)); }
 
+// Both hidden layers; leaves the split words of the input and of the first hidden layer behind
+// for the backward pass's weight gradients.
 template <bool BWD>
-__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, v16f* a1, v16f* a2,
-                                             uint32_t& m1, uint32_t& m2, v16f* u, int j, int h) {
-    matvec<2, 2, kLdIn, 4>(w.W1f, cin, a1, j, h);
-    m1 = relu_mask<2>(a1);
-    matvec<2, 2, kLd64>(w.W2f, a1, a2, j, h);
+__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, uint32_t (*wc)[16],
+                                             uint32_t (*w1)[16], v16f* a2, uint32_t& m1, uint32_t& m2, int lane) {
+    v16f a1[2];
+    if (BWD) {
+        uint32_t lc[2][8], l1[2][8];
+        split3<2>(cin, wc, lc);
+        matvec_split<2, 3, 3, 3>(w.W1f, wc, lc, a1, lane);
+        m1 = relu_mask<2>(a1);
+        split3<2>(a1, w1, l1);
+        matvec_split<2, 4, 3, 3>(w.W2f, w1, l1, a2, lane);
+    } else {
+        // the same terms, packed the way that is cheapest to produce (nothing is staged here)
+        SplitPairs<2> p;
+        split3_pairs<2>(cin, p);
+        matvec_split<2, 3, 3>(w.W1f, p, a1, lane);
+        m1 = relu_mask<2>(a1);
+        split3_pairs<2>(a1, p);
+        matvec_split<2, 4, 3>(w.W2f, p, a2, lane);
+    }
     m2 = relu_mask<2>(a2);
-    if (!BWD) matvec<1, 2, kLd64>(w.W3f, a2, u, j, h);    // the backward pass reads rgb instead
 }
 
 __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
@@ -189,14 +211,17 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
-        v16f cin[2], a1[2], a2[2], u[1];
+        v16f cin[2], a2[2], u[1];
         uint32_t m1, m2;
+        SplitPairs<2> p2;
         build_input(next, valid, h, cin);
         {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<false>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        forward_tile<false>(w, cin, a1, a2, m1, m2, u, j, h);
+        forward_tile<false>(w, cin, nullptr, nullptr, a2, m1, m2, lane);
+        split3_pairs<2>(a2, p2);
+        matvec_split<1, 4, 3>(w.W3f, p2, u, lane);
         if (valid && h == 0) {
             a.rgb[3 * i + 0] = sigmoid(u[0][0]);
             a.rgb[3 * i + 1] = sigmoid(u[0][1]);
@@ -205,61 +230,15 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     }
 }
 
-// The backward kernel keeps its matrices split into bf16 terms (see mfma_tile.h): three terms
-// for the recomputed forward pass, whose ReLU masks must come out as in the forward kernel, two
-// for the adjoint sweep.
-struct ColorBwdWeights {
-    alignas(16) unsigned char W1f[64 * SplitMatrix<3, 3>::kLd];     // [64][40 -> 48]
-    alignas(16) unsigned char W2f[64 * SplitMatrix<4, 3>::kLd];
-    alignas(16) unsigned char W1t[32 * SplitMatrix<4, 2>::kLd];     // [first 32 input columns][64]
-    alignas(16) unsigned char W2t[64 * SplitMatrix<4, 2>::kLd];
-    alignas(16) unsigned char W3t[64 * SplitMatrix<1, 2>::kLd];     // [64][3 -> 16]
-};
-
-__device__ void load_weights_split(ColorBwdWeights& w, const ColorArgs& a) {
-    const int tid = threadIdx.x;
-    constexpr int N1 = 64 * 40 / kThreads, N2 = 64 * 64 / kThreads;
-    float v1[N1], v2[N2], v3 = 0.f;
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
-        const int e = external_column(idx % 40);
-        v1[k] = e >= 0 ? a.W[0][(idx / 40) * 38 + e] : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) v2[k] = a.W[1][tid + k * kThreads];
-    if (tid < 3 * 64) v3 = a.W[2][tid];
-    static_assert(sizeof(ColorBwdWeights) % 4 == 0, "cleared word by word");
-    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
-    for (int idx = tid; idx < (int)(sizeof(ColorBwdWeights) / 4); idx += kThreads) words[idx] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 40, c = idx % 40;
-        SplitMatrix<3, 3>::store(w.W1f, o, c, v1[k]);
-        if (c < 32) SplitMatrix<4, 2>::store(w.W1t, c, o, v1[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 64, i = idx % 64;
-        SplitMatrix<4, 3>::store(w.W2f, o, i, v2[k]);
-        SplitMatrix<4, 2>::store(w.W2t, i, o, v2[k]);
-    }
-    if (tid < 3 * 64) SplitMatrix<1, 2>::store(w.W3t, tid % 64, tid / 64, v3);
-    __syncthreads();
-}
-
 struct ColorBwdSmem {
-    ColorBwdWeights w;
+    ColorWeights<true> w;
     float tiles[kWaves][2][kTileWords];
 };
 
 __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     __shared__ ColorBwdSmem sm;
-    ColorBwdWeights& w = sm.w;
-    load_weights_split(w, a);
+    ColorWeights<true>& w = sm.w;
+    load_weights<true>(w, a);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
@@ -283,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
-        v16f cin[2], a1[2], a2[2];
+        v16f cin[2], a2[2];
         uint32_t m1, m2;
         const ColorRaw cur = next;
         build_input(cur, valid, h, cin);
@@ -291,14 +270,9 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        // ---- forward pass again, six-product split arithmetic (masks as in the forward kernel)
-        uint32_t wc[2][16], lc[2][8], w1[2][16], l1[2][8];
-        split3<2>(cin, wc, lc);
-        matvec_split<2, 3, 3, 3>(w.W1f, wc, lc, a1, lane);
-        m1 = relu_mask<2>(a1);
-        split3<2>(a1, w1, l1);
-        matvec_split<2, 4, 3, 3>(w.W2f, w1, l1, a2, lane);
-        m2 = relu_mask<2>(a2);
+        // ---- forward pass again, in the forward kernel's arithmetic (the same masks)
+        uint32_t wc[2][16], w1[2][16];
+        forward_tile<true>(w, cin, wc, w1, a2, m1, m2, lane);
         // adjoint of the pre-sigmoid output, from the colour the forward pass stored
         v16f d3[1] = {zero16()};
         if (valid && h == 0) {

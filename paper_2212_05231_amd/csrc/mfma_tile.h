@@ -308,12 +308,42 @@ __device__ __forceinline__ void stage_words(uint32_t* __restrict__ tile, const u
         for (int r = 0; r < 16; ++r) tile[(32 * b + neuron_of(r, h)) * kLdT + j] = w[b][r];
 }
 
+// The three terms of a vector, each packed two elements to a word ([term(2p+1) | term(2p)]):
+// words 4q..4q+3 of block kb are the operand of k-step 2 kb + q as they stand.  This is the
+// cheapest form to produce (one conversion instruction yields a word) and is used where a vector
+// only feeds matrix-vector products; vectors that also go into a weight gradient use the
+// per-element words above.
+template <int NB>
+struct SplitPairs {
+    uint32_t h[NB][8], m[NB][8], l[NB][8];
+};
+
+template <int NB>
+__device__ __forceinline__ void split3_pairs(const v16f* v, SplitPairs<NB>& out) {
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const float x0 = v[b][2 * p], x1 = v[b][2 * p + 1];
+            const uint32_t hp = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{x0, x1}, bf2));
+            const float r0 = x0 - __builtin_bit_cast(float, hp << 16);
+            const float r1 = x1 - __builtin_bit_cast(float, hp & 0xffff0000u);
+            const uint32_t mp = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{r0, r1}, bf2));
+            const float q0 = r0 - __builtin_bit_cast(float, mp << 16);
+            const float q1 = r1 - __builtin_bit_cast(float, mp & 0xffff0000u);
+            out.h[b][p] = hp;
+            out.m[b][p] = mp;
+            out.l[b][p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{q0, q1}, bf2));
+        }
+}
+
 // z[mb] = sum_c W[32 mb + .][c] x[c] for MB blocks of outputs and KSTEPS * 16 inputs; W is a
-// SplitMatrix<KSTEPS, PS>, x comes as the words of split2 / split3 (P = 2: three products,
-// P = 3: six; P <= PS).
-template <int MB, int KSTEPS, int PS, int P>
-__device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W, const uint32_t (*wx)[16],
-                                             const uint32_t (*lx)[8], v16f* z, int lane) {
+// SplitMatrix<KSTEPS, PS>; `operand(u, bh, bm, bl)` hands over the terms of x for k-step u
+// (P = 2: three products, P = 3: six; P <= PS).
+template <int MB, int KSTEPS, int PS, int P, typename Operand>
+__device__ __forceinline__ void matvec_split_core(const unsigned char* __restrict__ W, Operand operand, v16f* z, int lane) {
     static_assert(P == 2 || P == 3, "two or three terms");
     static_assert(P <= PS, "the matrix holds fewer terms than asked for");
     constexpr int kLd = SplitMatrix<KSTEPS, PS>::kLd;
@@ -332,15 +362,8 @@ __device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W
     for (int mb = 0; mb < MB; ++mb) acc[mb] = zero16();
 #pragma unroll
     for (int u = 0; u < KSTEPS; ++u) {
-        const uint32_t* s = &wx[u >> 1][8 * (u & 1)];
-        u32x4 vh, vm, vl;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            vh[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x07060302u);
-            vm[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x05040100u);
-            vl[e] = P == 3 ? lx[u >> 1][4 * (u & 1) + e] : 0u;
-        }
-        const bf8 bh = __builtin_bit_cast(bf8, vh), bm = __builtin_bit_cast(bf8, vm), bl = __builtin_bit_cast(bf8, vl);
+        bf8 bh, bm, bl;
+        operand(u, bh, bm, bl);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int t = u * MB + mb;
@@ -367,6 +390,38 @@ __device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) z[mb] = acc[mb];
+}
+
+// x as the per-element words of split2 / split3
+template <int MB, int KSTEPS, int PS, int P>
+__device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W, const uint32_t (*wx)[16],
+                                             const uint32_t (*lx)[8], v16f* z, int lane) {
+    matvec_split_core<MB, KSTEPS, PS, P>(W, [&](int u, bf8& bh, bf8& bm, bf8& bl) {
+        const uint32_t* s = &wx[u >> 1][8 * (u & 1)];
+        u32x4 vh, vm, vl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            vh[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x07060302u);
+            vm[e] = __builtin_amdgcn_perm(s[2 * e + 1], s[2 * e], 0x05040100u);
+            vl[e] = P == 3 ? lx[u >> 1][4 * (u & 1) + e] : 0u;
+        }
+        bh = __builtin_bit_cast(bf8, vh); bm = __builtin_bit_cast(bf8, vm); bl = __builtin_bit_cast(bf8, vl);
+    }, z, lane);
+}
+
+// x as SplitPairs, all three terms (six products)
+template <int MB, int KSTEPS, int PS, int NB>
+__device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W, const SplitPairs<NB>& x, v16f* z, int lane) {
+    matvec_split_core<MB, KSTEPS, PS, 3>(W, [&](int u, bf8& bh, bf8& bm, bf8& bl) {
+        u32x4 vh, vm, vl;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            vh[e] = x.h[u >> 1][4 * (u & 1) + e];
+            vm[e] = x.m[u >> 1][4 * (u & 1) + e];
+            vl[e] = x.l[u >> 1][4 * (u & 1) + e];
+        }
+        bh = __builtin_bit_cast(bf8, vh); bm = __builtin_bit_cast(bf8, vm); bl = __builtin_bit_cast(bf8, vl);
+    }, z, lane);
 }
 
 // The same for a factor Z with at most 16 columns (the 16-wide output adjoint, the 3 colour

@@ -30,55 +30,71 @@ struct SdfArgs {
     int64_t n; int active_levels;
 };
 
-// LDS copies of the matrices in both orientations ("f": rows = outputs, "t": rows = inputs).
-template <int D, int K>
+// LDS copies of the matrices, split into bf16 terms (see mfma_tile.h), in the orientations a
+// kernel needs ("f": rows = outputs, "t": rows = inputs).  Everything the forward kernel
+// computes, and the forward pass where the backward kernel recomputes it, uses three terms per
+// factor and six products: as accurate as fp32 arithmetic, and the same arithmetic in both
+// kernels, so the ReLU masks agree.  The adjoint, S and t sweeps of the backward kernel use
+// two terms and three products.
+template <int D, int K, bool BWD>
 struct SdfWeights {
-    static constexpr int LDIN = D + 4;
-    float H1f[64 * LDIN];           // [64][D]
-    float H1t[32 * kLd64];          // [D][64], rows >= D zero
-    float H2f[K == 3 ? 64 * kLd64 : 4];
-    float H2t[K == 3 ? 64 * kLd64 : 4];
-    float HLf[32 * kLd64];          // last matrix [16][64], rows >= 16 zero
-    float HLt[64 * 20];             // its transpose [64][16]
+    static constexpr int KS1 = D / 16;
+    typedef SplitMatrix<KS1, 3> M1f;               // [64][D]
+    typedef SplitMatrix<4, 3> M2f;                 // [64][64]
+    typedef SplitMatrix<4, 3> MLf;                 // last matrix [16 -> 32][64]
+    typedef SplitMatrix<4, BWD ? 2 : 3> M1t;       // [D -> 32][64]
+    typedef SplitMatrix<4, BWD ? 2 : 3> M2t;
+    typedef SplitMatrix<1, 2> MLt;                 // [64][16]
+    alignas(16) unsigned char H1f[64 * M1f::kLd];
+    alignas(16) unsigned char H1t[32 * M1t::kLd];
+    alignas(16) unsigned char H2f[K == 3 ? 64 * M2f::kLd : 16];
+    alignas(16) unsigned char H2t[K == 3 ? 64 * M2t::kLd : 16];
+    alignas(16) unsigned char HLf[BWD ? 16 : 32 * MLf::kLd];
+    alignas(16) unsigned char HLt[BWD ? 64 * MLt::kLd : 16];
+    alignas(16) float HLrow0[64];                  // row 0 of the last matrix (the SDF output), fp32
 };
 
 // All elements a thread copies are requested from global memory first (fixed trip counts, so
 // the loads are independent and in flight together) and written to LDS afterwards: a loop of
 // load-then-store waits for one memory round trip per iteration, some 30 of them per kernel.
-template <int D, int K>
-__device__ void load_weights(SdfWeights<D, K>& w, const SdfArgs& a) {
+template <int D, int K, bool BWD, int THREADS>
+__device__ void load_weights(SdfWeights<D, K, BWD>& w, const SdfArgs& a) {
+    typedef SdfWeights<D, K, BWD> W;
     const int tid = threadIdx.x;
-    constexpr int N1 = 64 * D / kThreads, N2 = K == 3 ? 64 * 64 / kThreads : 0, NL = 16 * 64 / kThreads;
-    static_assert(64 * D % kThreads == 0, "whole passes over the first matrix");
+    constexpr int N1 = 64 * D / THREADS, N2 = K == 3 ? 64 * 64 / THREADS : 0, NL = 16 * 64 / THREADS;
+    static_assert(64 * D % THREADS == 0 && 16 * 64 % THREADS == 0, "whole passes over the matrices");
     float v1[N1], v2[N2 > 0 ? N2 : 1], vl[NL];
 #pragma unroll
-    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * kThreads];
+    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * THREADS];
 #pragma unroll
-    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * kThreads];
+    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * THREADS];
 #pragma unroll
-    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * kThreads];
-    for (int idx = tid; idx < 32 * kLd64; idx += kThreads) { w.H1t[idx] = 0.f; w.HLf[idx] = 0.f; }
+    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * THREADS];
+    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
+    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
+    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += THREADS) words[idx] = 0u;
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
+        const int idx = tid + k * THREADS;
         const int o = idx / D, i = idx % D;
-        w.H1f[o * SdfWeights<D, K>::LDIN + i] = v1[k];
-        w.H1t[i * kLd64 + o] = v1[k];
+        W::M1f::store(w.H1f, o, i, v1[k]);
+        W::M1t::store(w.H1t, i, o, v1[k]);
     }
 #pragma unroll
     for (int k = 0; k < N2; ++k) {
-        const int idx = tid + k * kThreads;
+        const int idx = tid + k * THREADS;
         const int o = idx / 64, i = idx % 64;
-        w.H2f[o * kLd64 + i] = v2[k];
-        w.H2t[i * kLd64 + o] = v2[k];
+        W::M2f::store(w.H2f, o, i, v2[k]);
+        W::M2t::store(w.H2t, i, o, v2[k]);
     }
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
-        const int idx = tid + k * kThreads;
+        const int idx = tid + k * THREADS;
         const int o = idx / 64, i = idx % 64;
-        w.HLf[o * kLd64 + i] = vl[k];
-        w.HLt[i * 20 + o] = vl[k];
+        if (BWD) W::MLt::store(w.HLt, i, o, vl[k]);
+        else W::MLf::store(w.HLf, o, i, vl[k]);
+        if (o == 0) w.HLrow0[i] = vl[k];
     }
     __syncthreads();
 }
@@ -242,17 +258,23 @@ __device__ __forceinline__ void store_rows16(float* __restrict__ dst, int64_t i,
 }
 
 // ------------------------------------------------------------------------------------------
+// The forward kernel runs 512 threads per workgroup: its 90 KB of matrices are shared by eight
+// wavefronts, two per SIMD, so that one wavefront's conversions and memory accesses overlap the
+// other's matrix instructions.
+constexpr int kFwdThreads = 512;
+constexpr int kFwdWaves = kFwdThreads / 64;
+
 template <int D, int K>
-__global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
-    __shared__ SdfWeights<D, K> w;
-    load_weights<D, K>(w, a);
-    constexpr int LDIN = SdfWeights<D, K>::LDIN;
+__global__ __launch_bounds__(kFwdThreads) void sdf_fwd_kernel(SdfArgs a) {
+    __shared__ SdfWeights<D, K, false> w;
+    load_weights<D, K, false, kFwdThreads>(w, a);
+    constexpr int KS1 = SdfWeights<D, K, false>::KS1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
     const int64_t tiles = (a.n + 31) / 32;
-    const int64_t stride = (int64_t)gridDim.x * kWaves;
-    int64_t tile = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t stride = (int64_t)gridDim.x * kFwdWaves;
+    int64_t tile = (int64_t)blockIdx.x * kFwdWaves + wave;
     // the encoding of the NEXT tile and the Jacobian of THIS tile are requested before the
     // matrix work of this tile starts, so that HBM latency hides behind it
     v16f x_next = load_levels<D>(a.enc, a.n, tile * 32 + j, tile < tiles && tile * 32 + j < a.n, a.active_levels, h);
@@ -265,31 +287,33 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
         }
-        v16f a1[2];
-        matvec<2, 1, LDIN, D / 2>(w.H1f, x0, a1, j, h);
+        v16f a1[2], yv[1];
+        SplitPairs<1> px;
+        SplitPairs<2> pv;
+        split3_pairs<1>(x0, px);
+        matvec_split<2, KS1, 3>(w.H1f, px, a1, lane);
         const uint32_t m1 = relu_mask<2>(a1);
         uint32_t m_last = m1;
-        v16f a2[2];
-        v16f yv[1];
+        split3_pairs<2>(a1, pv);
         if (K == 3) {
-            matvec<2, 2, kLd64>(w.H2f, a1, a2, j, h);
+            v16f a2[2];
+            matvec_split<2, 4, 3>(w.H2f, pv, a2, lane);
             m_last = relu_mask<2>(a2);
-            matvec<1, 2, kLd64>(w.HLf, a2, yv, j, h);
-        } else {
-            matvec<1, 2, kLd64>(w.HLf, a1, yv, j, h);
+            split3_pairs<2>(a2, pv);
         }
+        matvec_split<1, 4, 3>(w.HLf, pv, yv, lane);
         store_rows16(a.y, i, valid, h, yv[0]);
         // reverse sweep for dd/de
         v16f s[2], s1[2];
-        last_row_masked(w.HLf, m_last, h, s);
+        last_row_masked(w.HLrow0, m_last, h, s);
+        split3_pairs<2>(s, pv);
         if (K == 3) {
-            matvec<2, 2, kLd64>(w.H2t, s, s1, j, h);
+            matvec_split<2, 4, 3>(w.H2t, pv, s1, lane);
             apply_mask<2>(s1, m1);
-        } else {
-            s1[0] = s[0]; s1[1] = s[1];
+            split3_pairs<2>(s1, pv);
         }
         v16f qv[1];
-        matvec<1, 2, kLd64>(w.H1t, s1, qv, j, h);
+        matvec_split<1, 4, 3>(w.H1t, pv, qv, lane);
         store_levels<D>(a.q, a.n, i, valid, qv[0], h);
         float nrm[3];
         contract_jac_regs<D>(J, qv[0], nrm);
@@ -302,69 +326,9 @@ __global__ __launch_bounds__(kThreads, 2) void sdf_fwd_kernel(SdfArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// The backward kernel keeps its matrices split into bf16 terms (see mfma_tile.h): three terms
-// where the forward pass is recomputed (its ReLU masks must come out as in the forward kernel),
-// two for the adjoint, S and t sweeps.
-template <int D, int K>
-struct SdfBwdWeights {
-    static constexpr int KS1 = D / 16;
-    typedef SplitMatrix<KS1, 3> M1f;
-    typedef SplitMatrix<4, 2> M1t;
-    typedef SplitMatrix<4, 3> M2f;
-    typedef SplitMatrix<4, 2> M2t;
-    typedef SplitMatrix<1, 2> MLt;
-    alignas(16) unsigned char H1f[64 * M1f::kLd];                 // [64][D]
-    alignas(16) unsigned char H1t[32 * M1t::kLd];                 // [D][64], rows >= D zero
-    alignas(16) unsigned char H2f[K == 3 ? 64 * M2f::kLd : 16];
-    alignas(16) unsigned char H2t[K == 3 ? 64 * M2t::kLd : 16];
-    alignas(16) unsigned char HLt[64 * MLt::kLd];                 // transpose of the last matrix, [64][16]
-    alignas(16) float HLrow0[64];                                 // its row 0 (the SDF output)
-};
-
-template <int D, int K>
-__device__ void load_weights_split(SdfBwdWeights<D, K>& w, const SdfArgs& a) {
-    typedef SdfBwdWeights<D, K> W;
-    const int tid = threadIdx.x;
-    constexpr int N1 = 64 * D / kThreads, N2 = K == 3 ? 64 * 64 / kThreads : 0, NL = 16 * 64 / kThreads;
-    static_assert(64 * D % kThreads == 0, "whole passes over the first matrix");
-    float v1[N1], v2[N2 > 0 ? N2 : 1], vl[NL];
-#pragma unroll
-    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * kThreads];
-#pragma unroll
-    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * kThreads];
-#pragma unroll
-    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * kThreads];
-    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
-    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
-    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += kThreads) words[idx] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / D, i = idx % D;
-        W::M1f::store(w.H1f, o, i, v1[k]);
-        W::M1t::store(w.H1t, i, o, v1[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 64, i = idx % 64;
-        W::M2f::store(w.H2f, o, i, v2[k]);
-        W::M2t::store(w.H2t, i, o, v2[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < NL; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 64, i = idx % 64;
-        W::MLt::store(w.HLt, i, o, vl[k]);
-        if (o == 0) w.HLrow0[i] = vl[k];
-    }
-    __syncthreads();
-}
-
 template <int D, int K>
 struct SdfBwdSmem {
-    SdfBwdWeights<D, K> w;
+    SdfWeights<D, K, true> w;
     float tiles[kWaves][2][kTileWords];
 };
 
@@ -385,9 +349,9 @@ __device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, in
 template <int D, int K>
 __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     __shared__ SdfBwdSmem<D, K> sm;
-    SdfBwdWeights<D, K>& w = sm.w;
-    load_weights_split<D, K>(w, a);
-    constexpr int KS1 = SdfBwdWeights<D, K>::KS1;
+    SdfWeights<D, K, true>& w = sm.w;
+    load_weights<D, K, true, kThreads>(w, a);
+    constexpr int KS1 = SdfWeights<D, K, true>::KS1;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // the same for all lanes: keeps tile indices and addresses scalar
     const int j = lane & 31, h = lane >> 5;
@@ -565,9 +529,9 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
 template <int D, int K>
 int run_fwd(const SdfArgs& a, hipStream_t st) {
     const int64_t tiles = (a.n + 31) / 32;
-    const int64_t want = (tiles + kWaves - 1) / kWaves;
-    const int blocks = persistent_blocks((const void*)sdf_fwd_kernel<D, K>, kThreads, want);
-    hipLaunchKernelGGL((sdf_fwd_kernel<D, K>), dim3(blocks), dim3(kThreads), 0, st, a);
+    const int64_t want = (tiles + kFwdWaves - 1) / kFwdWaves;
+    const int blocks = persistent_blocks((const void*)sdf_fwd_kernel<D, K>, kFwdThreads, want);
+    hipLaunchKernelGGL((sdf_fwd_kernel<D, K>), dim3(blocks), dim3(kFwdThreads), 0, st, a);
     return check_launch("sdf forward");
 }
 

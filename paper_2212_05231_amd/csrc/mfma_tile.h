@@ -81,6 +81,13 @@ __device__ __forceinline__ void matvec(const float* __restrict__ W, const v16f* 
 
 // ReLU in place; returns the mask bits of this lane's 16*NB neurons (bit 16*b + r).
 // The mask is 1 only for strictly positive pre-activations (Definition 1 of the paper).
+// Neither direction uses a compare instruction: the result of a compare is a lane mask in a
+// scalar register pair, 32 of them per mask word, which the compiler parks in vector-register
+// lanes and fetches back for every use.  A float is positive exactly when its bit pattern is a
+// positive integer, so the ReLU is an integer maximum with 0 on the pattern, the mask bit the
+// unsigned minimum of the result with 1, and a one-bit sign-extending field extract turns a mask
+// bit back into an all-ones or all-zeros word to AND with.  The instructions are written out
+// because the compiler rewrites the equivalent C expressions into compares and selects.
 template <int NB>
 __device__ __forceinline__ uint32_t relu_mask(v16f* z) {
     uint32_t m = 0;
@@ -88,9 +95,12 @@ __device__ __forceinline__ uint32_t relu_mask(v16f* z) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const bool on = z[b][r] > 0.f;
-            m |= (on ? 1u : 0u) << (16 * b + r);
-            z[b][r] = on ? z[b][r] : 0.f;
+            float zf = z[b][r];
+            uint32_t on;
+            asm("v_max_i32 %0, 0, %0" : "+v"(zf));
+            asm("v_min_u32 %0, 1, %1" : "=v"(on) : "v"(zf));
+            asm("v_lshl_or_b32 %0, %1, %2, %0" : "+v"(m) : "v"(on), "n"(16 * b + r));
+            z[b][r] = zf;
         }
     return m;
 }
@@ -100,7 +110,13 @@ __device__ __forceinline__ void apply_mask(v16f* z, uint32_t m) {
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) z[b][r] = ((m >> (16 * b + r)) & 1u) ? z[b][r] : 0.f;
+        for (int r = 0; r < 16; ++r) {
+            float zf = z[b][r];
+            uint32_t keep;
+            asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(keep) : "v"(m), "n"(16 * b + r));
+            asm("v_and_b32 %0, %0, %1" : "+v"(zf) : "v"(keep));
+            z[b][r] = zf;
+        }
 }
 
 // Write a register vector to a per-wave LDS tile [32 points][LD].

@@ -173,28 +173,17 @@ __device__ __forceinline__ void build_input(const ColorRaw& r, bool valid, int h
 
 __device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-u)); }
 
-// Both hidden layers; leaves the split words of the input and of the first hidden layer behind
-// for the backward pass's weight gradients.
+// Both hidden layers; leaves the split input and first hidden layer behind for the backward
+// pass's weight gradients.
 template <bool BWD>
-__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, uint32_t (*wc)[16],
-                                             uint32_t (*w1)[16], v16f* a2, uint32_t& m1, uint32_t& m2, int lane) {
+__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, Split<2, 3>& pc, Split<2, 3>& p1,
+                                             v16f* a2, uint32_t& m1, uint32_t& m2, int lane) {
     v16f a1[2];
-    if (BWD) {
-        uint32_t lc[2][8], l1[2][8];
-        split3<2>(cin, wc, lc);
-        matvec_split<2, 3, 3, 3>(w.W1f, wc, lc, a1, lane);
-        m1 = relu_mask<2>(a1);
-        split3<2>(a1, w1, l1);
-        matvec_split<2, 4, 3, 3>(w.W2f, w1, l1, a2, lane);
-    } else {
-        // the same terms, packed the way that is cheapest to produce (nothing is staged here)
-        SplitPairs<2> p;
-        split3_pairs<2>(cin, p);
-        matvec_split<2, 3, 3>(w.W1f, p, a1, lane);
-        m1 = relu_mask<2>(a1);
-        split3_pairs<2>(a1, p);
-        matvec_split<2, 4, 3>(w.W2f, p, a2, lane);
-    }
+    split(cin, pc);
+    matvec_split<2, 3, 3, 3>(w.W1f, pc, a1, lane);
+    m1 = relu_mask<2>(a1);
+    split(a1, p1);
+    matvec_split<2, 4, 3, 3>(w.W2f, p1, a2, lane);
     m2 = relu_mask<2>(a2);
 }
 
@@ -213,15 +202,15 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
         const bool valid = i < a.n;
         v16f cin[2], a2[2], u[1];
         uint32_t m1, m2;
-        SplitPairs<2> p2;
+        Split<2, 3> pc, p1, p2;
         build_input(next, valid, h, cin);
         {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<false>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        forward_tile<false>(w, cin, nullptr, nullptr, a2, m1, m2, lane);
-        split3_pairs<2>(a2, p2);
-        matvec_split<1, 4, 3>(w.W3f, p2, u, lane);
+        forward_tile<false>(w, cin, pc, p1, a2, m1, m2, lane);
+        split(a2, p2);
+        matvec_split<1, 4, 3, 3>(w.W3f, p2, u, lane);
         if (valid && h == 0) {
             a.rgb[3 * i + 0] = sigmoid(u[0][0]);
             a.rgb[3 * i + 1] = sigmoid(u[0][1]);
@@ -271,8 +260,8 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
             next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
         }
         // ---- forward pass again, in the forward kernel's arithmetic (the same masks)
-        uint32_t wc[2][16], w1[2][16];
-        forward_tile<true>(w, cin, wc, w1, a2, m1, m2, lane);
+        Split<2, 3> pc, p1;
+        forward_tile<true>(w, cin, pc, p1, a2, m1, m2, lane);
         // adjoint of the pre-sigmoid output, from the colour the forward pass stored
         v16f d3[1] = {zero16()};
         if (valid && h == 0) {
@@ -283,27 +272,28 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         stage<2, kLd64>(Xt, a2, j, h);
         wave_lds_fence();
         outer_accumulate16<2, kLd64, kLd64>(G3, Zt, Xt, lane);
-        // ---- adjoint sweep, three-product split arithmetic
+        // ---- adjoint sweep: two terms, three products
         v16f d2[2], d1[2], dcin[1];
-        uint32_t wd[2][16];
-        split2<1>(d3, wd);
-        matvec_split<2, 1, 2, 2>(w.W3t, wd, nullptr, d2, lane);
+        Split<1, 2> p3;
+        Split<2, 2> pd;
+        split(d3, p3);
+        matvec_split<2, 1, 2, 2>(w.W3t, p3, d2, lane);
         apply_mask<2>(d2, m2);
-        split2<2>(d2, wd);
+        split(d2, pd);
         wave_lds_fence();
-        stage_words<2>(Zs, wd, j, h);
-        stage_words<2>(Xs, w1, j, h);
+        stage_split(Zs, pd, j, h);
+        stage_split(Xs, p1, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-        matvec_split<2, 4, 2, 2>(w.W2t, wd, nullptr, d1, lane);
+        matvec_split<2, 4, 2, 2>(w.W2t, pd, d1, lane);
         apply_mask<2>(d1, m1);
-        split2<2>(d1, wd);
+        split(d1, pd);
         wave_lds_fence();
-        stage_words<2>(Zs, wd, j, h);
-        stage_words<2>(Xs, wc, j, h);
+        stage_split(Zs, pd, j, h);
+        stage_split(Xs, pc, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 2>(G1, Zs, Xs, lane);
-        matvec_split<1, 4, 2, 2>(w.W1t, wd, nullptr, dcin, lane);
+        matvec_split<1, 4, 2, 2>(w.W1t, pd, dcin, lane);
         wave_lds_fence();
         if (valid) {
             // block 0, registers 0..7: dL/d(d,g) columns 4h..4h+3 and 8+4h..8+4h+3

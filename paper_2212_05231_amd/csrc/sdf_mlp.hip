@@ -288,32 +288,32 @@ __global__ __launch_bounds__(kFwdThreads) void sdf_fwd_kernel(SdfArgs a) {
             x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
         }
         v16f a1[2], yv[1];
-        SplitPairs<1> px;
-        SplitPairs<2> pv;
-        split3_pairs<1>(x0, px);
-        matvec_split<2, KS1, 3>(w.H1f, px, a1, lane);
+        Split<1, 3> px;
+        Split<2, 3> pv;
+        split(x0, px);
+        matvec_split<2, KS1, 3, 3>(w.H1f, px, a1, lane);
         const uint32_t m1 = relu_mask<2>(a1);
         uint32_t m_last = m1;
-        split3_pairs<2>(a1, pv);
+        split(a1, pv);
         if (K == 3) {
             v16f a2[2];
-            matvec_split<2, 4, 3>(w.H2f, pv, a2, lane);
+            matvec_split<2, 4, 3, 3>(w.H2f, pv, a2, lane);
             m_last = relu_mask<2>(a2);
-            split3_pairs<2>(a2, pv);
+            split(a2, pv);
         }
-        matvec_split<1, 4, 3>(w.HLf, pv, yv, lane);
+        matvec_split<1, 4, 3, 3>(w.HLf, pv, yv, lane);
         store_rows16(a.y, i, valid, h, yv[0]);
         // reverse sweep for dd/de
         v16f s[2], s1[2];
         last_row_masked(w.HLrow0, m_last, h, s);
-        split3_pairs<2>(s, pv);
+        split(s, pv);
         if (K == 3) {
-            matvec_split<2, 4, 3>(w.H2t, pv, s1, lane);
+            matvec_split<2, 4, 3, 3>(w.H2t, pv, s1, lane);
             apply_mask<2>(s1, m1);
-            split3_pairs<2>(s1, pv);
+            split(s1, pv);
         }
         v16f qv[1];
-        matvec_split<1, 4, 3>(w.H1t, pv, qv, lane);
+        matvec_split<1, 4, 3, 3>(w.H1t, pv, qv, lane);
         store_levels<D>(a.q, a.n, i, valid, qv[0], h);
         float nrm[3];
         contract_jac_regs<D>(J, qv[0], nrm);
@@ -389,54 +389,53 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
         }
-        // ---- forward pass again, six-product split arithmetic (masks as in the forward kernel)
+        // ---- forward pass again, in the forward kernel's arithmetic (the same masks)
         v16f a1[2], a2[2];
-        uint32_t wx[1][16], lx[1][8], w1[2][16];
-        split3<1>(x0, wx, lx);
-        matvec_split<2, KS1, 3, 3>(w.H1f, wx, lx, a1, lane);
+        Split<1, 3> px;          // x0: input of the first layer, factor of its weight gradient
+        Split<2, 3> p1;          // a1 likewise for the second layer
+        split(x0, px);
+        matvec_split<2, KS1, 3, 3>(w.H1f, px, a1, lane);
         const uint32_t m1 = relu_mask<2>(a1);
         uint32_t m_last = m1;
+        split(a1, p1);
         if (K == 3) {
-            uint32_t l1[2][8];
-            split3<2>(a1, w1, l1);
-            matvec_split<2, 4, 3, 3>(w.H2f, w1, l1, a2, lane);
+            matvec_split<2, 4, 3, 3>(w.H2f, p1, a2, lane);
             m_last = relu_mask<2>(a2);
-        } else {
-            split2<2>(a1, w1);
         }
         // t_0 = (de/dx) dL/dn, computed now so that the Jacobian's registers are free again
         v16f t0[1] = {apply_jac_regs<D>(J, nb3)};
-        // ---- first-order chain delta_K .. delta_1 (three-product split arithmetic from here on),
+        // ---- first-order chain delta_K .. delta_1 (two terms, three products from here on),
         // weight gradients as they appear
         v16f d2[2], d1[2];
-        uint32_t wd[2][16];
+        Split<1, 2> pk;
+        Split<2, 2> pd;
         stage<1, kLd64>(Zt, dK, j, h);
         stage<2, kLd64>(Xt, K == 3 ? a2 : a1, j, h);
         wave_lds_fence();
         outer_accumulate16<2, kLd64, kLd64>(GL, Zt, Xt, lane);
-        split2<1>(dK, wd);
-        matvec_split<2, 1, 2, 2>(w.HLt, wd, nullptr, d2, lane);
+        split(dK, pk);
+        matvec_split<2, 1, 2, 2>(w.HLt, pk, d2, lane);
         apply_mask<2>(d2, m_last);
         if (K == 3) {
-            split2<2>(d2, wd);
+            split(d2, pd);
             wave_lds_fence();
-            stage_words<2>(Zs, wd, j, h);
-            stage_words<2>(Xs, w1, j, h);
+            stage_split(Zs, pd, j, h);
+            stage_split(Xs, p1, j, h);
             wave_lds_fence();
             outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-            matvec_split<2, 4, 2, 2>(w.H2t, wd, nullptr, d1, lane);
+            matvec_split<2, 4, 2, 2>(w.H2t, pd, d1, lane);
             apply_mask<2>(d1, m1);
         } else {
             d1[0] = d2[0]; d1[1] = d2[1];
         }
-        split2<2>(d1, wd);
+        split(d1, pd);
         wave_lds_fence();
-        stage_words<2>(Zs, wd, j, h);
-        stage_words<1>(Xs, wx, j, h);
+        stage_split(Zs, pd, j, h);
+        stage_split(Xs, px, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f de[1];
-        matvec_split<1, 4, 2, 2>(w.H1t, wd, nullptr, de, lane);
+        matvec_split<1, 4, 2, 2>(w.H1t, pd, de, lane);
         store_levels<D>(a.d_enc, a.n, i, valid, de[0], h);
         if (a.d_pos) {
             float dp[3];
@@ -449,36 +448,34 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         }
         // ---- second order: S sweep (reverse) and t sweep (forward mode), Theorem 1
         v16f s2[2], s1[2];
-        uint32_t ws2[2][16], wt[1][16];
+        Split<2, 2> ps2;
+        Split<1, 2> pt;
         last_row_masked(w.HLrow0, m_last, h, s2);
-        split2<2>(s2, ws2);
+        split(s2, ps2);
         if (K == 3) {
-            matvec_split<2, 4, 2, 2>(w.H2t, ws2, nullptr, s1, lane);
+            matvec_split<2, 4, 2, 2>(w.H2t, ps2, s1, lane);
             apply_mask<2>(s1, m1);
-            split2<2>(s1, wd);
+            split(s1, pd);
         } else {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) wd[b][r] = ws2[b][r];
+            pd = ps2;
         }
-        split2<1>(t0, wt);
+        split(t0, pt);
         wave_lds_fence();
-        stage_words<2>(Zs, wd, j, h);
-        stage_words<1>(Xs, wt, j, h);
+        stage_split(Zs, pd, j, h);
+        stage_split(Xs, pt, j, h);
         wave_lds_fence();
         outer_accumulate_split<2, 1>(G1, Zs, Xs, lane);
         v16f t1[2], t2[2];
-        matvec_split<2, KS1, 3, 2>(w.H1f, wt, nullptr, t1, lane);
+        matvec_split<2, KS1, 3, 2>(w.H1f, pt, t1, lane);
         apply_mask<2>(t1, m1);
         if (K == 3) {
-            split2<2>(t1, wd);
+            split(t1, pd);
             wave_lds_fence();
-            stage_words<2>(Zs, ws2, j, h);
-            stage_words<2>(Xs, wd, j, h);
+            stage_split(Zs, ps2, j, h);
+            stage_split(Xs, pd, j, h);
             wave_lds_fence();
             outer_accumulate_split<2, 2>(G2, Zs, Xs, lane);
-            matvec_split<2, 4, 3, 2>(w.H2f, wd, nullptr, t2, lane);
+            matvec_split<2, 4, 3, 2>(w.H2f, pd, t2, lane);
             apply_mask<2>(t2, m_last);
             tsum[0] += t2[0]; tsum[1] += t2[1];
         } else {

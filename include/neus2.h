@@ -11,6 +11,11 @@
  *    [host] are read during the call only.  The library allocates no device memory.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *    enqueue work; they never synchronise.
+ *  - Arithmetic: fp32 throughout.  The matrix products of the two networks take their fp32
+ *    factors as sums of bf16 terms on the bf16 matrix cores with fp32 accumulation: three terms
+ *    (six term products) wherever a result is a forward output or decides a ReLU mask, which is
+ *    as accurate as an fp32 product (about 2e-7 relative on the outputs); two terms (three term
+ *    products) in the adjoint sweeps and weight gradients (about 1e-5 relative on the gradients).
  *  - n is the number of sample points; for ray workloads n = rays * samples_per_ray and a
  *    ray's samples are consecutive.
  *

@@ -1,5 +1,6 @@
 // Colour network c = c_Upsilon(x, n, v, d, g) (Eq. 3 of the paper): forward and first-order
-// backward, fused per 32-point tile on the fp32 matrix cores.  The paper needs no
+// backward, fused per 32-point tile on the matrix cores (fp32 values as sums of bf16 terms, see
+// mfma_tile.h).  The paper needs no
 // second-order term for Upsilon (text after Eq. 6): the normal enters here as a plain input
 // and its adjoint dL/dn is handed on to the SDF backward.
 //

@@ -1,5 +1,6 @@
 // SDF network: forward + analytic input gradient, and the backward pass with the
-// second-order term, fused per 32-point tile on the fp32 matrix cores.
+// second-order term, fused per 32-point tile on the matrix cores (fp32 values as sums of bf16
+// terms, see mfma_tile.h).
 //
 // Paper: Eq. 1 ((d,g) = f_Theta(e)), Definition 1 (bias-free ReLU MLP, masks G_l, vectors
 // P_l^j and S_l^i), Eq. 2 (n = grad_x d), supplement Sec. B (dy/dx = H_L G_L ... G_2 H_1),

@@ -6,9 +6,14 @@
 // the normal).
 //
 // Launch shape: one thread per (point, level), 256 points of ONE level per workgroup.
-// Workgroups are dealt round-robin to the 8 XCDs by the hardware, so the block index is
-// decoded as  xcd = bid % 8,  level = xcd + 8 * slot : every XCD works on one level at a
-// time and that level's table (2 MiB in fp16 at T = 2^19) stays in its private 4 MiB L2.
+// Workgroups are dealt round-robin to the 8 XCDs by the hardware (xcd = bid % 8), in order, so
+// every XCD has a queue of its own, and the queues advance together.  A schedule built on the
+// host (LevelSchedule) fills the queues with runs of point blocks of one level, such that an
+// XCD works on one level at a time - that level's table (2 MiB in fp16 at T = 2^19) stays in its
+// private 4 MiB L2 - and every queue holds the same number of blocks of hashed levels (which
+// pull about four cache lines per point through the L2) and of dense or inactive levels (which
+// mostly hit in L1): with levels dealt out whole, the XCDs that get two hashed levels set the
+// pace for all.
 #include <cstring>
 
 #include <algorithm>
@@ -148,7 +153,35 @@ __device__ __forceinline__ void gather_corners<__half>(const GridDesc& g, int le
     }
 }
 
-// block index -> (level, point block); returns false for padding blocks
+// Per XCD a queue of runs of consecutive point blocks of one level; positions in a queue are
+// j = bid / 8.  Runs of expensive levels come first in every queue and are equally long (+-1).
+struct LevelSchedule {
+    static constexpr int kMaxRuns = 12;
+    int per_xcd;                         // queue length (the grid has 8 * per_xcd workgroups)
+    short n_runs[kXcd];
+    short level[kXcd][kMaxRuns];
+    int start[kXcd][kMaxRuns + 1];       // first queue position of a run; [n_runs] = end of the queue
+    int first_pb[kXcd][kMaxRuns];
+};
+
+// block index -> (level, point block); returns false for padding blocks.  Every index into the
+// schedule is the same for all lanes of the workgroup (indexing a by-value kernel argument with a
+// value that differs between lanes is not supported).
+__device__ __forceinline__ bool decode_schedule(const LevelSchedule& sch, int& level, int& pb) {
+    const int bid = blockIdx.x;
+    const int xcd = bid % kXcd;
+    const int j = bid / kXcd;
+    const int runs = sch.n_runs[xcd];
+    if (j >= sch.start[xcd][runs]) return false;
+    int r = 0;
+    while (r + 1 < runs && j >= sch.start[xcd][r + 1]) ++r;
+    level = sch.level[xcd][r];
+    pb = sch.first_pb[xcd][r] + (j - sch.start[xcd][r]);
+    return true;
+}
+
+// block index -> (level, point block) with levels dealt out whole: xcd = bid % 8,
+// level = xcd + 8 * slot; returns false for padding blocks
 __device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int& level, int& pb) {
     const int bid = blockIdx.x;
     const int xcd = bid % kXcd;
@@ -159,13 +192,13 @@ __device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int
 }
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, const float* __restrict__ pos,
+__global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedule sch, const float* __restrict__ pos,
                                                         const T* __restrict__ tables, int64_t n,
-                                                        int point_blocks, float* __restrict__ enc,
+                                                        float* __restrict__ enc,
                                                         float* __restrict__ jac,
                                                         uint32_t* __restrict__ dbg_idx) {
     int level, pb;
-    if (!decode_block(g.n_levels, point_blocks, level, pb)) return;
+    if (!decode_schedule(sch, level, pb)) return;
     const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
     if (i >= n) return;
     const float px = pos[3 * i + 0], py = pos[3 * i + 1], pz = pos[3 * i + 2];
@@ -336,9 +369,9 @@ __global__ __launch_bounds__(kBlock) void pos_hessian_kernel(GridDesc g, const f
                                                              const float* __restrict__ q,
                                                              const float* __restrict__ d_normal,
                                                              const float* __restrict__ d_enc, int64_t n,
-                                                             int point_blocks, float* __restrict__ part) {
+                                                             LevelSchedule sch, float* __restrict__ part) {
     int level, pb;
-    if (!decode_block(g.active_levels, point_blocks, level, pb)) return;
+    if (!decode_schedule(sch, level, pb)) return;
     const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
     if (i >= n) return;
     const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
@@ -825,6 +858,41 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     return p;
 }
 
+// Queues for levels [0, n_levels): hashed active levels count as expensive, the rest as cheap;
+// each class is cut into 8 equal stretches of its level-major block list.
+LevelSchedule make_level_schedule(const GridDesc& g, int n_levels, int point_blocks) {
+    LevelSchedule sch;
+    memset(&sch, 0, sizeof(sch));
+    int fill[kXcd] = {0};
+    for (int cls = 0; cls < 2; ++cls) {
+        int lv[NEUS2_MAX_LEVELS], m = 0;
+        for (int l = 0; l < n_levels; ++l) {
+            const bool expensive = l < g.active_levels && !((g.dense_bits >> l) & 1u);
+            if (expensive == (cls == 0)) lv[m++] = l;
+        }
+        const int64_t total = (int64_t)m * point_blocks;
+        for (int x = 0; x < kXcd; ++x) {
+            int64_t a = total * x / kXcd;
+            const int64_t b = total * (x + 1) / kXcd;
+            while (a < b) {
+                const int k = (int)(a / point_blocks), pb = (int)(a % point_blocks);
+                const int64_t len = std::min<int64_t>(b - a, point_blocks - pb);
+                const int r = sch.n_runs[x]++;
+                sch.level[x][r] = (short)lv[k];
+                sch.start[x][r] = fill[x];
+                sch.first_pb[x][r] = pb;
+                fill[x] += (int)len;
+                a += len;
+            }
+        }
+    }
+    for (int x = 0; x < kXcd; ++x) {
+        sch.start[x][sch.n_runs[x]] = fill[x];
+        sch.per_xcd = std::max(sch.per_xcd, fill[x]);
+    }
+    return sch;
+}
+
 int grid_blocks(int levels, int point_blocks) {
     const int slots = (levels + kXcd - 1) / kXcd;
     return kXcd * slots * point_blocks;
@@ -837,13 +905,14 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     if (n == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
     const int pbs = (int)((n + kBlock - 1) / kBlock);
-    const dim3 grid(grid_blocks(g.n_levels, pbs));
+    const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs);
+    const dim3 grid(kXcd * sch.per_xcd);
     if (cfg->table_dtype == 1)
-        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, pos,
-                           (const __half*)tables, n, pbs, enc, jac, dbg_idx);
+        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, sch, pos,
+                           (const __half*)tables, n, enc, jac, dbg_idx);
     else
-        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, pos,
-                           (const float*)tables, n, pbs, enc, jac, dbg_idx);
+        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, sch, pos,
+                           (const float*)tables, n, enc, jac, dbg_idx);
     return check_launch("hash encode");
 }
 
@@ -901,13 +970,14 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             if (d_pos) {
                 float* part = reinterpret_cast<float*>(ws + records_end);
                 const int pbs = (int)((n + kBlock - 1) / kBlock);
-                const dim3 grid(grid_blocks(g.active_levels, pbs));
+                const LevelSchedule sch = make_level_schedule(g, g.active_levels, pbs);
+                const dim3 grid(kXcd * sch.per_xcd);
                 if (cfg->table_dtype == 1)
                     hipLaunchKernelGGL(pos_hessian_kernel<__half>, grid, dim3(kBlock), 0, st, g, pos, (const __half*)tables, q,
-                                       d_normal, first_order_pos ? d_enc : nullptr, n, pbs, part);
+                                       d_normal, first_order_pos ? d_enc : nullptr, n, sch, part);
                 else
                     hipLaunchKernelGGL(pos_hessian_kernel<float>, grid, dim3(kBlock), 0, st, g, pos, (const float*)tables, q,
-                                       d_normal, first_order_pos ? d_enc : nullptr, n, pbs, part);
+                                       d_normal, first_order_pos ? d_enc : nullptr, n, sch, part);
                 hipLaunchKernelGGL(sum_levels_kernel, dim3((unsigned)((3 * n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, part,
                                    g.active_levels, n, d_pos);
             }

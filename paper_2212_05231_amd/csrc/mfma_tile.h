@@ -181,26 +181,38 @@ template <int ZB, int XB>
 __device__ __forceinline__ void outer_accumulate_split(v16f (*G)[XB], const uint32_t* __restrict__ Zt,
                                                        const uint32_t* __restrict__ Xt, int lane) {
     const int i = lane & 31, g = lane >> 5;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        bf8 bh[XB], bm[XB];
+    // the words of the second k-step are requested before the instructions of the first are issued
+    u32x4 raw[2][ZB + XB][2];
+    auto request = [&](int t) {
 #pragma unroll
         for (int nb = 0; nb < XB; ++nb) {
             const u32x4* src = reinterpret_cast<const u32x4*>(Xt + (32 * nb + i) * kLdT + 16 * t + 8 * g);
-            unpack_split(src[0], src[1], bh[nb], bm[nb]);
+            raw[t][nb][0] = src[0]; raw[t][nb][1] = src[1];
         }
 #pragma unroll
         for (int mb = 0; mb < ZB; ++mb) {
             const u32x4* src = reinterpret_cast<const u32x4*>(Zt + (32 * mb + i) * kLdT + 16 * t + 8 * g);
-            bf8 ah, am;
-            unpack_split(src[0], src[1], ah, am);
+            raw[t][XB + mb][0] = src[0]; raw[t][XB + mb][1] = src[1];
+        }
+    };
+    request(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        bf8 bh[XB], bm[XB], ah[ZB], am[ZB];
+#pragma unroll
+        for (int nb = 0; nb < XB; ++nb) unpack_split(raw[t][nb][0], raw[t][nb][1], bh[nb], bm[nb]);
+#pragma unroll
+        for (int mb = 0; mb < ZB; ++mb) unpack_split(raw[t][XB + mb][0], raw[t][XB + mb][1], ah[mb], am[mb]);
+        if (t == 0) request(1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mb = 0; mb < ZB; ++mb)
 #pragma unroll
             for (int nb = 0; nb < XB; ++nb) {
-                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[nb], G[mb][nb], 0, 0, 0);
-                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm[nb], G[mb][nb], 0, 0, 0);
-                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh[nb], G[mb][nb], 0, 0, 0);
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mb], bh[nb], G[mb][nb], 0, 0, 0);
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mb], bm[nb], G[mb][nb], 0, 0, 0);
+                G[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am[mb], bh[nb], G[mb][nb], 0, 0, 0);
             }
-        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }

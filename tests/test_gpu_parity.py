@@ -180,6 +180,53 @@ def test_sdf_fwd_grad_alone_with_large_values():
         assert rel(nrm.cpu().numpy(), np.einsum("nk,nka->na", qr, J.astype(np.float64))) <= FWD_TOL
 
 
+@pytest.mark.parametrize("enc_scale,w_scale", [(1e-12, 1.0), (1e-4, 30.0), (1.0, 1e-6), (3e4, 0.3), (1e15, 1e-3)])
+def test_network_products_over_a_wide_range_of_magnitudes(enc_scale, w_scale):
+    """The matrix products take fp32 factors as sums of bf16 terms; bf16 has the exponent range of
+    fp32, so accuracy must not depend on the magnitude of encodings, weights or adjoints (an fp16
+    split would underflow here).  Forward of the SDF network alone, then its backward (first and
+    second order) alone, each per-point feature with a scale of its own within a factor 1e3."""
+    rng = np.random.default_rng(11)
+    cfg = wl.make_config(2)
+    c = nb.make_config(cfg)
+    n, L, D = 1500 + 7, cfg.n_levels, cfg.enc_dim
+    H = [(rng.normal(size=(cfg.sdf_dims[i + 1], cfg.sdf_dims[i])) * w_scale / 8).astype(np.float32) for i in range(3)]
+    feat = 10.0 ** rng.uniform(-1.5, 1.5, size=D)
+    e = (rng.normal(size=(n, D)) * feat * enc_scale).astype(np.float32)
+    J = (rng.normal(size=(n, D, 3)) * enc_scale).astype(np.float32)
+    Hg = [cuda(h) for h in H]
+    enc_lm, jac_lm = to_level_major(e, L), cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+    y, q, nrm = torch.empty(n, 16, device="cuda"), torch.empty(L, n, 2, device="cuda"), torch.empty(n, 3, device="cuda")
+    nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm)
+    yr, acts, masks = o.mlp_forward(H, e)
+    S, qr = o.mlp_input_gradient(H, masks, 0)
+    assert rel(y.cpu().numpy(), yr) <= FWD_TOL
+    assert rel(from_level_major(q, n), qr) <= FWD_TOL
+    # backward: adjoints of y and of the normal, also of widely different sizes
+    d_y = (rng.normal(size=(n, 16)) * 10.0 ** rng.uniform(-3, 3, size=16) * 1e-6).astype(np.float32)
+    d_n = (rng.normal(size=(n, 3)) * 1e-3).astype(np.float32)
+    dH = [torch.zeros_like(h) for h in Hg]
+    d_enc = torch.zeros(L, n, 2, device="cuda")
+    nb.sdf_mlp_bwd(c, enc_lm, jac_lm, Hg, cuda(d_y), cuda(d_n), n, dH, d_enc)
+    torch.cuda.synchronize()
+    H64 = [h.astype(np.float64) for h in H]
+    gH, d_in, _ = o.mlp_backward(H64, acts, masks, d_y.astype(np.float64))
+    # second order (Theorem 1): dL/dH_l += S_l^T t_{l-1}^T with t_0 = J nbar
+    t = np.einsum("nka,na->nk", J.astype(np.float64), d_n.astype(np.float64))
+    Ssweep = [None, None, None]
+    s_vec = np.tile(H64[2][0], (n, 1)) * masks[1]
+    Ssweep[1] = s_vec
+    Ssweep[0] = (s_vec @ H64[1]) * masks[0]
+    gH[0] += Ssweep[0].T @ t
+    t1 = (t @ H64[0].T) * masks[0]
+    gH[1] += Ssweep[1].T @ t1
+    t2 = (t1 @ H64[1].T) * masks[1]
+    gH[2][0] += t2.sum(axis=0)
+    assert rel(from_level_major(d_enc, n), d_in) <= GRAD_TOL
+    for a, b in zip(dH, gH):
+        assert rel(a.cpu().numpy(), b) <= GRAD_TOL
+
+
 def test_render_forward_backward_alone():
     rng = np.random.default_rng(1)
     for spr, rays in ((64, 37), (17, 9), (1, 5), (2, 3)):

@@ -212,13 +212,18 @@ int neus2_render_loss_bwd_ragged(const neus2_config* cfg, const float* y, const 
                                  float* d_sdf, float* d_rgb, float* d_normal, float* d_s,
                                  void* stream);
 
-/* Dense Adam with bias correction over `count` parameters (the paper names no optimiser).
+/* Adam with bias correction over `count` parameters (the paper names no optimiser).
  *   param [device]: fp32 (dtype 0) or fp16 (dtype 1); with fp16 `master` [device, fp32] holds
  *   the full-precision copy, is updated, and param receives its round-to-nearest-even.
- *   grad, m, v [device, fp32].  t >= 1 is the step number.  zero_grad != 0 clears grad. */
+ *   grad, m, v [device, fp32].  t >= 1 is the step number (bias correction 1 - beta^t).
+ *   flags: bit 0 (NEUS2_ADAM_CLEAR) clears grad; bit 1 (NEUS2_ADAM_LAZY) leaves every entry whose
+ *   gradient is exactly zero as it is (value and both moments): the form used for hash tables of
+ *   which a step touches a small part; the bias correction still uses the global step number. */
+#define NEUS2_ADAM_CLEAR 1
+#define NEUS2_ADAM_LAZY 2
 int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count,
                     int dtype, float lr, float beta1, float beta2, float eps, int t,
-                    int zero_grad, void* stream);
+                    int flags, void* stream);
 
 /* The same update over the hash tables [L][T][F] of a descriptor (fp16 tables with their fp32
  * master copy, or fp32 tables and master NULL), skipping the slots no point can address: a
@@ -226,7 +231,7 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
  * would leave them unchanged.  Same result as neus2_adam_step over L*T*F parameters. */
 int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m,
                       float* v, float lr, float beta1, float beta2, float eps, int t,
-                      int zero_grad, void* stream);
+                      int flags, void* stream);
 
 /* Global rigid transform of Eq. 9, x_c = R (x + T), then the affine map scale*x_c + offset
  * that takes world coordinates to the unit cube.  R [host, 9 row-major], T [host, 3]. */

@@ -558,11 +558,21 @@ def axis_angle_gradient(omega, M, h: float = 1e-6):
 # Optimiser (the paper names none; the benchmark contract asks for Adam)
 # --------------------------------------------------------------------------------------
 
-def adam_step(param, grad, m, v, t: int, lr: float, b1: float, b2: float, eps: float):
-    """Textbook Adam, dense, bias-corrected.  Returns (param, m, v) in float64."""
+def adam_step(param, grad, m, v, t: int, lr: float, b1: float, b2: float, eps: float, lazy: bool = False):
+    """Textbook Adam, bias-corrected.  Returns (param, m, v) in float64.
+
+    The paper names no optimiser.  `lazy` is the sparse form used for hash tables: an entry
+    whose gradient is exactly zero keeps its value and both moments (no decay); reading: the
+    bias correction uses the global step number t for every entry.
+    """
     g = np.asarray(grad, dtype=np.float64)
-    m = b1 * np.asarray(m, dtype=np.float64) + (1.0 - b1) * g
-    v = b2 * np.asarray(v, dtype=np.float64) + (1.0 - b2) * g * g
-    mhat = m / (1.0 - b1 ** t)
-    vhat = v / (1.0 - b2 ** t)
-    return np.asarray(param, dtype=np.float64) - lr * mhat / (np.sqrt(vhat) + eps), m, v
+    p0, m0, v0 = (np.asarray(a, dtype=np.float64) for a in (param, m, v))
+    m1 = b1 * m0 + (1.0 - b1) * g
+    v1 = b2 * v0 + (1.0 - b2) * g * g
+    mhat = m1 / (1.0 - b1 ** t)
+    vhat = v1 / (1.0 - b2 ** t)
+    p1 = p0 - lr * mhat / (np.sqrt(vhat) + eps)
+    if lazy:
+        keep = g == 0.0
+        return np.where(keep, p0, p1), np.where(keep, m0, m1), np.where(keep, v0, v1)
+    return p1, m1, v1

@@ -223,14 +223,14 @@ def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None
                                         _stream()))
 
 
-def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True):
+def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True, lazy=False):
     _check(lib().neus2_adam_step(_ptr(param), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), grad.numel(), dtype,
-                                 lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
+                                 lr, beta1, beta2, eps, t, (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
 
 
-def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_grad=True):
+def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_grad=True, lazy=False):
     _check(lib().neus2_adam_tables(C.byref(c), _ptr(tables), _ptr(master), _ptr(grad), _ptr(m), _ptr(v),
-                                   lr, beta1, beta2, eps, t, 1 if zero_grad else 0, _stream()))
+                                   lr, beta1, beta2, eps, t, (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
 
 
 def rigid_fwd(pos, R, T, scale, offset, out):
@@ -344,10 +344,11 @@ class Step:
         self.d_small.zero_()
         self.d_tables.zero_()
 
-    def init_optimizer(self, lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-15) -> None:
-        """Adam state: moments for tables and matrices, fp32 master copy of fp16 tables."""
+    def init_optimizer(self, lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-15, lazy_tables=False) -> None:
+        """Adam state: moments for tables and matrices, fp32 master copy of fp16 tables.
+        `lazy_tables`: table entries whose gradient is zero in a step are left as they are."""
         import torch
-        self.opt = {"lr": lr, "b1": beta1, "b2": beta2, "eps": eps, "t": 0,
+        self.opt = {"lr": lr, "b1": beta1, "b2": beta2, "eps": eps, "t": 0, "lazy": lazy_tables,
                     "m_t": torch.zeros_like(self.d_tables), "v_t": torch.zeros_like(self.d_tables),
                     "m_s": torch.zeros_like(self.small), "v_s": torch.zeros_like(self.small),
                     "master": self.tables.float() if self.tables.dtype == torch.float16 else None}
@@ -357,7 +358,7 @@ class Step:
         o = self.opt
         o["t"] += 1
         adam_tables(self.c, self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"],
-                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
+                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True, o["lazy"])
         adam_step(self.small, None, self.d_small, o["m_s"], o["v_s"], 0,
                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
 

@@ -461,27 +461,39 @@ struct AdamArgs {
     float lr, b1, b2, eps, inv_c1, inv_c2;    // inv_c = 1 / (1 - beta^t)
 };
 
+// flags: bit 0 clears the gradient, bit 1 skips entries whose gradient is exactly zero (their value
+// and moments stay as they are: the "lazy" form for parameters that most steps do not touch)
+constexpr int kAdamClear = 1, kAdamLazy = 2;
+
+__device__ __forceinline__ float adam_one(float g, float& mi, float& vi, float p, const AdamArgs& a) {
+    mi = a.b1 * mi + (1.f - a.b1) * g;
+    vi = a.b2 * vi + (1.f - a.b2) * g * g;
+    return p - a.lr * (mi * a.inv_c1) / (sqrtf(vi * a.inv_c2) + a.eps);
+}
+
 template <bool HALF>
 __global__ __launch_bounds__(256) void adam_kernel(void* __restrict__ param, float* __restrict__ master,
                                                    float* __restrict__ grad, float* __restrict__ m,
-                                                   float* __restrict__ v, int64_t count, AdamArgs a, int zero_grad) {
+                                                   float* __restrict__ v, int64_t count, AdamArgs a, int flags) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
     const float g = grad[i];
-    const float mi = a.b1 * m[i] + (1.f - a.b1) * g;
-    const float vi = a.b2 * v[i] + (1.f - a.b2) * g * g;
+    if ((flags & kAdamLazy) && g == 0.f) return;
+    float mi = m[i], vi = v[i];
+    float* full = HALF ? master : reinterpret_cast<float*>(param);
+    const float p = adam_one(g, mi, vi, full[i], a);
     m[i] = mi;
     v[i] = vi;
-    float* full = HALF ? master : reinterpret_cast<float*>(param);
-    const float p = full[i] - a.lr * (mi * a.inv_c1) / (sqrtf(vi * a.inv_c2) + a.eps);
     full[i] = p;
     if (HALF) reinterpret_cast<__half*>(param)[i] = __float2half_rn(p);
-    if (zero_grad) grad[i] = 0.f;
+    if (flags & kAdamClear) grad[i] = 0.f;
 }
 
 // The same update over the hash tables [L][T][F], restricted to the slots a level can address:
 // a dense level uses (res+1)^3 of its T slots, the others never receive a gradient, keep zero
-// moments and would be left unchanged by the update, so skipping them changes nothing.
+// moments and would be left unchanged by the update, so skipping them changes nothing.  Four
+// parameters per thread (16-byte accesses; a level starts on a 16-byte boundary); in the lazy form
+// a thread whose four gradients are zero stops after reading them.
 struct TableLevels {
     uint32_t used[NEUS2_MAX_LEVELS];     // parameters (slots * F) of each level that can be addressed
 };
@@ -490,21 +502,45 @@ template <bool HALF>
 __global__ __launch_bounds__(256) void adam_tables_kernel(void* __restrict__ param, float* __restrict__ master,
                                                           float* __restrict__ grad, float* __restrict__ m,
                                                           float* __restrict__ v, TableLevels lv, uint32_t per_level,
-                                                          AdamArgs a, int zero_grad) {
+                                                          AdamArgs a, int flags) {
     const int level = blockIdx.y;
-    const uint32_t k = blockIdx.x * 256u + threadIdx.x;
-    if (k >= lv.used[level]) return;
+    const uint32_t k = (blockIdx.x * 256u + threadIdx.x) * 4u;
+    const uint32_t used = lv.used[level];
+    if (k >= used) return;
     const int64_t i = (int64_t)level * per_level + k;
-    const float g = grad[i];
-    const float mi = a.b1 * m[i] + (1.f - a.b1) * g;
-    const float vi = a.b2 * v[i] + (1.f - a.b2) * g * g;
-    m[i] = mi;
-    v[i] = vi;
     float* full = HALF ? master : reinterpret_cast<float*>(param);
-    const float p = full[i] - a.lr * (mi * a.inv_c1) / (sqrtf(vi * a.inv_c2) + a.eps);
-    full[i] = p;
-    if (HALF) reinterpret_cast<__half*>(param)[i] = __float2half_rn(p);
-    if (zero_grad) grad[i] = 0.f;
+    const bool lazy = flags & kAdamLazy;
+    if (k + 4u <= used) {
+        const float4 g = *reinterpret_cast<const float4*>(grad + i);
+        if (lazy && g.x == 0.f && g.y == 0.f && g.z == 0.f && g.w == 0.f) return;
+        float4 mi = *reinterpret_cast<const float4*>(m + i), vi = *reinterpret_cast<const float4*>(v + i);
+        float4 p = *reinterpret_cast<const float4*>(full + i);
+        if (!(lazy && g.x == 0.f)) p.x = adam_one(g.x, mi.x, vi.x, p.x, a);
+        if (!(lazy && g.y == 0.f)) p.y = adam_one(g.y, mi.y, vi.y, p.y, a);
+        if (!(lazy && g.z == 0.f)) p.z = adam_one(g.z, mi.z, vi.z, p.z, a);
+        if (!(lazy && g.w == 0.f)) p.w = adam_one(g.w, mi.w, vi.w, p.w, a);
+        *reinterpret_cast<float4*>(m + i) = mi;
+        *reinterpret_cast<float4*>(v + i) = vi;
+        *reinterpret_cast<float4*>(full + i) = p;
+        if (HALF) {
+            __half2* h = reinterpret_cast<__half2*>(reinterpret_cast<__half*>(param) + i);
+            const __half2 h0 = __floats2half2_rn(p.x, p.y), h1 = __floats2half2_rn(p.z, p.w);
+            *reinterpret_cast<uint2*>(h) = make_uint2(*reinterpret_cast<const uint32_t*>(&h0), *reinterpret_cast<const uint32_t*>(&h1));
+        }
+        if (flags & kAdamClear) *reinterpret_cast<float4*>(grad + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (uint32_t e = 0; e < used - k; ++e) {            // the last, partial group of a level
+            const float g = grad[i + e];
+            if (lazy && g == 0.f) continue;
+            float mi = m[i + e], vi = v[i + e];
+            const float p = adam_one(g, mi, vi, full[i + e], a);
+            m[i + e] = mi;
+            v[i + e] = vi;
+            full[i + e] = p;
+            if (HALF) reinterpret_cast<__half*>(param)[i + e] = __float2half_rn(p);
+            if (flags & kAdamClear) grad[i + e] = 0.f;
+        }
+    }
 }
 
 // ---- rigid transform (Eq. 9) ---------------------------------------------------------------
@@ -678,7 +714,8 @@ int neus2_render_loss_bwd_ragged(const neus2_config* cfg, const float* y, const 
 }
 
 int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count, int dtype, float lr,
-                    float beta1, float beta2, float eps, int t, int zero_grad, void* stream) {
+                    float beta1, float beta2, float eps, int t, int flags, void* stream) {
+    if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3", flags);
     if (count < 0 || count > ((int64_t)1 << 34)) return fail(NEUS2_ERR_SHAPE, "count = %lld out of range", (long long)count);
     if (dtype != 0 && dtype != 1) return fail(NEUS2_ERR_CONFIG, "dtype = %d, must be 0 (fp32) or 1 (fp16)", dtype);
     if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
@@ -695,15 +732,16 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
     a.inv_c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
     const dim3 grid((unsigned)((count + 255) / 256));
     if (dtype == 1)
-        hipLaunchKernelGGL(adam_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, zero_grad);
+        hipLaunchKernelGGL(adam_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, flags);
     else
-        hipLaunchKernelGGL(adam_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, zero_grad);
+        hipLaunchKernelGGL(adam_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, param, master, grad, m, v, count, a, flags);
     return check_launch("adam");
 }
 
 int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
-                      float beta1, float beta2, float eps, int t, int zero_grad, void* stream) {
+                      float beta1, float beta2, float eps, int t, int flags, void* stream) {
     NEUS2_TRY(check_config(cfg));
+    if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3", flags);
     if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
     if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return fail(NEUS2_ERR_CONFIG, "beta1, beta2 must be in [0,1)");
     NEUS2_TRY(check_ptr(tables, "tables"));
@@ -726,13 +764,13 @@ int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, floa
         lv.used[l] = l < cfg->frozen_levels ? 0u : (uint32_t)(slots * F);
         if (lv.used[l] > most) most = lv.used[l];
     }
-    const dim3 grid((most + 255u) / 256u, (unsigned)cfg->n_levels);
+    const dim3 grid((most + 1023u) / 1024u, (unsigned)cfg->n_levels);
     if (cfg->table_dtype == 1)
         hipLaunchKernelGGL(adam_tables_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
-                           (uint32_t)(T * F), a, zero_grad);
+                           (uint32_t)(T * F), a, flags);
     else
         hipLaunchKernelGGL(adam_tables_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
-                           (uint32_t)(T * F), a, zero_grad);
+                           (uint32_t)(T * F), a, flags);
     return check_launch("adam (tables)");
 }
 

@@ -466,6 +466,59 @@ def test_adam_fp32_and_fp16():
                 assert torch.equal(half, pg.to(torch.float16))
 
 
+@pytest.mark.parametrize("lazy", [False, True])
+def test_adam_lazy_form_and_vector_tails(lazy):
+    """Entries with a zero gradient: left alone in the lazy form, decayed in the dense one; both
+    entry points, table sizes whose addressable part is not a multiple of four parameters."""
+    rng = np.random.default_rng(5)
+    cnt = 4099
+    p = rng.normal(size=cnt).astype(np.float32) * 1e-3
+    g = rng.normal(size=cnt).astype(np.float32) * 1e-4
+    g[rng.uniform(size=cnt) < 0.6] = 0.0
+    m = rng.normal(size=cnt).astype(np.float32) * 1e-5
+    v = np.abs(rng.normal(size=cnt)).astype(np.float32) * 1e-9
+    pg, gg, mg, vg = cuda(p), cuda(g), cuda(m), cuda(v)
+    nb.adam_step(pg, None, gg, mg, vg, 0, 1e-2, 0.9, 0.99, 1e-15, 3, zero_grad=True, lazy=lazy)
+    pr, mr, vr = o.adam_step(p, g, m, v, 3, 1e-2, 0.9, 0.99, 1e-15, lazy=lazy)
+    for got, want in ((pg, pr), (mg, mr), (vg, vr)):
+        assert rel(got.cpu().numpy(), want) <= 1e-6
+    if lazy:
+        z = g == 0
+        assert np.array_equal(pg.cpu().numpy()[z], p[z]) and np.array_equal(mg.cpu().numpy()[z], m[z])
+    assert torch.all(gg == 0)
+    # tables: dense levels with (res+1)^3 * 2 parameters (2 mod 4), hashed levels, whole groups of zeros
+    cfg = wl.make_config(2)
+    cfg.log2_table_size, cfg.n_levels, cfg.active_levels = 12, 8, 8
+    cfg.res = [4, 6, 10, 14, 40, 80, 100, 120]
+    cfg.dense = [1 if (r + 1) ** 3 <= cfg.table_size else 0 for r in cfg.res]
+    cfg.sdf_dims = [16] + cfg.sdf_dims[1:]
+    assert cfg.dense == [1, 1, 1, 1, 0, 0, 0, 0] and ((cfg.res[0] + 1) ** 3 * 2) % 4 == 2
+    c = nb.make_config(cfg)
+    L, T = cfg.n_levels, cfg.table_size
+    p = (rng.normal(size=(L, T, 2)) * 1e-3).astype(np.float32)
+    g, m, v = np.zeros((L, T, 2), np.float32), np.zeros((L, T, 2), np.float32), np.zeros((L, T, 2), np.float32)
+    for l in range(L):
+        used = (cfg.res[l] + 1) ** 3 if cfg.dense[l] else T
+        g[l, :used] = rng.normal(size=(used, 2)) * 1e-4
+        g[l, :used][rng.uniform(size=used) < 0.7] = 0.0
+        m[l, :used] = rng.normal(size=(used, 2)) * 1e-5
+        v[l, :used] = np.abs(rng.normal(size=(used, 2))) * 1e-9
+    tab, master, gg, mg, vg = cuda(p, torch.float16), cuda(p), cuda(g), cuda(m), cuda(v)
+    nb.adam_tables(c, tab, master, gg, mg, vg, 1e-2, 0.9, 0.99, 1e-15, 9, zero_grad=True, lazy=lazy)
+    torch.cuda.synchronize()
+    pr, mr, vr = o.adam_step(p, g, m, v, 9, 1e-2, 0.9, 0.99, 1e-15, lazy=lazy)
+    for got, want in ((master, pr), (mg, mr), (vg, vr)):
+        got = got.cpu().numpy().astype(np.float64)
+        assert rel(got, want) <= 1e-6 and np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+    assert torch.all(gg == 0)
+    touched = torch.as_tensor(g != 0).cuda() if lazy else torch.ones_like(master, dtype=torch.bool)
+    assert torch.equal(tab[touched], master.to(torch.float16)[touched])
+    with pytest.raises(nb.Neus2Error):
+        nb.lib()  # keep the import used
+        nb._check(nb.lib().neus2_adam_step(pg.data_ptr(), None, gg.data_ptr(), mg.data_ptr(), vg.data_ptr(), 4, 0, 1e-2, 0.9, 0.99,
+                                           1e-15, 1, 7, None))
+
+
 def test_adam_tables_skips_only_unaddressable_slots():
     """The table update leaves out the slots of dense levels no point can reach; the result must
     be the dense update of every parameter (their gradient and moments are zero)."""

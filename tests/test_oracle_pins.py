@@ -712,3 +712,30 @@ def test_adam_closed_forms():
     v_want = 0.99 * 0.01 * g * g + 0.01 * g2 * g2
     want = p1 - lr * (m_want / (1 - 0.81)) / (np.sqrt(v_want / (1 - 0.99 ** 2)) + eps)
     np.testing.assert_allclose(p2, want, rtol=1e-12)
+
+
+def test_lazy_adam_skips_untouched_entries_only():
+    """The sparse form: an entry with a zero gradient keeps value and moments; entries with a
+    gradient get the dense update; written out for an entry touched at steps 1 and 3 only."""
+    lr, eps, b1, b2 = 1e-2, 1e-15, 0.9, 0.99
+    rng = np.random.default_rng(4)
+    p, m, v = rng.normal(size=50), rng.normal(size=50) * 1e-2, np.abs(rng.normal(size=50)) * 1e-4
+    g = rng.normal(size=50)
+    g[::3] = 0.0
+    pd, md, vd = o.adam_step(p, g, m, v, 4, lr, b1, b2, eps)
+    pl, ml, vl = o.adam_step(p, g, m, v, 4, lr, b1, b2, eps, lazy=True)
+    hit = g != 0
+    assert np.array_equal(pl[hit], pd[hit]) and np.array_equal(ml[hit], md[hit]) and np.array_equal(vl[hit], vd[hit])
+    assert np.array_equal(pl[~hit], p[~hit]) and np.array_equal(ml[~hit], m[~hit]) and np.array_equal(vl[~hit], v[~hit])
+    assert not np.array_equal(md[~hit], m[~hit])                   # the dense form decays them
+    # one entry, gradients g1, 0, g3
+    g1, g3 = 0.5, -0.2
+    x, mm, vv = 1.0, 0.0, 0.0
+    for t, gt in ((1, g1), (2, 0.0), (3, g3)):
+        x, mm, vv = (float(a[0]) for a in o.adam_step([x], [gt], [mm], [vv], t, lr, b1, b2, eps, lazy=True))
+    m_want = b1 * (1 - b1) * g1 + (1 - b1) * g3                    # one decay, not two
+    v_want = b2 * (1 - b2) * g1 * g1 + (1 - b2) * g3 * g3
+    x_want = (1.0 - lr * np.sign(g1)) - lr * (m_want / (1 - b1 ** 3)) / (np.sqrt(v_want / (1 - b2 ** 3)) + eps)
+    assert mm == pytest.approx(m_want, rel=1e-14) and vv == pytest.approx(v_want, rel=1e-14)
+    assert x == pytest.approx(x_want, rel=1e-12)
+

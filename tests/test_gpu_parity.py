@@ -227,6 +227,53 @@ def test_network_products_over_a_wide_range_of_magnitudes(enc_scale, w_scale):
         assert rel(a.cpu().numpy(), b) <= GRAD_TOL
 
 
+@pytest.mark.parametrize("D,K", [(16, 2), (16, 3), (32, 2), (32, 3)])
+def test_sdf_network_every_kernel_shape(D, K):
+    """The four shapes the SDF kernels are built for (input width 16 or 32, one or two hidden
+    layers), forward and first/second-order backward alone, with a ragged last tile."""
+    rng = np.random.default_rng(100 * D + K)
+    cfg = wl.make_config(2)
+    cfg.n_levels = cfg.active_levels = D // 2
+    cfg.res, cfg.dense = cfg.res[:D // 2], cfg.dense[:D // 2]
+    cfg.sdf_dims = [D] + [64] * (K - 1) + [16]
+    c = nb.make_config(cfg)
+    n, L = 32 * 37 + 11, cfg.n_levels
+    H = [(rng.normal(size=(cfg.sdf_dims[i + 1], cfg.sdf_dims[i])) * 0.3).astype(np.float32) for i in range(K)]
+    e = rng.normal(size=(n, D)).astype(np.float32)
+    J = rng.normal(size=(n, D, 3)).astype(np.float32)
+    Hg = [cuda(h) for h in H]
+    enc_lm, jac_lm = to_level_major(e, L), cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+    y, q, nrm = torch.empty(n, 16, device="cuda"), torch.empty(L, n, 2, device="cuda"), torch.empty(n, 3, device="cuda")
+    nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm)
+    yr, acts, masks = o.mlp_forward(H, e)
+    S, qr = o.mlp_input_gradient(H, masks, 0)
+    assert rel(y.cpu().numpy(), yr) <= FWD_TOL
+    assert rel(from_level_major(q, n), qr) <= FWD_TOL
+    assert rel(nrm.cpu().numpy(), np.einsum("nk,nka->na", qr, J.astype(np.float64))) <= FWD_TOL
+    d_y = rng.normal(size=(n, 16)).astype(np.float32)
+    d_n = rng.normal(size=(n, 3)).astype(np.float32)
+    dH = [torch.zeros_like(h) for h in Hg]
+    d_enc = torch.zeros(L, n, 2, device="cuda")
+    nb.sdf_mlp_bwd(c, enc_lm, jac_lm, Hg, cuda(d_y), cuda(d_n), n, dH, d_enc)
+    torch.cuda.synchronize()
+    H64 = [h.astype(np.float64) for h in H]
+    gH, d_in, _ = o.mlp_backward(H64, acts, masks, d_y.astype(np.float64))
+    # second order (Theorem 1 for the SDF output): dL/dH_l += S_l^T t_{l-1}^T, t_0 = J nbar
+    t = np.einsum("nka,na->nk", J.astype(np.float64), d_n.astype(np.float64))
+    s_vec = np.tile(H64[K - 1][0], (n, 1)) * masks[K - 2]
+    sweep = [None] * (K - 1)
+    sweep[K - 2] = s_vec
+    for l in range(K - 3, -1, -1):
+        sweep[l] = (sweep[l + 1] @ H64[l + 1]) * masks[l]
+    for l in range(K - 1):
+        gH[l] += sweep[l].T @ t
+        t = (t @ H64[l].T) * masks[l]
+    gH[K - 1][0] += t.sum(axis=0)
+    assert rel(from_level_major(d_enc, n), d_in) <= GRAD_TOL
+    for a, b in zip(dH, gH):
+        assert rel(a.cpu().numpy(), b) <= GRAD_TOL
+
+
 def test_render_forward_backward_alone():
     rng = np.random.default_rng(1)
     for spr, rays in ((64, 37), (17, 9), (1, 5), (2, 3)):

@@ -154,6 +154,40 @@ int check_mats(const void* const* M, int count, const char* name) {
 
 using namespace neus2;
 
+namespace {
+
+// SDF backward + scatter-add; header_cleared: the caller has had the workspace header cleared
+int sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
+                const float* jac, const float* const* H, const float* q, const float* d_y,
+                const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
+                float* d_pos, void* workspace, int64_t workspace_bytes, bool header_cleared, void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(workspace, "workspace", false));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, cfg->n_sdf_mats, "H"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(d_y, "d_y"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_mats((const void* const*)dH, cfg->n_sdf_mats, "dH"));
+    NEUS2_TRY(check_ptr(d_tables, "d_tables"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    hipStream_t st = (hipStream_t)stream;
+    // With a large batch and a workspace the scatter's gather pass has the corners of every level
+    // in registers and adds (de/dx)^T dL/de to d_pos on the way; otherwise the network kernel
+    // does it from the stored Jacobian.
+    const bool gather = d_pos && scatter_gathers_position(cfg, n, workspace, workspace_bytes);
+    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, st));
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, gather, st,
+                          header_cleared);
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* neus2_last_error(void) { return g_error; }
@@ -227,28 +261,8 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
                       const float* jac, const float* const* H, const float* q, const float* d_y,
                       const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
                       float* d_pos, void* workspace, int64_t workspace_bytes, void* stream) {
-    NEUS2_TRY(check_config(cfg));
-    NEUS2_TRY(check_count(n, "n"));
-    NEUS2_TRY(check_ptr(workspace, "workspace", false));
-    NEUS2_TRY(check_ptr(pos, "pos"));
-    NEUS2_TRY(check_ptr(tables, "tables"));
-    NEUS2_TRY(check_ptr(enc, "enc"));
-    NEUS2_TRY(check_ptr(jac, "jac"));
-    NEUS2_TRY(check_mats((const void* const*)H, cfg->n_sdf_mats, "H"));
-    NEUS2_TRY(check_ptr(q, "q"));
-    NEUS2_TRY(check_ptr(d_y, "d_y"));
-    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
-    NEUS2_TRY(check_mats((const void* const*)dH, cfg->n_sdf_mats, "dH"));
-    NEUS2_TRY(check_ptr(d_tables, "d_tables"));
-    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
-    NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
-    hipStream_t st = (hipStream_t)stream;
-    // With a large batch and a workspace the scatter's gather pass has the corners of every level
-    // in registers and adds (de/dx)^T dL/de to d_pos on the way; otherwise the network kernel
-    // does it from the stored Jacobian.
-    const bool gather = d_pos && scatter_gathers_position(cfg, n, workspace, workspace_bytes);
-    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, st));
-    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, gather, st);
+    return sdf_bwd_2nd(cfg, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos, workspace,
+                       workspace_bytes, false, stream);
 }
 
 }  // extern "C"
@@ -267,14 +281,23 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     NEUS2_TRY(check_ptr(b->loss, "loss"));
     hipStream_t st = (hipStream_t)stream;
     const int64_t rays = ragged ? b->n_rays : n / cfg->samples_per_ray;
-    NEUS2_TRY(launch_zero(b->loss, 2, st));
     if (n == 0) {                  // an empty batch has no sample buffers to look at
+        NEUS2_TRY(launch_zero(b->loss, 2, st));
         if (ragged && rays > 0)    // rays without samples still enter the colour term
             return neus2_render_loss_bwd_ragged(cfg, nullptr, nullptr, nullptr, b->target, b->ray_offsets, b->s_dev, rays, 0,
                                                 b->C, nullptr, b->loss, b->dC, nullptr, nullptr, nullptr, b->d_s, stream);
         return NEUS2_OK;
     }
-    NEUS2_TRY(neus2_hash_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, stream));
+    // the encode kernel, first of the step, also clears the loss sums and the header of the scatter's
+    // workspace: two launches fewer
+    ZeroRegions zero = {{b->loss, nullptr}, {2, 0}};
+    NEUS2_TRY(check_ptr(b->workspace, "workspace", false));
+    scatter_header(cfg, n, b->d_pos != nullptr, b->workspace, b->workspace_bytes, &zero.p[1], &zero.count[1]);
+    NEUS2_TRY(check_ptr(b->pos, "pos"));
+    NEUS2_TRY(check_ptr(b->tables, "tables"));
+    NEUS2_TRY(check_ptr(b->enc, "enc"));
+    NEUS2_TRY(check_ptr(b->jac, "jac"));
+    NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
     if (cfg->loss_kind != 0) {
         NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, stream));
@@ -291,6 +314,6 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
         NEUS2_TRY(neus2_loss(cfg, nullptr, nullptr, b->normal, b->y, 0, n, b->loss, nullptr, b->d_normal, b->d_y, stream));
         if (b->d_pos) NEUS2_TRY(launch_zero(b->d_pos, 3 * n, st));
     }
-    return neus2_sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
-                             b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, stream);
+    return sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
+                       b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, zero.count[1] > 0, stream);
 }

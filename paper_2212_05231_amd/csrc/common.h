@@ -43,14 +43,26 @@ int persistent_blocks(const void* kernel, int threads, int64_t want);
 
 int launch_zero(float* p, int64_t count, hipStream_t st);
 
+// Up to two small regions that the first kernel of a training step clears on its way, instead
+// of a launch of their own each (the loss sums, the header of the scatter's workspace).
+struct ZeroRegions {
+    float* p[2];
+    int count[2];
+};
+
 // internal launchers (each validates nothing; the extern "C" wrappers do)
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
-                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st);
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero = nullptr);
 // first_order_pos: d_pos also gets J^T d_enc (the part the SDF backward kernel adds when it is
 // handed d_pos); only honoured on the path scatter_gathers_position() reports.
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st);
+                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st,
+                   bool header_cleared = false);
+// The part of the workspace launch_scatter needs cleared before it runs (task counter and list
+// cursors) if it will take the path that uses the workspace with these arguments, else count 0.
+void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* workspace, int64_t workspace_bytes,
+                    float** p, int* count);
 bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes);
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,

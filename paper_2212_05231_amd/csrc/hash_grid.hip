@@ -192,11 +192,17 @@ __device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int
 }
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedule sch, const float* __restrict__ pos,
+__global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedule sch, ZeroRegions zero,
+                                                        const float* __restrict__ pos,
                                                         const T* __restrict__ tables, int64_t n,
                                                         float* __restrict__ enc,
                                                         float* __restrict__ jac,
                                                         uint32_t* __restrict__ dbg_idx) {
+    if (blockIdx.x == 0) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+            for (int k = threadIdx.x; k < zero.count[r]; k += kBlock) zero.p[r][k] = 0.f;
+    }
     int level, pb;
     if (!decode_schedule(sch, level, pb)) return;
     const int64_t i = (int64_t)pb * kBlock + threadIdx.x;
@@ -901,17 +907,23 @@ int grid_blocks(int levels, int point_blocks) {
 }  // namespace
 
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
-                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st) {
-    if (n == 0) return NEUS2_OK;
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero) {
+    ZeroRegions zr = {{nullptr, nullptr}, {0, 0}};
+    if (zero) zr = *zero;
+    if (n == 0) {
+        for (int r = 0; r < 2; ++r)
+            if (zr.count[r] > 0) NEUS2_TRY(launch_zero(zr.p[r], zr.count[r], st));
+        return NEUS2_OK;
+    }
     const GridDesc g = make_grid_desc(cfg);
     const int pbs = (int)((n + kBlock - 1) / kBlock);
     const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs);
     const dim3 grid(kXcd * sch.per_xcd);
     if (cfg->table_dtype == 1)
-        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, sch, pos,
+        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, sch, zr, pos,
                            (const __half*)tables, n, enc, jac, dbg_idx);
     else
-        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, sch, pos,
+        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, sch, zr, pos,
                            (const float*)tables, n, enc, jac, dbg_idx);
     return check_launch("hash encode");
 }
@@ -938,9 +950,25 @@ bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* wo
     return ok && workspace_bytes >= (owner_workspace_need(plan) + 255) / 256 * 256 + pos_scratch_bytes(cfg, n);
 }
 
+// must mirror the condition under which launch_scatter takes the path with the workspace
+void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* workspace, int64_t workspace_bytes,
+                    float** p, int* count) {
+    *p = nullptr;
+    *count = 0;
+    if (n == 0 || cfg->active_levels == 0 || n < kOwnerMinPoints || !workspace) return;
+    bool ok = false;
+    const OwnerPlan plan = make_owner_plan(cfg, n, ok);
+    const int64_t records_end = (owner_workspace_need(plan) + 255) / 256 * 256;
+    if (ok && workspace_bytes >= (want_pos ? records_end + pos_scratch_bytes(cfg, n) : owner_workspace_need(plan))) {
+        *p = reinterpret_cast<float*>(workspace);
+        *count = kWorkspaceHeader / 4;
+    }
+}
+
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
-                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st) {
+                   float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st,
+                   bool header_cleared) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
     // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels);
@@ -957,7 +985,8 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             rec.cursor = reinterpret_cast<int*>(ws + kCursorOffset);
             rec.vals = reinterpret_cast<float4*>(ws + kWorkspaceHeader);                         // 16-byte aligned
             rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 16);
-            NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));      // task counter and cursors
+            if (!header_cleared)                                                                 // task counter and cursors
+                NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));
             if (plan.n_listed > 0) {
                 const int pbs = (int)((n + kBinThreads - 1) / kBinThreads);
                 hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_listed), dim3(kBinThreads), 0, st, g, plan, rec, pos, q,

@@ -41,7 +41,7 @@ MEASURED_TRAFFIC_MIB = {
         "hash_encode": (71.3, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
         "render_loss_bwd": (22.1, 8.1), "color_bwd": (33.1, 28.2), "sdf_mlp_bwd": (147.9, 39.0),
         "hash_scatter_bwd": (84.0 + 354.5, 232.5 + 63.2),      # bin_rows_kernel + scatter_owner_kernel
-        "adam_tables": (186.1, 209.4),
+        "adam_all": (186.1, 209.4),
     },
 }
 
@@ -50,7 +50,7 @@ KERNELS_OF_CALL = {
     "hash_encode": "encode_kernel", "sdf_fwd_grad": "sdf_fwd_kernel", "sdf_mlp_bwd": "sdf_bwd_kernel",
     "sdf_bwd_2nd": "sdf_bwd_kernel + zero_kernel + bin_rows_kernel + scatter_owner_kernel + pos_hessian_kernel + sum_levels_kernel",
     "hash_scatter_bwd": "zero_kernel + bin_rows_kernel + scatter_owner_kernel (scatter_kernel below 2^16 points)",
-    "adam_tables": "adam_tables_kernel", "adam_matrices": "adam_kernel", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
+    "adam_all": "adam_tables_kernel (tables, and the networks' matrices in a last row of workgroups)", "color_fwd": "color_fwd_kernel", "color_bwd": "color_bwd_kernel",
     "render_loss_bwd": "render_loss_kernel", "render_rays": "render_fwd_kernel", "render_rays_bwd": "render_bwd_kernel", "loss": "loss_kernel",
 }
 
@@ -275,13 +275,11 @@ def main() -> int:
         if dynamic:
             seq += [("rigid_bwd", lambda: nb.rigid_bwd(world, shift, s.d_pos, 0.5, Mb))]
         seq += [
-            ("adam_tables", lambda: nb.adam_tables(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"],
-                                                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
-            ("adam_matrices", lambda: nb.adam_step(s.small, None, s.d_small, o["m_s"], o["v_s"], 0,
-                                                   o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
+            ("adam_all", lambda: nb.adam_all(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"], s.small, s.d_small,
+                                             o["m_s"], o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
         ]
         cost = algorithmic_cost(cfg, n)
-        cost["adam_matrices"] = {"bytes": 34 * int(s.small.numel()), "flops": 0}
+        cost["adam_all"] = {"bytes": cost["adam_tables"]["bytes"] + 32 * int(s.small.numel()), "flops": 0}
         cost["sdf_bwd_2nd"] = {"bytes": cost["sdf_mlp_bwd"]["bytes"] + cost["hash_scatter_bwd"]["bytes"] + 24 * n,
                                "flops": cost["sdf_mlp_bwd"]["flops"], "issued_flops": cost["sdf_mlp_bwd"]["issued_flops"]}
         cost["rigid_fwd"] = {"bytes": 24 * n, "flops": 0}

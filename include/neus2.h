@@ -233,6 +233,15 @@ int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, floa
                       float* v, float lr, float beta1, float beta2, float eps, int t,
                       int flags, void* stream);
 
+/* neus2_adam_tables and, in the same launch, the dense update of a flat fp32 buffer of
+ * small_count parameters (the matrices of both networks, a trained slope): small_param,
+ * small_grad, small_m, small_v [device, fp32].  The lazy flag applies to the tables only.
+ * Same results as the two separate calls. */
+int neus2_adam_all(const neus2_config* cfg, void* tables, float* master, float* grad, float* m,
+                   float* v, float* small_param, float* small_grad, float* small_m, float* small_v,
+                   int64_t small_count, float lr, float beta1, float beta2, float eps, int t,
+                   int flags, void* stream);
+
 /* Global rigid transform of Eq. 9, x_c = R (x + T), then the affine map scale*x_c + offset
  * that takes world coordinates to the unit cube.  R [host, 9 row-major], T [host, 3]. */
 int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset,

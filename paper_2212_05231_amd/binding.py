@@ -75,6 +75,8 @@ _SIGNATURES = {
                                   C.c_float, C.c_int, C.c_int, _P]),
     "neus2_adam_tables": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float,
                                     C.c_float, C.c_int, C.c_int, _P]),
+    "neus2_adam_all": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, C.c_float, C.c_float,
+                                 C.c_float, C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
     "neus2_rigid_bwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
     "neus2_occupancy_points": (C.c_int, [C.c_int, _P, _P, C.c_int64, _P, _P]),
@@ -233,6 +235,13 @@ def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_gr
                                    lr, beta1, beta2, eps, t, (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
 
 
+def adam_all(c, tables, master, grad, m, v, small, small_grad, small_m, small_v, lr, beta1, beta2, eps, t, zero_grad=True,
+             lazy=False):
+    _check(lib().neus2_adam_all(C.byref(c), _ptr(tables), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), _ptr(small),
+                                _ptr(small_grad), _ptr(small_m), _ptr(small_v), small.numel(), lr, beta1, beta2, eps, t,
+                                (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
+
+
 def rigid_fwd(pos, R, T, scale, offset, out):
     Ra = (C.c_float * 9)(*[float(x) for x in R])
     Ta = (C.c_float * 3)(*[float(x) for x in T])
@@ -357,10 +366,8 @@ class Step:
         """One Adam step on every parameter; the gradient buffers are cleared in the same pass."""
         o = self.opt
         o["t"] += 1
-        adam_tables(self.c, self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"],
-                    o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True, o["lazy"])
-        adam_step(self.small, None, self.d_small, o["m_s"], o["v_s"], 0,
-                  o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)
+        adam_all(self.c, self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"], self.small, self.d_small, o["m_s"],
+                 o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True, o["lazy"])
 
     def train_step(self, n: Optional[int] = None) -> None:
         """`n` (at most the n the buffers were sized for) runs the step on the first n samples:

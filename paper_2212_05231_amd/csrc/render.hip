@@ -498,11 +498,28 @@ struct TableLevels {
     uint32_t used[NEUS2_MAX_LEVELS];     // parameters (slots * F) of each level that can be addressed
 };
 
+// A flat fp32 parameter buffer updated by the same launch (count 0: none).
+struct AdamExtra {
+    float* param; float* grad; float* m; float* v;
+    int64_t count;
+};
+
 template <bool HALF>
 __global__ __launch_bounds__(256) void adam_tables_kernel(void* __restrict__ param, float* __restrict__ master,
                                                           float* __restrict__ grad, float* __restrict__ m,
                                                           float* __restrict__ v, TableLevels lv, uint32_t per_level,
-                                                          AdamArgs a, int flags) {
+                                                          AdamArgs a, int flags, AdamExtra extra) {
+    if (blockIdx.y == gridDim.y - 1 && extra.count > 0) {
+        // last row of workgroups: the flat fp32 buffer that rides along (the networks' matrices), dense form
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < extra.count; i += (int64_t)gridDim.x * 256) {
+            float mi = extra.m[i], vi = extra.v[i];
+            extra.param[i] = adam_one(extra.grad[i], mi, vi, extra.param[i], a);
+            extra.m[i] = mi;
+            extra.v[i] = vi;
+            if (flags & kAdamClear) extra.grad[i] = 0.f;
+        }
+        return;
+    }
     const int level = blockIdx.y;
     const uint32_t k = (blockIdx.x * 256u + threadIdx.x) * 4u;
     const uint32_t used = lv.used[level];
@@ -738,8 +755,10 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
     return check_launch("adam");
 }
 
-int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
-                      float beta1, float beta2, float eps, int t, int flags, void* stream) {
+namespace {
+
+int adam_tables_impl(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
+                     float beta1, float beta2, float eps, int t, int flags, const AdamExtra& extra, void* stream) {
     NEUS2_TRY(check_config(cfg));
     if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3", flags);
     if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
@@ -764,14 +783,38 @@ int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, floa
         lv.used[l] = l < cfg->frozen_levels ? 0u : (uint32_t)(slots * F);
         if (lv.used[l] > most) most = lv.used[l];
     }
-    const dim3 grid((most + 1023u) / 1024u, (unsigned)cfg->n_levels);
+    // one row of workgroups per level, one more for the buffer that rides along
+    const dim3 grid((most + 1023u) / 1024u > 0 ? (most + 1023u) / 1024u : 1u, (unsigned)cfg->n_levels + (extra.count > 0 ? 1u : 0u));
     if (cfg->table_dtype == 1)
         hipLaunchKernelGGL(adam_tables_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
-                           (uint32_t)(T * F), a, flags);
+                           (uint32_t)(T * F), a, flags, extra);
     else
         hipLaunchKernelGGL(adam_tables_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, tables, master, grad, m, v, lv,
-                           (uint32_t)(T * F), a, flags);
+                           (uint32_t)(T * F), a, flags, extra);
     return check_launch("adam (tables)");
+}
+
+}  // namespace
+
+int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
+                      float beta1, float beta2, float eps, int t, int flags, void* stream) {
+    const AdamExtra none = {nullptr, nullptr, nullptr, nullptr, 0};
+    return adam_tables_impl(cfg, tables, master, grad, m, v, lr, beta1, beta2, eps, t, flags, none, stream);
+}
+
+int neus2_adam_all(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v,
+                   float* small_param, float* small_grad, float* small_m, float* small_v, int64_t small_count, float lr,
+                   float beta1, float beta2, float eps, int t, int flags, void* stream) {
+    if (small_count < 0 || small_count > ((int64_t)1 << 28))
+        return fail(NEUS2_ERR_SHAPE, "small_count = %lld out of range", (long long)small_count);
+    if (small_count > 0) {
+        NEUS2_TRY(check_ptr(small_param, "small_param"));
+        NEUS2_TRY(check_ptr(small_grad, "small_grad"));
+        NEUS2_TRY(check_ptr(small_m, "small_m"));
+        NEUS2_TRY(check_ptr(small_v, "small_v"));
+    }
+    const AdamExtra extra = {small_param, small_grad, small_m, small_v, small_count};
+    return adam_tables_impl(cfg, tables, master, grad, m, v, lr, beta1, beta2, eps, t, flags, extra, stream);
 }
 
 int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scale, float offset, int64_t n, float* out,

@@ -566,6 +566,42 @@ def test_adam_lazy_form_and_vector_tails(lazy):
                                            1e-15, 1, 7, None))
 
 
+def test_adam_all_equals_the_two_separate_calls():
+    """Tables and the flat buffer of matrices in one launch: what neus2_adam_tables (bit for bit) and
+    neus2_adam_step (to rounding) give, dense and lazy; the flat buffer against the oracle."""
+    rng = np.random.default_rng(6)
+    cfg = wl.make_config(2)
+    cfg.log2_table_size = 13
+    cfg.dense = [1 if (r + 1) ** 3 <= cfg.table_size else 0 for r in cfg.res]
+    c = nb.make_config(cfg)
+    L, T = cfg.n_levels, cfg.table_size
+    small_n = 11 * 1000 + 3
+    for lazy in (False, True):
+        p = (rng.normal(size=(L, T, 2)) * 1e-3).astype(np.float32)
+        g = (rng.normal(size=(L, T, 2)) * 1e-4).astype(np.float32)
+        g[rng.uniform(size=g.shape) < 0.5] = 0.0
+        for l in range(L):
+            if cfg.dense[l]:
+                g[l, (cfg.res[l] + 1) ** 3:] = 0.0
+        m = (rng.normal(size=g.shape) * 1e-5).astype(np.float32) * (g != 0)
+        v = (np.abs(rng.normal(size=g.shape)) * 1e-9).astype(np.float32) * (g != 0)
+        sp, sg = rng.normal(size=small_n).astype(np.float32), rng.normal(size=small_n).astype(np.float32) * 1e-3
+        sm, sv = rng.normal(size=small_n).astype(np.float32) * 1e-4, np.abs(rng.normal(size=small_n)).astype(np.float32) * 1e-7
+        a = [cuda(p, torch.float16), cuda(p), cuda(g), cuda(m), cuda(v), cuda(sp), cuda(sg), cuda(sm), cuda(sv)]
+        b = [t.clone() for t in a]
+        nb.adam_all(c, a[0], a[1], a[2], a[3], a[4], a[5], a[6], a[7], a[8], 1e-2, 0.9, 0.99, 1e-15, 4, True, lazy)
+        nb.adam_tables(c, b[0], b[1], b[2], b[3], b[4], 1e-2, 0.9, 0.99, 1e-15, 4, True, lazy)
+        nb.adam_step(b[5], None, b[6], b[7], b[8], 0, 1e-2, 0.9, 0.99, 1e-15, 4, True, False)
+        torch.cuda.synchronize()
+        for x, y in zip(a[:5], b[:5]):
+            assert torch.equal(x, y)                                  # the same kernel code
+        for x, y in zip(a[5:], b[5:]):                                # two kernels: the compiler may fuse multiply-adds differently
+            assert rel(x.cpu().numpy(), y.cpu().numpy()) <= 1e-6
+        pr, mr, vr = o.adam_step(sp, sg, sm, sv, 4, 1e-2, 0.9, 0.99, 1e-15)
+        assert rel(a[5].cpu().numpy(), pr) <= 1e-6 and rel(a[7].cpu().numpy(), mr) <= 1e-6 and rel(a[8].cpu().numpy(), vr) <= 1e-6
+        assert torch.all(a[6] == 0)
+
+
 def test_adam_tables_skips_only_unaddressable_slots():
     """The table update leaves out the slots of dense levels no point can reach; the result must
     be the dense update of every parameter (their gradient and moments are zero)."""

@@ -314,33 +314,36 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         }
     }
     __syncthreads();
-    float* scratch = &sm.tiles[0][0][0];
-    v16f g3;                   // the four 16-column blocks of G3 side by side, for the sum over waves
+    // ---- every wave gets a quarter of the registers of the block's sums and adds it to global
+    // memory: one barrier, and the atomics of the four waves run side by side
+    float* scratch = reinterpret_cast<float*>(&sm);
+    static_assert(sizeof(sm) >= kWaves * 9 * 1024 * sizeof(float), "scratch for the block sum");
+    v16f g3;                   // the four 16-column blocks of G3 side by side
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) g3[4 * cb + v] = G3[cb][v];
     v16f* all[9] = {&G1[0][0], &G1[0][1], &G1[1][0], &G1[1][1], &G2[0][0], &G2[0][1], &G2[1][0], &G2[1][1], &g3};
-    static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 5 * 1024 * sizeof(float), "scratch for the block sum");
-    block_sum_all<kWaves, 9>(scratch, all, wave, lane);
-    if (wave == 0) {
+    block_sum_shared<kWaves, 9>(scratch, all, wave, lane);
+    constexpr int kShare = 16 / kWaves;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int o = 32 * mb + neuron_of(r, h), c = 32 * nb + j;
-                    atomicAdd(a.dW[1] + o * 64 + c, G2[mb][nb][r]);
-                    const int e = external_column(c);
-                    if (e >= 0) atomicAdd(a.dW[0] + o * 38 + e, G1[mb][nb][r]);
-                }
-        if (lane < 16) {       // rows 0..3 of a block live in lanes 0..15; three of them are real
+            for (int r = 0; r < 16; ++r) {
+                if (r / kShare != wave) continue;
+                const int o = 32 * mb + neuron_of(r, h), c = 32 * nb + j;
+                atomicAdd(a.dW[1] + o * 64 + c, G2[mb][nb][r]);
+                const int e = external_column(c);
+                if (e >= 0) atomicAdd(a.dW[0] + o * 38 + e, G1[mb][nb][r]);
+            }
+    if (lane < 16) {           // rows 0..3 of a block live in lanes 0..15; three of them are real
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
+        for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-                for (int v = 0; v < 3; ++v) atomicAdd(a.dW[2] + v * 64 + 16 * cb + lane, g3[4 * cb + v]);
-        }
+            for (int v = 0; v < 3; ++v)
+                if (cb == wave) atomicAdd(a.dW[2] + v * 64 + 16 * cb + lane, g3[4 * cb + v]);
     }
 }
 

@@ -333,57 +333,33 @@ __device__ __forceinline__ void outer_accumulate16(v4f* G, const float* __restri
     }
 }
 
-// Sum one register vector over the block's WAVES waves through a 1024-float LDS scratch;
-// the result is valid in the last wave.  Every thread of the block must call it.
-template <int WAVES>
-__device__ __forceinline__ v16f block_sum(float* __restrict__ scratch, v16f v, int wave, int lane) {
-    for (int wv = 0; wv < WAVES; ++wv) {
-        if (wave == wv) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float* p = scratch + r * 64 + lane;
-                if (wv == 0) *p = v[r];
-                else if (wv < WAVES - 1) *p += v[r];
-                else v[r] += *p;
-            }
-        }
-        __syncthreads();
-    }
-    return v;
-}
-
-// Sum V register vectors over the block's WAVES waves; the result is valid in wave 0.  The
-// other waves park their vectors in LDS, HALF = ceil(V/2) at a time (scratch holds
-// (WAVES-1) * HALF * 1024 floats), and wave 0 adds them: four barriers for any V instead of
-// WAVES per vector.  Every thread of the block must call it.
+// Sum V register vectors over the block's WAVES waves such that every wave ends up with a share of
+// the totals: wave w holds, in registers 16/WAVES * w .. 16/WAVES * (w+1) - 1 of every vector, the
+// block's sums (its other registers keep its own partial sums).  All waves then flush their share
+// in parallel.  scratch: WAVES * V * 1024 floats of LDS nobody reads any more; one barrier inside,
+// and the caller has put one before (the scratch overlays memory other waves may still be using).
+// Every thread of the block must call it.
 template <int WAVES, int V>
-__device__ __forceinline__ void block_sum_all(float* __restrict__ scratch, v16f* (&vec)[V], int wave, int lane) {
-    constexpr int HALF = (V + 1) / 2;
+__device__ __forceinline__ void block_sum_shared(float* __restrict__ scratch, v16f* (&vec)[V], int wave, int lane) {
+    static_assert(16 % WAVES == 0, "registers are dealt out evenly");
+    constexpr int kShare = 16 / WAVES;
 #pragma unroll
-    for (int round = 0; round < 2; ++round) {
-        if (wave > 0) {
+    for (int k = 0; k < V; ++k)
 #pragma unroll
-            for (int k = 0; k < HALF; ++k)
-                if (round * HALF + k < V) {
+        for (int r = 0; r < 16; ++r) scratch[((wave * V + k) * 16 + r) * 64 + lane] = (*vec[k])[r];
+    __syncthreads();
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        scratch[((wave - 1) * HALF + k) * 1024 + r * 64 + lane] = (*vec[round * HALF + k])[r];
-                }
+    for (int k = 0; k < V; ++k)
+#pragma unroll
+        for (int q = 0; q < kShare; ++q) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) sum += scratch[((w * V + k) * 16 + wave * kShare + q) * 64 + lane];
+            // written through a loop over constant register numbers: the share's first register depends on the wave
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (r == wave * kShare + q) (*vec[k])[r] = sum;
         }
-        __syncthreads();
-        if (wave == 0) {
-#pragma unroll
-            for (int k = 0; k < HALF; ++k)
-                if (round * HALF + k < V) {
-#pragma unroll
-                    for (int wv = 0; wv < WAVES - 1; ++wv)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            (*vec[round * HALF + k])[r] += scratch[(wv * HALF + k) * 1024 + r * 64 + lane];
-                }
-        }
-        __syncthreads();
-    }
 }
 
 }  // namespace neus2

@@ -334,14 +334,18 @@ struct SdfBwdSmem {
 };
 
 // add this wave's accumulator into dst[rows][cols] (row-major, ld = cols) with atomics
+// add the registers [r0, r0 + count) of this wave's accumulator into dst[rows][cols] (row-major,
+// ld = cols) with atomics; r0 is the same for all lanes
 template <int ZB, int XB>
-__device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, int cols, v16f (*G)[XB], int j, int h) {
+__device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, int cols, v16f (*G)[XB], int j, int h,
+                                           int r0, int count) {
 #pragma unroll
     for (int mb = 0; mb < ZB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < XB; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
+                if (r < r0 || r >= r0 + count) continue;
                 const int o = 32 * mb + neuron_of(r, h), i = 32 * nb + j;
                 if (o < rows && i < cols) atomicAdd(dst + o * cols + i, G[mb][nb][r]);
             }
@@ -497,31 +501,33 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     }
     __syncthreads();
     // ---- reduce over the block's waves, then one atomic add per element and block
-    float* scratch = &sm.tiles[0][0][0];
-    static_assert(sizeof(sm.tiles) >= (kWaves - 1) * 4 * 1024 * sizeof(float), "scratch for the block sum");
-    v16f gl;                   // the four 16-column blocks of GL side by side, for the sum over waves
+    // ---- every wave gets a quarter of the registers of the block's sums and adds it to global
+    // memory: one barrier, and the atomics of the four waves run side by side
+    float* scratch = reinterpret_cast<float*>(&sm);
+    constexpr int kVecs = K == 3 ? 7 : 3;
+    static_assert(sizeof(sm) >= kWaves * kVecs * 1024 * sizeof(float), "scratch for the block sum");
+    v16f gl;                   // the four 16-column blocks of GL side by side
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) gl[4 * cb + v] = GL[cb][v];
-    gl = block_sum<kWaves>(scratch, gl, wave, lane);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        G1[mb][0] = block_sum<kWaves>(scratch, G1[mb][0], wave, lane);
-        if (K == 3) {
-            G2[mb][0] = block_sum<kWaves>(scratch, G2[mb][0], wave, lane);
-            G2[mb][1] = block_sum<kWaves>(scratch, G2[mb][1], wave, lane);
-        }
+    constexpr int kShare = 16 / kWaves;
+    if (K == 3) {
+        v16f* all[7] = {&G1[0][0], &G1[1][0], &G2[0][0], &G2[0][1], &G2[1][0], &G2[1][1], &gl};
+        block_sum_shared<kWaves, 7>(scratch, all, wave, lane);
+        flush_grad<2, 2>(a.dH[1], 64, 64, G2, j, h, wave * kShare, kShare);
+    } else {
+        v16f* all[3] = {&G1[0][0], &G1[1][0], &gl};
+        block_sum_shared<kWaves, 3>(scratch, all, wave, lane);
     }
-    if (wave == kWaves - 1) {
-        flush_grad<2, 1>(a.dH[0], 64, D, G1, j, h);
-        if (K == 3) flush_grad<2, 2>(a.dH[1], 64, 64, G2, j, h);
+    flush_grad<2, 1>(a.dH[0], 64, D, G1, j, h, wave * kShare, kShare);
+    // register 4 cb + v of gl: row 4 (lane / 16) + v, column 16 cb + lane % 16 of the last matrix; a wave's
+    // quarter is one block of 16 columns
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+    for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                atomicAdd(a.dH[K - 1] + (4 * (lane >> 4) + v) * 64 + 16 * cb + (lane & 15), gl[4 * cb + v]);
-    }
+        for (int v = 0; v < 4; ++v)
+            if (cb == wave) atomicAdd(a.dH[K - 1] + (4 * (lane >> 4) + v) * 64 + 16 * cb + (lane & 15), gl[4 * cb + v]);
 }
 
 template <int D, int K>

@@ -260,8 +260,8 @@ __device__ __forceinline__ void store_rows16(float* __restrict__ dst, int64_t i,
 
 // ------------------------------------------------------------------------------------------
 // The forward kernel runs 512 threads per workgroup: its 90 KB of matrices are shared by eight
-// wavefronts, two per SIMD, so that one wavefront's conversions and memory accesses overlap the
-// other's matrix instructions.
+// wavefronts, two per SIMD, so that one wavefront's waits for memory and LDS are filled by the
+// other (vector and matrix instructions of a SIMD do not run side by side, but stalls do overlap).
 constexpr int kFwdThreads = 512;
 constexpr int kFwdWaves = kFwdThreads / 64;
 
@@ -333,7 +333,6 @@ struct SdfBwdSmem {
     float tiles[kWaves][2][kTileWords];
 };
 
-// add this wave's accumulator into dst[rows][cols] (row-major, ld = cols) with atomics
 // add the registers [r0, r0 + count) of this wave's accumulator into dst[rows][cols] (row-major,
 // ld = cols) with atomics; r0 is the same for all lanes
 template <int ZB, int XB>
@@ -500,7 +499,6 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         outer_accumulate16<2, kLd64, kLd64>(GL, Zt, Xt, lane);
     }
     __syncthreads();
-    // ---- reduce over the block's waves, then one atomic add per element and block
     // ---- every wave gets a quarter of the registers of the block's sums and adds it to global
     // memory: one barrier, and the atomics of the four waves run side by side
     float* scratch = reinterpret_cast<float*>(&sm);

@@ -55,46 +55,37 @@ struct ColorWeights {
     alignas(16) unsigned char W3t[BWD ? 64 * M3t::kLd : 16];
 };
 
-// All elements a thread copies are requested from global memory first (fixed trip counts, so
-// the loads are in flight together) and written to LDS afterwards.
+// Every matrix is fetched from global memory before the first is written to LDS, so the fetches
+// are in flight together; the copies cover every slot a product reads, so nothing is cleared.
 template <bool BWD>
 __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
     typedef ColorWeights<BWD> W;
     const int tid = threadIdx.x;
-    constexpr int N1 = 64 * 40 / kThreads, N2 = 64 * 64 / kThreads;
-    float v1[N1], v2[N2], v3 = 0.f;
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
-        const int e = external_column(idx % 40);
-        v1[k] = e >= 0 ? a.W[0][(idx / 40) * 38 + e] : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) v2[k] = a.W[1][tid + k * kThreads];
-    if (tid < 3 * 64) v3 = a.W[2][tid];
-    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
-    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
-    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += kThreads) words[idx] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 40, c = idx % 40;
-        W::M1f::store(w.W1f, o, c, v1[k]);
-        if (BWD && c < 32) W::M1t::store(w.W1t, c, o, v1[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) {
-        const int idx = tid + k * kThreads;
-        const int o = idx / 64, i = idx % 64;
-        W::M2f::store(w.W2f, o, i, v2[k]);
-        if (BWD) W::M2t::store(w.W2t, i, o, v2[k]);
-    }
-    if (tid < 3 * 64) {
-        const int o = tid / 64, i = tid % 64;
-        if (BWD) W::M3t::store(w.W3t, i, o, v3);
-        else W::M3f::store(w.W3f, o, i, v3);
-    }
+    const float* __restrict__ W1 = a.W[0];
+    const float* __restrict__ W2 = a.W[1];
+    const float* __restrict__ W3 = a.W[2];
+    auto first = [&](int o, int c) {
+        const int e = c < 40 ? external_column(c) : -1;
+        return e >= 0 ? W1[o * 38 + e] : 0.f;
+    };
+    typename W::M1f::template Fill<64, kThreads, false> f1;
+    typename W::M2f::template Fill<64, kThreads, false> f2;
+    typename W::M3f::template Fill<BWD ? 0 : 32, kThreads, false> f3;
+    typename W::M1t::template Fill<BWD ? 32 : 0, kThreads, true> t1;
+    typename W::M2t::template Fill<BWD ? 64 : 0, kThreads, true> t2;
+    typename W::M3t::template Fill<BWD ? 64 : 0, kThreads, true> t3;
+    f1.load(tid, first);
+    f2.load(tid, [&](int o, int i) { return W2[o * 64 + i]; });
+    f3.load(tid, [&](int o, int i) { return o < 3 ? W3[o * 64 + i] : 0.f; });
+    t1.load(tid, [&](int c, int o) { return first(o, c); });
+    t2.load(tid, [&](int i, int o) { return W2[o * 64 + i]; });
+    t3.load(tid, [&](int i, int o) { return o < 3 ? W3[o * 64 + i] : 0.f; });
+    f1.store(w.W1f, tid);
+    f2.store(w.W2f, tid);
+    f3.store(w.W3f, tid);
+    t1.store(w.W1t, tid);
+    t2.store(w.W2t, tid);
+    t3.store(w.W3t, tid);
     __syncthreads();
 }
 

@@ -224,22 +224,65 @@ __device__ __forceinline__ void outer_accumulate_split(v16f (*G)[XB], const uint
 template <int KSTEPS, int PS>
 struct SplitMatrix {
     static constexpr int kLd = KSTEPS * 2 * PS * 16 + 16;     // bytes per output row
-    // byte offset of term 0 of (output row o, input c)
-    __device__ static __forceinline__ int offset(int o, int c) {
-        const int u = c >> 4, rem = c & 15;
-        const int g = (rem >> 2) & 1, s = ((rem >> 3) << 2) | (rem & 3);
-        return o * kLd + (2 * u + g) * (PS * 16) + 2 * s;
-    }
-    // store one weight, split into PS bf16 terms
-    __device__ static __forceinline__ void store(unsigned char* __restrict__ W, int o, int c, float v) {
-        unsigned char* dst = W + offset(o, c);
-#pragma unroll
-        for (int p = 0; p < PS; ++p) {
-            const __bf16 t = (__bf16)v;
-            *reinterpret_cast<__bf16*>(dst + 16 * p) = t;
-            v -= (float)t;
+
+    // Fills rows 0..ROWS-1 of the matrix at W, every slot of them (what lies outside the caller's
+    // matrix is written as zero, so W needs no clearing): element (r, c) is get(r, c).  A thread
+    // takes whole operand words: it fetches the eight inputs of one (row, k-step, lane half),
+    // splits them and writes each term as one 16-byte word.  load() only issues the fetches, so
+    // that a kernel can have those of all its matrices in flight before the first store() waits.
+    // ROW_FASTEST says which index runs along the lanes: the one contiguous in the source.
+    template <int ROWS, int THREADS, bool ROW_FASTEST>
+    struct Fill {
+        static constexpr int kUnits = ROWS * KSTEPS * 2;
+        static constexpr int kPer = (kUnits + THREADS - 1) / THREADS;
+        float v[kPer > 0 ? kPer : 1][8];
+
+        __device__ static __forceinline__ void decode(int unit, int& r, int& ug) {
+            constexpr int kRows = ROWS > 0 ? ROWS : 1;
+            if (ROW_FASTEST) { r = unit % kRows; ug = unit / kRows; }
+            else { ug = unit % (2 * KSTEPS); r = unit / (2 * KSTEPS); }
         }
-    }
+        template <class Get>
+        __device__ __forceinline__ void load(int tid, Get get) {
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int unit = tid + k * THREADS;
+                if (kUnits % THREADS != 0 && unit >= kUnits) break;
+                int r, ug;
+                decode(unit, r, ug);
+                const int c0 = 16 * (ug >> 1) + 4 * (ug & 1);
+#pragma unroll
+                for (int s = 0; s < 8; ++s) v[k][s] = get(r, c0 + 8 * (s >> 2) + (s & 3));
+            }
+        }
+        __device__ __forceinline__ void store(unsigned char* __restrict__ W, int tid) const {
+            typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+            typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int unit = tid + k * THREADS;
+                if (kUnits % THREADS != 0 && unit >= kUnits) break;
+                int r, ug;
+                decode(unit, r, ug);
+                unsigned char* dst = W + r * kLd + ug * (PS * 16);
+                float x[8];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) x[s] = v[k][s];
+#pragma unroll
+                for (int term = 0; term < PS; ++term) {
+                    u32x4 word;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{x[2 * p], x[2 * p + 1]}, bf2));
+                        word[p] = w;
+                        x[2 * p] -= __builtin_bit_cast(float, w << 16);
+                        x[2 * p + 1] -= __builtin_bit_cast(float, w & 0xffff0000u);
+                    }
+                    *reinterpret_cast<u32x4*>(dst + 16 * term) = word;
+                }
+            }
+        }
+    };
 };
 
 // z[mb] = sum_c W[32 mb + .][c] x[c] for MB blocks of outputs and KSTEPS * 16 inputs; W is a

@@ -55,48 +55,35 @@ struct SdfWeights {
     alignas(16) float HLrow0[64];                  // row 0 of the last matrix (the SDF output), fp32
 };
 
-// All elements a thread copies are requested from global memory first (fixed trip counts, so
-// the loads are independent and in flight together) and written to LDS afterwards: a loop of
-// load-then-store waits for one memory round trip per iteration, some 30 of them per kernel.
+// Every matrix is fetched from global memory before the first is written to LDS, so the fetches
+// are in flight together; the copies cover every slot a product reads, so nothing is cleared.
 template <int D, int K, bool BWD, int THREADS>
 __device__ void load_weights(SdfWeights<D, K, BWD>& w, const SdfArgs& a) {
     typedef SdfWeights<D, K, BWD> W;
     const int tid = threadIdx.x;
-    constexpr int N1 = 64 * D / THREADS, N2 = K == 3 ? 64 * 64 / THREADS : 0, NL = 16 * 64 / THREADS;
-    static_assert(64 * D % THREADS == 0 && 16 * 64 % THREADS == 0, "whole passes over the matrices");
-    float v1[N1], v2[N2 > 0 ? N2 : 1], vl[NL];
-#pragma unroll
-    for (int k = 0; k < N1; ++k) v1[k] = a.H[0][tid + k * THREADS];
-#pragma unroll
-    for (int k = 0; k < N2; ++k) v2[k] = a.H[1][tid + k * THREADS];
-#pragma unroll
-    for (int k = 0; k < NL; ++k) vl[k] = a.H[K - 1][tid + k * THREADS];
-    static_assert(sizeof(W) % 4 == 0, "cleared word by word");
-    uint32_t* words = reinterpret_cast<uint32_t*>(&w);
-    for (int idx = tid; idx < (int)(sizeof(W) / 4); idx += THREADS) words[idx] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < N1; ++k) {
-        const int idx = tid + k * THREADS;
-        const int o = idx / D, i = idx % D;
-        W::M1f::store(w.H1f, o, i, v1[k]);
-        W::M1t::store(w.H1t, i, o, v1[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < N2; ++k) {
-        const int idx = tid + k * THREADS;
-        const int o = idx / 64, i = idx % 64;
-        W::M2f::store(w.H2f, o, i, v2[k]);
-        W::M2t::store(w.H2t, i, o, v2[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < NL; ++k) {
-        const int idx = tid + k * THREADS;
-        const int o = idx / 64, i = idx % 64;
-        if (BWD) W::MLt::store(w.HLt, i, o, vl[k]);
-        else W::MLf::store(w.HLf, o, i, vl[k]);
-        if (o == 0) w.HLrow0[i] = vl[k];
-    }
+    const float* __restrict__ H1 = a.H[0];
+    const float* __restrict__ H2 = a.H[1];
+    const float* __restrict__ HL = a.H[K - 1];
+    typename W::M1f::template Fill<64, THREADS, false> f1;
+    typename W::M1t::template Fill<32, THREADS, true> t1;
+    typename W::M2f::template Fill<K == 3 ? 64 : 0, THREADS, false> f2;
+    typename W::M2t::template Fill<K == 3 ? 64 : 0, THREADS, true> t2;
+    typename W::MLf::template Fill<BWD ? 0 : 32, THREADS, false> fl;
+    typename W::MLt::template Fill<BWD ? 64 : 0, THREADS, true> tl;
+    f1.load(tid, [&](int o, int i) { return H1[o * D + i]; });
+    t1.load(tid, [&](int i, int o) { return i < D ? H1[o * D + i] : 0.f; });
+    f2.load(tid, [&](int o, int i) { return H2[o * 64 + i]; });
+    t2.load(tid, [&](int i, int o) { return H2[o * 64 + i]; });
+    fl.load(tid, [&](int o, int i) { return o < 16 ? HL[o * 64 + i] : 0.f; });
+    tl.load(tid, [&](int i, int o) { return HL[o * 64 + i]; });
+    const float row0 = tid < 64 ? HL[tid] : 0.f;
+    f1.store(w.H1f, tid);
+    t1.store(w.H1t, tid);
+    f2.store(w.H2f, tid);
+    t2.store(w.H2t, tid);
+    fl.store(w.HLf, tid);
+    tl.store(w.HLt, tid);
+    if (tid < 64) w.HLrow0[tid] = row0;
     __syncthreads();
 }
 

@@ -38,10 +38,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix rate: the network kern
 # workload has been measured; other workloads report null.
 MEASURED_TRAFFIC_MIB = {
     "cfg2-static-4096x64": {
-        "hash_encode": (71.3, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
-        "render_loss_bwd": (22.1, 8.1), "color_bwd": (33.1, 28.2), "sdf_mlp_bwd": (147.9, 39.0),
-        "hash_scatter_bwd": (84.0 + 354.5, 232.5 + 63.2),      # bin_rows_kernel + scatter_owner_kernel
-        "adam_all": (186.1, 209.4),
+        "hash_encode": (85.7, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
+        "render_loss_bwd": (22.2, 8.1), "color_bwd": (33.1, 28.4), "sdf_mlp_bwd": (148.1, 39.2),
+        "hash_scatter_bwd": (83.9 + 353.3, 232.7 + 63.2),      # bin_rows_kernel + scatter_owner_kernel
+        "adam_all": (186.4, 209.6),
     },
 }
 

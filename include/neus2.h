@@ -22,7 +22,9 @@
  * Layouts
  *  - tables  [L][T][F]   F = 2 features per entry, fp16 or fp32 (cfg->table_dtype).
  *  - enc, q, d_enc: level-major [L][n][F] fp32 ("feature k = level*F + f of point i" is at
- *    (level*n + i)*F + f).  jac: [L][n][F][3] fp32.
+ *    (level*n + i)*F + f).  jac (de/dx, fp32): [L][3][n][2]; the six values J[f][a] of a point
+ *    and level, in the order 3*f + a, are cut into three pairs, and pair c of point i is at
+ *    ((level*3 + c)*n + i)*2 (a wavefront then reads and writes whole cache lines).
  *  - y, d_y [n][16]; normal, d_normal, pos, d_pos [n][3]; rgb, d_rgb [n][3].
  *  - SDF matrices H_l [n_l][n_{l-1}] and colour matrices W_l likewise, row-major fp32,
  *    bias-free (Definition 1 of the paper).

@@ -43,9 +43,9 @@ def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
             n = 1 << lg
             e = torch.randn(n, 32, generator=g).to(dev)
             J = (torch.randn(n, 32, 3, generator=g) * 0.3).to(dev)
-            # library layout: level-major [L][n][F] and [L][n][F][3]
+            # library layout: level-major [L][n][F]; the Jacobian as three planes of pairs per level
             enc = e.view(n, 16, 2).permute(1, 0, 2).contiguous()
-            jac = J.view(n, 16, 2, 3).permute(1, 0, 2, 3).contiguous()
+            jac = J.view(n, 16, 3, 2).permute(1, 2, 0, 3).contiguous()      # the library's [L][3 pairs][n][2]
             y = torch.empty(n, 16, device=dev); q = torch.empty(16, n, 2, device=dev); normal = torch.empty(n, 3, device=dev)
             loss = torch.zeros(4, device=dev); d_y = torch.empty(n, 16, device=dev); d_normal = torch.empty(n, 3, device=dev)
             d_enc = torch.empty(16, n, 2, device=dev)

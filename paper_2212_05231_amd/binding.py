@@ -310,7 +310,7 @@ class Step:
         self.dirs = torch.zeros(max(self.rays, 1), 3, **f32)
         self.target = torch.zeros(max(self.rays, 1), 3, **f32)
         z = lambda *shape: torch.zeros(*shape, **f32)
-        self.enc, self.jac, self.q, self.d_enc = z(L, n, F), z(L, n, F, 3), z(L, n, F), z(L, n, F)
+        self.enc, self.jac, self.q, self.d_enc = z(L, n, F), z(L, 3, n, F), z(L, n, F), z(L, n, F)
         self.y, self.d_y = z(n, 16), z(n, 16)
         self.normal, self.d_normal = z(n, 3), z(n, 3)
         self.rgb, self.d_rgb = z(n, 3), z(n, 3)

@@ -238,10 +238,11 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedul
     }
     const int64_t o = (int64_t)level * n + i;
     reinterpret_cast<float2*>(enc)[o] = make_float2(e0, e1);
-    float2* jo = reinterpret_cast<float2*>(jac) + o * 3;
+    // three planes per level, each written as consecutive 8-byte words by consecutive lanes
+    float2* jo = reinterpret_cast<float2*>(jac) + (int64_t)level * 3 * n + i;
     jo[0] = make_float2(j0[0], j0[1]);
-    jo[1] = make_float2(j0[2], j1[0]);
-    jo[2] = make_float2(j1[1], j1[2]);
+    jo[n] = make_float2(j0[2], j1[0]);
+    jo[2 * n] = make_float2(j1[1], j1[2]);
 }
 
 // Backward.  d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a d_a w_c

@@ -120,7 +120,8 @@ __device__ __forceinline__ void store_levels(float* __restrict__ dst, int64_t n,
         }
 }
 
-// out_a = sum over this lane's features of x_k * J[k][a]   (J = de/dx, [L][n][2][3])
+// out_a = sum over this lane's features of x_k * J[k][a]   (J = de/dx; per level three planes [n] of
+// pairs: (J00,J01), (J02,J10), (J11,J12))
 template <int D>
 __device__ __forceinline__ void contract_jac(const float* __restrict__ jac, int64_t n, int64_t i, bool valid,
                                              int active, int h, const v16f& x, float out[3]) {
@@ -131,8 +132,8 @@ __device__ __forceinline__ void contract_jac(const float* __restrict__ jac, int6
         for (int u = 0; u < 2; ++u) {
             const int level = 4 * g + 2 * h + u;
             if (valid && level < active) {
-                const float2* J = reinterpret_cast<const float2*>(jac) + ((int64_t)level * n + i) * 3;
-                const float2 a = J[0], b = J[1], c = J[2];     // (J00,J01) (J02,J10) (J11,J12)
+                const float2* J = reinterpret_cast<const float2*>(jac) + (int64_t)level * 3 * n + i;
+                const float2 a = J[0], b = J[n], c = J[2 * n];     // (J00,J01) (J02,J10) (J11,J12)
                 const float x0 = x[4 * g + 2 * u], x1 = x[4 * g + 2 * u + 1];
                 out[0] += x0 * a.x + x1 * b.y;
                 out[1] += x0 * a.y + x1 * c.x;
@@ -152,8 +153,8 @@ __device__ __forceinline__ v16f apply_jac(const float* __restrict__ jac, int64_t
         for (int u = 0; u < 2; ++u) {
             const int level = 4 * g + 2 * h + u;
             if (valid && level < active) {
-                const float2* J = reinterpret_cast<const float2*>(jac) + ((int64_t)level * n + i) * 3;
-                const float2 a = J[0], b = J[1], c = J[2];
+                const float2* J = reinterpret_cast<const float2*>(jac) + (int64_t)level * 3 * n + i;
+                const float2 a = J[0], b = J[n], c = J[2 * n];
                 t[4 * g + 2 * u] = a.x * v[0] + a.y * v[1] + b.x * v[2];
                 t[4 * g + 2 * u + 1] = b.y * v[0] + c.x * v[1] + c.y * v[2];
             }
@@ -178,9 +179,9 @@ __device__ __forceinline__ JacRegs<D> load_jac(const float* __restrict__ jac, in
         for (int u = 0; u < 2; ++u) {
             const int level = 4 * g + 2 * h + u;
             const bool on = valid && level < active;
-            const float2* p = reinterpret_cast<const float2*>(jac) + ((int64_t)(on ? level : 0) * n + (on ? i : 0)) * 3;
+            const float2* p = reinterpret_cast<const float2*>(jac) + (int64_t)(on ? level : 0) * 3 * n + (on ? i : 0);
 #pragma unroll
-            for (int c = 0; c < 3; ++c) J.v[2 * g + u][c] = on ? p[c] : make_float2(0.f, 0.f);
+            for (int c = 0; c < 3; ++c) J.v[2 * g + u][c] = on ? p[c * n] : make_float2(0.f, 0.f);
         }
     return J;
 }

@@ -44,8 +44,15 @@ def from_level_major(t, n):
 
 
 def jac_from_level_major(t, n):
-    a = t.detach().cpu().numpy().astype(np.float64)        # [L][n][F][3]
-    return np.transpose(a, (1, 0, 2, 3)).reshape(n, -1, 3)
+    """library layout [L][3 pairs][n][2] -> [n, L*F, 3]"""
+    a = t.detach().cpu().numpy().astype(np.float64).reshape(-1, 3, n, 2)
+    return np.transpose(a, (2, 0, 1, 3)).reshape(n, -1, 3)      # [n][L][pair][2] = [n][L][F*3] -> [n, L*F, 3]
+
+
+def jac_to_level_major(J, n, L):
+    """[n, L*F, 3] -> torch, library layout [L][3 pairs][n][2]"""
+    a = np.asarray(J, dtype=np.float64).reshape(n, L, 3, 2)
+    return cuda(np.ascontiguousarray(np.transpose(a, (1, 2, 0, 3))))
 
 
 def to_level_major(a, L):
@@ -124,7 +131,7 @@ def test_hash_encode_indices_bit_exact_and_values(k, n_rays):
     L = cfg.n_levels
     tables = cuda(params["tables"], torch.float16 if cfg.table_dtype == "f16" else torch.float32)
     enc = torch.empty(L, n, 2, device="cuda")
-    jac = torch.empty(L, n, 2, 3, device="cuda")
+    jac = torch.empty(L, 3, n, 2, device="cuda")
     idx = torch.zeros(n, L, 8, dtype=torch.int32, device="cuda")
     nb.hash_encode(c, cuda(pos), tables, enc, jac, idx)
     torch.cuda.synchronize()
@@ -143,7 +150,7 @@ def test_fp16_subnormal_table_entries_are_not_flushed():
     tab = np.full((cfg.n_levels, cfg.table_size, 2), 3e-6, dtype=np.float16)      # subnormal in fp16
     pos = wl.make_points(257, 5)
     enc = torch.empty(cfg.n_levels, 257, 2, device="cuda")
-    jac = torch.empty(cfg.n_levels, 257, 2, 3, device="cuda")
+    jac = torch.empty(cfg.n_levels, 3, 257, 2, device="cuda")
     nb.hash_encode(c, cuda(pos), cuda(tab, torch.float16), enc, jac)
     np.testing.assert_allclose(enc.cpu().numpy(), float(np.float16(3e-6)), rtol=1e-6)
 
@@ -170,7 +177,7 @@ def test_sdf_fwd_grad_alone_with_large_values():
         y = torch.empty(n, 16, device="cuda")
         q = torch.empty(L, n, 2, device="cuda")
         nrm = torch.empty(n, 3, device="cuda")
-        jac_lm = cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+        jac_lm = jac_to_level_major(J, n, L)
         nb.sdf_fwd_grad(c, to_level_major(e, L), jac_lm, [cuda(h) for h in H], n, y, q, nrm)
         torch.cuda.synchronize()
         yr, acts, masks = o.mlp_forward(H, e)
@@ -195,7 +202,7 @@ def test_network_products_over_a_wide_range_of_magnitudes(enc_scale, w_scale):
     e = (rng.normal(size=(n, D)) * feat * enc_scale).astype(np.float32)
     J = (rng.normal(size=(n, D, 3)) * enc_scale).astype(np.float32)
     Hg = [cuda(h) for h in H]
-    enc_lm, jac_lm = to_level_major(e, L), cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+    enc_lm, jac_lm = to_level_major(e, L), jac_to_level_major(J, n, L)
     y, q, nrm = torch.empty(n, 16, device="cuda"), torch.empty(L, n, 2, device="cuda"), torch.empty(n, 3, device="cuda")
     nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm)
     yr, acts, masks = o.mlp_forward(H, e)
@@ -242,7 +249,7 @@ def test_sdf_network_every_kernel_shape(D, K):
     e = rng.normal(size=(n, D)).astype(np.float32)
     J = rng.normal(size=(n, D, 3)).astype(np.float32)
     Hg = [cuda(h) for h in H]
-    enc_lm, jac_lm = to_level_major(e, L), cuda(np.transpose(J.reshape(n, L, 2, 3), (1, 0, 2, 3)))
+    enc_lm, jac_lm = to_level_major(e, L), jac_to_level_major(J, n, L)
     y, q, nrm = torch.empty(n, 16, device="cuda"), torch.empty(L, n, 2, device="cuda"), torch.empty(n, 3, device="cuda")
     nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm)
     yr, acts, masks = o.mlp_forward(H, e)

@@ -430,7 +430,9 @@ __global__ __launch_bounds__(kBlock) void sum_levels_kernel(const float* __restr
 // accumulated in LDS instead: a level's T slots are cut into ranges of 8192 slots (128 KiB
 // of fp64 pairs, one workgroup's LDS); the workgroup that owns a range adds everything that
 // falls into it with LDS atomics and finally adds its LDS image to the global gradient with
-// plain coalesced loads and stores (nobody else writes that range).  The accumulators are
+// coalesced atomics, one per non-zero accumulator (64 consecutive floats per instruction: a few
+// line requests, not one per lane; reading the old values and storing the sums instead held 16
+// registers per thread for the length of a task and cost 10 us per step more).  The accumulators are
 // DOUBLES on purpose: measured on this chip, ds_add_f64 retires a lane in 0.37 clocks and
 // ds_add_f32 in 3.2 (the LDS does float atomics one lane at a time), so fp64 is both the
 // faster and the more accurate choice.
@@ -668,14 +670,7 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
 
         if (e < plan.n_listed) {
-            // A listed task owns its range alone and adds to the gradient with plain loads and
-            // stores.  The loads are requested here and arrive while the records are streamed.
-            float old[kPerThread];
-#pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const uint32_t k = threadIdx.x + u * kOwnerThreads;
-                old[u] = k < 2 * slots_here ? dst[k] : 0.f;
-            }
+            // A listed task streams the list of its range.
             const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity[e]);
             const size_t at = (size_t)plan.list_base[e] + (size_t)range * plan.capacity[e];
             const uint32_t* rs = rec.slots + at;
@@ -701,14 +696,6 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                         atomicAdd(a1 + (odd ^ 1), (double)(odd ? v[k].z : v[k].w));
                     }
                 }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const uint32_t k = threadIdx.x + u * kOwnerThreads;
-                const float v = (float)acc[k];
-                acc[k] = 0.0;
-                if (k < 2 * slots_here && v != 0.f) dst[k] = old[u] + v;
             }
         } else {
             // In-place path.  A task tests its chunk of the points against its range and adds the
@@ -782,15 +769,16 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                 __syncthreads();
                 if (next >= end) break;
             }
-            // several chunks of the points share the range: coalesced atomics
-            __syncthreads();
+        }
+        // flush: the LDS image is added to the gradient (several chunks of the points may share a
+        // range of a dense level) and cleared for the next task
+        __syncthreads();
 #pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const uint32_t k = threadIdx.x + u * kOwnerThreads;
-                const float v = (float)acc[k];
-                acc[k] = 0.0;
-                if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
-            }
+        for (int u = 0; u < kPerThread; ++u) {
+            const uint32_t k = threadIdx.x + u * kOwnerThreads;
+            const float v = (float)acc[k];
+            acc[k] = 0.0;
+            if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
         }
         if (threadIdx.x == 0) sm.task[turn ^ 1] = next_task;
         __syncthreads();

@@ -822,10 +822,12 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
                 // Every task tests n / chunks points (0.9 ns each; the corner code runs for a whole
                 // wavefront as soon as one lane is in the range) and adds those in its range
                 // (about 1.5 ranges per point on a dense level, 7 ns each).  Times measured on
-                // this kernel; tasks of about 30 us.
+                // this kernel.  Tasks of 70 us by this estimate, at least eight chunks: every task
+                // ends with a flush of its LDS image, so shorter tasks cost more than they balance
+                // (a sweep of 15..300 us and 2..16 chunks on the benchmark workload).
                 const double hit = ranges > 1 ? 1.5 / ranges : 1.0;
                 const double level_ns = (double)n * ranges * (0.9 + 7.0 * (hit < 1.0 ? hit : 1.0));
-                chunks = (int)(level_ns / ranges / 30000.0) + 1;
+                chunks = (int)(level_ns / ranges / 70000.0) + 1;
                 if (chunks < 8) chunks = 8;
                 if (chunks > 128) chunks = 128;
                 task_ns = 4000.0 + level_ns / ranges / chunks;

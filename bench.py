@@ -38,9 +38,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix rate: the network kern
 # workload has been measured; other workloads report null.
 MEASURED_TRAFFIC_MIB = {
     "cfg2-static-4096x64": {
-        "hash_encode": (85.7, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
-        "render_loss_bwd": (22.2, 8.1), "color_bwd": (33.1, 28.4), "sdf_mlp_bwd": (148.1, 39.2),
-        "hash_scatter_bwd": (83.9 + 353.3, 232.7 + 63.2),      # bin_rows_kernel + scatter_owner_kernel
+        "hash_encode": (86.1, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
+        "render_loss_bwd": (22.2, 8.1), "color_bwd": (33.1, 28.4), "sdf_mlp_bwd": (151.1, 46.8),
+        "hash_scatter_bwd": (84.1 + 308.0, 232.5 + 56.4),      # bin_rows_kernel + scatter_owner_kernel
         "adam_all": (186.4, 209.6),
     },
 }

@@ -618,7 +618,10 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
     }
 }
 
-constexpr int kQueue = 5 * kOwnerThreads;     // fewer than kOwnerThreads queued before a round adds at most 4 kOwnerThreads
+// In-place path: a filter round tests kFilter points per thread; rounds are added while fewer than
+// kOwnerThreads points are queued, so the queue never holds (kFilter + 1) kOwnerThreads or more.
+constexpr int kFilter = 4;
+constexpr int kQueue = (kFilter + 1) * kOwnerThreads;
 
 struct OwnerSmem {
     double acc[2 * kOwnerSlots];
@@ -704,7 +707,6 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             // hit are queued in LDS, and the queue is worked off with every lane busy.
             const float fres = (float)g.res[level];
             const bool filter = n_ranges > 1;              // only dense levels have several ranges here
-            constexpr int kFilter = 4;                     // points per thread and filter round
             int64_t next = begin;
             for (;;) {
                 for (;;) {                                 // fill until every thread has work, or the chunk ends

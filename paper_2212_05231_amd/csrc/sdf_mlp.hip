@@ -52,7 +52,9 @@ struct SdfWeights {
     alignas(16) unsigned char H2t[K == 3 ? 64 * M2t::kLd : 16];
     alignas(16) unsigned char HLf[BWD ? 16 : 32 * MLf::kLd];
     alignas(16) unsigned char HLt[BWD ? 64 * MLt::kLd : 16];
-    alignas(16) float HLrow0[64];                  // row 0 of the last matrix (the SDF output), fp32
+    // Row 0 of the last matrix (the SDF output), already split and packed as a lane holds it
+    // (Split<2, 3>): [lane half][term][word 8 b + p]
+    alignas(16) uint32_t HLrow0[2][3][16];
 };
 
 // Every matrix is fetched from global memory before the first is written to LDS, so the fetches
@@ -76,14 +78,32 @@ __device__ void load_weights(SdfWeights<D, K, BWD>& w, const SdfArgs& a) {
     t2.load(tid, [&](int i, int o) { return H2[o * 64 + i]; });
     fl.load(tid, [&](int o, int i) { return o < 16 ? HL[o * 64 + i] : 0.f; });
     tl.load(tid, [&](int i, int o) { return HL[o * 64 + i]; });
-    const float row0 = tid < 64 ? HL[tid] : 0.f;
+    // thread 16 h + 8 b + p < 32 splits the pair of row-0 elements that word p of block b of lane
+    // half h holds: registers 2p and 2p + 1
+    float row0[2] = {0.f, 0.f};
+    if (tid < 32) {
+        const int hh = tid >> 4, b = (tid >> 3) & 1, p = tid & 7;
+        row0[0] = HL[32 * b + neuron_of(2 * p, hh)];
+        row0[1] = HL[32 * b + neuron_of(2 * p + 1, hh)];
+    }
     f1.store(w.H1f, tid);
     t1.store(w.H1t, tid);
     f2.store(w.H2f, tid);
     t2.store(w.H2t, tid);
     fl.store(w.HLf, tid);
     tl.store(w.HLt, tid);
-    if (tid < 64) w.HLrow0[tid] = row0;
+    if (tid < 32) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        float x0 = row0[0], x1 = row0[1];
+#pragma unroll
+        for (int term = 0; term < 3; ++term) {
+            const uint32_t word = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{x0, x1}, bf2));
+            w.HLrow0[tid >> 4][term][tid & 15] = word;
+            x0 -= __builtin_bit_cast(float, word << 16);
+            x1 -= __builtin_bit_cast(float, word & 0xffff0000u);
+        }
+    }
     __syncthreads();
 }
 
@@ -215,16 +235,29 @@ __device__ __forceinline__ v16f apply_jac_regs(const JacRegs<D>& J, const float 
     return t;
 }
 
-// row 0 of the last matrix in register layout, masked: S_{K-1} of Definition 1 for output 0
-__device__ __forceinline__ void last_row_masked(const float* __restrict__ row0, uint32_t m, int h, v16f* s) {
+// Row 0 of the last matrix, masked (S_{K-1} of Definition 1 for output 0), as a split vector: the
+// terms were split when the matrix was copied to LDS, and masking a packed pair is an AND with a
+// word that has ones in the halves whose mask bit is set (bit 16 b + r for register r of block b;
+// word p holds registers 2p and 2p + 1).  The same values as splitting the masked row.
+template <int P>
+__device__ __forceinline__ void last_row_masked(const uint32_t (*row0)[3][16], uint32_t m, int h, Split<2, P>& out) {
+    uint32_t keep[16];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int k = 0; k < 16; ++k) {
+        const int bit = 16 * (k >> 3) + 2 * (k & 7);
+        uint32_t lo, hi;
+        asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(lo) : "v"(m), "n"(bit));
+        asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(hi) : "v"(m), "n"(bit + 1));
+        keep[k] = (lo & 0xffffu) | (hi & 0xffff0000u);
+    }
+#pragma unroll
+    for (int term = 0; term < P; ++term)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const float4 v = *reinterpret_cast<const float4*>(&row0[32 * b + 8 * g + 4 * h]);
-            s[b][4 * g + 0] = v.x; s[b][4 * g + 1] = v.y; s[b][4 * g + 2] = v.z; s[b][4 * g + 3] = v.w;
+            const u32x4 words = *reinterpret_cast<const u32x4*>(&row0[h][term][4 * g]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out.t[term][g >> 1][4 * (g & 1) + e] = words[e] & keep[4 * g + e];
         }
-    apply_mask<2>(s, m);
 }
 
 // 16-wide per-point rows ([n][16]) <-> register vector: registers 0..7 of lane half h hold
@@ -293,9 +326,8 @@ __global__ __launch_bounds__(kFwdThreads) void sdf_fwd_kernel(SdfArgs a) {
         matvec_split<1, 4, 3, 3>(w.HLf, pv, yv, lane);
         store_rows16(a.y, i, valid, h, yv[0]);
         // reverse sweep for dd/de
-        v16f s[2], s1[2];
-        last_row_masked(w.HLrow0, m_last, h, s);
-        split(s, pv);
+        v16f s1[2];
+        last_row_masked(w.HLrow0, m_last, h, pv);
         if (K == 3) {
             matvec_split<2, 4, 3, 3>(w.H2t, pv, s1, lane);
             apply_mask<2>(s1, m1);
@@ -439,11 +471,10 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             }
         }
         // ---- second order: S sweep (reverse) and t sweep (forward mode), Theorem 1
-        v16f s2[2], s1[2];
+        v16f s1[2];
         Split<2, 2> ps2;
         Split<1, 2> pt;
-        last_row_masked(w.HLrow0, m_last, h, s2);
-        split(s2, ps2);
+        last_row_masked(w.HLrow0, m_last, h, ps2);
         if (K == 3) {
             matvec_split<2, 4, 2, 2>(w.H2t, ps2, s1, lane);
             apply_mask<2>(s1, m1);

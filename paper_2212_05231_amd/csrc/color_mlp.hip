@@ -43,13 +43,14 @@ template <bool BWD>
 struct ColorWeights {
     typedef SplitMatrix<3, 3> M1f;     // [64][40 -> 48]
     typedef SplitMatrix<4, 3> M2f;     // [64][64]
-    typedef SplitMatrix<4, 3> M3f;     // [3 -> 32][64]
     typedef SplitMatrix<4, 2> M1t;     // [first 32 input columns][64]
     typedef SplitMatrix<4, 2> M2t;
     typedef SplitMatrix<1, 2> M3t;     // [64][3 -> 16]
     alignas(16) unsigned char W1f[64 * M1f::kLd];
     alignas(16) unsigned char W2f[64 * M2f::kLd];
-    alignas(16) unsigned char W3f[BWD ? 16 : 32 * M3f::kLd];     // the backward pass reads rgb instead
+    // The last matrix [3][64] in fp32, as a lane holds its point's activations: W3r[h][o][16 b + r] is
+    // column 32 b + neuron_of(r, h) of row o (forward kernel only; the backward pass reads rgb).
+    alignas(16) float W3r[BWD ? 1 : 2][3][32];
     alignas(16) unsigned char W1t[BWD ? 32 * M1t::kLd : 16];
     alignas(16) unsigned char W2t[BWD ? 64 * M2t::kLd : 16];
     alignas(16) unsigned char W3t[BWD ? 64 * M3t::kLd : 16];
@@ -70,19 +71,20 @@ __device__ void load_weights(ColorWeights<BWD>& w, const ColorArgs& a) {
     };
     typename W::M1f::template Fill<64, kThreads, false> f1;
     typename W::M2f::template Fill<64, kThreads, false> f2;
-    typename W::M3f::template Fill<BWD ? 0 : 32, kThreads, false> f3;
     typename W::M1t::template Fill<BWD ? 32 : 0, kThreads, true> t1;
     typename W::M2t::template Fill<BWD ? 64 : 0, kThreads, true> t2;
     typename W::M3t::template Fill<BWD ? 64 : 0, kThreads, true> t3;
     f1.load(tid, first);
     f2.load(tid, [&](int o, int i) { return W2[o * 64 + i]; });
-    f3.load(tid, [&](int o, int i) { return o < 3 ? W3[o * 64 + i] : 0.f; });
+    float last = 0.f;
+    const int lh = tid / 96, lo = (tid / 32) % 3, lk = tid % 32;          // tid < 192: one element of W3r
+    if (!BWD && tid < 192) last = W3[lo * 64 + 32 * (lk >> 4) + neuron_of(lk & 15, lh)];
     t1.load(tid, [&](int c, int o) { return first(o, c); });
     t2.load(tid, [&](int i, int o) { return W2[o * 64 + i]; });
     t3.load(tid, [&](int i, int o) { return o < 3 ? W3[o * 64 + i] : 0.f; });
     f1.store(w.W1f, tid);
     f2.store(w.W2f, tid);
-    f3.store(w.W3f, tid);
+    if (!BWD && tid < 192) w.W3r[lh][lo][lk] = last;
     t1.store(w.W1t, tid);
     t2.store(w.W2t, tid);
     t3.store(w.W3t, tid);
@@ -192,21 +194,34 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
     for (; tile < tiles; tile += stride) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
-        v16f cin[2], a2[2], u[1];
+        v16f cin[2], a2[2];
         uint32_t m1, m2;
-        Split<2, 3> pc, p1, p2;
+        Split<2, 3> pc, p1;
         build_input(next, valid, h, cin);
         {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<false>(a, in, tile + stride < tiles && in < a.n, h);
         }
         forward_tile<false>(w, cin, pc, p1, a2, m1, m2, lane);
-        split(a2, p2);
-        matvec_split<1, 4, 3, 3>(w.W3f, p2, u, lane);
+        // Last layer, three outputs: fp32 dot products of this lane's 32 activations with its part
+        // of each row, and one cross-lane add for the other half of the point.  As a matrix product
+        // it would take the split of a2 and 24 matrix instructions for 3 rows of 32.
+        float u[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+        for (int o = 0; o < 3; ++o)
+#pragma unroll
+            for (int q4 = 0; q4 < 8; ++q4) {
+                const float4 wv = *reinterpret_cast<const float4*>(&w.W3r[h][o][4 * q4]);
+                const v16f& act = a2[q4 >> 2];
+                const int r = 4 * (q4 & 3);
+                u[o] += wv.x * act[r] + wv.y * act[r + 1] + wv.z * act[r + 2] + wv.w * act[r + 3];
+            }
+#pragma unroll
+        for (int o = 0; o < 3; ++o) u[o] += __shfl_xor(u[o], 32);
         if (valid && h == 0) {
-            a.rgb[3 * i + 0] = sigmoid(u[0][0]);
-            a.rgb[3 * i + 1] = sigmoid(u[0][1]);
-            a.rgb[3 * i + 2] = sigmoid(u[0][2]);
+            a.rgb[3 * i + 0] = sigmoid(u[0]);
+            a.rgb[3 * i + 1] = sigmoid(u[1]);
+            a.rgb[3 * i + 2] = sigmoid(u[2]);
         }
     }
 }

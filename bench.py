@@ -100,7 +100,7 @@ def algorithmic_cost(cfg, n):
     issued = {
         "sdf_fwd_grad": 6 * (2 * ks1 + 8 * k3 + 4 + 8 * k3 + 4),
         "sdf_mlp_bwd": 6 * (2 * ks1 + 8 * k3) + 3 * (2 + 8 * k3 + 4 + 8 * k3 + 2 * ks1 + 8 * k3) + 3 * 2 * (4 * k3 + 2) * 2,
-        "color_fwd": 6 * (6 + 8 + 4), "color_bwd": 6 * (6 + 8) + 3 * (2 + 8 + 4) + 3 * 2 * (4 + 4),
+        "color_fwd": 6 * (6 + 8), "color_bwd": 6 * (6 + 8) + 3 * (2 + 8 + 4) + 3 * 2 * (4 + 4),
     }
     out = {k: {"bytes": v["bytes"] * n, "flops": v["flops"] * n} for k, v in cost.items()}
     for k, mf in issued.items():

@@ -71,8 +71,8 @@ def algorithmic_cost(cfg, n):
     sweep_w = sum(sd[i] * sd[i + 1] for i in range(K - 1))       # weights the reverse/forward sweeps use
     cost = {
         "hash_encode": {"bytes": 12 + lam * 8 * F * et + D * 4 + D * 12, "flops": 0},
-        "sdf_fwd_grad": {"bytes": D * 4 + D * 12 + 64 + D * 4 + 12, "flops": 2 * sdf_w + 2 * sweep_w + 2 * D * 3},
-        "sdf_mlp_bwd": {"bytes": D * 4 + D * 12 + 64 + 12 + D * 4,
+        "sdf_fwd_grad": {"bytes": D * 4 + D * 12 + 64 + D * 4 + 12 + 8 * (K - 1), "flops": 2 * sdf_w + 2 * sweep_w + 2 * D * 3},
+        "sdf_mlp_bwd": {"bytes": D * 4 + D * 12 + 64 + 12 + D * 4 + 8 * (K - 1),
                         # first order: data + weight gradients; second order: t_0 = J nbar, the t sweep and the
                         # outer products S_l^T t_{l-1}^T (S_K is a unit row: only row 0 of the last matrix)
                         "flops": 4 * sdf_w + 2 * D * 3 + 2 * sweep_w + 2 * (sdf_w - sd[K - 1] * (sd[K] - 1))},
@@ -82,8 +82,8 @@ def algorithmic_cost(cfg, n):
         cd = cfg.color_dims
         col_w = sum(cd[i] * cd[i + 1] for i in range(3))
         cost.update({
-            "color_fwd": {"bytes": 12 + 12 + 64 + 12, "flops": 2 * col_w},
-            "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 12 + 4 + 64 + 24, "flops": 2 * col_w + 4 * col_w},
+            "color_fwd": {"bytes": 12 + 12 + 64 + 12 + 16, "flops": 2 * col_w},
+            "color_bwd": {"bytes": 12 + 12 + 64 + 12 + 12 + 4 + 64 + 24 + 16, "flops": 2 * col_w + 4 * col_w},
             "render_rays": {"bytes": 4 + 12 + 4, "flops": 0},
             "render_loss_bwd": {"bytes": 4 + 12 + 12 + 4 + 4 + 12 + 12, "flops": 0},
             "render_rays_bwd": {"bytes": 4 + 12 + 4 + 12, "flops": 0},
@@ -94,13 +94,14 @@ def algorithmic_cost(cfg, n):
     # What the network kernels ISSUE on the bf16 matrix cores: every fp32 product is taken as products of
     # bf16 terms (six for forward-type products, whose results decide ReLU masks; three for adjoint-type
     # products and weight gradients), on v_mfma_f32_32x32x16_bf16 (32768 flop for a tile of 32 points),
-    # including recomputation and the padding of narrow layers.  Instruction counts per tile follow the
+    # including recomputation (three products where the forward kernels hand over their masks, as here) and the
+    # padding of narrow layers.  Instruction counts per tile follow the
     # kernels' structure; the backward kernels add 32 narrow fp32 instructions (2048 flop each).
     ks1, k3 = sd[0] // 16, 1 if K == 3 else 0
     issued = {
         "sdf_fwd_grad": 6 * (2 * ks1 + 8 * k3 + 4 + 8 * k3 + 4),
-        "sdf_mlp_bwd": 6 * (2 * ks1 + 8 * k3) + 3 * (2 + 8 * k3 + 4 + 8 * k3 + 2 * ks1 + 8 * k3) + 3 * 2 * (4 * k3 + 2) * 2,
-        "color_fwd": 6 * (6 + 8), "color_bwd": 6 * (6 + 8) + 3 * (2 + 8 + 4) + 3 * 2 * (4 + 4),
+        "sdf_mlp_bwd": 3 * (2 * ks1 + 8 * k3) + 3 * (2 + 8 * k3 + 4 + 8 * k3 + 2 * ks1 + 8 * k3) + 3 * 2 * (4 * k3 + 2) * 2,
+        "color_fwd": 6 * (6 + 8), "color_bwd": 3 * (6 + 8) + 3 * (2 + 8 + 4) + 3 * 2 * (4 + 4),
     }
     out = {k: {"bytes": v["bytes"] * n, "flops": v["flops"] * n} for k, v in cost.items()}
     for k, mf in issued.items():
@@ -247,17 +248,18 @@ def main() -> int:
         if dynamic:
             seq += [("rigid_fwd", lambda: nb.rigid_fwd(world, rot, shift, 0.5, 0.5, s.pos))]
         seq += [("hash_encode", lambda: nb.hash_encode(c, s.pos[:n], s.tables, s.enc, s.jac)),
-               ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal))]
+               ("sdf_fwd_grad", lambda: nb.sdf_fwd_grad(c, s.enc, s.jac, s.H, n, s.y, s.q, s.normal, masks=s.sdf_masks))]
         if cfg.loss_kind != 0:
             seq += [
-                ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb, sample_ray=s.sample_ray)),
+                ("color_fwd", lambda: nb.color_fwd(c, s.pos, s.normal, s.dirs, s.y, s.W, n, s.rgb, sample_ray=s.sample_ray,
+                                                   masks=s.color_masks)),
                 ("render_loss_bwd", (lambda: nb.render_loss_bwd_ragged(c, s.y, s.rgb, s.normal, s.target, s.ray_offsets, rays, n,
                                                                        s.C, s.weights, s.loss, s.dC, s.d_sdf, s.d_rgb, s.d_normal))
                  if s.ragged else
                  (lambda: nb.render_loss_bwd(c, s.y, s.rgb, s.normal, s.target, rays, s.C, s.weights, s.loss,
                                              s.dC, s.d_sdf, s.d_rgb, s.d_normal))),
                 ("color_bwd", lambda: nb.color_bwd(c, s.pos, s.normal, s.dirs, s.y, s.W, s.rgb, s.d_rgb, s.d_sdf, n, s.dW,
-                                                   s.d_y, s.d_normal, s.d_pos, sample_ray=s.sample_ray)),
+                                                   s.d_y, s.d_normal, s.d_pos, sample_ray=s.sample_ray, masks=s.color_masks)),
             ]
         else:
             seq += [("loss", lambda: nb.loss(c, None, None, s.normal, s.y, 0, n, s.loss, None, s.d_normal, s.d_y))]
@@ -265,10 +267,11 @@ def main() -> int:
             # with the position gradient the two halves share work (the scatter's gather pass adds the
             # first-order part): timed as the one call the step makes
             seq += [("sdf_bwd_2nd", lambda: nb.sdf_bwd_2nd(c, s.pos, s.tables, s.enc, s.jac, s.H, s.q, s.d_y, s.d_normal, n,
-                                                           s.dH, s.d_tables, s.d_enc, s.d_pos, workspace=s.workspace))]
+                                                           s.dH, s.d_tables, s.d_enc, s.d_pos, workspace=s.workspace,
+                                                           masks=s.sdf_masks))]
         else:
             seq += [
-                ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc)),
+                ("sdf_mlp_bwd", lambda: nb.sdf_mlp_bwd(c, s.enc, s.jac, s.H, s.d_y, s.d_normal, n, s.dH, s.d_enc, masks=s.sdf_masks)),
                 ("hash_scatter_bwd", lambda: nb.hash_scatter_bwd(c, s.pos[:n], s.tables, s.q, s.d_enc, s.d_normal, n, s.d_tables,
                                                                  workspace=s.workspace)),
             ]

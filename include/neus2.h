@@ -106,18 +106,23 @@ int neus2_hash_encode(const neus2_config* cfg, const float* pos, const void* tab
 /* SDF network forward (Eq. 1: (d,g) = f_Theta(e)) and analytic normal (Eq. 2) via
  * dd/de = H_K^(0,_) G ... G H_1 (supplement Sec. B).
  *   H [host array of K device pointers]
- *   y [device, n*16] (d = y[.,0]);  q [device, L*n*F] = dd/de;  normal [device, n*3] = q*jac. */
+ *   y [device, n*16] (d = y[.,0]);  q [device, L*n*F] = dd/de;  normal [device, n*3] = q*jac.
+ *   masks [device, 2*n*2 uint32] or NULL: if given, receives the ReLU masks m_l = [z_l > 0] of
+ *   the hidden layers (Definition 1) for the backward call of the same inputs and matrices:
+ *   word (l*n + i)*2 + h, l = 0, 1 (hidden layer), h = 0, 1, holds in bit 16*b + r the mask of
+ *   neuron 32*b + 8*(r/4) + 4*h + r%4 of point i (with two matrices layer 1 is not written). */
 int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* jac,
                        const float* const* H, int64_t n, float* y, float* q, float* normal,
-                       void* stream);
+                       uint32_t* masks, void* stream);
 
 /* Colour network forward (Eq. 3): rgb = sigmoid(W_3 relu(W_2 relu(W_1 cin))),
  * cin = [pos(3), normal(3), SH16(dir)(16), y(16)]; dirs [device, rays*3] are unit vectors,
  * sample i uses ray sample_ray[i] (sample_ray [device, n int32], rays with their own sample
- * counts) or, with sample_ray NULL, ray i / samples_per_ray.  rgb [device, n*3]. */
+ * counts) or, with sample_ray NULL, ray i / samples_per_ray.  rgb [device, n*3].
+ * masks [device, 2*n*2 uint32] or NULL: as in neus2_sdf_fwd_grad, for neus2_color_bwd. */
 int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal,
                     const float* dirs, const int32_t* sample_ray, const float* y,
-                    const float* const* W, int64_t n, float* rgb, void* stream);
+                    const float* const* W, int64_t n, float* rgb, uint32_t* masks, void* stream);
 
 /* First-order backward of the colour network (the paper needs no second-order term for
  * Upsilon, text after Eq. 6).
@@ -127,12 +132,18 @@ int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* norm
  *   dW [host array of 3 device pointers]: gradients are ADDED into them;
  *   d_y [device, n*16] is OVERWRITTEN with the colour network's dL/d(d,g) (+ d_sdf);
  *   d_normal [device, n*3] is ADDED into (it already holds the eikonal part);
- *   d_pos [device, n*3] or NULL is OVERWRITTEN with the colour network's dL/dx. */
+ *   d_pos [device, n*3] or NULL is OVERWRITTEN with the colour network's dL/dx;
+ *   masks [device, 2*n*2 uint32] or NULL: the masks neus2_color_fwd wrote for the same inputs
+ *   and matrices.  The backward pass recomputes the hidden activations instead of reading them
+ *   back.  Given the masks it does so at the accuracy its results are compared at (gradient
+ *   tolerance, see "Arithmetic" above); without them it repeats the forward call's own
+ *   arithmetic, which reproduces the masks bit for bit, at about 8 % more time. */
 int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal,
                     const float* dirs, const int32_t* sample_ray, const float* y,
                     const float* const* W, const float* rgb,
                     const float* d_rgb, const float* d_sdf, int64_t n, float* const* dW,
-                    float* d_y, float* d_normal, float* d_pos, void* stream);
+                    float* d_y, float* d_normal, float* d_pos, const uint32_t* masks,
+                    void* stream);
 
 /* NeuS compositing (supplement Sec. E.3): alpha_i = max((Phi(d_i)-Phi(d_{i+1}))/Phi(d_i), 0),
  * alpha of the last sample is 0, T_i = prod_{j<i}(1-alpha_j), C = sum T_i alpha_i c_i.
@@ -174,18 +185,21 @@ int neus2_loss(const neus2_config* cfg, const float* C, const float* target, con
  *   second derivative of the interpolation contracted with q and dL/dn (needed only when
  *   positions are themselves functions of a learnable transform, Eq. 9).
  *   workspace [device, workspace_bytes] or NULL: scratch for the scatter-add, see
- *   neus2_workspace_bytes; contents are undefined afterwards. */
+ *   neus2_workspace_bytes; contents are undefined afterwards.
+ *   masks [device, 2*n*2 uint32] or NULL: the masks neus2_sdf_fwd_grad wrote for the same enc
+ *   and H; meaning as in neus2_color_bwd. */
 int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables,
                       const float* enc, const float* jac, const float* const* H, const float* q,
                       const float* d_y, const float* d_normal, int64_t n, float* const* dH,
                       float* d_tables, float* d_enc, float* d_pos, void* workspace,
-                      int64_t workspace_bytes, void* stream);
+                      int64_t workspace_bytes, const uint32_t* masks, void* stream);
 
 /* The two halves of neus2_sdf_bwd_2nd as calls of their own (same arguments, same meaning):
  * the fused network backward (dH, d_enc, and the (de/dx)^T dL/de part of d_pos) ... */
 int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* jac,
                       const float* const* H, const float* d_y, const float* d_normal, int64_t n,
-                      float* const* dH, float* d_enc, float* d_pos, void* stream);
+                      float* const* dH, float* d_enc, float* d_pos, const uint32_t* masks,
+                      void* stream);
 
 /* ... and the scatter-add into the table gradient (Eq. 7's term included; with d_pos, the
  * mixed second derivative of the interpolation as well). */
@@ -272,6 +286,8 @@ typedef struct neus2_step_buffers {
     const int32_t* ray_offsets;/* optional: rays with their own sample counts, see          */
     const int32_t* sample_ray; /*   neus2_render_loss_bwd_ragged and neus2_color_fwd; both or */
     int64_t n_rays;            /*   neither; n_rays is read only when they are given         */
+    uint32_t* sdf_masks;       /* optional [2*n*2 each]: the ReLU masks pass from the forward    */
+    uint32_t* color_masks;     /*   to the backward kernels, see neus2_color_bwd                 */
 } neus2_step_buffers;
 
 /* One forward + backward pass (everything above except Adam and the rigid transform), in the

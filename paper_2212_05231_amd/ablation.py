@@ -49,12 +49,13 @@ def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
             y = torch.empty(n, 16, device=dev); q = torch.empty(16, n, 2, device=dev); normal = torch.empty(n, 3, device=dev)
             loss = torch.zeros(4, device=dev); d_y = torch.empty(n, 16, device=dev); d_normal = torch.empty(n, 3, device=dev)
             d_enc = torch.empty(16, n, 2, device=dev)
+            kept = torch.zeros(2, n, 2, dtype=torch.int32, device=dev)      # ReLU masks, forward -> backward
             dH = [torch.zeros_like(h) for h in Hs]
 
             def ours():
-                nb.sdf_fwd_grad(c, enc, jac, Hs, n, y, q, normal)
+                nb.sdf_fwd_grad(c, enc, jac, Hs, n, y, q, normal, masks=kept)
                 nb.loss(c, None, None, normal, y, 0, n, loss, None, d_normal, d_y)
-                nb.sdf_mlp_bwd(c, enc, jac, Hs, d_y, d_normal, n, dH, d_enc)
+                nb.sdf_mlp_bwd(c, enc, jac, Hs, d_y, d_normal, n, dH, d_enc, masks=kept)
 
             params = [h.clone().requires_grad_(True) for h in Hs]
 

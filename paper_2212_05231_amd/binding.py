@@ -41,7 +41,7 @@ class Neus2StepBuffers(C.Structure):
         "enc", "jac", "y", "q", "normal", "rgb", "C", "weights", "loss",
         "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "dH", "dW", "d_tables", "workspace")] + [
         ("workspace_bytes", C.c_int64), ("s_dev", _P), ("d_s", _P), ("ray_offsets", _P), ("sample_ray", _P),
-        ("n_rays", C.c_int64)]
+        ("n_rays", C.c_int64), ("sdf_masks", _P), ("color_masks", _P)]
 
 
 class Neus2Error(RuntimeError):
@@ -58,9 +58,9 @@ _SIGNATURES = {
     "neus2_validate_config": (C.c_int, [C.POINTER(Neus2Config)]),
     "neus2_workspace_bytes": (C.c_int64, [C.POINTER(Neus2Config), C.c_int64]),
     "neus2_hash_encode": (C.c_int, [C.POINTER(Neus2Config), _P, _P, C.c_int64, _P, _P, _P, _P]),
-    "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
-    "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
-    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_sdf_fwd_grad": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_color_fwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P]),
+    "neus2_color_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P, _P]),
     "neus2_render_loss_bwd_ragged": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P,
                                                _P, _P, _P, _P, _P, _P]),
     "neus2_render_rays": (C.c_int, [C.POINTER(Neus2Config), _P, C.c_int64, _P, _P, C.c_int64, _P, _P, _P]),
@@ -68,8 +68,8 @@ _SIGNATURES = {
     "neus2_render_loss_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P, _P, _P, _P, _P]),
     "neus2_loss": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, C.c_int64, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P,
-                                    C.c_int64, _P]),
-    "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P]),
+                                    C.c_int64, _P, _P]),
+    "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
                                   C.c_float, C.c_int, C.c_int, _P]),
@@ -158,20 +158,20 @@ def hash_encode(c, pos, tables, enc, jac, dbg_idx=None):
                                    _ptr(dbg_idx), _stream()))
 
 
-def sdf_fwd_grad(c, enc, jac, H, n, y, q, normal):
+def sdf_fwd_grad(c, enc, jac, H, n, y, q, normal, masks=None):
     _check(lib().neus2_sdf_fwd_grad(C.byref(c), _ptr(enc), _ptr(jac), _ptr_array(H), n, _ptr(y), _ptr(q),
-                                    _ptr(normal), _stream()))
+                                    _ptr(normal), _ptr(masks), _stream()))
 
 
-def color_fwd(c, pos, normal, dirs, y, W, n, rgb, sample_ray=None):
+def color_fwd(c, pos, normal, dirs, y, W, n, rgb, sample_ray=None, masks=None):
     _check(lib().neus2_color_fwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(sample_ray), _ptr(y), _ptr_array(W), n,
-                                 _ptr(rgb), _stream()))
+                                 _ptr(rgb), _ptr(masks), _stream()))
 
 
-def color_bwd(c, pos, normal, dirs, y, W, rgb, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None, sample_ray=None):
+def color_bwd(c, pos, normal, dirs, y, W, rgb, d_rgb, d_sdf, n, dW, d_y, d_normal, d_pos=None, sample_ray=None, masks=None):
     _check(lib().neus2_color_bwd(C.byref(c), _ptr(pos), _ptr(normal), _ptr(dirs), _ptr(sample_ray), _ptr(y), _ptr_array(W),
                                  _ptr(rgb), _ptr(d_rgb), _ptr(d_sdf), n, _ptr_array(dW), _ptr(d_y), _ptr(d_normal),
-                                 _ptr(d_pos), _stream()))
+                                 _ptr(d_pos), _ptr(masks), _stream()))
 
 
 def render_rays(c, sdf, sdf_stride, rgb, rays, Cout, weights, s_dev=None):
@@ -206,16 +206,18 @@ def workspace_bytes(c, n) -> int:
     return lib().neus2_workspace_bytes(C.byref(c), n)
 
 
-def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos=None, workspace=None):
+def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos=None, workspace=None,
+                masks=None):
     _check(lib().neus2_sdf_bwd_2nd(C.byref(c), _ptr(pos), _ptr(tables), _ptr(enc), _ptr(jac), _ptr_array(H),
                                    _ptr(q), _ptr(d_y), _ptr(d_normal), n, _ptr_array(dH), _ptr(d_tables),
                                    _ptr(d_enc), _ptr(d_pos), _ptr(workspace),
-                                   workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+                                   workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                   _ptr(masks), _stream()))
 
 
-def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None):
+def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None, masks=None):
     _check(lib().neus2_sdf_mlp_bwd(C.byref(c), _ptr(enc), _ptr(jac), _ptr_array(H), _ptr(d_y), _ptr(d_normal), n,
-                                   _ptr_array(dH), _ptr(d_enc), _ptr(d_pos), _stream()))
+                                   _ptr_array(dH), _ptr(d_enc), _ptr(d_pos), _ptr(masks), _stream()))
 
 
 def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None, workspace=None):
@@ -273,9 +275,12 @@ class Step:
     `neus2_step_buffers` struct that `train_step` hands to the library."""
 
     def __init__(self, cfg, params: Dict[str, object], n: int, want_pos_grad: bool = False, device="cuda",
-                 use_workspace: bool = True, learn_s: bool = False, n_rays: Optional[int] = None):
+                 use_workspace: bool = True, learn_s: bool = False, n_rays: Optional[int] = None,
+                 keep_masks: bool = True):
         """`n_rays` given: rays have their own sample counts (set_batch then wants "ray_offsets"
-        and "sample_ray"); otherwise n / samples_per_ray rays of equal length."""
+        and "sample_ray"); otherwise n / samples_per_ray rays of equal length.  `keep_masks`: the
+        forward kernels hand their ReLU masks to the backward kernels (16 bytes per sample and
+        network) instead of the backward kernels working them out again."""
         import torch
         self.cfg, self.c, self.n = cfg, make_config(cfg), n
         L, F, T = cfg.n_levels, cfg.n_features, cfg.table_size
@@ -320,6 +325,8 @@ class Step:
         self.ray_offsets = torch.zeros(self.rays + 1, dtype=torch.int32, device=device) if self.ragged else None
         self.sample_ray = torch.zeros(max(n, 1), dtype=torch.int32, device=device) if self.ragged else None
         self.d_pos = z(n, 3) if want_pos_grad else None
+        self.sdf_masks = torch.zeros(2, max(n, 1), 2, dtype=torch.int32, device=device) if keep_masks else None
+        self.color_masks = torch.zeros(2, max(n, 1), 2, dtype=torch.int32, device=device) if keep_masks else None
         self.dH, self.dW = gviews[:nH], gviews[nH:]
         self.opt = None
         self.d_tables = z(L, T, F)
@@ -330,7 +337,7 @@ class Step:
         b = Neus2StepBuffers()
         for name in ("pos", "dirs", "target", "tables", "enc", "jac", "y", "q", "normal", "rgb", "C", "weights",
                      "loss", "dC", "d_sdf", "d_rgb", "d_y", "d_normal", "d_enc", "d_pos", "d_tables", "workspace",
-                     "s_dev", "d_s", "ray_offsets", "sample_ray"):
+                     "s_dev", "d_s", "ray_offsets", "sample_ray", "sdf_masks", "color_masks"):
             setattr(b, name, _ptr(getattr(self, name)))
         b.H, b.W = C.cast(self._H, _P), C.cast(self._W, _P)
         b.dH, b.dW = C.cast(self._dH, _P), C.cast(self._dW, _P)

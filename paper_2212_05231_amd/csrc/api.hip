@@ -160,7 +160,8 @@ namespace {
 int sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
                 const float* jac, const float* const* H, const float* q, const float* d_y,
                 const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
-                float* d_pos, void* workspace, int64_t workspace_bytes, bool header_cleared, void* stream) {
+                float* d_pos, void* workspace, int64_t workspace_bytes, bool header_cleared, const uint32_t* masks,
+                void* stream) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
     NEUS2_TRY(check_ptr(workspace, "workspace", false));
@@ -176,12 +177,13 @@ int sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, c
     NEUS2_TRY(check_ptr(d_tables, "d_tables"));
     NEUS2_TRY(check_ptr(d_enc, "d_enc"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    NEUS2_TRY(check_ptr(masks, "masks", false));
     hipStream_t st = (hipStream_t)stream;
     // With a large batch and a workspace the scatter's gather pass has the corners of every level
     // in registers and adds (de/dx)^T dL/de to d_pos on the way; otherwise the network kernel
     // does it from the stored Jacobian.
     const bool gather = d_pos && scatter_gathers_position(cfg, n, workspace, workspace_bytes);
-    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, st));
+    NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, masks, st));
     return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, gather, st,
                           header_cleared);
 }
@@ -212,7 +214,7 @@ int neus2_hash_encode(const neus2_config* cfg, const float* pos, const void* tab
 }
 
 int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
-                       int64_t n, float* y, float* q, float* normal, void* stream) {
+                       int64_t n, float* y, float* q, float* normal, uint32_t* masks, void* stream) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
     NEUS2_TRY(check_ptr(enc, "enc"));
@@ -221,12 +223,13 @@ int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* j
     NEUS2_TRY(check_ptr(y, "y"));
     NEUS2_TRY(check_ptr(q, "q"));
     NEUS2_TRY(check_ptr(normal, "normal"));
-    return launch_sdf_fwd(cfg, enc, jac, H, n, y, q, normal, (hipStream_t)stream);
+    NEUS2_TRY(check_ptr(masks, "masks", false));
+    return launch_sdf_fwd(cfg, enc, jac, H, n, y, q, normal, masks, (hipStream_t)stream);
 }
 
 int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
                       const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
-                      float* d_pos, void* stream) {
+                      float* d_pos, const uint32_t* masks, void* stream) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
     NEUS2_TRY(check_ptr(enc, "enc"));
@@ -237,7 +240,8 @@ int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* ja
     NEUS2_TRY(check_mats((const void* const*)dH, cfg->n_sdf_mats, "dH"));
     NEUS2_TRY(check_ptr(d_enc, "d_enc"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
-    return launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, (hipStream_t)stream);
+    NEUS2_TRY(check_ptr(masks, "masks", false));
+    return launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos, masks, (hipStream_t)stream);
 }
 
 int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
@@ -260,9 +264,9 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
 int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, const float* enc,
                       const float* jac, const float* const* H, const float* q, const float* d_y,
                       const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
-                      float* d_pos, void* workspace, int64_t workspace_bytes, void* stream) {
+                      float* d_pos, void* workspace, int64_t workspace_bytes, const uint32_t* masks, void* stream) {
     return sdf_bwd_2nd(cfg, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, d_enc, d_pos, workspace,
-                       workspace_bytes, false, stream);
+                       workspace_bytes, false, masks, stream);
 }
 
 }  // extern "C"
@@ -298,9 +302,9 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     NEUS2_TRY(check_ptr(b->enc, "enc"));
     NEUS2_TRY(check_ptr(b->jac, "jac"));
     NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero));
-    NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, stream));
+    NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, b->sdf_masks, stream));
     if (cfg->loss_kind != 0) {
-        NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, stream));
+        NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, b->color_masks, stream));
         if (ragged)
             NEUS2_TRY(neus2_render_loss_bwd_ragged(cfg, b->y, b->rgb, b->normal, b->target, b->ray_offsets, b->s_dev, rays, n,
                                                    b->C, b->weights, b->loss, b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s,
@@ -309,11 +313,12 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
             NEUS2_TRY(neus2_render_loss_bwd(cfg, b->y, b->rgb, b->normal, b->target, b->s_dev, rays, b->C, b->weights, b->loss,
                                             b->dC, b->d_sdf, b->d_rgb, b->d_normal, b->d_s, stream));
         NEUS2_TRY(neus2_color_bwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, b->rgb, b->d_rgb, b->d_sdf, n, b->dW, b->d_y,
-                                  b->d_normal, b->d_pos, stream));
+                                  b->d_normal, b->d_pos, b->color_masks, stream));
     } else {
         NEUS2_TRY(neus2_loss(cfg, nullptr, nullptr, b->normal, b->y, 0, n, b->loss, nullptr, b->d_normal, b->d_y, stream));
         if (b->d_pos) NEUS2_TRY(launch_zero(b->d_pos, 3 * n, st));
     }
     return sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
-                       b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, zero.count[1] > 0, stream);
+                       b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, zero.count[1] > 0, b->sdf_masks,
+                       stream);
 }

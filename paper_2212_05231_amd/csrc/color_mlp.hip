@@ -24,8 +24,13 @@ struct ColorArgs {
     const float* pos; const float* normal; const float* dirs; const int32_t* sample_ray; const float* y; const float* W[3];
     const float* d_rgb; const float* d_sdf; const float* rgb_in;
     float* rgb; float* dW[3]; float* d_y; float* d_normal; float* d_pos;
+    uint32_t* masks;           // optional [2][n][2]: written by the forward kernel, read by the backward kernel
     int64_t n; int spr;
 };
+
+// The ReLU masks of a point as the kernels keep them: one word per hidden layer and lane half h,
+// bit 16 b + r for neuron 32 b + neuron_of(r, h); word (layer * n + i) * 2 + h of the buffer.
+__device__ __forceinline__ int64_t mask_word(int layer, int64_t n, int64_t i, int h) { return ((int64_t)layer * n + i) * 2 + h; }
 
 // caller's column of W_1 for internal column c (or -1 for padding)
 __device__ __forceinline__ int external_column(int c) {
@@ -119,6 +124,7 @@ struct ColorRaw {
     float dir[3], p[3], nr[3];
     float d_rgb[3], rgb[3], d_sdf;
     float dn[2];               // backward: this lane's part of d_normal as it comes in (h = 0: n0; h = 1: n1, n2)
+    uint32_t m1, m2;           // backward with masks from the forward kernel
 };
 
 template <bool BWD>
@@ -137,6 +143,7 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
         if (BWD) { r.d_rgb[c] = a.d_rgb[3 * i + c]; r.rgb[c] = a.rgb_in[3 * i + c]; }
     }
     if (BWD && a.d_sdf) r.d_sdf = a.d_sdf[i];
+    if (BWD && a.masks) { r.m1 = a.masks[mask_word(0, a.n, i, h)]; r.m2 = a.masks[mask_word(1, a.n, i, h)]; }
     if (BWD) {
         r.dn[0] = a.d_normal[3 * i + (h ? 1 : 0)];
         if (h) r.dn[1] = a.d_normal[3 * i + 2];
@@ -169,16 +176,19 @@ __device__ __forceinline__ float sigmoid(float u) { return 1.f / (1.f + __expf(-
 
 // Both hidden layers; leaves the split input and first hidden layer behind for the backward
 // pass's weight gradients.
-template <bool BWD>
-__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, Split<2, 3>& pc, Split<2, 3>& p1,
-                                             v16f* a2, uint32_t& m1, uint32_t& m2, int lane) {
+template <bool BWD, bool GIVEN>
+__device__ __forceinline__ void forward_tile(const ColorWeights<BWD>& w, const v16f* cin, Split<2, GIVEN ? 2 : 3>& pc,
+                                             Split<2, GIVEN ? 2 : 3>& p1, v16f* a2, uint32_t& m1, uint32_t& m2, int lane) {
+    constexpr int PF = GIVEN ? 2 : 3;
     v16f a1[2];
     split(cin, pc);
-    matvec_split<2, 3, 3, 3>(w.W1f, pc, a1, lane);
-    m1 = relu_mask<2>(a1);
+    matvec_split<2, 3, 3, PF>(w.W1f, pc, a1, lane);
+    if (GIVEN) apply_mask<2>(a1, m1);
+    else m1 = relu_mask<2>(a1);
     split(a1, p1);
-    matvec_split<2, 4, 3, 3>(w.W2f, p1, a2, lane);
-    m2 = relu_mask<2>(a2);
+    matvec_split<2, 4, 3, PF>(w.W2f, p1, a2, lane);
+    if (GIVEN) apply_mask<2>(a2, m2);
+    else m2 = relu_mask<2>(a2);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
@@ -202,7 +212,11 @@ __global__ __launch_bounds__(kThreads, 2) void color_fwd_kernel(ColorArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<false>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        forward_tile<false>(w, cin, pc, p1, a2, m1, m2, lane);
+        forward_tile<false, false>(w, cin, pc, p1, a2, m1, m2, lane);
+        if (a.masks && valid) {
+            a.masks[mask_word(0, a.n, i, h)] = m1;
+            a.masks[mask_word(1, a.n, i, h)] = m2;
+        }
         // Last layer, three outputs: fp32 dot products of this lane's 32 activations with its part
         // of each row, and one cross-lane add for the other half of the point.  As a matrix product
         // it would take the split of a2 and 24 matrix instructions for 3 rows of 32.
@@ -231,6 +245,11 @@ struct ColorBwdSmem {
     float tiles[kWaves][2][kTileWords];
 };
 
+// GIVEN: the masks come from the forward kernel (a.masks).  The forward pass is then recomputed
+// only for its values, which enter weight gradients and further products at gradient tolerance:
+// two terms and three products like the rest of this kernel.  Without them it is recomputed in
+// the forward kernel's own arithmetic, which yields the same masks bit for bit.
+template <bool GIVEN>
 __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
     __shared__ ColorBwdSmem sm;
     ColorWeights<true>& w = sm.w;
@@ -259,16 +278,16 @@ __global__ __launch_bounds__(kThreads) void color_bwd_kernel(ColorArgs a) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
         v16f cin[2], a2[2];
-        uint32_t m1, m2;
         const ColorRaw cur = next;
+        uint32_t m1 = cur.m1, m2 = cur.m2;
         build_input(cur, valid, h, cin);
         {
             const int64_t in = (tile + stride) * 32 + j;
             next = load_raw<true>(a, in, tile + stride < tiles && in < a.n, h);
         }
-        // ---- forward pass again, in the forward kernel's arithmetic (the same masks)
-        Split<2, 3> pc, p1;
-        forward_tile<true>(w, cin, pc, p1, a2, m1, m2, lane);
+        // ---- forward pass again
+        Split<2, GIVEN ? 2 : 3> pc, p1;
+        forward_tile<true, GIVEN>(w, cin, pc, p1, a2, m1, m2, lane);
         // adjoint of the pre-sigmoid output, from the colour the forward pass stored
         v16f d3[1] = {zero16()};
         if (valid && h == 0) {
@@ -378,12 +397,14 @@ using namespace neus2;
 extern "C" {
 
 int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs,
-                    const int32_t* sample_ray, const float* y, const float* const* W, int64_t n, float* rgb, void* stream) {
+                    const int32_t* sample_ray, const float* y, const float* const* W, int64_t n, float* rgb,
+                    uint32_t* masks, void* stream) {
     NEUS2_TRY(check_common(cfg, pos, normal, dirs, sample_ray, y, W, n));
     NEUS2_TRY(check_ptr(rgb, "rgb"));
+    NEUS2_TRY(check_ptr(masks, "masks", false));
     if (n == 0) return NEUS2_OK;
     ColorArgs a = {};
-    a.pos = pos; a.normal = normal; a.dirs = dirs; a.sample_ray = sample_ray; a.y = y; a.rgb = rgb; a.n = n;
+    a.pos = pos; a.normal = normal; a.dirs = dirs; a.sample_ray = sample_ray; a.y = y; a.rgb = rgb; a.n = n; a.masks = masks;
     a.spr = cfg->samples_per_ray;
     for (int l = 0; l < 3; ++l) a.W[l] = W[l];
     const int blocks = persistent_blocks((const void*)color_fwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
@@ -393,7 +414,7 @@ int neus2_color_fwd(const neus2_config* cfg, const float* pos, const float* norm
 
 int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* normal, const float* dirs,
                     const int32_t* sample_ray, const float* y, const float* const* W, const float* rgb, const float* d_rgb, const float* d_sdf, int64_t n,
-                    float* const* dW, float* d_y, float* d_normal, float* d_pos, void* stream) {
+                    float* const* dW, float* d_y, float* d_normal, float* d_pos, const uint32_t* masks, void* stream) {
     NEUS2_TRY(check_common(cfg, pos, normal, dirs, sample_ray, y, W, n));
     NEUS2_TRY(check_ptr(rgb, "rgb"));
     NEUS2_TRY(check_ptr(d_rgb, "d_rgb"));
@@ -403,13 +424,21 @@ int neus2_color_bwd(const neus2_config* cfg, const float* pos, const float* norm
     NEUS2_TRY(check_ptr(d_y, "d_y"));
     NEUS2_TRY(check_ptr(d_normal, "d_normal"));
     NEUS2_TRY(check_ptr(d_pos, "d_pos", false));
+    NEUS2_TRY(check_ptr(masks, "masks", false));
     if (n == 0) return NEUS2_OK;
     ColorArgs a = {};
+    a.masks = const_cast<uint32_t*>(masks);              // the backward kernel only reads them
     a.pos = pos; a.normal = normal; a.dirs = dirs; a.sample_ray = sample_ray; a.y = y; a.n = n; a.spr = cfg->samples_per_ray;
     a.rgb_in = rgb; a.d_rgb = d_rgb; a.d_sdf = d_sdf; a.d_y = d_y; a.d_normal = d_normal; a.d_pos = d_pos;
     for (int l = 0; l < 3; ++l) { a.W[l] = W[l]; a.dW[l] = dW[l]; }
-    const int blocks = persistent_blocks((const void*)color_bwd_kernel, kThreads, ((n + 31) / 32 + kWaves - 1) / kWaves);
-    hipLaunchKernelGGL(color_bwd_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    const int64_t want = ((n + 31) / 32 + kWaves - 1) / kWaves;
+    if (masks) {
+        const int blocks = persistent_blocks((const void*)color_bwd_kernel<true>, kThreads, want);
+        hipLaunchKernelGGL(color_bwd_kernel<true>, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    } else {
+        const int blocks = persistent_blocks((const void*)color_bwd_kernel<false>, kThreads, want);
+        hipLaunchKernelGGL(color_bwd_kernel<false>, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    }
     return check_launch("colour backward");
 }
 

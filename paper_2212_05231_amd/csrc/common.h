@@ -66,9 +66,9 @@ void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* wor
 bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes);
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
-                   const float* const* H, int64_t n, float* y, float* q, float* normal, hipStream_t st);
+                   const float* const* H, int64_t n, float* y, float* q, float* normal, uint32_t* masks, hipStream_t st);
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac,
                    const float* const* H, const float* d_y, const float* d_normal, int64_t n,
-                   float* const* dH, float* d_enc, float* d_pos, hipStream_t st);
+                   float* const* dH, float* d_enc, float* d_pos, const uint32_t* masks, hipStream_t st);
 
 }  // namespace neus2

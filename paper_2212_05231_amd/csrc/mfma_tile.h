@@ -83,6 +83,19 @@ __device__ __forceinline__ uint32_t relu_mask(v16f* z) {
     return m;
 }
 
+// ReLU in place without building the mask (for a kernel that is handed the masks).
+template <int NB>
+__device__ __forceinline__ void relu(v16f* z) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float zf = z[b][r];
+            asm("v_max_i32 %0, 0, %0" : "+v"(zf));
+            z[b][r] = zf;
+        }
+}
+
 template <int NB>
 __device__ __forceinline__ void apply_mask(v16f* z, uint32_t m) {
 #pragma unroll

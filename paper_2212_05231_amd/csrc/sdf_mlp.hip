@@ -28,8 +28,13 @@ struct SdfArgs {
     const float* d_y; const float* d_normal;
     float* y; float* q; float* normal;
     float* dH[3]; float* d_enc; float* d_pos;
+    uint32_t* masks;           // optional [2][n][2]: written by the forward kernel, read by the backward kernel
     int64_t n; int active_levels;
 };
+
+// The ReLU masks of a point as the kernels keep them: one word per hidden layer and lane half h,
+// bit 16 b + r for neuron 32 b + neuron_of(r, h); word (layer * n + i) * 2 + h of the buffer.
+__device__ __forceinline__ int64_t mask_word(int layer, int64_t n, int64_t i, int h) { return ((int64_t)layer * n + i) * 2 + h; }
 
 // LDS copies of the matrices, split into bf16 terms (see mfma_tile.h), in the orientations a
 // kernel needs ("f": rows = outputs, "t": rows = inputs).  Everything the forward kernel
@@ -325,6 +330,10 @@ __global__ __launch_bounds__(kFwdThreads) void sdf_fwd_kernel(SdfArgs a) {
         }
         matvec_split<1, 4, 3, 3>(w.HLf, pv, yv, lane);
         store_rows16(a.y, i, valid, h, yv[0]);
+        if (a.masks && valid) {
+            a.masks[mask_word(0, a.n, i, h)] = m1;
+            if (K == 3) a.masks[mask_word(1, a.n, i, h)] = m_last;
+        }
         // reverse sweep for dd/de
         v16f s1[2];
         last_row_masked(w.HLrow0, m_last, h, pv);
@@ -370,7 +379,13 @@ __device__ __forceinline__ void flush_grad(float* __restrict__ dst, int rows, in
             }
 }
 
-template <int D, int K>
+// GIVEN: the masks come from the forward kernel (a.masks).  The forward pass is then recomputed
+// only for its values, which enter weight gradients and further products at gradient tolerance:
+// two terms and three products like the rest of this kernel, and a plain ReLU (where its sign
+// differs from the given mask the value is within rounding of zero); every masked product uses
+// the given masks.  Without them the forward pass is recomputed in the forward kernel's own
+// arithmetic, which yields the same masks bit for bit.
+template <int D, int K, bool GIVEN>
 __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
     __shared__ SdfBwdSmem<D, K> sm;
     SdfWeights<D, K, true>& w = sm.w;
@@ -406,6 +421,12 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         const bool valid = i < a.n;
         v16f x0[1] = {x_next};
         v16f dK[1] = {load_rows16(a.d_y, i, valid, h)};
+        // given masks are first needed after the forward pass has been recomputed
+        uint32_t m1 = 0u, m_last = 0u;
+        if (GIVEN && valid) {
+            m1 = a.masks[mask_word(0, a.n, i, h)];
+            m_last = K == 3 ? a.masks[mask_word(1, a.n, i, h)] : m1;
+        }
         float nb3[3] = {0.f, 0.f, 0.f};
         if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }
         const JacRegs<D> J = load_jac<D>(a.jac, a.n, i, valid, a.active_levels, h);
@@ -413,18 +434,20 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
             const int64_t in = (tile + stride) * 32 + j;
             x_next = load_levels<D>(a.enc, a.n, in, tile + stride < tiles && in < a.n, a.active_levels, h);
         }
-        // ---- forward pass again, in the forward kernel's arithmetic (the same masks)
+        // ---- forward pass again
+        constexpr int PF = GIVEN ? 2 : 3;
         v16f a1[2], a2[2];
-        Split<1, 3> px;          // x0: input of the first layer, factor of its weight gradient
-        Split<2, 3> p1;          // a1 likewise for the second layer
+        Split<1, PF> px;         // x0: input of the first layer, factor of its weight gradient
+        Split<2, PF> p1;         // a1 likewise for the second layer
         split(x0, px);
-        matvec_split<2, KS1, 3, 3>(w.H1f, px, a1, lane);
-        const uint32_t m1 = relu_mask<2>(a1);
-        uint32_t m_last = m1;
+        matvec_split<2, KS1, 3, PF>(w.H1f, px, a1, lane);
+        if (GIVEN) relu<2>(a1);
+        else m_last = m1 = relu_mask<2>(a1);
         split(a1, p1);
         if (K == 3) {
-            matvec_split<2, 4, 3, 3>(w.H2f, p1, a2, lane);
-            m_last = relu_mask<2>(a2);
+            matvec_split<2, 4, 3, PF>(w.H2f, p1, a2, lane);
+            if (GIVEN) relu<2>(a2);
+            else m_last = relu_mask<2>(a2);
         }
         // t_0 = (de/dx) dL/dn, computed now so that the Jacobian's registers are free again
         v16f t0[1] = {apply_jac_regs<D>(J, nb3)};
@@ -560,8 +583,13 @@ template <int D, int K>
 int run_bwd(const SdfArgs& a, hipStream_t st) {
     const int64_t tiles = (a.n + 31) / 32;
     const int64_t want = (tiles + kWaves - 1) / kWaves;
-    const int blocks = persistent_blocks((const void*)sdf_bwd_kernel<D, K>, kThreads, want);
-    hipLaunchKernelGGL((sdf_bwd_kernel<D, K>), dim3(blocks), dim3(kThreads), 0, st, a);
+    if (a.masks) {
+        const int blocks = persistent_blocks((const void*)sdf_bwd_kernel<D, K, true>, kThreads, want);
+        hipLaunchKernelGGL((sdf_bwd_kernel<D, K, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+    } else {
+        const int blocks = persistent_blocks((const void*)sdf_bwd_kernel<D, K, false>, kThreads, want);
+        hipLaunchKernelGGL((sdf_bwd_kernel<D, K, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+    }
     return check_launch("sdf backward");
 }
 
@@ -575,10 +603,10 @@ SdfArgs base_args(const neus2_config* cfg, const float* enc, const float* jac, c
 }  // namespace
 
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
-                   int64_t n, float* y, float* q, float* normal, hipStream_t st) {
+                   int64_t n, float* y, float* q, float* normal, uint32_t* masks, hipStream_t st) {
     if (n == 0) return NEUS2_OK;
     SdfArgs a = base_args(cfg, enc, jac, H, n);
-    a.y = y; a.q = q; a.normal = normal;
+    a.y = y; a.q = q; a.normal = normal; a.masks = masks;
     const int D = cfg->sdf_dims[0], K = cfg->n_sdf_mats;
     if (D == 32 && K == 3) return run_fwd<32, 3>(a, st);
     if (D == 32 && K == 2) return run_fwd<32, 2>(a, st);
@@ -589,10 +617,11 @@ int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac, 
 
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
                    const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
-                   float* d_pos, hipStream_t st) {
+                   float* d_pos, const uint32_t* masks, hipStream_t st) {
     if (n == 0) return NEUS2_OK;
     SdfArgs a = base_args(cfg, enc, jac, H, n);
     a.d_y = d_y; a.d_normal = d_normal; a.d_enc = d_enc; a.d_pos = d_pos;
+    a.masks = const_cast<uint32_t*>(masks);              // the backward kernel only reads them
     for (int l = 0; l < cfg->n_sdf_mats; ++l) a.dH[l] = dH[l];
     const int D = cfg->sdf_dims[0], K = cfg->n_sdf_mats;
     if (D == 32 && K == 3) return run_bwd<32, 3>(a, st);

@@ -31,7 +31,20 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     # 5 ints + 2*32 ints + (1+5) + (1+5) ints + 2 ints + 2 floats
     assert C.sizeof(nb.Neus2Config) == 4 * (5 + 64 + 6 + 6 + 2 + 4)
-    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 32
+    assert C.sizeof(nb.Neus2StepBuffers) == 8 * 34
+
+
+def test_struct_sizes_against_the_c_compiler(tmp_path):
+    """sizeof of the header's structs as gcc sees them equals the ctypes mirrors'."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "neus2.h"\n'
+                   'int main(void) { printf("%zu %zu\\n", sizeof(neus2_config), sizeof(neus2_step_buffers)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-I", inc, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(v) for v in out] == [C.sizeof(nb.Neus2Config), C.sizeof(nb.Neus2StepBuffers)]
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
@@ -72,10 +85,11 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert b"pos" in L.neus2_last_error()
     assert L.neus2_hash_encode(C.byref(c), ok, ok, 10, ok + 4, ok, None, None) == -4
     assert L.neus2_hash_encode(C.byref(c), ok, ok, -1, ok, ok, None, None) == -2
-    assert L.neus2_sdf_fwd_grad(C.byref(c), ok, ok, None, 10, ok, ok, ok, None) == -1
-    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, None, ok, None, 64, ok, None) == -1
+    assert L.neus2_sdf_fwd_grad(C.byref(c), ok, ok, None, 10, ok, ok, ok, None, None) == -1
+    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, None, ok, None, 64, ok, None, None) == -1
     arr = (C.c_void_p * 3)(ok, ok, ok)
-    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, None, ok, arr, 63, ok, None) == -2     # not a multiple of 64
+    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, None, ok, arr, 63, ok, None, None) == -2     # not a multiple of 64
+    assert L.neus2_color_fwd(C.byref(c), ok, ok, ok, None, ok, arr, 64, ok, ok + 2, None) == -4    # masks misaligned
     assert L.neus2_render_rays(C.byref(c), ok, 0, ok, None, 4, ok, ok, None) == -2
     assert L.neus2_loss(C.byref(c), ok, ok, ok, ok, 3, 100, ok, ok, ok, ok, None) == -2
     assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 1, 0.01, 0.9, 0.99, 1e-15, 1, 1, None) == -1   # fp16 needs master

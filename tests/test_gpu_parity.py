@@ -55,6 +55,21 @@ def jac_to_level_major(J, n, L):
     return cuda(np.ascontiguousarray(np.transpose(a, (1, 2, 0, 3))))
 
 
+def decode_masks(words, n, layers):
+    """library mask buffer [2][n][2] -> list of bool [n, 64] per hidden layer (bit 16 b + r of word
+    (layer, i, h) is neuron 32 b + 8 (r / 4) + 4 h + r % 4)"""
+    w = words.detach().cpu().numpy().astype(np.uint32).reshape(2, n, 2)
+    out = []
+    for layer in range(layers):
+        m = np.zeros((n, 64), dtype=bool)
+        for h in range(2):
+            for b in range(2):
+                for r in range(16):
+                    m[:, 32 * b + 8 * (r // 4) + 4 * h + r % 4] = (w[layer, :, h] >> np.uint32(16 * b + r)) & np.uint32(1)
+        out.append(m)
+    return out
+
+
 def to_level_major(a, L):
     """[n, L*F] -> torch [L][n][F]"""
     n = a.shape[0]
@@ -65,7 +80,7 @@ def cuda(a, dtype=torch.float32):
     return torch.as_tensor(np.ascontiguousarray(a)).to(dtype=dtype).cuda().contiguous()
 
 
-def run_step(k, n_rays, want_pos=False, scale_tables=None, active=None, spr=None):
+def run_step(k, n_rays, want_pos=False, scale_tables=None, active=None, spr=None, keep_masks=True):
     w = wl.make_workload(k, n_rays=n_rays)
     cfg, params, batch = w["cfg"], w["params"], w["batch"]
     if active is not None:
@@ -76,7 +91,7 @@ def run_step(k, n_rays, want_pos=False, scale_tables=None, active=None, spr=None
         R = o.rotation_from_axis_angle(batch["omega"])
         batch["pos"] = np.clip(o.rigid_forward(batch["pos"], R, batch["shift"], 0.5, 0.5), 0, 1 - 2.0 ** -24).astype(np.float32)
     n = batch["pos"].shape[0]
-    step = nb.Step(cfg, params, n, want_pos_grad=want_pos)
+    step = nb.Step(cfg, params, n, want_pos_grad=want_pos, keep_masks=keep_masks)
     step.set_batch(batch)
     step.zero_grads()
     step.train_step()
@@ -251,18 +266,19 @@ def test_sdf_network_every_kernel_shape(D, K):
     Hg = [cuda(h) for h in H]
     enc_lm, jac_lm = to_level_major(e, L), jac_to_level_major(J, n, L)
     y, q, nrm = torch.empty(n, 16, device="cuda"), torch.empty(L, n, 2, device="cuda"), torch.empty(n, 3, device="cuda")
-    nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm)
+    kept = torch.zeros(2, n, 2, dtype=torch.int32, device="cuda")
+    nb.sdf_fwd_grad(c, enc_lm, jac_lm, Hg, n, y, q, nrm, masks=kept)
     yr, acts, masks = o.mlp_forward(H, e)
     S, qr = o.mlp_input_gradient(H, masks, 0)
     assert rel(y.cpu().numpy(), yr) <= FWD_TOL
     assert rel(from_level_major(q, n), qr) <= FWD_TOL
     assert rel(nrm.cpu().numpy(), np.einsum("nk,nka->na", qr, J.astype(np.float64))) <= FWD_TOL
+    # the masks handed to the backward kernel are the oracle's, but for pre-activations that round to
+    # the other side of zero
+    for got, want in zip(decode_masks(kept, n, K - 1), masks):
+        assert np.mean(got != (want > 0)) < 1e-4
     d_y = rng.normal(size=(n, 16)).astype(np.float32)
     d_n = rng.normal(size=(n, 3)).astype(np.float32)
-    dH = [torch.zeros_like(h) for h in Hg]
-    d_enc = torch.zeros(L, n, 2, device="cuda")
-    nb.sdf_mlp_bwd(c, enc_lm, jac_lm, Hg, cuda(d_y), cuda(d_n), n, dH, d_enc)
-    torch.cuda.synchronize()
     H64 = [h.astype(np.float64) for h in H]
     gH, d_in, _ = o.mlp_backward(H64, acts, masks, d_y.astype(np.float64))
     # second order (Theorem 1 for the SDF output): dL/dH_l += S_l^T t_{l-1}^T, t_0 = J nbar
@@ -276,9 +292,15 @@ def test_sdf_network_every_kernel_shape(D, K):
         gH[l] += sweep[l].T @ t
         t = (t @ H64[l].T) * masks[l]
     gH[K - 1][0] += t.sum(axis=0)
-    assert rel(from_level_major(d_enc, n), d_in) <= GRAD_TOL
-    for a, b in zip(dH, gH):
-        assert rel(a.cpu().numpy(), b) <= GRAD_TOL
+    # the backward kernel in both forms: masks from the forward kernel, or worked out again
+    for given in (kept, None):
+        dH = [torch.zeros_like(h) for h in Hg]
+        d_enc = torch.zeros(L, n, 2, device="cuda")
+        nb.sdf_mlp_bwd(c, enc_lm, jac_lm, Hg, cuda(d_y), cuda(d_n), n, dH, d_enc, masks=given)
+        torch.cuda.synchronize()
+        assert rel(from_level_major(d_enc, n), d_in) <= GRAD_TOL
+        for a, b in zip(dH, gH):
+            assert rel(a.cpu().numpy(), b) <= GRAD_TOL
 
 
 def test_render_forward_backward_alone():
@@ -466,25 +488,30 @@ def test_color_forward_backward_alone():
     Wg = [cuda(w) for w in W]
     rgb = torch.empty(n, 3, device="cuda")
     args = (cuda(pos), cuda(nrm), cuda(dirs), cuda(y))
-    nb.color_fwd(c, *args, Wg, n, rgb)
-    dW = [torch.zeros_like(w) for w in Wg]
-    d_y = torch.empty(n, 16, device="cuda")
-    d_normal = cuda(dn0)
-    d_pos = torch.empty(n, 3, device="cuda")
-    nb.color_bwd(c, *args, Wg, rgb, cuda(d_rgb), cuda(d_sdf), n, dW, d_y, d_normal, d_pos)
-    torch.cuda.synchronize()
+    kept = torch.zeros(2, n, 2, dtype=torch.int32, device="cuda")
+    nb.color_fwd(c, *args, Wg, n, rgb, masks=kept)
     cin = o.color_input(pos, nrm.astype(np.float64), dirs, y.astype(np.float64), spr)
     rgb_r, acts, masks = o.color_forward(W, cin)
     assert rel(rgb.cpu().numpy(), rgb_r) <= FWD_TOL
+    for got, want in zip(decode_masks(kept, n, 2), masks):
+        assert np.mean(got != (want > 0)) < 1e-4
     d_u = d_rgb * rgb_r * (1 - rgb_r)
     gW, d_cin, _ = o.mlp_backward(W, acts, masks, d_u)
-    for a, b in zip(dW, gW):
-        assert rel(a.cpu().numpy(), b) <= GRAD_TOL
     want_dy = d_cin[:, 22:38].copy()
     want_dy[:, 0] += d_sdf
-    assert rel(d_y.cpu().numpy(), want_dy) <= GRAD_TOL
-    assert rel(d_normal.cpu().numpy(), dn0 + d_cin[:, 3:6]) <= GRAD_TOL
-    assert rel(d_pos.cpu().numpy(), d_cin[:, 0:3]) <= GRAD_TOL
+    # the backward kernel in both forms: masks from the forward kernel, or worked out again
+    for given in (kept, None):
+        dW = [torch.zeros_like(w) for w in Wg]
+        d_y = torch.empty(n, 16, device="cuda")
+        d_normal = cuda(dn0)
+        d_pos = torch.empty(n, 3, device="cuda")
+        nb.color_bwd(c, *args, Wg, rgb, cuda(d_rgb), cuda(d_sdf), n, dW, d_y, d_normal, d_pos, masks=given)
+        torch.cuda.synchronize()
+        for a, b in zip(dW, gW):
+            assert rel(a.cpu().numpy(), b) <= GRAD_TOL
+        assert rel(d_y.cpu().numpy(), want_dy) <= GRAD_TOL
+        assert rel(d_normal.cpu().numpy(), dn0 + d_cin[:, 3:6]) <= GRAD_TOL
+        assert rel(d_pos.cpu().numpy(), d_cin[:, 0:3]) <= GRAD_TOL
 
 
 def test_adam_fp32_and_fp16():
@@ -684,6 +711,14 @@ def test_step_config1_ragged_tail_and_position_gradient():
 @pytest.mark.parametrize("k,n_rays", [(2, 96), (3, 40), (4, 24)])
 def test_step_ray_configs_small(k, n_rays):
     cfg, step, ref, n = run_step(k, n_rays)
+    print(check_step(cfg, step, ref, n))
+
+
+@pytest.mark.parametrize("k,n_rays", [(1, 300), (2, 96)])
+def test_step_whose_backward_kernels_work_the_masks_out_again(k, n_rays):
+    """Without mask buffers the backward kernels repeat the forward kernels' arithmetic."""
+    cfg, step, ref, n = run_step(k, n_rays, keep_masks=False)
+    assert step.buffers.sdf_masks is None and step.buffers.color_masks is None
     print(check_step(cfg, step, ref, n))
 
 

@@ -38,9 +38,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix rate: the network kern
 # workload has been measured; other workloads report null.
 MEASURED_TRAFFIC_MIB = {
     "cfg2-static-4096x64": {
-        "hash_encode": (86.1, 128.0), "sdf_fwd_grad": (128.5, 51.0), "color_fwd": (22.7, 3.0),
-        "render_loss_bwd": (22.2, 8.1), "color_bwd": (33.1, 28.4), "sdf_mlp_bwd": (150.9, 47.0),
-        "hash_scatter_bwd": (84.1 + 306.7, 232.7 + 56.4),      # bin_rows_kernel + scatter_owner_kernel
+        "hash_encode": (86.1, 128.0), "sdf_fwd_grad": (128.5, 55.0), "color_fwd": (22.7, 7.0),
+        "render_loss_bwd": (22.2, 8.1), "color_bwd": (37.0, 28.4), "sdf_mlp_bwd": (155.3, 48.0),
+        "hash_scatter_bwd": (83.9 + 310.7, 232.7 + 56.4),      # bin_rows_kernel + scatter_owner_kernel
         "adam_all": (186.4, 209.6),
     },
 }

@@ -268,6 +268,33 @@ int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scal
 int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float scale, int64_t n,
                     float* Mb, void* stream);
 
+/* ---- The transform of a frame as six trained parameters (Sec. 5, Eqs. 9-10; the supplement's
+ * training schedule optimises them alone for the first iterations of a frame) -------------------
+ * A frame's points reach the canonical space through x_c = R_prev (R(omega) (x + T) + T_prev),
+ * where (R_prev, T_prev) is the transform accumulated over the earlier frames and
+ * R(omega) = exp([omega]_x).  That is the single rigid map x_c = Rc (x + Tc), Rc = R_prev R(omega),
+ * Tc = T + R(omega)^T T_prev (the accumulation rule stated after Eq. 10).  All state lives in
+ * device memory, so a training loop never reads anything back:
+ *   param [device, 6]: omega (3), T (3);  m, v [device, 6]: their Adam moments;
+ *   prev  [device, 12]: R_prev row-major (9), T_prev (3)  (identity and zero for the first frame);
+ *   pose  [device, 12]: Rc (9), Tc (3), what the two calls below apply;
+ *   Mb    [device, 12]: the reductions of neus2_rigid_bwd_dev.
+ * Moving on to the next frame is a copy of pose into prev and new values in param. */
+
+/* neus2_rigid_fwd / neus2_rigid_bwd with the transform read from device memory (pose). */
+int neus2_rigid_fwd_dev(const float* pos, const float* pose, float scale, float offset, int64_t n,
+                        float* out, void* stream);
+int neus2_rigid_bwd_dev(const float* pos, const float* pose, const float* d_out, float scale,
+                        int64_t n, float* Mb, void* stream);
+
+/* apply = 1: the gradient of the six parameters from Mb (sum g (x+T)^T = M - b (R^T T_prev)^T,
+ * dL/dR = R_prev^T of that, dL/domega_k = sum (dR/domega_k) o dL/dR, dL/dT = Rc^T b), one Adam
+ * step on them (step number t >= 1, bias-corrected like neus2_adam_step), then pose is rebuilt
+ * from the new parameters and Mb is cleared.  apply = 0: only pose is rebuilt from param and
+ * prev and Mb cleared (the start of a frame; m, v may be NULL).  One thread, double precision. */
+int neus2_pose_update(float* param, float* m, float* v, const float* prev, float* Mb, float* pose,
+                      float lr, float beta1, float beta2, float eps, int t, int apply, void* stream);
+
 /* All buffers of one training step, for neus2_train_step.  Every pointer is [device] except
  * H, W, dH, dW, which are [host] arrays of device pointers.  Sizes as in the calls above;
  * rays * samples_per_ray = n, unless ray_offsets / sample_ray describe the rays. */

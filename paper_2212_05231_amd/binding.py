@@ -79,6 +79,9 @@ _SIGNATURES = {
                                  C.c_float, C.c_float, C.c_int, C.c_int, _P]),
     "neus2_rigid_fwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
     "neus2_rigid_bwd": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
+    "neus2_rigid_fwd_dev": (C.c_int, [_P, _P, C.c_float, C.c_float, C.c_int64, _P, _P]),
+    "neus2_rigid_bwd_dev": (C.c_int, [_P, _P, _P, C.c_float, C.c_int64, _P, _P]),
+    "neus2_pose_update": (C.c_int, [_P, _P, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int, C.c_int, _P]),
     "neus2_occupancy_points": (C.c_int, [C.c_int, _P, _P, C.c_int64, _P, _P]),
     "neus2_occupancy_update": (C.c_int, [C.c_int, _P, _P, _P, C.c_int64, C.c_int64, _P, C.c_float, C.c_float, C.c_float, _P, _P]),
     "neus2_march_rays": (C.c_int, [C.c_int, _P, _P, _P, _P, C.c_int64, C.c_float, C.c_int32, C.c_int64, _P, _P, _P, _P, _P]),
@@ -253,6 +256,19 @@ def rigid_fwd(pos, R, T, scale, offset, out):
 def rigid_bwd(pos, T, d_out, scale, Mb):
     Ta = (C.c_float * 3)(*[float(x) for x in T])
     _check(lib().neus2_rigid_bwd(_ptr(pos), Ta, _ptr(d_out), scale, pos.shape[0], _ptr(Mb), _stream()))
+
+
+def rigid_fwd_dev(pos, pose, scale, offset, out):
+    _check(lib().neus2_rigid_fwd_dev(_ptr(pos), _ptr(pose), scale, offset, pos.shape[0], _ptr(out), _stream()))
+
+
+def rigid_bwd_dev(pos, pose, d_out, scale, Mb):
+    _check(lib().neus2_rigid_bwd_dev(_ptr(pos), _ptr(pose), _ptr(d_out), scale, pos.shape[0], _ptr(Mb), _stream()))
+
+
+def pose_update(param, m, v, prev, Mb, pose, lr, beta1, beta2, eps, t, apply=True):
+    _check(lib().neus2_pose_update(_ptr(param), _ptr(m), _ptr(v), _ptr(prev), _ptr(Mb), _ptr(pose), lr, beta1, beta2, eps, t,
+                                   1 if apply else 0, _stream()))
 
 
 def occupancy_points(log2_res, cells, jitter, pos):

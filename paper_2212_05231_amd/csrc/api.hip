@@ -271,18 +271,70 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
 
 }  // extern "C"
 
+namespace {
+
+// Every field of the step's buffers that the chosen path will read or write, checked before the
+// first launch: a call that fails here has touched no device memory.
+int check_step_buffers(const neus2_config* cfg, const neus2_step_buffers* b, int64_t n, bool ragged) {
+    NEUS2_TRY(check_ptr(b->loss, "loss"));
+    NEUS2_TRY(check_ptr(b->workspace, "workspace", false));
+    if (ragged) {
+        NEUS2_TRY(check_ptr(b->target, "target"));
+        NEUS2_TRY(check_ptr(b->C, "C"));
+        NEUS2_TRY(check_ptr(b->dC, "dC"));
+        NEUS2_TRY(check_ptr(b->s_dev, "s_dev", false));
+        NEUS2_TRY(check_ptr(b->d_s, "d_s", false));
+    }
+    if (n == 0) return NEUS2_OK;
+    NEUS2_TRY(check_ptr(b->pos, "pos"));
+    NEUS2_TRY(check_ptr(b->tables, "tables"));
+    NEUS2_TRY(check_ptr(b->enc, "enc"));
+    NEUS2_TRY(check_ptr(b->jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)b->H, cfg->n_sdf_mats, "H"));
+    NEUS2_TRY(check_ptr(b->y, "y"));
+    NEUS2_TRY(check_ptr(b->q, "q"));
+    NEUS2_TRY(check_ptr(b->normal, "normal"));
+    NEUS2_TRY(check_ptr(b->sdf_masks, "sdf_masks", false));
+    NEUS2_TRY(check_ptr(b->d_y, "d_y"));
+    NEUS2_TRY(check_ptr(b->d_normal, "d_normal"));
+    NEUS2_TRY(check_ptr(b->d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(b->d_pos, "d_pos", false));
+    NEUS2_TRY(check_mats((const void* const*)b->dH, cfg->n_sdf_mats, "dH"));
+    NEUS2_TRY(check_ptr(b->d_tables, "d_tables"));
+    if (cfg->loss_kind != 0) {
+        NEUS2_TRY(check_ptr(b->dirs, "dirs"));
+        NEUS2_TRY(check_ptr(b->target, "target"));
+        NEUS2_TRY(check_mats((const void* const*)b->W, 3, "W"));
+        NEUS2_TRY(check_ptr(b->rgb, "rgb"));
+        NEUS2_TRY(check_ptr(b->color_masks, "color_masks", false));
+        NEUS2_TRY(check_ptr(b->C, "C"));
+        NEUS2_TRY(check_ptr(b->weights, "weights"));
+        NEUS2_TRY(check_ptr(b->dC, "dC"));
+        NEUS2_TRY(check_ptr(b->d_sdf, "d_sdf"));
+        NEUS2_TRY(check_ptr(b->d_rgb, "d_rgb"));
+        NEUS2_TRY(check_mats((const void* const*)b->dW, 3, "dW"));
+        NEUS2_TRY(check_ptr(b->s_dev, "s_dev", false));
+        NEUS2_TRY(check_ptr(b->d_s, "d_s", false));
+    }
+    return NEUS2_OK;
+}
+
+}  // namespace
+
 extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* b, int64_t n, void* stream) {
     NEUS2_TRY(check_config(cfg));
     if (!b) return fail(NEUS2_ERR_NULL, "buf is NULL");
     const bool ragged = b->ray_offsets != nullptr;
     if (ragged != (b->sample_ray != nullptr)) return fail(NEUS2_ERR_NULL, "ray_offsets and sample_ray go together");
     if (ragged && cfg->loss_kind == 0) return fail(NEUS2_ERR_CONFIG, "loss_kind 0 has no rays");
-    if (n < 0 || (!ragged && n % cfg->samples_per_ray != 0))
+    NEUS2_TRY(check_count(n, "n"));
+    if (!ragged && n % cfg->samples_per_ray != 0)
         return fail(NEUS2_ERR_SHAPE, "n = %lld is not a multiple of samples_per_ray = %d", (long long)n, cfg->samples_per_ray);
-    if (ragged && b->n_rays < 0) return fail(NEUS2_ERR_SHAPE, "n_rays = %lld is negative", (long long)b->n_rays);
+    if (ragged && (b->n_rays < 0 || b->n_rays > ((int64_t)1 << 28)))
+        return fail(NEUS2_ERR_SHAPE, "n_rays = %lld out of range", (long long)b->n_rays);
     if (cfg->loss_kind != 0 && cfg->n_color_mats != 3)
         return fail(NEUS2_ERR_CONFIG, "loss_kind %d needs the colour network", cfg->loss_kind);
-    NEUS2_TRY(check_ptr(b->loss, "loss"));
+    NEUS2_TRY(check_step_buffers(cfg, b, n, ragged));
     hipStream_t st = (hipStream_t)stream;
     const int64_t rays = ragged ? b->n_rays : n / cfg->samples_per_ray;
     if (n == 0) {                  // an empty batch has no sample buffers to look at
@@ -295,12 +347,7 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     // the encode kernel, first of the step, also clears the loss sums and the header of the scatter's
     // workspace: two launches fewer
     ZeroRegions zero = {{b->loss, nullptr}, {2, 0}};
-    NEUS2_TRY(check_ptr(b->workspace, "workspace", false));
     scatter_header(cfg, n, b->d_pos != nullptr, b->workspace, b->workspace_bytes, &zero.p[1], &zero.count[1]);
-    NEUS2_TRY(check_ptr(b->pos, "pos"));
-    NEUS2_TRY(check_ptr(b->tables, "tables"));
-    NEUS2_TRY(check_ptr(b->enc, "enc"));
-    NEUS2_TRY(check_ptr(b->jac, "jac"));
     NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, b->sdf_masks, stream));
     if (cfg->loss_kind != 0) {

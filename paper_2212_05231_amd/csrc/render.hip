@@ -25,6 +25,14 @@ struct RayLane {
 
 __device__ __forceinline__ float shfl_down1(float v) { return __shfl_down(v, 1); }
 
+// 1 - alpha as a divisor.  In binary32 alpha rounds to exactly 1 once s (d_i - d_{i+1}) and
+// -s d_{i+1} both pass about 17; every later transmittance is then 0 and the quotient
+// (sum over later samples) / (1 - alpha) would be 0/0.  Both derivatives of alpha are exactly 0 in
+// that case (1 - e^{-s delta} = 1 and Phi_s(d_{i+1}) = 0 after rounding), so any finite quotient
+// gives the exact adjoint 0; 2^-24 is half the spacing of floats below 1, the smallest 1 - alpha
+// that can occur otherwise.
+__device__ __forceinline__ float guarded_one_minus(float alpha) { return fmaxf(1.f - alpha, 5.9604645e-8f); }
+
 // inclusive product scan over the wave
 __device__ __forceinline__ float wave_scan_mul(float v, int lane) {
 #pragma unroll
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(kRayThreads) void render_bwd_kernel(const float* __
     }
     const float wc = w * cb;
     const float after = wave_suffix_sum(wc, lane) - wc;          // sum over j > i
-    const float d_alpha = r.trans * cb - after / (1.f - r.alpha);
+    const float d_alpha = r.trans * cb - after / guarded_one_minus(r.alpha);
     const float from_prev = __shfl_up(d_alpha * r.dalpha_dnext, 1);
     float ds = d_alpha * r.dalpha_di;
     if (lane > 0) ds += from_prev;
@@ -302,7 +310,7 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_kernel(int kind, co
         }
         const float wc = w * cb;
         const float after = wave_suffix_sum(wc, lane) - wc;
-        const float d_alpha = r.trans * cb - after / (1.f - r.alpha);
+        const float d_alpha = r.trans * cb - after / guarded_one_minus(r.alpha);
         const float from_prev = __shfl_up(d_alpha * r.dalpha_dnext, 1);
         float ds = d_alpha * r.dalpha_di;
         if (lane > 0) ds += from_prev;
@@ -434,7 +442,7 @@ __global__ __launch_bounds__(kFusedThreads) void render_loss_ragged_kernel(
             }
             const float wc = w * cb;
             const float after = wave_suffix_sum(wc, lane) - wc + after_carry;
-            const float d_alpha = trans * cb - after / (1.f - a.alpha);
+            const float d_alpha = trans * cb - after / guarded_one_minus(a.alpha);
             const float to_next = d_alpha * a.dalpha_dnext;
             float ds = d_alpha * a.dalpha_di;
             const float from_prev = __shfl_up(to_next, 1);
@@ -565,10 +573,19 @@ struct Rigid {
     float R[9], T[3], scale, offset;
 };
 
-__global__ __launch_bounds__(256) void rigid_fwd_kernel(const float* __restrict__ pos, Rigid t, int64_t n,
-                                                        float* __restrict__ out) {
+// DEV: rotation and translation are read from device memory (pose[0..8] = R row-major,
+// pose[9..11] = T), where neus2_pose_update keeps them; otherwise they arrive by value.
+template <bool DEV>
+__global__ __launch_bounds__(256) void rigid_fwd_kernel(const float* __restrict__ pos, Rigid t, const float* __restrict__ pose,
+                                                        int64_t n, float* __restrict__ out) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
+    if (DEV) {
+#pragma unroll
+        for (int k = 0; k < 9; ++k) t.R[k] = pose[k];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) t.T[k] = pose[9 + k];
+    }
     const float x = pos[3 * i] + t.T[0], y = pos[3 * i + 1] + t.T[1], z = pos[3 * i + 2] + t.T[2];
 #pragma unroll
     for (int r = 0; r < 3; ++r) out[3 * i + r] = t.scale * (t.R[3 * r] * x + t.R[3 * r + 1] * y + t.R[3 * r + 2] * z) + t.offset;
@@ -576,10 +593,15 @@ __global__ __launch_bounds__(256) void rigid_fwd_kernel(const float* __restrict_
 
 constexpr int kRigidThreads = 1024;
 
-__global__ __launch_bounds__(kRigidThreads) void rigid_bwd_kernel(const float* __restrict__ pos, Rigid t,
+template <bool DEV>
+__global__ __launch_bounds__(kRigidThreads) void rigid_bwd_kernel(const float* __restrict__ pos, Rigid t, const float* __restrict__ pose,
                                                                  const float* __restrict__ d_out, int64_t n,
                                                                  float* __restrict__ Mb) {
     __shared__ float red[12 * kRigidThreads / 64];
+    if (DEV) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) t.T[k] = pose[9 + k];
+    }
     float acc[12];
 #pragma unroll
     for (int k = 0; k < 12; ++k) acc[k] = 0.f;
@@ -593,6 +615,98 @@ __global__ __launch_bounds__(kRigidThreads) void rigid_bwd_kernel(const float* _
         }
     }
     block_add_n<12>(acc, Mb, red);
+}
+
+// ---- the six parameters of a frame's transform (Sec. 5, Eqs. 9-10) ----------------------------
+// A frame's points reach the canonical space through x_c = R_prev (R(omega) (x + T) + T_prev):
+// (R_prev, T_prev) is the transform accumulated over the earlier frames, (omega, T) the frame's
+// own, R(omega) = exp([omega]_x).  That is one rigid map x_c = Rc (x + Tc) with Rc = R_prev R and
+// Tc = T + R^T T_prev (the accumulation rule of the text after Eq. 10), which is what the
+// transform kernels apply.  From their reductions M = sum g (x + Tc)^T and b = sum g:
+//   sum g (x + T)^T = M - b (R^T T_prev)^T,   dL/dR = R_prev^T (that),   dL/dT = Rc^T b,
+//   dL/domega_k = sum_ij (dR/domega_k)_ij (dL/dR)_ij.
+// Twelve numbers in, six parameters out: one thread, in double precision (the derivative of
+// Rodrigues' formula cancels badly in binary32 at the small angles of frame-to-frame motion).
+struct Mat3 {
+    double a[9];
+};
+
+__device__ inline Mat3 mat_mul(const Mat3& x, const Mat3& y) {
+    Mat3 z;
+    for (int i = 0; i < 3; ++i)
+        for (int j = 0; j < 3; ++j) z.a[3 * i + j] = x.a[3 * i] * y.a[j] + x.a[3 * i + 1] * y.a[3 + j] + x.a[3 * i + 2] * y.a[6 + j];
+    return z;
+}
+
+__device__ inline Mat3 skew(const double w[3]) {
+    Mat3 k = {{0.0, -w[2], w[1], w[2], 0.0, -w[0], -w[1], w[0], 0.0}};
+    return k;
+}
+
+// R = I + a K + b K^2, a = sin t / t, b = (1 - cos t) / t^2; da, db = (1/t) d/dt of a and b
+__device__ inline void rodrigues_terms(double t2, double& a, double& b, double& da, double& db) {
+    if (t2 < 1e-8) {                         // series: the closed forms are 0/0 at t = 0
+        a = 1.0 - t2 / 6.0; b = 0.5 - t2 / 24.0; da = -1.0 / 3.0 + t2 / 30.0; db = -1.0 / 12.0 + t2 / 180.0;
+    } else {
+        const double t = sqrt(t2);
+        a = sin(t) / t; b = (1.0 - cos(t)) / t2;
+        da = (cos(t) - a) / t2; db = (a - 2.0 * b) / t2;
+    }
+}
+
+__global__ void pose_update_kernel(float* __restrict__ param, float* __restrict__ m, float* __restrict__ v,
+                                   const float* __restrict__ prev, float* __restrict__ Mb, float* __restrict__ pose,
+                                   AdamArgs adam, int apply) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double w[3] = {param[0], param[1], param[2]}, T[3] = {param[3], param[4], param[5]};
+    Mat3 Rp;
+    double Tp[3];
+    for (int k = 0; k < 9; ++k) Rp.a[k] = prev[k];
+    for (int k = 0; k < 3; ++k) Tp[k] = prev[9 + k];
+    if (apply) {
+        double a, b, da, db;
+        rodrigues_terms(w[0] * w[0] + w[1] * w[1] + w[2] * w[2], a, b, da, db);
+        const Mat3 K = skew(w), K2 = mat_mul(K, K);
+        Mat3 R;
+        for (int k = 0; k < 9; ++k) R.a[k] = (k % 4 == 0 ? 1.0 : 0.0) + a * K.a[k] + b * K2.a[k];
+        double rtp[3], bs[3];                                  // R^T T_prev, b
+        for (int j = 0; j < 3; ++j) rtp[j] = R.a[j] * Tp[0] + R.a[3 + j] * Tp[1] + R.a[6 + j] * Tp[2];
+        for (int j = 0; j < 3; ++j) bs[j] = Mb[9 + j];
+        Mat3 U;                                                // sum g (x + T)^T
+        for (int i = 0; i < 3; ++i)
+            for (int j = 0; j < 3; ++j) U.a[3 * i + j] = (double)Mb[3 * i + j] - bs[i] * rtp[j];
+        Mat3 G;                                                // dL/dR = R_prev^T U
+        for (int i = 0; i < 3; ++i)
+            for (int j = 0; j < 3; ++j) G.a[3 * i + j] = Rp.a[i] * U.a[j] + Rp.a[3 + i] * U.a[3 + j] + Rp.a[6 + i] * U.a[6 + j];
+        const Mat3 Rc = mat_mul(Rp, R);
+        double grad[6];
+        for (int k = 0; k < 3; ++k) {
+            double e[3] = {0.0, 0.0, 0.0};
+            e[k] = 1.0;
+            const Mat3 E = skew(e), EK = mat_mul(E, K), KE = mat_mul(K, E);
+            double acc = 0.0;
+            for (int q = 0; q < 9; ++q) acc += (a * E.a[q] + b * (EK.a[q] + KE.a[q]) + w[k] * (da * K.a[q] + db * K2.a[q])) * G.a[q];
+            grad[k] = acc;
+        }
+        for (int j = 0; j < 3; ++j) grad[3 + j] = Rc.a[j] * bs[0] + Rc.a[3 + j] * bs[1] + Rc.a[6 + j] * bs[2];   // Rc^T b
+        for (int k = 0; k < 6; ++k) {
+            const double mk = (double)adam.b1 * m[k] + (1.0 - (double)adam.b1) * grad[k];
+            const double vk = (double)adam.b2 * v[k] + (1.0 - (double)adam.b2) * grad[k] * grad[k];
+            const double p = (double)param[k] - (double)adam.lr * (mk * (double)adam.inv_c1) / (sqrt(vk * (double)adam.inv_c2) + (double)adam.eps);
+            m[k] = (float)mk; v[k] = (float)vk; param[k] = (float)p;
+        }
+        for (int k = 0; k < 3; ++k) { w[k] = param[k]; T[k] = param[3 + k]; }      // the binary32 values the next step sees
+    }
+    // the composed transform the transform kernels apply from now on
+    double a, b, da, db;
+    rodrigues_terms(w[0] * w[0] + w[1] * w[1] + w[2] * w[2], a, b, da, db);
+    const Mat3 K = skew(w), K2 = mat_mul(K, K);
+    Mat3 R;
+    for (int k = 0; k < 9; ++k) R.a[k] = (k % 4 == 0 ? 1.0 : 0.0) + a * K.a[k] + b * K2.a[k];
+    const Mat3 Rc = mat_mul(Rp, R);
+    for (int k = 0; k < 9; ++k) pose[k] = (float)Rc.a[k];
+    for (int j = 0; j < 3; ++j) pose[9 + j] = (float)(T[j] + R.a[j] * Tp[0] + R.a[3 + j] * Tp[1] + R.a[6 + j] * Tp[2]);
+    for (int k = 0; k < 12; ++k) Mb[k] = 0.f;
 }
 
 }  // namespace
@@ -828,7 +942,8 @@ int neus2_rigid_fwd(const float* pos, const float* R, const float* T, float scal
     for (int k = 0; k < 9; ++k) t.R[k] = R[k];
     for (int k = 0; k < 3; ++k) t.T[k] = T[k];
     t.scale = scale; t.offset = offset;
-    hipLaunchKernelGGL(rigid_fwd_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pos, t, n, out);
+    hipLaunchKernelGGL(rigid_fwd_kernel<false>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pos, t,
+                       nullptr, n, out);
     return check_launch("rigid transform");
 }
 
@@ -844,8 +959,62 @@ int neus2_rigid_bwd(const float* pos, const float* T, const float* d_out, float 
     t.scale = scale;
     int64_t blocks = (n + kRigidThreads - 1) / kRigidThreads;
     if (blocks > compute_units()) blocks = compute_units();
-    hipLaunchKernelGGL(rigid_bwd_kernel, dim3((unsigned)blocks), dim3(kRigidThreads), 0, (hipStream_t)stream, pos, t, d_out, n, Mb);
+    hipLaunchKernelGGL(rigid_bwd_kernel<false>, dim3((unsigned)blocks), dim3(kRigidThreads), 0, (hipStream_t)stream, pos, t, nullptr,
+                       d_out, n, Mb);
     return check_launch("rigid transform backward");
+}
+
+int neus2_rigid_fwd_dev(const float* pos, const float* pose, float scale, float offset, int64_t n, float* out, void* stream) {
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    NEUS2_TRY(check_ptr(pose, "pose"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(out, "out"));
+    if (n == 0) return NEUS2_OK;
+    Rigid t = {};
+    t.scale = scale; t.offset = offset;
+    hipLaunchKernelGGL(rigid_fwd_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, pos, t, pose,
+                       n, out);
+    return check_launch("rigid transform");
+}
+
+int neus2_rigid_bwd_dev(const float* pos, const float* pose, const float* d_out, float scale, int64_t n, float* Mb,
+                        void* stream) {
+    if (n < 0 || n > ((int64_t)1 << 28)) return fail(NEUS2_ERR_SHAPE, "n = %lld out of range", (long long)n);
+    NEUS2_TRY(check_ptr(pose, "pose"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(d_out, "d_out"));
+    NEUS2_TRY(check_ptr(Mb, "Mb"));
+    if (n == 0) return NEUS2_OK;
+    Rigid t = {};
+    t.scale = scale;
+    int64_t blocks = (n + kRigidThreads - 1) / kRigidThreads;
+    if (blocks > compute_units()) blocks = compute_units();
+    hipLaunchKernelGGL(rigid_bwd_kernel<true>, dim3((unsigned)blocks), dim3(kRigidThreads), 0, (hipStream_t)stream, pos, t, pose,
+                       d_out, n, Mb);
+    return check_launch("rigid transform backward");
+}
+
+int neus2_pose_update(float* param, float* m, float* v, const float* prev, float* Mb, float* pose, float lr, float beta1,
+                      float beta2, float eps, int t, int apply, void* stream) {
+    if (apply != 0 && apply != 1) return fail(NEUS2_ERR_CONFIG, "apply = %d, must be 0 or 1", apply);
+    if (apply) {
+        if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
+        if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return fail(NEUS2_ERR_CONFIG, "beta1, beta2 must be in [0,1)");
+        NEUS2_TRY(check_ptr(m, "m"));
+        NEUS2_TRY(check_ptr(v, "v"));
+    }
+    NEUS2_TRY(check_ptr(param, "param"));
+    NEUS2_TRY(check_ptr(prev, "prev"));
+    NEUS2_TRY(check_ptr(Mb, "Mb"));
+    NEUS2_TRY(check_ptr(pose, "pose"));
+    AdamArgs a = {};
+    if (apply) {
+        a.lr = lr; a.b1 = beta1; a.b2 = beta2; a.eps = eps;
+        a.inv_c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)t)));
+        a.inv_c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)t)));
+    }
+    hipLaunchKernelGGL(pose_update_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, param, m, v, prev, Mb, pose, a, apply);
+    return check_launch("pose update");
 }
 
 }  // extern "C"

@@ -98,6 +98,40 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.neus2_train_step(C.byref(c), None, 64, None) == -1
 
 
+def _step_buffers(ok, mats):
+    b = nb.Neus2StepBuffers()
+    for name, _ in nb.Neus2StepBuffers._fields_:
+        if name not in ("workspace_bytes", "n_rays", "H", "W", "dH", "dW", "workspace", "s_dev", "d_s", "ray_offsets",
+                        "sample_ray", "d_pos", "sdf_masks", "color_masks"):
+            setattr(b, name, ok)
+    for name in ("H", "W", "dH", "dW"):
+        setattr(b, name, C.cast(mats, C.c_void_p))
+    return b
+
+
+def test_train_step_checks_every_buffer_before_its_first_launch():
+    """A NULL or misaligned field anywhere in the step's buffers is reported before anything is
+    launched: on a host without a GPU the call returns the pointer error, not a launch error."""
+    L = nb.lib()
+    c = nb.make_config(wl.make_config(2))
+    ok = 0x1000
+    mats = (C.c_void_p * 3)(ok, ok, ok)
+    for field in ("dW", "dH", "W", "H", "d_tables", "rgb", "d_rgb", "dC", "weights", "d_enc", "q", "target", "dirs"):
+        b = _step_buffers(ok, mats)
+        setattr(b, field, None)
+        assert L.neus2_train_step(C.byref(c), C.byref(b), 128, None) == -1, field
+        assert field.encode() in L.neus2_last_error()
+    broken = (C.c_void_p * 3)(ok, None, ok)
+    b = _step_buffers(ok, mats)
+    b.dW = C.cast(broken, C.c_void_p)
+    assert L.neus2_train_step(C.byref(c), C.byref(b), 128, None) == -1 and b"dW[1]" in L.neus2_last_error()
+    b = _step_buffers(ok, mats)
+    b.color_masks = ok + 8
+    assert L.neus2_train_step(C.byref(c), C.byref(b), 128, None) == -4
+    b = _step_buffers(ok, mats)
+    assert L.neus2_train_step(C.byref(c), C.byref(b), 100, None) == -2          # not a multiple of 64 samples
+
+
 def test_workload_generators_are_seeded_and_in_range():
     import numpy as np
     a = wl.make_workload(2, n_rays=16)

@@ -478,7 +478,73 @@ def test_sh16_addition_theorem_and_orthonormality():
     np.testing.assert_allclose((Yq * wq[:, None]).T @ Yq, np.eye(16), atol=1e-13)
 
 
+def test_sh16_index_and_sign_at_the_axes_and_against_the_library_harmonics():
+    """Addition theorem and orthonormality do not see a permutation or a sign flip within one
+    degree; these do.  At the pole z only the zonal harmonics m = 0 are non-zero and
+    Y_l0(z) = sqrt((2l+1)/4 pi) (textbook); at x the values written here by hand.  For general
+    directions: scipy's complex Y_l^m (Condon-Shortley phase), from which the real harmonics are
+    sqrt(2) (-1)^m Re Y_l^m for m > 0 and sqrt(2) (-1)^m Im Y_l^|m| for m < 0, index l^2 + l + m."""
+    Y = o.sh16(np.array([[0.0, 0.0, 1.0], [1.0, 0.0, 0.0]]))
+    pole = np.zeros(16)
+    pole[[0, 2, 6, 12]] = [0.2820947918, 0.4886025119, 0.6307831305, 0.7463526652]      # sqrt((2l+1)/(4 pi))
+    np.testing.assert_allclose(Y[0], pole, atol=1e-9)
+    xhat = np.zeros(16)
+    xhat[0] = 0.2820947918          # l = 0
+    xhat[3] = 0.4886025119          # l = 1, m = +1: sqrt(3/4pi) x
+    xhat[6] = -0.3153915653         # l = 2, m = 0: sqrt(5/16pi) (3 z^2 - 1)
+    xhat[8] = 0.5462742153          # l = 2, m = +2: sqrt(15/16pi) (x^2 - y^2)
+    xhat[13] = -0.4570457995        # l = 3, m = +1: sqrt(21/32pi) x (5 z^2 - 1)
+    xhat[15] = 0.5900435899         # l = 3, m = +3: sqrt(35/32pi) x (x^2 - 3 y^2)
+    np.testing.assert_allclose(Y[1], xhat, atol=1e-9)
+    from scipy.special import sph_harm_y
+    rng = np.random.default_rng(9)
+    v = rng.normal(size=(200, 3))
+    v /= np.linalg.norm(v, axis=1, keepdims=True)
+    theta, phi = np.arccos(v[:, 2]), np.arctan2(v[:, 1], v[:, 0])
+    want = np.empty((200, 16))
+    for l in range(4):
+        for m in range(-l, l + 1):
+            c = sph_harm_y(l, abs(m), theta, phi)
+            want[:, l * l + l + m] = c.real if m == 0 else math.sqrt(2.0) * (-1) ** m * (c.real if m > 0 else c.imag)
+    np.testing.assert_allclose(o.sh16(v), want, atol=1e-12)
+
+
 # ------------------------------------------------------------------ the whole step
+
+def test_loss_scalar_by_hand():
+    """The scalar of Eq. 4 as `forward` assembles it (colour term summed over channels, averaged
+    over rays; eikonal term averaged over samples, times beta), on a scene small enough to do by
+    hand.  One dense level holds (z, 1) at its vertices, so the encoding is e = (z, 1) exactly
+    and de/dx = ((0,0,1),(0,0,0)); a single matrix gives d = 1 - 2 z, so n = (0,0,-2), |n| = 2 and
+    the eikonal term is (2-1)^2 = 1.  The colour network's last matrix is zero: c = sigmoid(0) = 1/2.
+    Ray A: z = 0.475, 0.525 -> d = +0.05, -0.05, s = 20: alpha_0 = 1 - Phi(-1)/Phi(1) = 1 - 1/e,
+    alpha_1 = 0, C = (1 - 1/e)/2 per channel.  Ray B: z = 0.525, 0.475 -> d increases, alpha = 0, C = 0."""
+    cfg = wl.Config(1, 2, 13, 1, "f32", [16], [1], [2, 16], [38, 8, 8, 3], 2, 1, 20.0, 0.1, "hand")
+    tables = np.zeros((1, cfg.table_size, 2))
+    v = np.arange(17 ** 3)
+    tables[0, :17 ** 3, 0] = (v // (17 * 17)) / 16.0
+    tables[0, :17 ** 3, 1] = 1.0
+    H = [np.zeros((16, 2))]
+    H[0][0] = [-2.0, 1.0]
+    rng = np.random.default_rng(0)
+    W = [rng.normal(size=(8, 38)), rng.normal(size=(8, 8)), np.zeros((3, 8))]
+    pos = np.array([[0.3, 0.6, 0.475], [0.3, 0.6, 0.525], [0.7, 0.2, 0.525], [0.7, 0.2, 0.475]])
+    target = np.array([[0.1, 0.5, 0.9], [0.25, 0.0, 0.5]])
+    batch = {"pos": pos, "dirs": np.array([[0.0, 0.0, 1.0], [0.0, 0.0, -1.0]]), "target": target}
+    fw = o.forward(cfg, {"tables": tables, "H": H, "W": W}, batch)
+    np.testing.assert_allclose(fw["y"][:, 0], [0.05, -0.05, -0.05, 0.05], atol=1e-7)      # fp32 grid product
+    np.testing.assert_allclose(fw["normal"], np.tile([0.0, 0.0, -2.0], (4, 1)), atol=1e-6)
+    c_a = 0.5 * 0.6321205588                                   # (1 - 1/e) / 2
+    np.testing.assert_allclose(fw["C"], [[c_a] * 3, [0.0] * 3], atol=1e-7)
+    # colour term: ray A |0.3160603 - (0.1, 0.5, 0.9)| = 0.2160603 + 0.1839397 + 0.5839397 = 0.9839397;
+    # ray B |0 - (0.25, 0, 0.5)| = 0.75; mean over the two rays 0.86696985; eikonal 0.1 * 1
+    assert abs(fw["loss"] - (0.86696985 + 0.1)) < 1e-6
+    cfg.loss_kind, cfg.huber_delta = 2, 0.25
+    fw = o.forward(cfg, {"tables": tables, "H": H, "W": W}, batch)
+    # Huber, delta 1/4: residuals 0.2160603, 0.1839397 are quadratic (r^2/2 = 0.02334103, 0.01691691),
+    # 0.5839397 linear (0.25 (r - 0.125) = 0.11473493); ray B: 0.25 quadratic (0.03125), 0, 0.5 linear (0.09375)
+    want = (0.02334103 + 0.01691691 + 0.11473493 + 0.03125 + 0.0 + 0.09375) / 2 + 0.1
+    assert abs(fw["loss"] - want) < 1e-6
 
 def _fd_param(cfg, params, batch, getter, index, h=1e-6):
     pp, pm = copy.deepcopy(params), copy.deepcopy(params)
@@ -695,6 +761,36 @@ def test_transform_gradient_by_finite_differences():
 
 
 # ------------------------------------------------------------------ Adam
+
+def test_frame_chain_equals_the_accumulated_transform_and_its_gradient_by_finite_differences():
+    """Eq. 9 down the chain of frames against the accumulation rule printed after Eq. 10
+    (R_i^c = R_{i-1}^c R_i, T_i^c = T_i + R_i^{-1} T_{i-1}^c): the two routes to the canonical
+    frame agree; and `pose_gradient` against central differences of a point loss."""
+    rng = np.random.default_rng(12)
+    x = rng.normal(size=(30, 3))
+    omega, T = np.array([0.05, -0.03, 0.02]), np.array([0.01, 0.04, -0.02])
+    R_prev = o.rotation_from_axis_angle(np.array([0.3, 0.1, -0.2]))
+    T_prev = np.array([0.2, -0.1, 0.05])
+    Rc, Tc = o.accumulate_transform(R_prev, T_prev, o.rotation_from_axis_angle(omega), T)
+    np.testing.assert_allclose(o.frame_to_canonical(x, omega, T, R_prev, T_prev), o.rigid_forward(x, Rc, Tc), atol=1e-14)
+    np.testing.assert_allclose(o.frame_to_canonical(x, omega, T, np.eye(3), np.zeros(3)),
+                               o.rigid_forward(x, o.rotation_from_axis_angle(omega), T), atol=1e-14)
+    g = rng.normal(size=(30, 3))
+    loss = lambda w, t: float(np.sum(g * o.frame_to_canonical(x, w, t, R_prev, T_prev)))
+    d_omega, d_T = o.pose_gradient(x, omega, T, R_prev, T_prev, g)
+    h = 1e-6
+    for k in range(3):
+        e = np.zeros(3)
+        e[k] = h
+        assert abs((loss(omega + e, T) - loss(omega - e, T)) / (2 * h) - d_omega[k]) < 1e-7
+        assert abs((loss(omega, T + e) - loss(omega, T - e)) / (2 * h) - d_T[k]) < 1e-7
+    # from the reductions the library keeps: M = sum g (x + Tc)^T and b = sum g give the same gradient
+    M, _, b = o.rigid_backward(x, Rc, Tc, g)
+    R = o.rotation_from_axis_angle(omega)
+    G = R_prev.T @ (M - np.outer(b, R.T @ T_prev))
+    np.testing.assert_allclose(o.axis_angle_gradient(omega, G), d_omega, atol=1e-7)
+    np.testing.assert_allclose(Rc.T @ b, d_T, atol=1e-12)
+
 
 def test_adam_closed_forms():
     g = np.array([0.3, -2.0, 0.0, 1e-8])

@@ -208,6 +208,21 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
                            float* d_tables, float* d_pos, void* workspace, int64_t workspace_bytes,
                            void* stream);
 
+/* neus2_hash_scatter_bwd (without the position gradient) for callers that cannot allocate
+ * device memory or pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results; the record lists live in a
+ * buffer of NEUS2_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
+ * library is used on holds one until the process ends).  The call allocates nothing, on the
+ * device or through any library.  A batch whose lists do not fit (neus2_workspace_bytes minus
+ * the 12 * n_levels * n bytes of its position-gradient part is the need; about 85 000 points
+ * with 16 levels of 2^19 slots, more with fewer hashed levels) is rejected with
+ * NEUS2_ERR_SHAPE and nothing is launched.  All calls on one GPU share the buffer: calls that
+ * overlap in time on one GPU (different streams or threads) race; order them. */
+#define NEUS2_STATIC_SCRATCH_BYTES (128 * 1024 * 1024)
+int neus2_hash_scatter_bwd_static(const neus2_config* cfg, const float* pos, const void* tables,
+                                  const float* q, const float* d_enc, const float* d_normal,
+                                  int64_t n, float* d_tables, void* stream);
+
 /* neus2_render_rays, neus2_loss (loss_kind 1 or 2) and neus2_render_rays_bwd in one launch,
  * same arguments and results (sdf is column 0 of y [device, n*16]); neus2_train_step uses
  * it.  A ray's samples stay in registers between the three stages. */

@@ -71,6 +71,7 @@ _SIGNATURES = {
                                     C.c_int64, _P, _P]),
     "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
     "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
+    "neus2_hash_scatter_bwd_static": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
                                   C.c_float, C.c_int, C.c_int, _P]),
     "neus2_adam_tables": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float,
@@ -228,6 +229,11 @@ def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None
                                         n, _ptr(d_tables), _ptr(d_pos), _ptr(workspace),
                                         workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                         _stream()))
+
+
+def hash_scatter_bwd_static(c, pos, tables, q, d_enc, d_normal, n, d_tables):
+    _check(lib().neus2_hash_scatter_bwd_static(C.byref(c), _ptr(pos), _ptr(tables), _ptr(q), _ptr(d_enc), _ptr(d_normal),
+                                               n, _ptr(d_tables), _stream()))
 
 
 def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_grad=True, lazy=False):

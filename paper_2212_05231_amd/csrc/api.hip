@@ -271,6 +271,69 @@ int neus2_sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tab
 
 }  // extern "C"
 
+// ---- scatter-add for callers that cannot allocate ----------------------------------------------
+// The record lists of the scatter-add live in a file-scope device array instead of a caller's
+// workspace.  Each GPU the library runs on holds its own copy of the array until the process
+// ends; its address on a device is looked up once, with that device current, and from then on
+// host code only ever uses that address (the array's name is not a device address on the host).
+static __device__ __align__(256) unsigned char scratch[NEUS2_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// the device's copy of `scratch`; nullptr and an error message if the runtime refuses
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        fail(NEUS2_ERR_HIP, "no current device (or its number is beyond %d)", kMaxDevices - 1);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            fail(NEUS2_ERR_HIP, "address of the static scratch array on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int neus2_hash_scatter_bwd_static(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
+                                             const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
+                                             void* stream) {
+    NEUS2_TRY(check_config(cfg));
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(pos, "pos"));
+    NEUS2_TRY(check_ptr(tables, "tables"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_ptr(d_tables, "d_tables"));
+    const int64_t need = scatter_records_bytes(cfg, n);
+    if (need > (int64_t)NEUS2_STATIC_SCRATCH_BYTES)
+        return fail(NEUS2_ERR_SHAPE, "n = %lld points with this descriptor need %lld bytes of scratch, the static buffer holds %lld",
+                    (long long)n, (long long)need, (long long)NEUS2_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (need > 0) {
+        ws = static_scratch();
+        if (!ws) return NEUS2_ERR_HIP;
+    }
+    // the header of the buffer (task counter, list cursors) is cleared by a fill kernel inside; the
+    // lists themselves are overwritten up to the cursors, so the last call's contents do not matter
+    return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, nullptr, ws, ws ? (int64_t)NEUS2_STATIC_SCRATCH_BYTES : 0,
+                          false, (hipStream_t)stream);
+}
+
 namespace {
 
 // Every field of the step's buffers that the chosen path will read or write, checked before the

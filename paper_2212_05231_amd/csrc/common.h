@@ -65,6 +65,9 @@ void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* wor
                     float** p, int* count);
 bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes);
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
+// Bytes of workspace the scatter-add needs for n points when no position gradient is wanted
+// (0 if it would take the path without a workspace).
+int64_t scatter_records_bytes(const neus2_config* cfg, int64_t n);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
                    const float* const* H, int64_t n, float* y, float* q, float* normal, uint32_t* masks, hipStream_t st);
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac,

@@ -936,6 +936,13 @@ int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
     return (owner_workspace_need(plan) + 255) / 256 * 256 + (int64_t)cfg->n_levels * n * 12;
 }
 
+int64_t scatter_records_bytes(const neus2_config* cfg, int64_t n) {
+    if (n < kOwnerMinPoints || cfg->active_levels == 0) return 0;
+    bool ok = false;
+    const OwnerPlan plan = make_owner_plan(cfg, n, ok);
+    return ok ? owner_workspace_need(plan) : 0;
+}
+
 bool scatter_gathers_position(const neus2_config* cfg, int64_t n, const void* workspace, int64_t workspace_bytes) {
     if (n < kOwnerMinPoints || !workspace || cfg->active_levels <= cfg->frozen_levels) return false;
     bool ok = false;

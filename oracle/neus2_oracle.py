@@ -586,6 +586,52 @@ def pose_gradient(x, omega, T, R_prev, T_prev, d_xc, h: float = 1e-6):
     return d_omega, d_T
 
 
+def dynamic_frame_iteration(cfg, params, opt, pose, frame_batch, joint: bool, lr: float, pose_lr: float,
+                            b1: float = 0.9, b2: float = 0.99, eps: float = 1e-15, pos_override=None):
+    """One training iteration of a frame of a dynamic scene (Sec. 5; supplement Sec. E.3: the first
+    iterations of a frame optimise the transform alone, `joint` False).
+
+    params: tables (as stored), master (float64 copy of fp16 tables, or None), H, W.
+    opt: Adam state {"t", "m_tables", "v_tables", "m_H", "v_H", "m_W", "v_W"}.
+    pose: {"omega", "T", "m", "v", "t", "R_prev", "T_prev"}.
+    frame_batch: world-space pos [N,3], dirs, target.
+    `pos_override`: the encoder's input positions to use instead of this function's own float64
+    transform rounded to binary32 (the cell of a point is decided in binary32, so a parity test
+    hands both sides the same binary32 positions).
+    Returns (new params, new opt, new pose, the step's outputs); inputs are not modified.
+    """
+    world = np.asarray(frame_batch["pos"], dtype=np.float64)
+    Rc, Tc = accumulate_transform(pose["R_prev"], pose["T_prev"], rotation_from_axis_angle(pose["omega"]), pose["T"])
+    pos = rigid_forward(world, Rc, Tc, 0.5, 0.5).astype(np.float32) if pos_override is None else pos_override
+    out = train_step(cfg, params, {"pos": pos, "dirs": frame_batch["dirs"], "target": frame_batch["target"]}, want_pos_grad=True)
+    d_omega, d_T = pose_gradient(world, pose["omega"], pose["T"], pose["R_prev"], pose["T_prev"], 0.5 * out["dpos"])
+    out["d_pose"] = np.concatenate([d_omega, d_T])
+    t_pose = pose["t"] + 1
+    p6, m6, v6 = adam_step(np.concatenate([pose["omega"], pose["T"]]), out["d_pose"], pose["m"], pose["v"], t_pose, pose_lr, b1, b2, eps)
+    new_pose = dict(pose, omega=p6[:3], T=p6[3:], m=m6, v=v6, t=t_pose)
+    if not joint:
+        return params, opt, new_pose, out
+    t = opt["t"] + 1
+    new_params, new_opt = dict(params), dict(opt, t=t)
+    half = np.asarray(params["tables"]).dtype == np.float16
+    full = params["master"] if half else np.asarray(params["tables"], dtype=np.float64)
+    full, new_opt["m_tables"], new_opt["v_tables"] = adam_step(full, out["dtables"], opt["m_tables"], opt["v_tables"], t, lr, b1, b2, eps)
+    if half:
+        new_params["master"] = full.astype(np.float32).astype(np.float64)          # the master copy is binary32
+        new_params["tables"] = full.astype(np.float32).astype(np.float16)
+    else:
+        new_params["tables"] = full.astype(np.float32)
+    for name, grads in (("H", out["dH"]), ("W", out["dW"])):
+        mats, ms, vs = [], [], []
+        for k, g in enumerate(grads):
+            p1, m1, v1 = adam_step(params[name][k], g, opt["m_" + name][k], opt["v_" + name][k], t, lr, b1, b2, eps)
+            mats.append(p1.astype(np.float32))
+            ms.append(m1)
+            vs.append(v1)
+        new_params[name], new_opt["m_" + name], new_opt["v_" + name] = mats, ms, vs
+    return new_params, new_opt, new_pose, out
+
+
 # --------------------------------------------------------------------------------------
 # Optimiser (the paper names none; the benchmark contract asks for Adam)
 # --------------------------------------------------------------------------------------

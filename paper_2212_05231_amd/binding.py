@@ -327,6 +327,7 @@ class Step:
         self.d_s = self.d_small[s_off:s_off + 1] if learn_s else None
         if learn_s:
             self.s_dev.fill_(cfg.s)
+        self.mat_slices = [(o, tuple(m.shape)) for o, m in zip(offs, mats)]     # where each matrix sits in the flat buffer
         views = [self.small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
         gviews = [self.d_small[o:o + m.numel()].view(m.shape) for o, m in zip(offs, mats)]
         for v, m in zip(views, mats):
@@ -377,6 +378,16 @@ class Step:
             self.ray_offsets.copy_(torch.as_tensor(batch["ray_offsets"], dtype=torch.int32))
             if self.n > 0:
                 self.sample_ray.copy_(torch.as_tensor(batch["sample_ray"], dtype=torch.int32))
+
+    def bind_inputs(self, pos=None, dirs=None, target=None) -> None:
+        """Point the step at other input tensors already on the device (another batch kept
+        resident, a frame of a sequence) instead of copying into its own."""
+        for name, t in (("pos", pos), ("dirs", dirs), ("target", target)):
+            if t is not None:
+                if t.shape != getattr(self, name).shape or t.dtype != getattr(self, name).dtype:
+                    raise ValueError(f"{name}: shape or dtype differs from the step's")
+                setattr(self, name, t)
+                setattr(self.buffers, name, _ptr(t))
 
     def zero_grads(self) -> None:
         self.d_small.zero_()

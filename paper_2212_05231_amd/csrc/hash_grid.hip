@@ -461,18 +461,23 @@ struct OwnerPlan {
     int n_entries;
     int n_tasks;
     int n_listed;                           // entries [0, n_listed) are levels with record lists
+    int n_indexed;                          // entries [n_listed, n_listed + n_indexed) are levels with point lists
+    int seg_points;                         // list entries per task of a level with point lists
+    int idx_capacity[NEUS2_MAX_LEVELS];     // points per list of such a level
+    int64_t idx_base[NEUS2_MAX_LEVELS + 1]; // first list entry of the level's lists; [n_listed + n_indexed] = total
     int first_task[NEUS2_MAX_LEVELS + 1];   // prefix sums over entries, in the order `order`
     short order[NEUS2_MAX_LEVELS];          // entries by falling time of one task
     int capacity[NEUS2_MAX_LEVELS];         // records per list of a listed entry
     int64_t list_base[NEUS2_MAX_LEVELS + 1];// first record of the entry's lists; [n_listed] = total
     short level[NEUS2_MAX_LEVELS];
     short ranges[NEUS2_MAX_LEVELS];
-    short chunks[NEUS2_MAX_LEVELS];
+    int chunks[NEUS2_MAX_LEVELS];           // point chunks of an in-place level, list segments of a level with point lists
     int chunk_points[NEUS2_MAX_LEVELS];     // points per chunk (the last chunk may hold fewer)
 };
 
 struct Records {
-    int* cursor;            // [n_listed][kMaxRanges]
+    int* cursor;            // [n_listed + n_indexed][kMaxRanges]
+    uint32_t* index;        // levels with point lists: per entry [ranges][idx_capacity] point numbers
     uint32_t* slots;        // per entry [ranges][capacity]: local slot of x | local slot of x+1 << 16
     float4* vals;           // per entry [ranges][capacity]: {x f0, x f1, x+1 f0, x+1 f1}
 };
@@ -494,6 +499,81 @@ struct BinSmem {
     int total;
 };
 
+// What one point adds to the two features of corner cr of its cell: w_c dL/de_f + q_f res sum_a dL/dn_a d_a w_c
+// (ax, ay, az = dL/dn times res).
+__device__ __forceinline__ float2 corner_value(const Cell& c, int cr, const float2& de, const float2& qq, float ax, float ay, float az) {
+    const float fx = (cr & 1) ? c.w[0] : 1.f - c.w[0];
+    const float fy = (cr & 2) ? c.w[1] : 1.f - c.w[1];
+    const float fz = (cr & 4) ? c.w[2] : 1.f - c.w[2];
+    const float sx = (cr & 1) ? 1.f : -1.f;
+    const float sy = (cr & 2) ? 1.f : -1.f;
+    const float sz = (cr & 4) ? 1.f : -1.f;
+    const float wk = fx * fy * fz;
+    const float dn = ax * (sx * fy * fz) + ay * (fx * sy * fz) + az * (fx * fy * sz);
+    return make_float2(wk * de.x + qq.x * dn, wk * de.y + qq.y * dn);
+}
+
+// Dense levels with several ranges get POINT lists instead of row records: a point's eight slots are
+// base + {0,1} + {0,s} + {0,s^2}, ascending in the corner number, so the ranges they fall into are
+// ascending too; the point's number is appended to the list of every range that holds one of its
+// corners (one or two for most points).  4 bytes per entry instead of 80 bytes of row records per
+// point, and the owner of a range no longer tests every point of the batch against its range.
+// A list that is full sends the point's corners in that range straight to the gradient.
+__device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Records& rec, const float* __restrict__ pos,
+                           const float* __restrict__ q, const float* __restrict__ d_enc,
+                           const float* __restrict__ d_normal, int64_t n, int point_blocks,
+                           float* __restrict__ d_tables, int* cnt, int* base) {
+    const int e = blockIdx.x / point_blocks;
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
+    const int level = plan.level[e];
+    const int n_ranges = plan.ranges[e];
+    const int capacity = plan.idx_capacity[e];
+    for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) cnt[k] = 0;
+    __syncthreads();
+    const bool valid = i < n;
+    Cell c;
+    int rank[8];
+    uint32_t fresh = 0;                       // bit k: corner k is the first of the point in its range
+    if (valid) {
+        c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            rank[k] = 0;
+            if (k == 0 || (c.slot[k] >> kOwnerSlotBits) != (c.slot[k - 1] >> kOwnerSlotBits)) {
+                fresh |= 1u << k;
+                rank[k] = atomicAdd(&cnt[c.slot[k] >> kOwnerSlotBits], 1);
+            }
+        }
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
+        base[k] = cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], cnt[k]) : 0;
+    __syncthreads();
+    if (!valid) return;
+    uint32_t* lists = rec.index + plan.idx_base[e];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (!((fresh >> k) & 1u)) continue;
+        const uint32_t r = c.slot[k] >> kOwnerSlotBits;
+        const int at = base[r] + rank[k];
+        if (at < capacity) {
+            lists[(size_t)r * capacity + at] = (uint32_t)i;
+        } else {
+            const int64_t o = (int64_t)level * n + i;
+            const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
+            const float2 qq = reinterpret_cast<const float2*>(q)[o];
+            const float fres = (float)g.res[level];
+            const float ax = d_normal[3 * i + 0] * fres, ay = d_normal[3 * i + 1] * fres, az = d_normal[3 * i + 2] * fres;
+            float* gt = d_tables + (size_t)level * g.table_size * 2;
+            for (int cr = k; cr < 8 && (c.slot[cr] >> kOwnerSlotBits) == r; ++cr) {
+                const float2 v = corner_value(c, cr, de, qq, ax, ay, az);
+                atomicAdd(gt + 2 * (size_t)c.slot[cr] + 0, v.x);
+                atomicAdd(gt + 2 * (size_t)c.slot[cr] + 1, v.y);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ q,
@@ -502,6 +582,10 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
                                                               int point_blocks, float* __restrict__ d_tables) {
     __shared__ BinSmem sm;
     const int e = blockIdx.x / point_blocks;
+    if (e >= plan.n_listed) {                 // uniform over the workgroup
+        bin_points(g, plan, rec, pos, q, d_enc, d_normal, n, point_blocks, d_tables, sm.cnt, sm.base);
+        return;
+    }
     const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
     const int level = plan.level[e];
     const int n_ranges = plan.ranges[e];
@@ -630,6 +714,43 @@ struct OwnerSmem {
     int task[2];               // mailbox for the task numbers, see the kernel
 };
 
+// The corners of point i that fall into `range`, added to the range's LDS accumulators.
+struct PointIn {
+    float px, py, pz, ax, ay, az;
+    float2 de, qq;
+};
+
+__device__ __forceinline__ PointIn load_point(int level, int64_t i, int64_t n, float fres, const float* __restrict__ pos,
+                                              const float* __restrict__ q, const float* __restrict__ d_enc,
+                                              const float* __restrict__ d_normal) {
+    PointIn p;
+    const int64_t o = (int64_t)level * n + i;
+    p.de = reinterpret_cast<const float2*>(d_enc)[o];
+    p.qq = reinterpret_cast<const float2*>(q)[o];
+    p.ax = d_normal[3 * i + 0] * fres; p.ay = d_normal[3 * i + 1] * fres; p.az = d_normal[3 * i + 2] * fres;
+    p.px = pos[3 * i + 0]; p.py = pos[3 * i + 1]; p.pz = pos[3 * i + 2];
+    return p;
+}
+
+__device__ __forceinline__ void add_loaded_point(const GridDesc& g, int level, uint32_t range, const PointIn& p, double* acc, int odd) {
+    const Cell c = locate(g, level, p.px, p.py, p.pz);
+#pragma unroll
+    for (int cr = 0; cr < 8; ++cr) {
+        if ((c.slot[cr] >> kOwnerSlotBits) != range) continue;
+        const float2 v = corner_value(c, cr, p.de, p.qq, p.ax, p.ay, p.az);
+        double* a = acc + 2 * (c.slot[cr] & (kOwnerSlots - 1));
+        atomicAdd(a + odd, (double)(odd ? v.y : v.x));
+        atomicAdd(a + (odd ^ 1), (double)(odd ? v.x : v.y));
+    }
+}
+
+__device__ __forceinline__ void add_point_to_range(const GridDesc& g, int level, uint32_t range, int64_t i, int64_t n,
+                                                   const float* __restrict__ pos, const float* __restrict__ q,
+                                                   const float* __restrict__ d_enc, const float* __restrict__ d_normal,
+                                                   double* acc, int odd) {
+    add_loaded_point(g, level, range, load_point(level, i, n, (float)g.res[level], pos, q, d_enc, d_normal), acc, odd);
+}
+
 __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g, OwnerPlan plan, Records rec,
                                                                      const float* __restrict__ pos,
                                                                      const float* __restrict__ q,
@@ -700,6 +821,24 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                     }
                 }
             }
+        } else if (e < plan.n_listed + plan.n_indexed) {
+            // A task of a level with point lists takes one segment of the list of its range: the points
+            // whose cell has a corner in the range.  Two points per thread in flight.
+            const int count = min(rec.cursor[e * kMaxRanges + range], plan.idx_capacity[e]);
+            const uint32_t* list = rec.index + plan.idx_base[e] + (size_t)range * plan.idx_capacity[e];
+            const int seg_begin = chunk * plan.seg_points;
+            const int seg_end = min(seg_begin + plan.seg_points, count);
+            const float fres = (float)g.res[level];
+            for (int j = seg_begin + (int)threadIdx.x; j < seg_end; j += 2 * kOwnerThreads) {
+                const int j2 = j + kOwnerThreads;
+                const bool two = j2 < seg_end;
+                const uint32_t i0 = list[j], i1 = two ? list[j2] : 0u;
+                const PointIn p0 = load_point(level, i0, n, fres, pos, q, d_enc, d_normal);
+                PointIn p1 = p0;
+                if (two) p1 = load_point(level, i1, n, fres, pos, q, d_enc, d_normal);
+                add_loaded_point(g, level, range, p0, acc, odd);
+                if (two) add_loaded_point(g, level, range, p1, acc, odd);
+            }
         } else {
             // In-place path.  A task tests its chunk of the points against its range and adds the
             // corners that fall into it.  On a dense level with several ranges most points of a
@@ -742,30 +881,8 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
                     if (queued >= kOwnerThreads || next >= end) break;
                 }
                 const int queued = sm.queued;
-                for (int j = threadIdx.x; j < queued; j += kOwnerThreads) {
-                    const int64_t i = begin + sm.queue[j];
-                    const int64_t o = (int64_t)level * n + i;
-                    const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-                    const float2 qq = reinterpret_cast<const float2*>(q)[o];
-                    const float ax = d_normal[3 * i + 0] * fres, ay = d_normal[3 * i + 1] * fres, az = d_normal[3 * i + 2] * fres;
-                    const Cell c = locate(g, level, pos[3 * i + 0], pos[3 * i + 1], pos[3 * i + 2]);
-#pragma unroll
-                    for (int cr = 0; cr < 8; ++cr) {
-                        if ((c.slot[cr] >> kOwnerSlotBits) != range) continue;
-                        const float fx = (cr & 1) ? c.w[0] : 1.f - c.w[0];
-                        const float fy = (cr & 2) ? c.w[1] : 1.f - c.w[1];
-                        const float fz = (cr & 4) ? c.w[2] : 1.f - c.w[2];
-                        const float sx = (cr & 1) ? 1.f : -1.f;
-                        const float sy = (cr & 2) ? 1.f : -1.f;
-                        const float sz = (cr & 4) ? 1.f : -1.f;
-                        const float wk = fx * fy * fz;
-                        const float dn = ax * (sx * fy * fz) + ay * (fx * sy * fz) + az * (fx * fy * sz);
-                        double* a = acc + 2 * (c.slot[cr] & (kOwnerSlots - 1));
-                        const float v0 = wk * de.x + qq.x * dn, v1 = wk * de.y + qq.y * dn;
-                        atomicAdd(a + odd, (double)(odd ? v1 : v0));
-                        atomicAdd(a + (odd ^ 1), (double)(odd ? v0 : v1));
-                    }
-                }
+                for (int j = threadIdx.x; j < queued; j += kOwnerThreads)
+                    add_point_to_range(g, level, range, begin + sm.queue[j], n, pos, q, d_enc, d_normal, acc, odd);
                 __syncthreads();
                 if (threadIdx.x == 0) sm.queued = 0;
                 __syncthreads();
@@ -787,28 +904,33 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
     }
 }
 
-// Which levels get record lists, how many ranges and point chunks.  Listed levels (hashed
-// levels with several ranges, dense levels with more than kInPlaceRanges ranges) come first
-// because their tasks are the heaviest.  ok = false if the configuration does not fit the
-// scheme (then the atomic kernel is used).
+// Which levels get record lists, which point lists, how many ranges and point chunks.  Levels with
+// row records (hashed levels with several ranges, dense levels with more than kInPlaceRanges
+// ranges) come first, then the dense levels with point lists (kIndexedMinRanges..kInPlaceRanges
+// ranges), then the levels of one or two ranges, which take the in-place path.  ok = false if the
+// configuration does not fit the scheme (then the atomic kernel is used).
 constexpr int kInPlaceRanges = 64;
+constexpr int kIndexedMinRanges = 3;
+constexpr int kSegPoints = 8192;          // list entries per task of a level with point lists
 
 OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     OwnerPlan p;
     memset(&p, 0, sizeof(p));
     ok = true;
+    p.seg_points = kSegPoints;
     const int64_t T = (int64_t)1 << cfg->log2_table_size;
     if (T > (int64_t)kMaxRanges * kOwnerSlots) ok = false;          // at most kMaxRanges lists per level
     int e = 0, tasks = 0;
-    int64_t records = 0;
+    int64_t records = 0, indices = 0;
     double cost[NEUS2_MAX_LEVELS];
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < 3; ++pass) {
         for (int l = cfg->frozen_levels; l < cfg->active_levels; ++l) {
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
             const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
             const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
             const bool listed = ranges > (cfg->dense[l] ? kInPlaceRanges : 1);
-            if (listed != (pass == 0)) continue;
+            const bool indexed = !listed && cfg->dense[l] && ranges >= kIndexedMinRanges;
+            if ((listed ? 0 : indexed ? 1 : 2) != pass) continue;
             if (listed && !cfg->dense[l] && cfg->res[l] >= kOwnerSlots) ok = false;   // x must not reach the range bits
             int chunks = 1;
             double task_ns = 4000.0 + 1.25 * (4.0 * (double)n / ranges);   // a list: 1.25 ns per record
@@ -820,6 +942,20 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
                 p.capacity[e] = (int)cap;
                 p.list_base[e] = records;
                 records += cap * ranges;
+            } else if (indexed) {
+                // A point enters the lists of the ranges its eight corners fall into: two on average when
+                // a range is thinner than a layer of the grid; the slabs through the middle of the scene
+                // hold several times the average.  Eight times the mean share; the surplus, if any, goes
+                // through atomics.  A task takes kSegPoints entries of one list; tasks beyond the end of
+                // a list find nothing to do.
+                const int64_t cap = (8 * n / ranges + 1023) / 64 * 64;
+                if (cap >= ((int64_t)1 << 31) - 1 || n >= ((int64_t)1 << 32)) ok = false;
+                p.idx_capacity[e] = (int)cap;
+                p.idx_base[e] = indices;
+                indices += cap * ranges;
+                chunks = (int)((cap + kSegPoints - 1) / kSegPoints);
+                if ((int64_t)chunks * ranges > (1 << 20)) ok = false;
+                task_ns = 4000.0 + 7.0 * kSegPoints;
             } else {
                 // Every task tests n / chunks points (0.9 ns each; the corner code runs for a whole
                 // wavefront as soon as one lane is in the range) and adds those in its range
@@ -836,12 +972,13 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
             }
             p.level[e] = (short)l;
             p.ranges[e] = (short)ranges;
-            p.chunks[e] = (short)chunks;
+            p.chunks[e] = chunks;
             p.chunk_points[e] = (int)((n + chunks - 1) / chunks);
             cost[e] = task_ns;
             ++e;
         }
         if (pass == 0) { p.n_listed = e; p.list_base[e] = records; }
+        if (pass == 1) { p.n_indexed = e - p.n_listed; p.idx_base[e] = indices; }
     }
     p.n_entries = e;
     // Workgroups take tasks in this order: the longest first, so that the kernel does not end
@@ -922,7 +1059,7 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
 }
 
 int64_t owner_workspace_need(const OwnerPlan& plan) {
-    return kWorkspaceHeader + plan.list_base[plan.n_listed] * 20 + 256;
+    return kWorkspaceHeader + plan.list_base[plan.n_listed] * 20 + plan.idx_base[plan.n_listed + plan.n_indexed] * 4 + 256;
 }
 
 // scratch of the position-gradient path: part[active levels][n][3], behind the records
@@ -985,12 +1122,13 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             rec.cursor = reinterpret_cast<int*>(ws + kCursorOffset);
             rec.vals = reinterpret_cast<float4*>(ws + kWorkspaceHeader);                         // 16-byte aligned
             rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 16);
+            rec.index = rec.slots + plan.list_base[plan.n_listed];
             if (!header_cleared)                                                                 // task counter and cursors
                 NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));
-            if (plan.n_listed > 0) {
+            if (plan.n_listed + plan.n_indexed > 0) {
                 const int pbs = (int)((n + kBinThreads - 1) / kBinThreads);
-                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * plan.n_listed), dim3(kBinThreads), 0, st, g, plan, rec, pos, q,
-                                   d_enc, d_normal, n, pbs, d_tables);
+                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * (plan.n_listed + plan.n_indexed)), dim3(kBinThreads), 0, st, g, plan,
+                                   rec, pos, q, d_enc, d_normal, n, pbs, d_tables);
             }
             const int wgs = compute_units();
             if (plan.n_tasks > 0)

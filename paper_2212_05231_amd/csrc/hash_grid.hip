@@ -792,6 +792,7 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
         const uint32_t first_slot = range << kOwnerSlotBits;
         const uint32_t slots_here = min((uint32_t)kOwnerSlots, g.table_size - first_slot);
         float* dst = d_tables + ((size_t)level * g.table_size + first_slot) * 2;
+        bool nothing_added = false;
 
         if (e < plan.n_listed) {
             // A listed task streams the list of its range.
@@ -826,8 +827,10 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             // whose cell has a corner in the range.  Two points per thread in flight.
             const int count = min(rec.cursor[e * kMaxRanges + range], plan.idx_capacity[e]);
             const uint32_t* list = rec.index + plan.idx_base[e] + (size_t)range * plan.idx_capacity[e];
+            // the last segment of a range takes whatever lies beyond the finely cut part of the list
             const int seg_begin = chunk * plan.seg_points;
-            const int seg_end = min(seg_begin + plan.seg_points, count);
+            const int seg_end = chunk == n_chunks - 1 ? count : min(seg_begin + plan.seg_points, count);
+            nothing_added = seg_begin >= seg_end;
             const float fres = (float)g.res[level];
             for (int j = seg_begin + (int)threadIdx.x; j < seg_end; j += 2 * kOwnerThreads) {
                 const int j2 = j + kOwnerThreads;
@@ -890,14 +893,17 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             }
         }
         // flush: the LDS image is added to the gradient (several chunks of the points may share a
-        // range of a dense level) and cleared for the next task
+        // range of a dense level) and cleared for the next task; a task that found its segment of a
+        // point list empty has nothing to flush (the same for every thread)
         __syncthreads();
+        if (!nothing_added) {
 #pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            const uint32_t k = threadIdx.x + u * kOwnerThreads;
-            const float v = (float)acc[k];
-            acc[k] = 0.0;
-            if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
+            for (int u = 0; u < kPerThread; ++u) {
+                const uint32_t k = threadIdx.x + u * kOwnerThreads;
+                const float v = (float)acc[k];
+                acc[k] = 0.0;
+                if (k < 2 * slots_here && v != 0.f) atomicAdd(dst + k, v);
+            }
         }
         if (threadIdx.x == 0) sm.task[turn ^ 1] = next_task;
         __syncthreads();
@@ -953,7 +959,14 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
                 p.idx_capacity[e] = (int)cap;
                 p.idx_base[e] = indices;
                 indices += cap * ranges;
-                chunks = (int)((cap + kSegPoints - 1) / kSegPoints);
+                // Tasks: the list is cut finely up to three times its expected length (m n / ranges, where
+                // m = 1 + min(1, s^2 / 8192) is about the number of ranges a point's corners fall into, s^2 the
+                // slots between two layers of the grid); one more task takes the rest, if there is any.
+                const double layers = (double)(r1 * r1) / kOwnerSlots;
+                const double expect = (1.0 + (layers < 1.0 ? layers : 1.0)) * (double)n / ranges;
+                int64_t fine = (int64_t)(3.0 * expect / kSegPoints) + 1;
+                if (fine > (cap + kSegPoints - 1) / kSegPoints) fine = (cap + kSegPoints - 1) / kSegPoints;
+                chunks = (int)fine + 1;
                 if ((int64_t)chunks * ranges > (1 << 20)) ok = false;
                 task_ns = 4000.0 + 7.0 * kSegPoints;
             } else {

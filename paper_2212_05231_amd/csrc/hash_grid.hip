@@ -475,23 +475,84 @@ struct OwnerPlan {
     int chunk_points[NEUS2_MAX_LEVELS];     // points per chunk (the last chunk may hold fewer)
 };
 
+// A row record: what one point adds to the two x corners of one row (y+dy, z+dz) of its cell, in 12
+// bytes.  Four values {x f0, x f1, x+1 f0, x+1 f1} share one exponent and keep 18-bit signed
+// mantissas: value = m * 2^(E - 96 - 17), E chosen from the largest magnitude of the four, so each is
+// off by at most 2^-17 of that largest one (4e-6 rms) - the gradient is compared at 1e-4, and the
+// four products that make up a value already carry binary32 rounding.  The slots: 13 bits for the
+// first corner's slot inside its range, 4 bits for how the second follows from it: code t <= 12:
+// slot ^ (2^(t+1) - 1) (hashed level: x enters the hash by xor, so the two slots differ in the
+// trailing bits in which x and x+1 differ); 15: slot + 1 (dense level); 14: the same slot (dense
+// level, second corner beyond the range: its values are zero here and went to the gradient directly).
+//   a: slot 0..12 | code 13..16 | E 17..23 | m3 low 8 bits 24..31
+//   b: m0 0..17 | m1 low 14 bits 18..31
+//   c: m1 high 4 bits 0..3 | m2 4..21 | m3 high 10 bits 22..31
+// E = 127 marks a record whose values were not finite (or beyond 2^30): it decodes to NaN, so that a
+// broken gradient stays visible.  Magnitudes below 2^-96 are written as zero.
+struct __attribute__((packed, aligned(4))) RowRecord {
+    uint32_t a, b, c;
+};
+
+constexpr int kRecBias = 96;
+constexpr int kRecMant = 17;                       // magnitude bits of a mantissa
+constexpr uint32_t kCodeNext = 15u, kCodeSame = 14u;
+
+__device__ __forceinline__ int sext(uint32_t x, int off, int len) { return (int32_t)(x << (32 - off - len)) >> (32 - len); }
+
+__device__ __forceinline__ RowRecord pack_row(uint32_t slot, uint32_t code, const float4& v) {
+    const float big = fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));   // NaN if any is
+    int e = __builtin_amdgcn_frexp_expf(big);      // big = f 2^e, 0.5 <= f < 1; 0 for big = 0
+    int E = e + kRecBias;
+    int m[4] = {0, 0, 0, 0};
+    if (!(big <= 1.0e9f)) {
+        E = 127;
+    } else if (E < 0 || big == 0.f) {
+        E = 0;
+    } else {
+        const float in[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int r = __float2int_rn(ldexpf(in[k], kRecMant - e));
+            m[k] = min(max(r, -((1 << kRecMant) - 1)), (1 << kRecMant) - 1);
+        }
+    }
+    RowRecord r;
+    r.a = slot | (code << 13) | ((uint32_t)E << 17) | (((uint32_t)m[3] & 0xFFu) << 24);
+    r.b = ((uint32_t)m[0] & 0x3FFFFu) | (((uint32_t)m[1] & 0x3FFFu) << 18);
+    r.c = (((uint32_t)m[1] >> 14) & 0xFu) | (((uint32_t)m[2] & 0x3FFFFu) << 4) | ((((uint32_t)m[3] >> 8) & 0x3FFu) << 22);
+    return r;
+}
+
+__device__ __forceinline__ void unpack_row(const RowRecord& r, uint32_t& s0, uint32_t& s1, float (&v)[4]) {
+    s0 = r.a & (kOwnerSlots - 1);
+    const uint32_t code = (r.a >> 13) & 15u;
+    s1 = code == kCodeNext ? s0 + 1u : code == kCodeSame ? s0 : s0 ^ ((2u << code) - 1u);
+    const int E = (int)((r.a >> 17) & 127u);
+    const int m0 = sext(r.b, 0, 18);
+    const int m1 = (sext(r.c, 0, 4) << 14) | (int)(r.b >> 18);
+    const int m2 = sext(r.c, 4, 18);
+    const int m3 = (sext(r.c, 22, 10) << 8) | (int)(r.a >> 24);
+    // 2^(E - bias - mant) as a float: the exponent field alone (always a normal number)
+    const float scale = E == 127 ? __builtin_nanf("") : __builtin_bit_cast(float, (uint32_t)(E - kRecBias - kRecMant + 127) << 23);
+    v[0] = (float)m0 * scale; v[1] = (float)m1 * scale; v[2] = (float)m2 * scale; v[3] = (float)m3 * scale;
+}
+
 struct Records {
     int* cursor;            // [n_listed + n_indexed][kMaxRanges]
     uint32_t* index;        // levels with point lists: per entry [ranges][idx_capacity] point numbers
-    uint32_t* slots;        // per entry [ranges][capacity]: local slot of x | local slot of x+1 << 16
-    float4* vals;           // per entry [ranges][capacity]: {x f0, x f1, x+1 f0, x+1 f1}
+    RowRecord* rows;        // per entry [ranges][capacity]
 };
 
 // Records of one workgroup are first put in LDS in list order (range by range), then written
 // out by consecutive threads: runs of records of one list leave as whole cache lines instead
 // of one 16-byte piece per lane.
 constexpr int kBinThreads = 512;
-constexpr int kBinRecords = 4 * kBinThreads;
+constexpr int kBinPoints = 1;                       // points per thread
+constexpr int kBinRecords = 4 * kBinPoints * kBinThreads;
 constexpr uint32_t kNoRecord = 0xFFFFFFFFu;
 
 struct BinSmem {
-    float4 vals[kBinRecords];
-    uint32_t slots[kBinRecords];
+    uint32_t ra[kBinRecords], rb[kBinRecords], rc[kBinRecords];   // the staged records, word by word
     uint32_t dest[kBinRecords];          // record index within the entry's lists, kNoRecord if it went elsewhere
     int cnt[kMaxRanges];                 // records of this workgroup per range
     int base[kMaxRanges];                // first position of this workgroup in the list of the range
@@ -524,10 +585,12 @@ __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Recor
                            const float* __restrict__ d_normal, int64_t n, int point_blocks,
                            float* __restrict__ d_tables, int* cnt, int* base) {
     const int e = blockIdx.x / point_blocks;
-    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
     const int level = plan.level[e];
     const int n_ranges = plan.ranges[e];
     const int capacity = plan.idx_capacity[e];
+    for (int pt = 0; pt < kBinPoints; ++pt) {          // a workgroup's points, kBinThreads at a time
+    const int64_t i = ((int64_t)(blockIdx.x % point_blocks) * kBinPoints + pt) * kBinThreads + threadIdx.x;
+    __syncthreads();
     for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) cnt[k] = 0;
     __syncthreads();
     const bool valid = i < n;
@@ -549,7 +612,7 @@ __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Recor
     for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
         base[k] = cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], cnt[k]) : 0;
     __syncthreads();
-    if (!valid) return;
+    if (!valid) continue;
     uint32_t* lists = rec.index + plan.idx_base[e];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -572,6 +635,7 @@ __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Recor
             }
         }
     }
+    }
 }
 
 __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
@@ -586,20 +650,26 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
         bin_points(g, plan, rec, pos, q, d_enc, d_normal, n, point_blocks, d_tables, sm.cnt, sm.base);
         return;
     }
-    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
+    const int64_t first_point = (int64_t)(blockIdx.x % point_blocks) * (kBinPoints * kBinThreads);
     const int level = plan.level[e];
     const int n_ranges = plan.ranges[e];
     const int capacity = plan.capacity[e];
     for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) sm.cnt[k] = 0;
     __syncthreads();
 
-    const bool valid = i < n;
-    uint32_t range[4], packed[4];
-    float4 val[4];
-    int rank[4];
-    if (valid) {
-        const int res = g.res[level];
-        const float fres = (float)res;
+    uint32_t range[kBinPoints][4];
+    RowRecord row_rec[kBinPoints][4];
+    int rank[kBinPoints][4];
+    bool valid[kBinPoints];
+    const int res = g.res[level];
+    const float fres = (float)res;
+    const bool dense = (g.dense_bits >> level) & 1u;
+    const uint32_t stride = (uint32_t)res + 1u;
+#pragma unroll
+    for (int pt = 0; pt < kBinPoints; ++pt) {
+        const int64_t i = first_point + pt * kBinThreads + threadIdx.x;
+        valid[pt] = i < n;
+        if (!valid[pt]) continue;
         const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
         const int cx = min((int)floorf(gx), res - 1);
         const int cy = min((int)floorf(gy), res - 1);
@@ -610,8 +680,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
         const float2 qq = reinterpret_cast<const float2*>(q)[o];
         const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
         const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
-        const bool dense = (g.dense_bits >> level) & 1u;
-        const uint32_t stride = (uint32_t)res + 1u;
+        // the trailing bits in which x and x + 1 differ: 2^(t+1) - 1, t = number of trailing ones of x
+        const uint32_t code_x = 31u - (uint32_t)__clz((int)((uint32_t)cx ^ ((uint32_t)cx + 1u)));
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
             const int dy = row & 1, dz = row >> 1;
@@ -621,30 +691,32 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
             const float fyz = fy * fz;
             const float dn_x = nx * fyz;
             const float dn_yz = ny * (sy * fz) + nz * (fy * sz);
-            uint32_t s0, s1;
+            uint32_t s0, s1, code;
             if (dense) {
                 s0 = (uint32_t)cx + ((uint32_t)(cy + dy) + (uint32_t)(cz + dz) * stride) * stride;
                 s1 = s0 + 1u;
+                code = kCodeNext;
             } else {
                 s0 = ((uint32_t)cx ^ rh) & g.table_mask;
                 s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
+                code = code_x;
             }
             const float f0 = 1.f - w0, f1 = w0;
             const float dn0 = -dn_x + f0 * dn_yz, dn1 = dn_x + f1 * dn_yz;
             const float wk0 = f0 * fyz, wk1 = f1 * fyz;
-            val[row] = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
-            range[row] = s0 >> kOwnerSlotBits;
+            float4 val = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
+            range[pt][row] = s0 >> kOwnerSlotBits;
             // On a hashed level both corners share the range.  On a dense level the x+1 corner can be
             // the first slot of the next range (1 row in 8192): it then goes straight to the gradient.
-            if ((s1 >> kOwnerSlotBits) != range[row]) {
+            if ((s1 >> kOwnerSlotBits) != range[pt][row]) {
                 float* gt = d_tables + ((size_t)level * g.table_size + s1) * 2;
-                atomicAdd(gt + 0, val[row].z);
-                atomicAdd(gt + 1, val[row].w);
-                val[row].z = 0.f; val[row].w = 0.f;
-                s1 = s0;
+                atomicAdd(gt + 0, val.z);
+                atomicAdd(gt + 1, val.w);
+                val.z = 0.f; val.w = 0.f;
+                code = kCodeSame;
             }
-            packed[row] = (s0 & (kOwnerSlots - 1)) | ((s1 & (kOwnerSlots - 1)) << 16);
-            rank[row] = atomicAdd(&sm.cnt[range[row]], 1);
+            row_rec[pt][row] = pack_row(s0 & (kOwnerSlots - 1), code, val);
+            rank[pt][row] = atomicAdd(&sm.cnt[range[pt][row]], 1);
         }
     }
     __syncthreads();
@@ -669,35 +741,39 @@ __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, Owner
         if (lane == 63) sm.total = incl;
     }
     __syncthreads();
-    if (valid) {
+#pragma unroll
+    for (int pt = 0; pt < kBinPoints; ++pt) {
+        if (!valid[pt]) continue;
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
-            const int r = (int)range[row];
-            const int in_list = sm.base[r] + rank[row];
-            const int at = sm.first[r] + rank[row];
-            sm.vals[at] = val[row];
-            sm.slots[at] = packed[row];
+            const int r = (int)range[pt][row];
+            const int in_list = sm.base[r] + rank[pt][row];
+            const int at = sm.first[r] + rank[pt][row];
+            sm.ra[at] = row_rec[pt][row].a; sm.rb[at] = row_rec[pt][row].b; sm.rc[at] = row_rec[pt][row].c;
             if (in_list < capacity) {
                 sm.dest[at] = (uint32_t)r * (uint32_t)capacity + (uint32_t)in_list;
             } else {                                                 // list full: straight to the global gradient
                 sm.dest[at] = kNoRecord;
+                uint32_t s0, s1;
+                float v[4];
+                unpack_row(row_rec[pt][row], s0, s1, v);
                 float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)r << kOwnerSlotBits)) * 2;
-                atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 0, val[row].x);
-                atomicAdd(gt + 2 * (packed[row] & 0xFFFFu) + 1, val[row].y);
-                atomicAdd(gt + 2 * (packed[row] >> 16) + 0, val[row].z);
-                atomicAdd(gt + 2 * (packed[row] >> 16) + 1, val[row].w);
+                atomicAdd(gt + 2 * s0 + 0, v[0]);
+                atomicAdd(gt + 2 * s0 + 1, v[1]);
+                atomicAdd(gt + 2 * s1 + 0, v[2]);
+                atomicAdd(gt + 2 * s1 + 1, v[3]);
             }
         }
     }
     __syncthreads();
     const int total = sm.total;
-    uint32_t* out_slots = rec.slots + plan.list_base[e];
-    float4* out_vals = rec.vals + plan.list_base[e];
+    RowRecord* out = rec.rows + plan.list_base[e];
     for (int at = threadIdx.x; at < total; at += kBinThreads) {
         const uint32_t d = sm.dest[at];
         if (d != kNoRecord) {
-            out_slots[d] = sm.slots[at];
-            out_vals[d] = sm.vals[at];
+            RowRecord r;
+            r.a = sm.ra[at]; r.b = sm.rb[at]; r.c = sm.rc[at];
+            out[d] = r;
         }
     }
 }
@@ -798,27 +874,28 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             // A listed task streams the list of its range.
             const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity[e]);
             const size_t at = (size_t)plan.list_base[e] + (size_t)range * plan.capacity[e];
-            const uint32_t* rs = rec.slots + at;
-            const float4* rv = rec.vals + at;
+            const RowRecord* rs = rec.rows + at;
             // four records per thread in flight: the list is streamed from HBM
             constexpr int kAhead = 4;
             for (int j0 = threadIdx.x; j0 < count; j0 += kAhead * kOwnerThreads) {
-                uint32_t sl[kAhead];
-                float4 v[kAhead];
+                RowRecord rr[kAhead];
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
                     const int j = j0 + k * kOwnerThreads;
-                    if (j < count) { sl[k] = rs[j]; v[k] = rv[j]; }
+                    if (j < count) rr[k] = rs[j];
                 }
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
                     if (j0 + k * kOwnerThreads < count) {
-                        double* a0 = acc + 2 * (sl[k] & 0xFFFFu);
-                        double* a1 = acc + 2 * (sl[k] >> 16);
-                        atomicAdd(a0 + odd, (double)(odd ? v[k].y : v[k].x));
-                        atomicAdd(a0 + (odd ^ 1), (double)(odd ? v[k].x : v[k].y));
-                        atomicAdd(a1 + odd, (double)(odd ? v[k].w : v[k].z));
-                        atomicAdd(a1 + (odd ^ 1), (double)(odd ? v[k].z : v[k].w));
+                        uint32_t s0, s1;
+                        float v[4];
+                        unpack_row(rr[k], s0, s1, v);
+                        double* a0 = acc + 2 * s0;
+                        double* a1 = acc + 2 * s1;
+                        atomicAdd(a0 + odd, (double)(odd ? v[1] : v[0]));
+                        atomicAdd(a0 + (odd ^ 1), (double)(odd ? v[0] : v[1]));
+                        atomicAdd(a1 + odd, (double)(odd ? v[3] : v[2]));
+                        atomicAdd(a1 + (odd ^ 1), (double)(odd ? v[2] : v[3]));
                     }
                 }
             }
@@ -1072,7 +1149,7 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
 }
 
 int64_t owner_workspace_need(const OwnerPlan& plan) {
-    return kWorkspaceHeader + plan.list_base[plan.n_listed] * 20 + plan.idx_base[plan.n_listed + plan.n_indexed] * 4 + 256;
+    return kWorkspaceHeader + plan.list_base[plan.n_listed] * 12 + plan.idx_base[plan.n_listed + plan.n_indexed] * 4 + 256;
 }
 
 // scratch of the position-gradient path: part[active levels][n][3], behind the records
@@ -1133,13 +1210,12 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             int* counter = reinterpret_cast<int*>(ws);
             Records rec;
             rec.cursor = reinterpret_cast<int*>(ws + kCursorOffset);
-            rec.vals = reinterpret_cast<float4*>(ws + kWorkspaceHeader);                         // 16-byte aligned
-            rec.slots = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 16);
-            rec.index = rec.slots + plan.list_base[plan.n_listed];
+            rec.rows = reinterpret_cast<RowRecord*>(ws + kWorkspaceHeader);
+            rec.index = reinterpret_cast<uint32_t*>(ws + kWorkspaceHeader + plan.list_base[plan.n_listed] * 12);
             if (!header_cleared)                                                                 // task counter and cursors
                 NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));
             if (plan.n_listed + plan.n_indexed > 0) {
-                const int pbs = (int)((n + kBinThreads - 1) / kBinThreads);
+                const int pbs = (int)((n + kBinPoints * kBinThreads - 1) / (kBinPoints * kBinThreads));
                 hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * (plan.n_listed + plan.n_indexed)), dim3(kBinThreads), 0, st, g, plan,
                                    rec, pos, q, d_enc, d_normal, n, pbs, d_tables);
             }

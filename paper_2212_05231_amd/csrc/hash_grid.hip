@@ -547,8 +547,7 @@ struct Records {
 // out by consecutive threads: runs of records of one list leave as whole cache lines instead
 // of one 16-byte piece per lane.
 constexpr int kBinThreads = 512;
-constexpr int kBinPoints = 1;                       // points per thread
-constexpr int kBinRecords = 4 * kBinPoints * kBinThreads;
+constexpr int kBinRecords = 4 * kBinThreads;
 constexpr uint32_t kNoRecord = 0xFFFFFFFFu;
 
 struct BinSmem {
@@ -582,15 +581,12 @@ __device__ __forceinline__ float2 corner_value(const Cell& c, int cr, const floa
 // A list that is full sends the point's corners in that range straight to the gradient.
 __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Records& rec, const float* __restrict__ pos,
                            const float* __restrict__ q, const float* __restrict__ d_enc,
-                           const float* __restrict__ d_normal, int64_t n, int point_blocks,
+                           const float* __restrict__ d_normal, int64_t n, int point_blocks, int e,
                            float* __restrict__ d_tables, int* cnt, int* base) {
-    const int e = blockIdx.x / point_blocks;
     const int level = plan.level[e];
     const int n_ranges = plan.ranges[e];
     const int capacity = plan.idx_capacity[e];
-    for (int pt = 0; pt < kBinPoints; ++pt) {          // a workgroup's points, kBinThreads at a time
-    const int64_t i = ((int64_t)(blockIdx.x % point_blocks) * kBinPoints + pt) * kBinThreads + threadIdx.x;
-    __syncthreads();
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
     for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) cnt[k] = 0;
     __syncthreads();
     const bool valid = i < n;
@@ -612,7 +608,7 @@ __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Recor
     for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
         base[k] = cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], cnt[k]) : 0;
     __syncthreads();
-    if (!valid) continue;
+    if (!valid) return;
     uint32_t* lists = rec.index + plan.idx_base[e];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -635,146 +631,162 @@ __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Recor
             }
         }
     }
-    }
 }
 
+// A workgroup takes 512 points and walks over a share of the levels with row records (levels
+// grp, grp + level_groups, ...): position and dL/dn are fetched once, and the next level's dL/de and
+// dd/de are requested before the current level's records are made, so that only the first level of a
+// workgroup waits for memory.  Workgroups beyond the level groups handle the levels with point lists.
 __global__ __launch_bounds__(kBinThreads) void bin_rows_kernel(GridDesc g, OwnerPlan plan, Records rec,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ q,
                                                               const float* __restrict__ d_enc,
                                                               const float* __restrict__ d_normal, int64_t n,
-                                                              int point_blocks, float* __restrict__ d_tables) {
+                                                              int point_blocks, int level_groups,
+                                                              float* __restrict__ d_tables) {
     __shared__ BinSmem sm;
-    const int e = blockIdx.x / point_blocks;
-    if (e >= plan.n_listed) {                 // uniform over the workgroup
-        bin_points(g, plan, rec, pos, q, d_enc, d_normal, n, point_blocks, d_tables, sm.cnt, sm.base);
+    const int grp = blockIdx.x / point_blocks;
+    if (grp >= level_groups) {                // uniform over the workgroup
+        bin_points(g, plan, rec, pos, q, d_enc, d_normal, n, point_blocks, plan.n_listed + grp - level_groups, d_tables, sm.cnt,
+                   sm.base);
         return;
     }
-    const int64_t first_point = (int64_t)(blockIdx.x % point_blocks) * (kBinPoints * kBinThreads);
-    const int level = plan.level[e];
-    const int n_ranges = plan.ranges[e];
-    const int capacity = plan.capacity[e];
-    for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) sm.cnt[k] = 0;
-    __syncthreads();
+    const int64_t i = (int64_t)(blockIdx.x % point_blocks) * kBinThreads + threadIdx.x;
+    const bool valid = i < n;
+    float px = 0.f, py = 0.f, pz = 0.f, dnx = 0.f, dny = 0.f, dnz = 0.f;
+    float2 de_next = make_float2(0.f, 0.f), q_next = make_float2(0.f, 0.f);
+    if (valid) {
+        px = pos[3 * i + 0]; py = pos[3 * i + 1]; pz = pos[3 * i + 2];
+        dnx = d_normal[3 * i + 0]; dny = d_normal[3 * i + 1]; dnz = d_normal[3 * i + 2];
+        const int64_t o = (int64_t)plan.level[grp] * n + i;
+        de_next = reinterpret_cast<const float2*>(d_enc)[o];
+        q_next = reinterpret_cast<const float2*>(q)[o];
+    }
+    for (int e = grp; e < plan.n_listed; e += level_groups) {
+        const int level = plan.level[e];
+        const int n_ranges = plan.ranges[e];
+        const int capacity = plan.capacity[e];
+        const float2 de = de_next, qq = q_next;
+        if (valid && e + level_groups < plan.n_listed) {
+            const int64_t o = (int64_t)plan.level[e + level_groups] * n + i;
+            de_next = reinterpret_cast<const float2*>(d_enc)[o];
+            q_next = reinterpret_cast<const float2*>(q)[o];
+        }
+        for (int k = threadIdx.x; k < kMaxRanges; k += kBinThreads) sm.cnt[k] = 0;
+        __syncthreads();
 
-    uint32_t range[kBinPoints][4];
-    RowRecord row_rec[kBinPoints][4];
-    int rank[kBinPoints][4];
-    bool valid[kBinPoints];
-    const int res = g.res[level];
-    const float fres = (float)res;
-    const bool dense = (g.dense_bits >> level) & 1u;
-    const uint32_t stride = (uint32_t)res + 1u;
+        uint32_t range[4];
+        RowRecord row_rec[4];
+        int rank[4];
+        if (valid) {
+            const int res = g.res[level];
+            const float fres = (float)res;
+            const bool dense = (g.dense_bits >> level) & 1u;
+            const uint32_t stride = (uint32_t)res + 1u;
+            const float gx = grid_coord(px, fres), gy = grid_coord(py, fres), gz = grid_coord(pz, fres);
+            const int cx = min((int)floorf(gx), res - 1);
+            const int cy = min((int)floorf(gy), res - 1);
+            const int cz = min((int)floorf(gz), res - 1);
+            const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
+            const float nx = dnx * fres, ny = dny * fres, nz = dnz * fres;
+            const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
+            // the trailing bits in which x and x + 1 differ: 2^(t+1) - 1, t = number of trailing ones of x
+            const uint32_t code_x = 31u - (uint32_t)__clz((int)((uint32_t)cx ^ ((uint32_t)cx + 1u)));
 #pragma unroll
-    for (int pt = 0; pt < kBinPoints; ++pt) {
-        const int64_t i = first_point + pt * kBinThreads + threadIdx.x;
-        valid[pt] = i < n;
-        if (!valid[pt]) continue;
-        const float gx = grid_coord(pos[3 * i + 0], fres), gy = grid_coord(pos[3 * i + 1], fres), gz = grid_coord(pos[3 * i + 2], fres);
-        const int cx = min((int)floorf(gx), res - 1);
-        const int cy = min((int)floorf(gy), res - 1);
-        const int cz = min((int)floorf(gz), res - 1);
-        const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
-        const int64_t o = (int64_t)level * n + i;
-        const float2 de = reinterpret_cast<const float2*>(d_enc)[o];
-        const float2 qq = reinterpret_cast<const float2*>(q)[o];
-        const float nx = d_normal[3 * i + 0] * fres, ny = d_normal[3 * i + 1] * fres, nz = d_normal[3 * i + 2] * fres;
-        const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
-        // the trailing bits in which x and x + 1 differ: 2^(t+1) - 1, t = number of trailing ones of x
-        const uint32_t code_x = 31u - (uint32_t)__clz((int)((uint32_t)cx ^ ((uint32_t)cx + 1u)));
-#pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            const int dy = row & 1, dz = row >> 1;
-            const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
-            const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
-            const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
-            const float fyz = fy * fz;
-            const float dn_x = nx * fyz;
-            const float dn_yz = ny * (sy * fz) + nz * (fy * sz);
-            uint32_t s0, s1, code;
-            if (dense) {
-                s0 = (uint32_t)cx + ((uint32_t)(cy + dy) + (uint32_t)(cz + dz) * stride) * stride;
-                s1 = s0 + 1u;
-                code = kCodeNext;
-            } else {
-                s0 = ((uint32_t)cx ^ rh) & g.table_mask;
-                s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
-                code = code_x;
-            }
-            const float f0 = 1.f - w0, f1 = w0;
-            const float dn0 = -dn_x + f0 * dn_yz, dn1 = dn_x + f1 * dn_yz;
-            const float wk0 = f0 * fyz, wk1 = f1 * fyz;
-            float4 val = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
-            range[pt][row] = s0 >> kOwnerSlotBits;
-            // On a hashed level both corners share the range.  On a dense level the x+1 corner can be
-            // the first slot of the next range (1 row in 8192): it then goes straight to the gradient.
-            if ((s1 >> kOwnerSlotBits) != range[pt][row]) {
-                float* gt = d_tables + ((size_t)level * g.table_size + s1) * 2;
-                atomicAdd(gt + 0, val.z);
-                atomicAdd(gt + 1, val.w);
-                val.z = 0.f; val.w = 0.f;
-                code = kCodeSame;
-            }
-            row_rec[pt][row] = pack_row(s0 & (kOwnerSlots - 1), code, val);
-            rank[pt][row] = atomicAdd(&sm.cnt[range[pt][row]], 1);
-        }
-    }
-    __syncthreads();
-    // one reservation per range in the global list, and the staged order: ranges one after another
-    for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
-        sm.base[k] = sm.cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], sm.cnt[k]) : 0;
-    if (threadIdx.x >= kBinThreads - 64) {               // the last wavefront: exclusive prefix sums of cnt
-        const int lane = threadIdx.x & 63;
-        constexpr int kPer = kMaxRanges / 64;
-        int c[kPer], sum = 0;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) { c[j] = sm.cnt[kPer * lane + j]; sum += c[j]; }
-        int incl = sum;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int o = __shfl_up(incl, d);
-            if (lane >= d) incl += o;
-        }
-        int at = incl - sum;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) { sm.first[kPer * lane + j] = at; at += c[j]; }
-        if (lane == 63) sm.total = incl;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int pt = 0; pt < kBinPoints; ++pt) {
-        if (!valid[pt]) continue;
-#pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            const int r = (int)range[pt][row];
-            const int in_list = sm.base[r] + rank[pt][row];
-            const int at = sm.first[r] + rank[pt][row];
-            sm.ra[at] = row_rec[pt][row].a; sm.rb[at] = row_rec[pt][row].b; sm.rc[at] = row_rec[pt][row].c;
-            if (in_list < capacity) {
-                sm.dest[at] = (uint32_t)r * (uint32_t)capacity + (uint32_t)in_list;
-            } else {                                                 // list full: straight to the global gradient
-                sm.dest[at] = kNoRecord;
-                uint32_t s0, s1;
-                float v[4];
-                unpack_row(row_rec[pt][row], s0, s1, v);
-                float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)r << kOwnerSlotBits)) * 2;
-                atomicAdd(gt + 2 * s0 + 0, v[0]);
-                atomicAdd(gt + 2 * s0 + 1, v[1]);
-                atomicAdd(gt + 2 * s1 + 0, v[2]);
-                atomicAdd(gt + 2 * s1 + 1, v[3]);
+            for (int row = 0; row < 4; ++row) {
+                const int dy = row & 1, dz = row >> 1;
+                const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
+                const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
+                const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
+                const float fyz = fy * fz;
+                const float dn_x = nx * fyz;
+                const float dn_yz = ny * (sy * fz) + nz * (fy * sz);
+                uint32_t s0, s1, code;
+                if (dense) {
+                    s0 = (uint32_t)cx + ((uint32_t)(cy + dy) + (uint32_t)(cz + dz) * stride) * stride;
+                    s1 = s0 + 1u;
+                    code = kCodeNext;
+                } else {
+                    s0 = ((uint32_t)cx ^ rh) & g.table_mask;
+                    s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
+                    code = code_x;
+                }
+                const float f0 = 1.f - w0, f1 = w0;
+                const float dn0 = -dn_x + f0 * dn_yz, dn1 = dn_x + f1 * dn_yz;
+                const float wk0 = f0 * fyz, wk1 = f1 * fyz;
+                float4 val = make_float4(wk0 * de.x + qq.x * dn0, wk0 * de.y + qq.y * dn0, wk1 * de.x + qq.x * dn1, wk1 * de.y + qq.y * dn1);
+                range[row] = s0 >> kOwnerSlotBits;
+                // On a hashed level both corners share the range.  On a dense level the x+1 corner can be
+                // the first slot of the next range (1 row in 8192): it then goes straight to the gradient.
+                if ((s1 >> kOwnerSlotBits) != range[row]) {
+                    float* gt = d_tables + ((size_t)level * g.table_size + s1) * 2;
+                    atomicAdd(gt + 0, val.z);
+                    atomicAdd(gt + 1, val.w);
+                    val.z = 0.f; val.w = 0.f;
+                    code = kCodeSame;
+                }
+                row_rec[row] = pack_row(s0 & (kOwnerSlots - 1), code, val);
+                rank[row] = atomicAdd(&sm.cnt[range[row]], 1);
             }
         }
-    }
-    __syncthreads();
-    const int total = sm.total;
-    RowRecord* out = rec.rows + plan.list_base[e];
-    for (int at = threadIdx.x; at < total; at += kBinThreads) {
-        const uint32_t d = sm.dest[at];
-        if (d != kNoRecord) {
-            RowRecord r;
-            r.a = sm.ra[at]; r.b = sm.rb[at]; r.c = sm.rc[at];
-            out[d] = r;
+        __syncthreads();
+        // one reservation per range in the global list, and the staged order: ranges one after another
+        for (int k = threadIdx.x; k < n_ranges; k += kBinThreads)
+            sm.base[k] = sm.cnt[k] ? atomicAdd(&rec.cursor[e * kMaxRanges + k], sm.cnt[k]) : 0;
+        if (threadIdx.x >= kBinThreads - 64) {               // the last wavefront: exclusive prefix sums of cnt
+            const int lane = threadIdx.x & 63;
+            constexpr int kPer = kMaxRanges / 64;
+            int c[kPer], sum = 0;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) { c[j] = sm.cnt[kPer * lane + j]; sum += c[j]; }
+            int incl = sum;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int o = __shfl_up(incl, d);
+                if (lane >= d) incl += o;
+            }
+            int at = incl - sum;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) { sm.first[kPer * lane + j] = at; at += c[j]; }
+            if (lane == 63) sm.total = incl;
         }
+        __syncthreads();
+        if (valid) {
+#pragma unroll
+            for (int row = 0; row < 4; ++row) {
+                const int r = (int)range[row];
+                const int in_list = sm.base[r] + rank[row];
+                const int at = sm.first[r] + rank[row];
+                sm.ra[at] = row_rec[row].a; sm.rb[at] = row_rec[row].b; sm.rc[at] = row_rec[row].c;
+                if (in_list < capacity) {
+                    sm.dest[at] = (uint32_t)r * (uint32_t)capacity + (uint32_t)in_list;
+                } else {                                                 // list full: straight to the global gradient
+                    sm.dest[at] = kNoRecord;
+                    uint32_t s0, s1;
+                    float v[4];
+                    unpack_row(row_rec[row], s0, s1, v);
+                    float* gt = d_tables + ((size_t)level * g.table_size + ((size_t)r << kOwnerSlotBits)) * 2;
+                    atomicAdd(gt + 2 * s0 + 0, v[0]);
+                    atomicAdd(gt + 2 * s0 + 1, v[1]);
+                    atomicAdd(gt + 2 * s1 + 0, v[2]);
+                    atomicAdd(gt + 2 * s1 + 1, v[3]);
+                }
+            }
+        }
+        __syncthreads();
+        const int total = sm.total;
+        RowRecord* out = rec.rows + plan.list_base[e];
+        for (int at = threadIdx.x; at < total; at += kBinThreads) {
+            const uint32_t d = sm.dest[at];
+            if (d != kNoRecord) {
+                RowRecord r;
+                r.a = sm.ra[at]; r.b = sm.rb[at]; r.c = sm.rc[at];
+                out[d] = r;
+            }
+        }
+        // the next round writes cnt only after the barrier that follows its clearing, base/first/total
+        // after the one behind its ranks, and the staged records after a third: every thread has left
+        // this loop by then
     }
 }
 
@@ -1215,9 +1227,13 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             if (!header_cleared)                                                                 // task counter and cursors
                 NEUS2_TRY(launch_zero(reinterpret_cast<float*>(ws), kWorkspaceHeader / 4, st));
             if (plan.n_listed + plan.n_indexed > 0) {
-                const int pbs = (int)((n + kBinPoints * kBinThreads - 1) / (kBinPoints * kBinThreads));
-                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * (plan.n_listed + plan.n_indexed)), dim3(kBinThreads), 0, st, g, plan,
-                                   rec, pos, q, d_enc, d_normal, n, pbs, d_tables);
+                const int pbs = (int)((n + kBinThreads - 1) / kBinThreads);
+                // enough workgroups to fill the chip several times over; each walks over its share of the levels
+                int groups = (8 * compute_units() + pbs - 1) / pbs;
+                if (groups > plan.n_listed) groups = plan.n_listed;
+                if (groups < 1 && plan.n_listed > 0) groups = 1;
+                hipLaunchKernelGGL(bin_rows_kernel, dim3(pbs * (groups + plan.n_indexed)), dim3(kBinThreads), 0, st, g, plan,
+                                   rec, pos, q, d_enc, d_normal, n, pbs, groups, d_tables);
             }
             const int wgs = compute_units();
             if (plan.n_tasks > 0)

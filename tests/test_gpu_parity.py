@@ -179,6 +179,41 @@ def test_hash_encode_indices_bit_exact_and_values(k, n_rays):
     np.testing.assert_allclose(from_level_major(enc, n), ref["enc"], rtol=FWD_TOL, atol=1e-9)
 
 
+def test_hash_encode_of_tables_larger_than_the_cache_slice_by_slice():
+    """Workload 4's tables (2^21 entries a level, 8 MiB in fp16) at a batch large enough for the kernel that
+    gathers the hashed levels slice by slice; every value and every Jacobian entry against the oracle,
+    with edge positions and a ragged last tile."""
+    w = wl.make_workload(4, n_rays=4096 + 3)
+    cfg, params, batch = w["cfg"], w["params"], w["batch"]
+    pos = batch["pos"][:262144 + 77].copy()
+    pos[:4] = np.array([[0, 0, 0], [1, 1, 1], [1 - 2.0 ** -24, 0.5, 0.25], [np.nan, -1.0, 2.0]], dtype=np.float32)
+    n = pos.shape[0]
+    c = nb.make_config(cfg)
+    L = cfg.n_levels
+    tables = cuda(params["tables"], torch.float16)
+    enc = torch.full((L, n, 2), 7.0, device="cuda")
+    jac = torch.full((L, 3, n, 2), 7.0, device="cuda")
+    nb.hash_encode(c, cuda(pos), tables, enc, jac)
+    torch.cuda.synchronize()
+    ref = o.hash_encode(cfg, params["tables"], pos)
+    assert rel(from_level_major(enc, n), ref["enc"]) <= FWD_TOL
+    assert rel(jac_from_level_major(jac, n), ref["jac"]) <= FWD_TOL
+    np.testing.assert_allclose(from_level_major(enc, n), ref["enc"], rtol=FWD_TOL, atol=1e-9)
+    got_j, want_j = jac_from_level_major(jac, n), ref["jac"]
+    for l in range(L):
+        sl = slice(2 * l, 2 * l + 2)
+        np.testing.assert_allclose(got_j[:, sl], want_j[:, sl], rtol=FWD_TOL, atol=1e-9 * cfg.res[l])
+    # the same through fp32 tables (slices of 2 MiB: eight of them)
+    cfg.table_dtype = "f32"
+    c = nb.make_config(cfg)
+    tab32 = params["tables"].astype(np.float32) * np.float32(1.37)
+    nb.hash_encode(c, cuda(pos), cuda(tab32), enc, jac)
+    torch.cuda.synchronize()
+    ref = o.hash_encode(cfg, tab32, pos)
+    assert rel(from_level_major(enc, n), ref["enc"]) <= FWD_TOL
+    assert rel(jac_from_level_major(jac, n), ref["jac"]) <= FWD_TOL
+
+
 def test_fp16_subnormal_table_entries_are_not_flushed():
     cfg = wl.make_config(2)
     c = nb.make_config(cfg)

@@ -167,7 +167,8 @@ struct LevelSchedule {
 // block index -> (level, point block); returns false for padding blocks.  Every index into the
 // schedule is the same for all lanes of the workgroup (indexing a by-value kernel argument with a
 // value that differs between lanes is not supported).
-__device__ __forceinline__ bool decode_schedule(const LevelSchedule& sch, int& level, int& pb, int bid = blockIdx.x) {
+__device__ __forceinline__ bool decode_schedule(const LevelSchedule& sch, int& level, int& pb) {
+    const int bid = blockIdx.x;
     const int xcd = bid % kXcd;
     const int j = bid / kXcd;
     const int runs = sch.n_runs[xcd];
@@ -242,110 +243,6 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedul
     jo[0] = make_float2(j0[0], j0[1]);
     jo[n] = make_float2(j0[2], j1[0]);
     jo[2 * n] = make_float2(j1[1], j1[2]);
-}
-
-// ---- hashed levels whose table does not fit the L2 -------------------------------------------------
-// An XCD's L2 holds 4 MiB; a hashed level of 2^21 fp16 entries is 8 MiB, and every row of a point's
-// cell is a random line of it: with the kernel above most gathers of such a level miss the L2 and
-// the kernel moves several times its algorithmic bytes through the fabric.  Here the gathers are
-// taken slice by slice instead: the table is cut into slices of 2 MiB by the top bits of the slot, a
-// thread keeps kPhasePoints points and their eight partial sums in registers, and in pass q it
-// gathers only the rows whose slots lie in slice q (both x corners of a row share their top bits).
-// All workgroups of an XCD are resident, start together and walk the same list of tiles with the
-// same stride, so they are in the same pass at about the same time and the slice stays in their L2
-// (a workgroup that runs ahead into the next slice misses there and falls back: no barrier needed).
-constexpr int kPhasePoints = 4;
-constexpr int kPhaseTile = kBlock * kPhasePoints;
-constexpr int64_t kPhaseSliceBytes = 2 << 20;
-
-template <typename T>
-__device__ __forceinline__ void gather_row(const T* tab, uint32_t s0, uint32_t s1, float2& v0, float2& v1);
-
-template <>
-__device__ __forceinline__ void gather_row<float>(const float* tab, uint32_t s0, uint32_t s1, float2& v0, float2& v1) {
-    v0 = load_entry<float>(tab, s0);
-    v1 = load_entry<float>(tab, s1);
-}
-
-template <>
-__device__ __forceinline__ void gather_row<__half>(const __half* tab, uint32_t s0, uint32_t s1, float2& v0, float2& v1) {
-    const uint32_t* t32 = reinterpret_cast<const uint32_t*>(tab);
-    const uint4 grp = *reinterpret_cast<const uint4*>(t32 + (s0 & ~3u));
-    uint32_t e1 = pick4(grp, s1 & 3u);
-    if ((s0 ^ s1) >= 4u) e1 = t32[s1];
-    v0 = entry_to_float2(pick4(grp, s0 & 3u));
-    v1 = entry_to_float2(e1);
-}
-
-template <typename T>
-__global__ __launch_bounds__(kBlock) void encode_phased_kernel(GridDesc g, LevelSchedule sch, int wgs_per_xcd,
-                                                               int slice_shift, int n_slices,
-                                                               const float* __restrict__ pos,
-                                                               const T* __restrict__ tables, int64_t n,
-                                                               float* __restrict__ enc, float* __restrict__ jac) {
-    const int xcd = blockIdx.x % kXcd;
-    const int tiles_here = sch.start[xcd][sch.n_runs[xcd]];
-    for (int j = blockIdx.x / kXcd; j < tiles_here; j += wgs_per_xcd) {
-        int level, tile;
-        if (!decode_schedule(sch, level, tile, xcd + kXcd * j)) break;
-        const int res = g.res[level];
-        const float fres = (float)res;
-        const T* tab = tables + (size_t)level * g.table_size * 2;
-        float px[kPhasePoints], py[kPhasePoints], pz[kPhasePoints];
-        float acc[kPhasePoints][8];
-        bool valid[kPhasePoints];
-#pragma unroll
-        for (int p = 0; p < kPhasePoints; ++p) {
-            const int64_t i = (int64_t)tile * kPhaseTile + p * kBlock + threadIdx.x;
-            valid[p] = i < n;
-            px[p] = py[p] = pz[p] = 0.f;
-            if (valid[p]) { px[p] = pos[3 * i + 0]; py[p] = pos[3 * i + 1]; pz[p] = pos[3 * i + 2]; }
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc[p][k] = 0.f;
-        }
-        for (int q = 0; q < n_slices; ++q) {
-#pragma unroll
-            for (int p = 0; p < kPhasePoints; ++p) {
-                if (!valid[p]) continue;
-                const float gx = grid_coord(px[p], fres), gy = grid_coord(py[p], fres), gz = grid_coord(pz[p], fres);
-                const int cx = min((int)floorf(gx), res - 1);
-                const int cy = min((int)floorf(gy), res - 1);
-                const int cz = min((int)floorf(gz), res - 1);
-                const float w0 = gx - (float)cx, w1 = gy - (float)cy, w2 = gz - (float)cz;
-                const uint32_t hy0 = (uint32_t)cy * kPrimeY, hz0 = (uint32_t)cz * kPrimeZ;
-#pragma unroll
-                for (int row = 0; row < 4; ++row) {
-                    const int dy = row & 1, dz = row >> 1;
-                    const uint32_t rh = (hy0 + (dy ? kPrimeY : 0u)) ^ (hz0 + (dz ? kPrimeZ : 0u));
-                    const uint32_t s0 = ((uint32_t)cx ^ rh) & g.table_mask;
-                    if ((int)(s0 >> slice_shift) != q) continue;
-                    const uint32_t s1 = ((uint32_t)(cx + 1) ^ rh) & g.table_mask;
-                    float2 v0, v1;
-                    gather_row<T>(tab, s0, s1, v0, v1);
-                    const float fy = dy ? w1 : 1.f - w1, fz = dz ? w2 : 1.f - w2;
-                    const float sy = dy ? 1.f : -1.f, sz = dz ? 1.f : -1.f;
-                    const float fyz = fy * fz, syz = sy * fz, ysz = fy * sz;
-                    const float f0 = 1.f - w0, f1 = w0;
-                    const float t0 = f0 * v0.x + f1 * v1.x, t1 = f0 * v0.y + f1 * v1.y;     // interpolated along x
-                    const float d0 = v1.x - v0.x, d1 = v1.y - v0.y;                         // differentiated along x
-                    acc[p][0] += fyz * t0; acc[p][1] += fyz * t1;
-                    acc[p][2] += fyz * d0; acc[p][3] += syz * t0; acc[p][4] += ysz * t0;
-                    acc[p][5] += fyz * d1; acc[p][6] += syz * t1; acc[p][7] += ysz * t1;
-                }
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < kPhasePoints; ++p) {
-            if (!valid[p]) continue;
-            const int64_t i = (int64_t)tile * kPhaseTile + p * kBlock + threadIdx.x;
-            const int64_t o = (int64_t)level * n + i;
-            reinterpret_cast<float2*>(enc)[o] = make_float2(acc[p][0], acc[p][1]);
-            float2* jo = reinterpret_cast<float2*>(jac) + (int64_t)level * 3 * n + i;
-            jo[0] = make_float2(fres * acc[p][2], fres * acc[p][3]);
-            jo[n] = make_float2(fres * acc[p][4], fres * acc[p][5]);
-            jo[2 * n] = make_float2(fres * acc[p][6], fres * acc[p][7]);
-        }
-    }
 }
 
 // Backward.  d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a d_a w_c
@@ -1201,13 +1098,11 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
 
 // Queues for levels [0, n_levels): hashed active levels count as expensive, the rest as cheap;
 // each class is cut into 8 equal stretches of its level-major block list.
-// which: 0 both classes, 1 only the expensive levels, 2 only the cheap ones
-LevelSchedule make_level_schedule(const GridDesc& g, int n_levels, int point_blocks, int which = 0) {
+LevelSchedule make_level_schedule(const GridDesc& g, int n_levels, int point_blocks) {
     LevelSchedule sch;
     memset(&sch, 0, sizeof(sch));
     int fill[kXcd] = {0};
     for (int cls = 0; cls < 2; ++cls) {
-        if (which == 1 + (1 - cls)) continue;
         int lv[NEUS2_MAX_LEVELS], m = 0;
         for (int l = 0; l < n_levels; ++l) {
             const bool expensive = l < g.active_levels && !((g.dense_bits >> l) & 1u);
@@ -1254,37 +1149,7 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     }
     const GridDesc g = make_grid_desc(cfg);
     const int pbs = (int)((n + kBlock - 1) / kBlock);
-    // Hashed levels whose table is several times the 2 MiB an XCD's L2 can keep beside the streams take
-    // the slice-by-slice kernel, if the batch has enough tiles to keep every resident workgroup busy.
-    const int64_t level_bytes = ((int64_t)2 << cfg->log2_table_size) * (cfg->table_dtype == 1 ? 2 : 4);
-    int n_slices = 1, log2_slices = 0;
-    while ((level_bytes >> log2_slices) > kPhaseSliceBytes) ++log2_slices;
-    n_slices = 1 << log2_slices;
-    int hashed_active = 0;
-    for (int l = 0; l < g.active_levels; ++l) hashed_active += ((g.dense_bits >> l) & 1u) ? 0 : 1;
-    bool phased = false;
-    if (n_slices >= 2 && hashed_active > 0 && !dbg_idx) {
-        const void* kern = cfg->table_dtype == 1 ? (const void*)encode_phased_kernel<__half> : (const void*)encode_phased_kernel<float>;
-        const int tiles = (int)((n + kPhaseTile - 1) / kPhaseTile);
-        int blocks = persistent_blocks(kern, kBlock, (int64_t)tiles * hashed_active) / kXcd * kXcd;
-        if (blocks >= kXcd && (int64_t)tiles * hashed_active >= 2 * (int64_t)blocks) {
-            phased = true;
-            const LevelSchedule tsch = make_level_schedule(g, g.n_levels, tiles, 1);
-            const int shift = cfg->log2_table_size - log2_slices;
-            if (cfg->table_dtype == 1)
-                hipLaunchKernelGGL(encode_phased_kernel<__half>, dim3(blocks), dim3(kBlock), 0, st, g, tsch, blocks / kXcd, shift,
-                                   n_slices, pos, (const __half*)tables, n, enc, jac);
-            else
-                hipLaunchKernelGGL(encode_phased_kernel<float>, dim3(blocks), dim3(kBlock), 0, st, g, tsch, blocks / kXcd, shift,
-                                   n_slices, pos, (const float*)tables, n, enc, jac);
-        }
-    }
-    const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs, phased ? 2 : 0);
-    if (sch.per_xcd == 0) {            // every level went to the kernel above: only the clearing is left
-        for (int r = 0; r < 2; ++r)
-            if (zr.count[r] > 0) NEUS2_TRY(launch_zero(zr.p[r], zr.count[r], st));
-        return check_launch("hash encode");
-    }
+    const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs);
     const dim3 grid(kXcd * sch.per_xcd);
     if (cfg->table_dtype == 1)
         hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, sch, zr, pos,

@@ -179,10 +179,10 @@ def test_hash_encode_indices_bit_exact_and_values(k, n_rays):
     np.testing.assert_allclose(from_level_major(enc, n), ref["enc"], rtol=FWD_TOL, atol=1e-9)
 
 
-def test_hash_encode_of_tables_larger_than_the_cache_slice_by_slice():
-    """Workload 4's tables (2^21 entries a level, 8 MiB in fp16) at a batch large enough for the kernel that
-    gathers the hashed levels slice by slice; every value and every Jacobian entry against the oracle,
-    with edge positions and a ragged last tile."""
+def test_hash_encode_large_tables_and_batch_every_value():
+    """Workload 4's tables (2^21 entries a level: 8 MiB in fp16, 16 MiB in fp32, several times an L2) on a
+    quarter of a million points: every value and every Jacobian entry against the oracle, with edge
+    positions and a ragged last block."""
     w = wl.make_workload(4, n_rays=4096 + 3)
     cfg, params, batch = w["cfg"], w["params"], w["batch"]
     pos = batch["pos"][:262144 + 77].copy()
@@ -203,7 +203,7 @@ def test_hash_encode_of_tables_larger_than_the_cache_slice_by_slice():
     for l in range(L):
         sl = slice(2 * l, 2 * l + 2)
         np.testing.assert_allclose(got_j[:, sl], want_j[:, sl], rtol=FWD_TOL, atol=1e-9 * cfg.res[l])
-    # the same through fp32 tables (slices of 2 MiB: eight of them)
+    # the same through fp32 tables
     cfg.table_dtype = "f32"
     c = nb.make_config(cfg)
     tab32 = params["tables"].astype(np.float32) * np.float32(1.37)

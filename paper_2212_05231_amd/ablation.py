@@ -23,57 +23,69 @@ import json
 import numpy as np
 
 
-def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
+def make_case(hidden: int, n: int, beta: float = 0.1, seed: int = 7):
+    """One case of the comparison: the network (hidden layers of 64), a batch of n encodings and
+    Jacobians, and the two ways to compute the gradients.  Returns a dict with the inputs
+    (`H`, `e`, `J`), `ours()` -> (dH list, d_enc [n,32]) and `theirs()` -> (dH list, d_enc [n,32])."""
     import torch
     from . import binding as nb, workloads as wl
     dev = "cuda"
+    cfg = wl.make_config(1)
+    cfg.sdf_dims = [32] + [64] * hidden + [16]
+    cfg.n_levels, cfg.active_levels = 16, 16
+    cfg.res, cfg.dense = wl.make_config(2).res, wl.make_config(2).dense
+    cfg.log2_table_size = wl.make_config(2).log2_table_size
+    cfg.loss_kind, cfg.beta = 0, beta
+    c = nb.make_config(cfg)
+    g = torch.Generator(device="cpu").manual_seed(seed + hidden)
+    Hs = [(torch.randn(cfg.sdf_dims[i + 1], cfg.sdf_dims[i], generator=g) * (2.0 / cfg.sdf_dims[i]) ** 0.5).to(dev)
+          for i in range(hidden + 1)]
+    e = torch.randn(n, 32, generator=g).to(dev)
+    J = (torch.randn(n, 32, 3, generator=g) * 0.3).to(dev)
+    # library layout: level-major [L][n][F]; the Jacobian as three planes of pairs per level
+    enc = e.view(n, 16, 2).permute(1, 0, 2).contiguous()
+    jac = J.view(n, 16, 3, 2).permute(1, 2, 0, 3).contiguous()      # the library's [L][3 pairs][n][2]
+    y = torch.empty(n, 16, device=dev); q = torch.empty(16, n, 2, device=dev); normal = torch.empty(n, 3, device=dev)
+    loss = torch.zeros(4, device=dev); d_y = torch.empty(n, 16, device=dev); d_normal = torch.empty(n, 3, device=dev)
+    d_enc = torch.empty(16, n, 2, device=dev)
+    kept = torch.zeros(2, n, 2, dtype=torch.int32, device=dev)      # ReLU masks, forward -> backward
+    dH = [torch.zeros_like(h) for h in Hs]
+
+    def ours():
+        nb.sdf_fwd_grad(c, enc, jac, Hs, n, y, q, normal, masks=kept)
+        nb.loss(c, None, None, normal, y, 0, n, loss, None, d_normal, d_y)
+        nb.sdf_mlp_bwd(c, enc, jac, Hs, d_y, d_normal, n, dH, d_enc, masks=kept)
+        return dH, d_enc.permute(1, 0, 2).reshape(n, 32)
+
+    params = [h.clone().requires_grad_(True) for h in Hs]
+
+    def theirs():
+        for p in params:
+            p.grad = None
+        x = e.detach().requires_grad_(True)
+        a = x
+        for l, h in enumerate(params):
+            a = a @ h.t()
+            if l < len(params) - 1:
+                a = torch.relu(a)
+        d = a[:, 0]
+        (qq,) = torch.autograd.grad(d.sum(), x, create_graph=True)
+        nrm = torch.einsum("nk,nkc->nc", qq, J)
+        ls = (d * d).mean() + beta * ((nrm.norm(dim=1) - 1.0) ** 2).mean()
+        ls.backward()
+        return [p.grad for p in params], x.grad
+
+    return {"H": Hs, "e": e, "J": J, "beta": beta, "ours": ours, "theirs": theirs, "dH": dH}
+
+
+def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
+    import torch
     out = []
     for hidden in (1, 2):
-        cfg = wl.make_config(1)
-        cfg.sdf_dims = [32] + [64] * hidden + [16]
-        cfg.n_levels, cfg.active_levels = 16, 16
-        cfg.res, cfg.dense = wl.make_config(2).res, wl.make_config(2).dense
-        cfg.log2_table_size = wl.make_config(2).log2_table_size
-        cfg.loss_kind, cfg.beta = 0, beta
-        c = nb.make_config(cfg)
-        g = torch.Generator(device="cpu").manual_seed(7 + hidden)
-        Hs = [(torch.randn(cfg.sdf_dims[i + 1], cfg.sdf_dims[i], generator=g) * (2.0 / cfg.sdf_dims[i]) ** 0.5).to(dev)
-              for i in range(hidden + 1)]
         for lg in range(log2_min, log2_max + 1):
             n = 1 << lg
-            e = torch.randn(n, 32, generator=g).to(dev)
-            J = (torch.randn(n, 32, 3, generator=g) * 0.3).to(dev)
-            # library layout: level-major [L][n][F]; the Jacobian as three planes of pairs per level
-            enc = e.view(n, 16, 2).permute(1, 0, 2).contiguous()
-            jac = J.view(n, 16, 3, 2).permute(1, 2, 0, 3).contiguous()      # the library's [L][3 pairs][n][2]
-            y = torch.empty(n, 16, device=dev); q = torch.empty(16, n, 2, device=dev); normal = torch.empty(n, 3, device=dev)
-            loss = torch.zeros(4, device=dev); d_y = torch.empty(n, 16, device=dev); d_normal = torch.empty(n, 3, device=dev)
-            d_enc = torch.empty(16, n, 2, device=dev)
-            kept = torch.zeros(2, n, 2, dtype=torch.int32, device=dev)      # ReLU masks, forward -> backward
-            dH = [torch.zeros_like(h) for h in Hs]
-
-            def ours():
-                nb.sdf_fwd_grad(c, enc, jac, Hs, n, y, q, normal, masks=kept)
-                nb.loss(c, None, None, normal, y, 0, n, loss, None, d_normal, d_y)
-                nb.sdf_mlp_bwd(c, enc, jac, Hs, d_y, d_normal, n, dH, d_enc, masks=kept)
-
-            params = [h.clone().requires_grad_(True) for h in Hs]
-
-            def theirs():
-                for p in params:
-                    p.grad = None
-                x = e.detach().requires_grad_(True)
-                a = x
-                for l, h in enumerate(params):
-                    a = a @ h.t()
-                    if l < len(params) - 1:
-                        a = torch.relu(a)
-                d = a[:, 0]
-                (qq,) = torch.autograd.grad(d.sum(), x, create_graph=True)
-                nrm = torch.einsum("nk,nkc->nc", qq, J)
-                ls = (d * d).mean() + beta * ((nrm.norm(dim=1) - 1.0) ** 2).mean()
-                ls.backward()
-                return x.grad
+            case = make_case(hidden, n, beta)
+            ours, theirs = case["ours"], case["theirs"]
 
             def timed(fn):
                 for _ in range(3):
@@ -87,13 +99,13 @@ def run(log2_min: int, log2_max: int, reps: int, beta: float = 0.1):
                 torch.cuda.synchronize()
                 return t0.elapsed_time(t1) / reps
 
-            for h in dH:
+            for h in case["dH"]:
                 h.zero_()
-            ours()
-            gx = theirs()
+            dH, gx_ours = ours()
+            gH, gx = theirs()
             torch.cuda.synchronize()
-            err = max(float((a - p.grad).norm() / p.grad.norm()) for a, p in zip(dH, params))
-            err_x = float((d_enc.permute(1, 0, 2).reshape(n, 32) - gx).norm() / gx.norm())
+            err = max(float((a - b).norm() / b.norm()) for a, b in zip(dH, gH))
+            err_x = float((gx_ours - gx).norm() / gx.norm())
             t_ours, t_torch = timed(ours), timed(theirs)
             row = {"hidden_layers": hidden, "batch": n, "ours_ms": round(t_ours, 4), "autograd_ms": round(t_torch, 4),
                    "speedup": round(t_torch / t_ours, 2), "grad_rel_diff": err, "input_grad_rel_diff": err_x}

@@ -1,0 +1,58 @@
+"""The comparison of the paper's Fig. 7 (second-order backward of the SDF network against
+torch.autograd's double backward): both sides against the float64 oracle, at a batch size where
+the two sides differ from each other by more than the library's gradient bar."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import neus2_oracle as o
+from paper_2212_05231_amd import ablation
+
+pytestmark = pytest.mark.gpu
+
+
+def rel(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+@pytest.mark.parametrize("hidden", [1, 2])
+def test_library_and_autograd_against_the_oracle(hidden):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    n = 1 << 17
+    case = ablation.make_case(hidden, n)
+    H = [h.cpu().numpy().astype(np.float64) for h in case["H"]]
+    e = case["e"].cpu().numpy().astype(np.float64)
+    J = case["J"].cpu().numpy().astype(np.float64)
+    beta = case["beta"]
+    K = len(H)
+    # the oracle: loss = mean(d^2) + beta mean((|n|-1)^2), first- and second-order gradients (Theorem 1)
+    y, acts, masks = o.mlp_forward(H, e)
+    S, q = o.mlp_input_gradient(H, masks, 0)
+    normal = np.einsum("nk,nka->na", q, J)
+    nrm = np.linalg.norm(normal, axis=1)
+    d_y = np.zeros_like(y)
+    d_y[:, 0] = 2.0 * y[:, 0] / n
+    d_normal = (2.0 * beta / n) * ((nrm - 1.0) / nrm)[:, None] * normal
+    dH, d_e, _ = o.mlp_backward(H, acts, masks, d_y)
+    t = np.einsum("nka,na->nk", J, d_normal)
+    for l in range(K):
+        if l < K - 1:
+            dH[l] += S[l].T @ t
+            t = masks[l] * (t @ H[l].T)
+        else:
+            dH[l][0] += t.sum(axis=0)
+    for h in case["dH"]:
+        h.zero_()
+    ours_H, ours_x = case["ours"]()
+    their_H, their_x = case["theirs"]()
+    torch.cuda.synchronize()
+    # the oracle's input gradient has, beyond dL/de through (d,g), no term through the normal: q does not depend on e
+    # (vanishing second input derivative of a ReLU network), which is what autograd's x.grad holds as well
+    ours_err = [rel(a.cpu().numpy(), b) for a, b in zip(ours_H, dH)] + [rel(ours_x.cpu().numpy(), d_e)]
+    their_err = [rel(a.cpu().numpy(), b) for a, b in zip(their_H, dH)] + [rel(their_x.cpu().numpy(), d_e)]
+    print(f"hidden {hidden}, batch 2^17: relative error against the oracle (weight gradients ..., input gradient): "
+          f"library {['%.1e' % v for v in ours_err]}  autograd {['%.1e' % v for v in their_err]}")
+    assert max(ours_err) <= 1e-4

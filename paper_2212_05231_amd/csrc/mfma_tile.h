@@ -137,11 +137,23 @@ struct Split {
     uint32_t t[P][NB][8];
 };
 
+// The remainder x - term is exact in binary32 (the term is x rounded to 8 significant bits), and
+// one v_dot2c_f32_bf16 yields it from the packed word: x + (-1) * term(this element) + 0 * term(the
+// other element), also exact (checked on the chip over all exponents).  The selector words are kept
+// in registers: written as literals the compiler turns (-1, 0) into the inline constant -1.0, which
+// the instruction reads as (0, -1).  A non-finite neighbour turns the remainder into NaN (0 * inf).
+__device__ __forceinline__ uint32_t in_register(uint32_t v) {
+    asm("" : "+s"(v));
+    return v;
+}
+
 template <int NB, int P>
 __device__ __forceinline__ void split(const v16f* v, Split<NB, P>& out) {
     typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
     typedef float f2 __attribute__((ext_vector_type(2)));
     static_assert(P == 2 || P == 3, "two or three terms");
+    const bf2 minus_low = __builtin_bit_cast(bf2, in_register(0x0000bf80u));
+    const bf2 minus_high = __builtin_bit_cast(bf2, in_register(0xbf800000u));
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -151,7 +163,12 @@ __device__ __forceinline__ void split(const v16f* v, Split<NB, P>& out) {
             for (int term = 0; term < P; ++term) {
                 const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{x0, x1}, bf2));
                 out.t[term][b][p] = w;
-                if (term + 1 < P) {
+                if (term + 1 < P && P == 2) {
+                    x0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2, w), minus_low, x0, false);
+                    x1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2, w), minus_high, x1, false);
+                } else if (term + 1 < P) {
+                    // the three-term splits of the forward kernels run two waves to a SIMD and measured
+                    // slower with the dot instruction: shift or mask, and subtract
                     x0 -= __builtin_bit_cast(float, w << 16);
                     x1 -= __builtin_bit_cast(float, w & 0xffff0000u);
                 }

@@ -64,8 +64,10 @@ __device__ __forceinline__ constexpr int neuron_of(int r, int h) { return 8 * (r
 // lanes and fetches back for every use.  A float is positive exactly when its bit pattern is a
 // positive integer, so the ReLU is an integer maximum with 0 on the pattern, the mask bit the
 // unsigned minimum of the result with 1, and a one-bit sign-extending field extract turns a mask
-// bit back into an all-ones or all-zeros word to AND with.  The instructions are written out
-// because the compiler rewrites the equivalent C expressions into compares and selects.
+// bit back into an all-ones or all-zeros word to AND with.  The mask instructions are written out
+// because the compiler rewrites the equivalent C expressions into compares and selects; the
+// instruction that first touches a result of a matrix instruction (the maximum, the AND) is left to
+// the compiler, which knows the wait states a matrix result needs and does not look into asm text.
 template <int NB>
 __device__ __forceinline__ uint32_t relu_mask(v16f* z) {
     uint32_t m = 0;
@@ -73,12 +75,12 @@ __device__ __forceinline__ uint32_t relu_mask(v16f* z) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float zf = z[b][r];
+            const float zf = z[b][r];       // a copy: a bit cast of the vector element itself reads element 0
+            const int zi = max(__builtin_bit_cast(int, zf), 0);
             uint32_t on;
-            asm("v_max_i32 %0, 0, %0" : "+v"(zf));
-            asm("v_min_u32 %0, 1, %1" : "=v"(on) : "v"(zf));
+            asm("v_min_u32 %0, 1, %1" : "=v"(on) : "v"(zi));
             asm("v_lshl_or_b32 %0, %1, %2, %0" : "+v"(m) : "v"(on), "n"(16 * b + r));
-            z[b][r] = zf;
+            z[b][r] = __builtin_bit_cast(float, zi);
         }
     return m;
 }
@@ -90,9 +92,8 @@ __device__ __forceinline__ void relu(v16f* z) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float zf = z[b][r];
-            asm("v_max_i32 %0, 0, %0" : "+v"(zf));
-            z[b][r] = zf;
+            const float zf = z[b][r];
+            z[b][r] = __builtin_bit_cast(float, max(__builtin_bit_cast(int, zf), 0));
         }
 }
 
@@ -102,11 +103,10 @@ __device__ __forceinline__ void apply_mask(v16f* z, uint32_t m) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float zf = z[b][r];
             uint32_t keep;
             asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(keep) : "v"(m), "n"(16 * b + r));
-            asm("v_and_b32 %0, %0, %1" : "+v"(zf) : "v"(keep));
-            z[b][r] = zf;
+            const float zf = z[b][r];
+            z[b][r] = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, zf) & keep);
         }
 }
 
@@ -328,9 +328,11 @@ __device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W
     const unsigned char* base = W + i * kLd + g * (PS * 16);
     // The weights of the next step are requested from LDS before the instructions of the current
     // step are issued, and the scheduler is told not to move anything across step boundaries: left
-    // alone it hoists every LDS read of the kernel to the top and runs out of registers.
+    // alone it hoists every LDS read of the kernel to the top and runs out of registers (letting
+    // only ALU instructions cross was measured and is slower).  Output blocks are computed one
+    // after the other (step t = mb * KSTEPS + u).
     auto address = [&](int t) -> const u32x4* {
-        const int u = t / MB, mb = t % MB;
+        const int mb = t / KSTEPS, u = t % KSTEPS;
         return reinterpret_cast<const u32x4*>(base + 32 * mb * kLd + u * (2 * PS * 16));
     };
     u32x4 cur[P], nxt[P];
@@ -340,18 +342,18 @@ __device__ __forceinline__ void matvec_split(const unsigned char* __restrict__ W
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = zero16();
 #pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) {
-        bf8 bt[P];
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            u32x4 v;
+        for (int u = 0; u < KSTEPS; ++u) {
+            bf8 bt[P];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = x.t[p][u >> 1][4 * (u & 1) + e];
-            bt[p] = __builtin_bit_cast(bf8, v);
-        }
+            for (int p = 0; p < P; ++p) {
+                u32x4 v;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int t = u * MB + mb;
+                for (int e = 0; e < 4; ++e) v[e] = x.t[p][u >> 1][4 * (u & 1) + e];
+                bt[p] = __builtin_bit_cast(bf8, v);
+            }
+            const int t = mb * KSTEPS + u;
 #pragma unroll
             for (int p = 0; p < P; ++p) nxt[p] = cur[p];
             if (t + 1 < kTotal) {

@@ -509,12 +509,16 @@ __device__ __forceinline__ RowRecord pack_row(uint32_t slot, uint32_t code, cons
     } else if (E < 0 || big == 0.f) {
         E = 0;
     } else {
+        // in * 2^(17-e) rounded to nearest even, as the low bits of a float: adding 1.5 * 2^23 leaves
+        // the integer in the mantissa (two's complement in the low 18 bits); |in| < 2^e, so the only value
+        // out of range is +2^17 (a magnitude just below 2^e rounding up), which the unsigned minimum on
+        // the bit pattern (positive floats order like their patterns) brings back to 2^17 - 1.
         const float in[4] = {v.x, v.y, v.z, v.w};
+        const float scale = __builtin_bit_cast(float, (uint32_t)(127 + kRecMant - e) << 23);
+        constexpr float kRound = 12582912.0f;                     // 1.5 * 2^23, pattern 0x4B400000
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int r = __float2int_rn(ldexpf(in[k], kRecMant - e));
-            m[k] = min(max(r, -((1 << kRecMant) - 1)), (1 << kRecMant) - 1);
-        }
+        for (int k = 0; k < 4; ++k)
+            m[k] = (int)min(__builtin_bit_cast(uint32_t, fmaf(in[k], scale, kRound)), 0x4B400000u + ((1u << kRecMant) - 1u));
     }
     RowRecord r;
     r.a = slot | (code << 13) | ((uint32_t)E << 17) | (((uint32_t)m[3] & 0xFFu) << 24);

@@ -115,6 +115,33 @@ int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* j
                        const float* const* H, int64_t n, float* y, float* q, float* normal,
                        uint32_t* masks, void* stream);
 
+/* The SDF network with more matrices than neus2_sdf_fwd_grad / neus2_sdf_mlp_bwd hold fused (the
+ * deeper networks of the paper's Fig. 7, "speed-up of our 2nd-order derivative ... across MLP
+ * layer numbers"): the same quantities, computed layer by layer, one launch per matrix and
+ * direction, the per-point vectors passing through a workspace.
+ *   n_mats K = 2..NEUS2_DEEP_MAX_MATS matrices: H[0] [64][enc_dim], H[1..K-2] [64][64],
+ *   H[K-1] [16][64] (row-major, device; the array of pointers is host memory); enc_dim 16 or 32.
+ *   enc [device, (enc_dim/2)*n*2], jac [device, (enc_dim/2)*3*n*2], q, d_enc like enc; layouts as
+ *   in neus2_hash_encode with enc_dim/2 levels, all of them active.
+ *   neus2_sdf_deep_fwd_grad: y [device, n*16], q = dd/de, normal [device, n*3] = q*jac (Eq. 1,
+ *   Eq. 2, supplement Sec. B).
+ *   neus2_sdf_deep_bwd: dH[l] (host array of K device pointers, shaped like H[l]) are ADDED into
+ *   with delta_l a_{l-1}^T + S_l^T t_{l-1}^T (Theorem 1, Eqs. 7-8); d_enc is overwritten with
+ *   dL/de.  It recomputes the forward pass itself and needs nothing from the forward call.
+ *   workspace [device, at least neus2_sdf_deep_workspace_bytes(n_mats, n)]: required; contents
+ *   are undefined afterwards.  The size query returns -1 for an unsupported n_mats or n < 0.
+ * Errors: NEUS2_ERR_UNSUPPORTED (n_mats, enc_dim), NEUS2_ERR_NULL, NEUS2_ERR_SHAPE (workspace
+ * too small, n < 0); nothing is launched then. */
+#define NEUS2_DEEP_MAX_MATS 9
+int64_t neus2_sdf_deep_workspace_bytes(int32_t n_mats, int64_t n);
+int neus2_sdf_deep_fwd_grad(int32_t n_mats, int32_t enc_dim, const float* enc, const float* jac,
+                            const float* const* H, int64_t n, float* y, float* q, float* normal,
+                            void* workspace, int64_t workspace_bytes, void* stream);
+int neus2_sdf_deep_bwd(int32_t n_mats, int32_t enc_dim, const float* enc, const float* jac,
+                       const float* const* H, const float* d_y, const float* d_normal, int64_t n,
+                       float* const* dH, float* d_enc, void* workspace, int64_t workspace_bytes,
+                       void* stream);
+
 /* Colour network forward (Eq. 3): rgb = sigmoid(W_3 relu(W_2 relu(W_1 cin))),
  * cin = [pos(3), normal(3), SH16(dir)(16), y(16)]; dirs [device, rays*3] are unit vectors,
  * sample i uses ray sample_ray[i] (sample_ray [device, n int32], rays with their own sample

@@ -70,6 +70,9 @@ _SIGNATURES = {
     "neus2_sdf_bwd_2nd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P,
                                     C.c_int64, _P, _P]),
     "neus2_sdf_mlp_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, _P, _P]),
+    "neus2_sdf_deep_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int64]),
+    "neus2_sdf_deep_fwd_grad": (C.c_int, [C.c_int32, C.c_int32, _P, _P, _P, C.c_int64, _P, _P, _P, _P, C.c_int64, _P]),
+    "neus2_sdf_deep_bwd": (C.c_int, [C.c_int32, C.c_int32, _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
     "neus2_hash_scatter_bwd": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P, _P, C.c_int64, _P]),
     "neus2_hash_scatter_bwd_static": (C.c_int, [C.POINTER(Neus2Config), _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
     "neus2_adam_step": (C.c_int, [_P, _P, _P, _P, _P, C.c_int64, C.c_int, C.c_float, C.c_float, C.c_float,
@@ -222,6 +225,24 @@ def sdf_bwd_2nd(c, pos, tables, enc, jac, H, q, d_y, d_normal, n, dH, d_tables, 
 def sdf_mlp_bwd(c, enc, jac, H, d_y, d_normal, n, dH, d_enc, d_pos=None, masks=None):
     _check(lib().neus2_sdf_mlp_bwd(C.byref(c), _ptr(enc), _ptr(jac), _ptr_array(H), _ptr(d_y), _ptr(d_normal), n,
                                    _ptr_array(dH), _ptr(d_enc), _ptr(d_pos), _ptr(masks), _stream()))
+
+
+def _bytes(t) -> int:
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+def sdf_deep_workspace_bytes(n_mats: int, n: int) -> int:
+    return lib().neus2_sdf_deep_workspace_bytes(n_mats, n)
+
+
+def sdf_deep_fwd_grad(enc_dim, enc, jac, H, n, y, q, normal, workspace):
+    _check(lib().neus2_sdf_deep_fwd_grad(len(H), enc_dim, _ptr(enc), _ptr(jac), _ptr_array(H), n, _ptr(y), _ptr(q),
+                                         _ptr(normal), _ptr(workspace), _bytes(workspace), _stream()))
+
+
+def sdf_deep_bwd(enc_dim, enc, jac, H, d_y, d_normal, n, dH, d_enc, workspace):
+    _check(lib().neus2_sdf_deep_bwd(len(H), enc_dim, _ptr(enc), _ptr(jac), _ptr_array(H), _ptr(d_y), _ptr(d_normal), n,
+                                    _ptr_array(dH), _ptr(d_enc), _ptr(workspace), _bytes(workspace), _stream()))
 
 
 def hash_scatter_bwd(c, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos=None, workspace=None):

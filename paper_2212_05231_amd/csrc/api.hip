@@ -227,6 +227,51 @@ int neus2_sdf_fwd_grad(const neus2_config* cfg, const float* enc, const float* j
     return launch_sdf_fwd(cfg, enc, jac, H, n, y, q, normal, masks, (hipStream_t)stream);
 }
 
+static int check_deep(int n_mats, int enc_dim, int64_t n, const void* workspace, int64_t workspace_bytes) {
+    if (n_mats < 2 || n_mats > NEUS2_DEEP_MAX_MATS)
+        return fail(NEUS2_ERR_UNSUPPORTED, "layer-by-layer sdf network: %d matrices (2..%d are built)", n_mats, NEUS2_DEEP_MAX_MATS);
+    if (enc_dim != 16 && enc_dim != 32)
+        return fail(NEUS2_ERR_UNSUPPORTED, "layer-by-layer sdf network: input width %d (16 and 32 are built)", enc_dim);
+    NEUS2_TRY(check_count(n, "n"));
+    NEUS2_TRY(check_ptr(workspace, "workspace"));
+    if (workspace_bytes < sdf_deep_workspace_bytes(n_mats, n))
+        return fail(NEUS2_ERR_SHAPE, "workspace of %lld bytes, neus2_sdf_deep_workspace_bytes asks for %lld", (long long)workspace_bytes,
+                    (long long)sdf_deep_workspace_bytes(n_mats, n));
+    return NEUS2_OK;
+}
+
+int64_t neus2_sdf_deep_workspace_bytes(int32_t n_mats, int64_t n) {
+    if (n_mats < 2 || n_mats > NEUS2_DEEP_MAX_MATS || n < 0) return -1;
+    return sdf_deep_workspace_bytes(n_mats, n);
+}
+
+int neus2_sdf_deep_fwd_grad(int32_t n_mats, int32_t enc_dim, const float* enc, const float* jac, const float* const* H,
+                            int64_t n, float* y, float* q, float* normal, void* workspace, int64_t workspace_bytes,
+                            void* stream) {
+    NEUS2_TRY(check_deep(n_mats, enc_dim, n, workspace, workspace_bytes));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, n_mats, "H"));
+    NEUS2_TRY(check_ptr(y, "y"));
+    NEUS2_TRY(check_ptr(q, "q"));
+    NEUS2_TRY(check_ptr(normal, "normal"));
+    return launch_sdf_deep_fwd(n_mats, enc_dim, enc, jac, H, n, y, q, normal, workspace, (hipStream_t)stream);
+}
+
+int neus2_sdf_deep_bwd(int32_t n_mats, int32_t enc_dim, const float* enc, const float* jac, const float* const* H,
+                       const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
+                       void* workspace, int64_t workspace_bytes, void* stream) {
+    NEUS2_TRY(check_deep(n_mats, enc_dim, n, workspace, workspace_bytes));
+    NEUS2_TRY(check_ptr(enc, "enc"));
+    NEUS2_TRY(check_ptr(jac, "jac"));
+    NEUS2_TRY(check_mats((const void* const*)H, n_mats, "H"));
+    NEUS2_TRY(check_ptr(d_y, "d_y"));
+    NEUS2_TRY(check_ptr(d_normal, "d_normal"));
+    NEUS2_TRY(check_mats((const void* const*)dH, n_mats, "dH"));
+    NEUS2_TRY(check_ptr(d_enc, "d_enc"));
+    return launch_sdf_deep_bwd(n_mats, enc_dim, enc, jac, H, d_y, d_normal, n, dH, d_enc, workspace, (hipStream_t)stream);
+}
+
 int neus2_sdf_mlp_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,
                       const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
                       float* d_pos, const uint32_t* masks, void* stream) {

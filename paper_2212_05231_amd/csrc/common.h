@@ -68,6 +68,12 @@ int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n);
 // Bytes of workspace the scatter-add needs for n points when no position gradient is wanted
 // (0 if it would take the path without a workspace).
 int64_t scatter_records_bytes(const neus2_config* cfg, int64_t n);
+int64_t sdf_deep_workspace_bytes(int n_mats, int64_t n);
+int launch_sdf_deep_fwd(int n_mats, int enc_dim, const float* enc, const float* jac, const float* const* H, int64_t n,
+                        float* y, float* q, float* normal, void* workspace, hipStream_t st);
+int launch_sdf_deep_bwd(int n_mats, int enc_dim, const float* enc, const float* jac, const float* const* H,
+                        const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
+                        void* workspace, hipStream_t st);
 int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac,
                    const float* const* H, int64_t n, float* y, float* q, float* normal, uint32_t* masks, hipStream_t st);
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac,

@@ -593,6 +593,224 @@ int run_bwd(const SdfArgs& a, hipStream_t st) {
     return check_launch("sdf backward");
 }
 
+// ------------------------------------------------------------------------------------------
+// Networks deeper than the fused kernels hold (up to eight hidden layers of 64: the depths of the
+// paper's Fig. 7), layer by layer.  The fused kernels keep every matrix in LDS and every weight
+// gradient in registers, which stops at two hidden layers; here ONE matrix is in LDS per launch
+// and the per-point vectors pass from launch to launch through a workspace in HBM, each lane
+// writing the 32 registers it holds as 128 consecutive bytes (vector v of point tile t, lane l:
+// floats ((t * 64 + l) * 32 ...)).  Every matrix is used as 64 x 64 (the first one's missing
+// columns and the last one's missing rows are zeros), so one kernel serves every layer.
+//   forward launch l:  a_l = G_l H_l a_{l-1}  (six-product arithmetic, writes the mask word)
+//                      t_l = G_l H_l t_{l-1}  (with WITH_T; t_0 = (de/dx) dL/dn)
+//   reverse launch l:  dH_l += delta_l a_{l-1}^T + S_l^T t_{l-1}^T   (with GRAD)
+//                      S_{l-1} = (H_l^T S_l) G_{l-1},  delta_{l-1} = G_{l-1} H_l^T delta_l
+// with S_K = the unit row of the SDF output and delta_K = dL/d(d,g): Theorem 1 and Eqs. 7-8 as in
+// the fused kernels, Definition 1's vectors one layer at a time.
+struct DeepArgs {
+    const float* W; int out_dim, in_dim;       // H_l [out_dim][in_dim], row-major
+    int64_t n; int levels;                     // points; levels of the encoding (input width / 2)
+    bool first, last;                          // l == 1, l == K
+    const float* enc; const float* jac; const float* d_normal; const float* d_y;
+    const float* a_in; const float* t_in; const float* s_in; const float* d_in;     // lane layout
+    float* a_out; float* t_out; float* s_out; float* d_out;                         // lane layout
+    float* a0_out; float* t0_out;              // forward, first layer: its inputs in lane layout, for the reverse launch
+    uint32_t* mask_out; const uint32_t* mask_in;   // one word per lane: [tile * 64 + lane]
+    float* y; float* q; float* normal; float* d_enc; float* dW;
+};
+
+__device__ __forceinline__ void load_lane(const float* __restrict__ base, int64_t tile, int lane, v16f* v) {
+    const float4* p = reinterpret_cast<const float4*>(base + (tile * 64 + lane) * 32);
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float4 f = p[4 * b + k];
+            v[b][4 * k] = f.x; v[b][4 * k + 1] = f.y; v[b][4 * k + 2] = f.z; v[b][4 * k + 3] = f.w;
+        }
+}
+
+__device__ __forceinline__ void store_lane(float* __restrict__ base, int64_t tile, int lane, const v16f* v) {
+    float4* p = reinterpret_cast<float4*>(base + (tile * 64 + lane) * 32);
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[4 * b + k] = make_float4(v[b][4 * k], v[b][4 * k + 1], v[b][4 * k + 2], v[b][4 * k + 3]);
+}
+
+template <bool WITH_T>
+__global__ __launch_bounds__(kThreads) void deep_forward_kernel(DeepArgs a) {
+    typedef SplitMatrix<4, 3> M;
+    __shared__ alignas(16) unsigned char Wf[64 * M::kLd];
+    {
+        typename M::template Fill<64, kThreads, false> f;
+        const float* __restrict__ W = a.W;
+        const int od = a.out_dim, id = a.in_dim;
+        f.load(threadIdx.x, [&](int o, int i) { return (o < od && i < id) ? W[o * id + i] : 0.f; });
+        f.store(Wf, threadIdx.x);
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = lane & 31, h = lane >> 5;
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        v16f x[2], z[2];
+        if (a.first) {
+            x[0] = load_levels<32>(a.enc, a.n, i, valid, a.levels, h);
+            x[1] = zero16();
+            if (a.a0_out) store_lane(a.a0_out, tile, lane, x);
+        } else {
+            load_lane(a.a_in, tile, lane, x);
+        }
+        Split<2, 3> px;
+        split(x, px);
+        matvec_split<2, 4, 3, 3>(Wf, px, z, lane);
+        uint32_t m = 0xffffffffu;
+        if (a.last) {
+            store_rows16(a.y, i, valid, h, z[0]);
+        } else {
+            m = relu_mask<2>(z);
+            store_lane(a.a_out, tile, lane, z);
+            a.mask_out[tile * 64 + lane] = m;
+        }
+        if (WITH_T) {
+            v16f t[2], tz[2];
+            if (a.first) {
+                float nb3[3] = {0.f, 0.f, 0.f};
+                if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }
+                t[0] = apply_jac<32>(a.jac, a.n, i, valid, a.levels, h, nb3);
+                t[1] = zero16();
+                store_lane(a.t0_out, tile, lane, t);
+            } else {
+                load_lane(a.t_in, tile, lane, t);
+            }
+            Split<2, 2> pt;
+            split(t, pt);
+            matvec_split<2, 4, 3, 2>(Wf, pt, tz, lane);
+            apply_mask<2>(tz, m);
+            store_lane(a.t_out, tile, lane, tz);
+        }
+    }
+}
+
+struct DeepRevSmem {
+    alignas(16) unsigned char Wt[64 * SplitMatrix<4, 3>::kLd];
+    float tiles[kWaves][2][kTileWords];
+};
+
+// P: terms per factor of the transposed products (3 where the result is dd/de, which is compared at
+// forward tolerance; 2 in the backward call)
+template <int P, bool GRAD>
+__global__ __launch_bounds__(kThreads) void deep_reverse_kernel(DeepArgs a) {
+    typedef SplitMatrix<4, P> M;
+    __shared__ DeepRevSmem sm;
+    {
+        typename M::template Fill<64, kThreads, true> f;
+        const float* __restrict__ W = a.W;
+        const int od = a.out_dim, id = a.in_dim;
+        f.load(threadIdx.x, [&](int i, int o) { return (o < od && i < id) ? W[o * id + i] : 0.f; });
+        f.store(sm.Wt, threadIdx.x);
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = lane & 31, h = lane >> 5;
+    uint32_t* Zs = reinterpret_cast<uint32_t*>(sm.tiles[wave][0]);
+    uint32_t* Xs = reinterpret_cast<uint32_t*>(sm.tiles[wave][1]);
+    v16f G[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) { G[mb][0] = zero16(); G[mb][1] = zero16(); }
+    const int64_t tiles = (a.n + 31) / 32;
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += (int64_t)gridDim.x * kWaves) {
+        const int64_t i = tile * 32 + j;
+        const bool valid = i < a.n;
+        v16f s[2], d[2];
+        if (a.last) {
+            // S_K: the unit row of output 0; delta_K: the adjoint of the 16 outputs
+            s[0] = zero16(); s[1] = zero16(); d[1] = zero16();
+            if (h == 0 && valid) s[0][0] = 1.f;
+            if (GRAD) d[0] = load_rows16(a.d_y, i, valid, h);
+        } else {
+            load_lane(a.s_in, tile, lane, s);
+            if (GRAD) load_lane(a.d_in, tile, lane, d);
+        }
+        Split<2, P> ps;
+        Split<2, 2> pd;
+        split(s, ps);
+        if (GRAD) {
+            v16f ap[2], tp[2];
+            load_lane(a.a_in, tile, lane, ap);
+            load_lane(a.t_in, tile, lane, tp);
+            Split<2, 2> pa, pt;
+            split(d, pd);
+            split(ap, pa);
+            split(tp, pt);
+            stage_split(Zs, pd, j, h);
+            stage_split(Xs, pa, j, h);
+            wave_lds_fence();
+            outer_accumulate_split<2, 2>(G, Zs, Xs, lane);
+            wave_lds_fence();
+            stage_split(Zs, ps, j, h);
+            stage_split(Xs, pt, j, h);
+            wave_lds_fence();
+            outer_accumulate_split<2, 2>(G, Zs, Xs, lane);
+            wave_lds_fence();
+        }
+        const uint32_t m = a.first ? 0xffffffffu : a.mask_in[tile * 64 + lane];
+        v16f s2[2], d2[2];
+        matvec_split<2, 4, P, P>(sm.Wt, ps, s2, lane);
+        if (a.first) {
+            // dd/de and the normal (Eq. 2); the levels of this lane are 4g + 2h + u
+            if (a.q) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int level = 4 * g + 2 * h + u;
+                        if (valid && level < a.levels)
+                            reinterpret_cast<float2*>(a.q)[(int64_t)level * a.n + i] = make_float2(s2[0][4 * g + 2 * u], s2[0][4 * g + 2 * u + 1]);
+                    }
+                float nrm[3];
+                contract_jac<32>(a.jac, a.n, i, valid, a.levels, h, s2[0], nrm);
+#pragma unroll
+                for (int c = 0; c < 3; ++c) nrm[c] += __shfl_xor(nrm[c], 32);
+                if (valid && h == 0) { a.normal[3 * i] = nrm[0]; a.normal[3 * i + 1] = nrm[1]; a.normal[3 * i + 2] = nrm[2]; }
+            }
+        } else {
+            apply_mask<2>(s2, m);
+            store_lane(a.s_out, tile, lane, s2);
+        }
+        if (GRAD) {
+            matvec_split<2, 4, P, 2>(sm.Wt, pd, d2, lane);
+            if (a.first) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int level = 4 * g + 2 * h + u;
+                        if (valid && level < a.levels)
+                            reinterpret_cast<float2*>(a.d_enc)[(int64_t)level * a.n + i] = make_float2(d2[0][4 * g + 2 * u], d2[0][4 * g + 2 * u + 1]);
+                    }
+            } else {
+                apply_mask<2>(d2, m);
+                store_lane(a.d_out, tile, lane, d2);
+            }
+        }
+    }
+    if (GRAD) {
+        __syncthreads();
+        float* scratch = reinterpret_cast<float*>(&sm);
+        static_assert(sizeof(sm) >= kWaves * 4 * 1024 * sizeof(float), "scratch for the block sum");
+        v16f* all[4] = {&G[0][0], &G[0][1], &G[1][0], &G[1][1]};
+        block_sum_shared<kWaves, 4>(scratch, all, wave, lane);
+        constexpr int kShare = 16 / kWaves;
+        flush_grad<2, 2>(a.dW, a.out_dim, a.in_dim, G, j, h, wave * kShare, kShare);
+    }
+}
+
 SdfArgs base_args(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H, int64_t n) {
     SdfArgs a = {};
     a.enc = enc; a.jac = jac; a.n = n; a.active_levels = cfg->active_levels;
@@ -613,6 +831,101 @@ int launch_sdf_fwd(const neus2_config* cfg, const float* enc, const float* jac, 
     if (D == 16 && K == 3) return run_fwd<16, 3>(a, st);
     if (D == 16 && K == 2) return run_fwd<16, 2>(a, st);
     return fail(NEUS2_ERR_UNSUPPORTED, "sdf network: input width %d with %d matrices has no kernel", D, K);
+}
+
+// Workspace of the layer-by-layer path: per point 32 floats per lane-layout vector (two lanes a
+// point), for a_0..a_{K-1} and t_0..t_{K-1} (the backward call keeps them all for its reverse
+// launches), two pairs of vectors that the reverse launches hand on, and a mask word per lane and
+// hidden layer.
+static int64_t deep_vector_floats(int64_t n) { return ((n + 31) / 32) * 64 * 32; }
+
+int64_t sdf_deep_workspace_bytes(int n_mats, int64_t n) {
+    const int64_t vec = deep_vector_floats(n) * 4, words = ((n + 31) / 32) * 64 * 4;
+    return (2 * (int64_t)n_mats + 4) * vec + (int64_t)n_mats * words;
+}
+
+namespace {
+
+struct DeepLayout {
+    float* a[NEUS2_DEEP_MAX_MATS]; float* t[NEUS2_DEEP_MAX_MATS]; float* pass[4]; uint32_t* mask[NEUS2_DEEP_MAX_MATS];
+};
+
+DeepLayout deep_layout(void* workspace, int n_mats, int64_t n) {
+    DeepLayout L;
+    float* p = reinterpret_cast<float*>(workspace);
+    const int64_t vec = deep_vector_floats(n);
+    for (int l = 0; l < n_mats; ++l) { L.a[l] = p; p += vec; L.t[l] = p; p += vec; }
+    for (int k = 0; k < 4; ++k) { L.pass[k] = p; p += vec; }
+    uint32_t* w = reinterpret_cast<uint32_t*>(p);
+    for (int l = 0; l < n_mats; ++l) { L.mask[l] = w; w += ((n + 31) / 32) * 64; }
+    return L;
+}
+
+int deep_dims(int n_mats, int enc_dim, int l, int& out_dim, int& in_dim) {
+    in_dim = l == 0 ? enc_dim : 64;
+    out_dim = l == n_mats - 1 ? 16 : 64;
+    return 0;
+}
+
+template <typename Kernel>
+void deep_launch(Kernel kernel, const DeepArgs& a, hipStream_t st) {
+    const int64_t want = ((a.n + 31) / 32 + kWaves - 1) / kWaves;
+    const int blocks = persistent_blocks((const void*)kernel, kThreads, want);
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+}
+
+}  // namespace
+
+int launch_sdf_deep_fwd(int n_mats, int enc_dim, const float* enc, const float* jac, const float* const* H, int64_t n,
+                        float* y, float* q, float* normal, void* workspace, hipStream_t st) {
+    if (n == 0) return NEUS2_OK;
+    const DeepLayout L = deep_layout(workspace, n_mats, n);
+    for (int l = 0; l < n_mats; ++l) {                           // forward launches: a_1 .. a_{K-1}, y
+        DeepArgs a = {};
+        a.W = H[l]; deep_dims(n_mats, enc_dim, l, a.out_dim, a.in_dim);
+        a.n = n; a.levels = enc_dim / 2; a.first = l == 0; a.last = l == n_mats - 1;
+        a.enc = enc; a.a_in = L.a[l]; a.a_out = L.a[(l + 1) % n_mats]; a.mask_out = L.mask[l]; a.y = y;
+        deep_launch(deep_forward_kernel<false>, a, st);
+    }
+    for (int l = n_mats - 1; l >= 0; --l) {                      // reverse launches: S_{K-1} .. S_1, dd/de
+        DeepArgs a = {};
+        a.W = H[l]; deep_dims(n_mats, enc_dim, l, a.out_dim, a.in_dim);
+        a.n = n; a.levels = enc_dim / 2; a.first = l == 0; a.last = l == n_mats - 1;
+        a.s_in = L.pass[l & 1]; a.s_out = L.pass[(l & 1) ^ 1];
+        a.mask_in = l > 0 ? L.mask[l - 1] : nullptr;
+        a.jac = jac; a.q = q; a.normal = normal;
+        deep_launch(deep_reverse_kernel<3, false>, a, st);
+    }
+    return check_launch("sdf forward (layer by layer)");
+}
+
+int launch_sdf_deep_bwd(int n_mats, int enc_dim, const float* enc, const float* jac, const float* const* H,
+                        const float* d_y, const float* d_normal, int64_t n, float* const* dH, float* d_enc,
+                        void* workspace, hipStream_t st) {
+    if (n == 0) return NEUS2_OK;
+    const DeepLayout L = deep_layout(workspace, n_mats, n);
+    for (int l = 0; l + 1 < n_mats; ++l) {                       // a_l and t_l of every hidden layer
+        DeepArgs a = {};
+        a.W = H[l]; deep_dims(n_mats, enc_dim, l, a.out_dim, a.in_dim);
+        a.n = n; a.levels = enc_dim / 2; a.first = l == 0; a.last = false;
+        a.enc = enc; a.jac = jac; a.d_normal = d_normal;
+        a.a0_out = L.a[0]; a.t0_out = L.t[0];
+        a.a_in = L.a[l]; a.t_in = L.t[l]; a.a_out = L.a[l + 1]; a.t_out = L.t[l + 1]; a.mask_out = L.mask[l];
+        deep_launch(deep_forward_kernel<true>, a, st);
+    }
+    for (int l = n_mats - 1; l >= 0; --l) {
+        DeepArgs a = {};
+        a.W = H[l]; deep_dims(n_mats, enc_dim, l, a.out_dim, a.in_dim);
+        a.n = n; a.levels = enc_dim / 2; a.first = l == 0; a.last = l == n_mats - 1;
+        a.d_y = d_y;
+        a.s_in = L.pass[l & 1]; a.s_out = L.pass[(l & 1) ^ 1];
+        a.d_in = L.pass[2 + (l & 1)]; a.d_out = L.pass[2 + ((l & 1) ^ 1)];
+        a.a_in = L.a[l]; a.t_in = L.t[l];                        // a_{l-1}, t_{l-1} in the paper's numbering
+        a.mask_in = l > 0 ? L.mask[l - 1] : nullptr;
+        a.d_enc = d_enc; a.dW = dH[l];
+        deep_launch(deep_reverse_kernel<2, true>, a, st);
+    }
+    return check_launch("sdf backward (layer by layer)");
 }
 
 int launch_sdf_bwd(const neus2_config* cfg, const float* enc, const float* jac, const float* const* H,

@@ -1,6 +1,6 @@
 """The comparison of the paper's Fig. 7 (second-order backward of the SDF network against
-torch.autograd's double backward): both sides against the float64 oracle, at a batch size where
-the two sides differ from each other by more than the library's gradient bar."""
+torch.autograd's double backward, 1 to 8 hidden layers): both sides against the float64 oracle, at a
+batch size where the two sides differ from each other by more than the library's gradient bar."""
 import numpy as np
 import pytest
 
@@ -17,7 +17,7 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / np.linalg.norm(b))
 
 
-@pytest.mark.parametrize("hidden", [1, 2])
+@pytest.mark.parametrize("hidden", [1, 2, 4, 8])
 def test_library_and_autograd_against_the_oracle(hidden):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
@@ -51,8 +51,24 @@ def test_library_and_autograd_against_the_oracle(hidden):
     torch.cuda.synchronize()
     # the oracle's input gradient has, beyond dL/de through (d,g), no term through the normal: q does not depend on e
     # (vanishing second input derivative of a ReLU network), which is what autograd's x.grad holds as well
-    ours_err = [rel(a.cpu().numpy(), b) for a, b in zip(ours_H, dH)] + [rel(ours_x.cpu().numpy(), d_e)]
-    their_err = [rel(a.cpu().numpy(), b) for a, b in zip(their_H, dH)] + [rel(their_x.cpu().numpy(), d_e)]
-    print(f"hidden {hidden}, batch 2^17: relative error against the oracle (weight gradients ..., input gradient): "
-          f"library {['%.1e' % v for v in ours_err]}  autograd {['%.1e' % v for v in their_err]}")
+    # Input gradient, point by point: a hidden unit whose pre-activation is within rounding of zero falls on
+    # different sides of zero in binary32-class and in float64 arithmetic; that point's gradient then differs
+    # by the unit's whole contribution.  Both sides have such points (the deeper the network the more:
+    # about 2e-4 n at 4 and 8 hidden layers, the same number for autograd); they are counted, bounded, and
+    # left out of the norm.
+    def input_gradient_error(x):
+        x = x.cpu().numpy().astype(np.float64)
+        per_point = np.linalg.norm(x - d_e, axis=1) / np.maximum(np.linalg.norm(d_e, axis=1), 1e-300)
+        flipped = per_point > 1e-3
+        return rel(x[~flipped], d_e[~flipped]), int(flipped.sum())
+
+    ours_err = [rel(a.cpu().numpy(), b) for a, b in zip(ours_H, dH)]
+    their_err = [rel(a.cpu().numpy(), b) for a, b in zip(their_H, dH)]
+    ours_x_err, ours_flipped = input_gradient_error(ours_x)
+    their_x_err, their_flipped = input_gradient_error(their_x)
+    print(f"hidden {hidden} ({case['path']}), batch 2^17: relative error against the oracle, weight gradients: "
+          f"library {['%.1e' % v for v in ours_err]}  autograd {['%.1e' % v for v in their_err]}; input gradient: "
+          f"library {ours_x_err:.1e} ({ours_flipped} points with a flipped mask left out)  "
+          f"autograd {their_x_err:.1e} ({their_flipped} left out)")
     assert max(ours_err) <= 1e-4
+    assert ours_x_err <= 1e-4 and ours_flipped <= 5e-4 * n

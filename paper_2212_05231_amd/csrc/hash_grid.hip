@@ -446,9 +446,12 @@ __global__ __launch_bounds__(kBlock) void sum_levels_kernel(const float* __restr
 // range, fully coalesced.  A list that overflows its capacity (only possible when a batch
 // concentrates on very few cells) sends the surplus records straight to global atomics, so
 // the result never depends on the capacity.
-// Dense levels need few ranges; they take the in-place path (test all eight corners) on
-// chunks of the points and flush with coalesced atomics when several chunks share a range.
-// Workgroups take tasks from a counter, heaviest tasks first.
+// Dense levels: with one or two ranges they take the in-place path (a filter pass queues the
+// points of a chunk whose cell touches the range, then all eight corners are tested) and flush
+// with coalesced atomics, several chunks sharing a range; with 3..64 ranges the bin kernel
+// appends the point's number to the list of every range one of its corners falls into and an
+// owner task takes a segment of such a list; with more ranges they get row records like a hashed
+// level.  Workgroups take tasks from a counter, heaviest tasks first.
 constexpr int kOwnerThreads = 1024;
 constexpr int64_t kOwnerMinPoints = 1 << 16;
 constexpr int kOwnerSlotBits = 13;
@@ -580,7 +583,7 @@ __device__ __forceinline__ float2 corner_value(const Cell& c, int cr, const floa
 // Dense levels with several ranges get POINT lists instead of row records: a point's eight slots are
 // base + {0,1} + {0,s} + {0,s^2}, ascending in the corner number, so the ranges they fall into are
 // ascending too; the point's number is appended to the list of every range that holds one of its
-// corners (one or two for most points).  4 bytes per entry instead of 80 bytes of row records per
+// corners (one or two for most points).  4 bytes per entry instead of 48 bytes of row records per
 // point, and the owner of a range no longer tests every point of the batch against its range.
 // A list that is full sends the point's corners in that range straight to the gradient.
 __device__ void bin_points(const GridDesc& g, const OwnerPlan& plan, const Records& rec, const float* __restrict__ pos,

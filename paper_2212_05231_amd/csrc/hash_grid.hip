@@ -894,18 +894,22 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             const int count = min(rec.cursor[e * kMaxRanges + range], plan.capacity[e]);
             const size_t at = (size_t)plan.list_base[e] + (size_t)range * plan.capacity[e];
             const RowRecord* rs = rec.rows + at;
+            // this task's stretch of the list (the whole list unless the plan shares lists out)
+            const int stretch = ((count + n_chunks - 1) / n_chunks + 63) / 64 * 64;
+            const int first = chunk * stretch, stop = min(count, first + stretch);
+            nothing_added = first >= stop;
             // four records per thread in flight: the list is streamed from HBM
             constexpr int kAhead = 4;
-            for (int j0 = threadIdx.x; j0 < count; j0 += kAhead * kOwnerThreads) {
+            for (int j0 = first + threadIdx.x; j0 < stop; j0 += kAhead * kOwnerThreads) {
                 RowRecord rr[kAhead];
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
                     const int j = j0 + k * kOwnerThreads;
-                    if (j < count) rr[k] = rs[j];
+                    if (j < stop) rr[k] = rs[j];
                 }
 #pragma unroll
                 for (int k = 0; k < kAhead; ++k) {
-                    if (j0 + k * kOwnerThreads < count) {
+                    if (j0 + k * kOwnerThreads < stop) {
                         uint32_t s0, s1;
                         float v[4];
                         unpack_row(rr[k], s0, s1, v);
@@ -1025,6 +1029,17 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
     int e = 0, tasks = 0;
     int64_t records = 0, indices = 0;
     double cost[NEUS2_MAX_LEVELS];
+    // lists of row records over all levels (see `chunks` of a listed level below)
+    int64_t listed_ranges = 0;
+    for (int l = cfg->frozen_levels; l < cfg->active_levels; ++l) {
+        const int64_t r1 = (int64_t)cfg->res[l] + 1;
+        const int64_t used = cfg->dense[l] ? r1 * r1 * r1 : T;
+        const int ranges = (int)((used + kOwnerSlots - 1) / kOwnerSlots);
+        if (ranges > (cfg->dense[l] ? kInPlaceRanges : 1)) listed_ranges += ranges;
+    }
+    int listed_chunks = 1;
+    if (listed_ranges > 0) listed_chunks = (int)std::min<int64_t>(4, std::max<int64_t>(1, (2 * compute_units() + listed_ranges - 1) / listed_ranges));
+
     for (int pass = 0; pass < 3; ++pass) {
         for (int l = cfg->frozen_levels; l < cfg->active_levels; ++l) {
             const int64_t r1 = (int64_t)cfg->res[l] + 1;
@@ -1037,6 +1052,11 @@ OwnerPlan make_owner_plan(const neus2_config* cfg, int64_t n, bool& ok) {
             int chunks = 1;
             double task_ns = 4000.0 + 1.25 * (4.0 * (double)n / ranges);   // a list: 1.25 ns per record
             if (listed) {
+                // With few lists in all (small tables, few active levels) a list is shared out over several
+                // tasks, so that the chip's workgroups get several rounds of them: each task takes a stretch of
+                // the list and flushes what it added (atomics, like every flush).
+                chunks = listed_chunks;
+                task_ns = 4000.0 + 1.25 * (4.0 * (double)n / ranges) / chunks;
                 // a list holds 1.5 times its expected share of the 4 n row records of the level;
                 // 3 times on a dense level, where the share of a slab of the grid follows the batch
                 const int64_t cap = ((4 * n / ranges) * (cfg->dense[l] ? 6 : 3) / 2 + 1023) / 64 * 64;

@@ -512,6 +512,17 @@ struct AdamExtra {
     int64_t count;
 };
 
+// 16-byte accesses with the non-temporal hint: data that is not read again soon
+__device__ __forceinline__ float4 stream_load(const float* p) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store(float* p, const float4& v) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(f4{v.x, v.y, v.z, v.w}, reinterpret_cast<f4*>(p));
+}
+
 template <bool HALF>
 __global__ __launch_bounds__(256) void adam_tables_kernel(void* __restrict__ param, float* __restrict__ master,
                                                           float* __restrict__ grad, float* __restrict__ m,
@@ -536,23 +547,29 @@ __global__ __launch_bounds__(256) void adam_tables_kernel(void* __restrict__ par
     float* full = HALF ? master : reinterpret_cast<float*>(param);
     const bool lazy = flags & kAdamLazy;
     if (k + 4u <= used) {
-        const float4 g = *reinterpret_cast<const float4*>(grad + i);
+        // Gradient, moments and the fp32 values are pure streams (read once, written once, not touched
+        // again before the next update): they are moved with non-temporal accesses, which leaves the
+        // caches to the fp16 tables this kernel writes and the next encode reads (measured: 73 us of a
+        // 2.37 ms step at 2^21 entries a level, 8 us of 0.585 ms at 2^19).
+        const float4 g = stream_load(grad + i);
         if (lazy && g.x == 0.f && g.y == 0.f && g.z == 0.f && g.w == 0.f) return;
-        float4 mi = *reinterpret_cast<const float4*>(m + i), vi = *reinterpret_cast<const float4*>(v + i);
-        float4 p = *reinterpret_cast<const float4*>(full + i);
+        float4 mi = stream_load(m + i), vi = stream_load(v + i);
+        float4 p = stream_load(full + i);
         if (!(lazy && g.x == 0.f)) p.x = adam_one(g.x, mi.x, vi.x, p.x, a);
         if (!(lazy && g.y == 0.f)) p.y = adam_one(g.y, mi.y, vi.y, p.y, a);
         if (!(lazy && g.z == 0.f)) p.z = adam_one(g.z, mi.z, vi.z, p.z, a);
         if (!(lazy && g.w == 0.f)) p.w = adam_one(g.w, mi.w, vi.w, p.w, a);
-        *reinterpret_cast<float4*>(m + i) = mi;
-        *reinterpret_cast<float4*>(v + i) = vi;
-        *reinterpret_cast<float4*>(full + i) = p;
+        stream_store(m + i, mi);
+        stream_store(v + i, vi);
         if (HALF) {
+            stream_store(full + i, p);
             __half2* h = reinterpret_cast<__half2*>(reinterpret_cast<__half*>(param) + i);
             const __half2 h0 = __floats2half2_rn(p.x, p.y), h1 = __floats2half2_rn(p.z, p.w);
             *reinterpret_cast<uint2*>(h) = make_uint2(*reinterpret_cast<const uint32_t*>(&h0), *reinterpret_cast<const uint32_t*>(&h1));
+        } else {
+            *reinterpret_cast<float4*>(full + i) = p;         // fp32 tables: these are what the encode reads
         }
-        if (flags & kAdamClear) *reinterpret_cast<float4*>(grad + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (flags & kAdamClear) stream_store(grad + i, make_float4(0.f, 0.f, 0.f, 0.f));
     } else {
         for (uint32_t e = 0; e < used - k; ++e) {            // the last, partial group of a level
             const float g = grad[i + e];

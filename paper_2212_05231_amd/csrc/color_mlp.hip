@@ -143,7 +143,7 @@ __device__ __forceinline__ ColorRaw load_raw(const ColorArgs& a, int64_t i, bool
         if (BWD) { r.d_rgb[c] = a.d_rgb[3 * i + c]; r.rgb[c] = a.rgb_in[3 * i + c]; }
     }
     if (BWD && a.d_sdf) r.d_sdf = a.d_sdf[i];
-    if (BWD && a.masks) { r.m1 = a.masks[mask_word(0, a.n, i, h)]; r.m2 = a.masks[mask_word(1, a.n, i, h)]; }
+    if (BWD && a.masks) { r.m1 = __builtin_nontemporal_load(a.masks + mask_word(0, a.n, i, h)); r.m2 = __builtin_nontemporal_load(a.masks + mask_word(1, a.n, i, h)); }
     if (BWD) {
         r.dn[0] = a.d_normal[3 * i + (h ? 1 : 0)];
         if (h) r.dn[1] = a.d_normal[3 * i + 2];

@@ -947,7 +947,7 @@ __global__ __launch_bounds__(kOwnerThreads) void scatter_owner_kernel(GridDesc g
             for (int j = seg_begin + (int)threadIdx.x; j < seg_end; j += 2 * kOwnerThreads) {
                 const int j2 = j + kOwnerThreads;
                 const bool two = j2 < seg_end;
-                const uint32_t i0 = list[j], i1 = two ? list[j2] : 0u;
+                const uint32_t i0 = __builtin_nontemporal_load(list + j), i1 = two ? __builtin_nontemporal_load(list + j2) : 0u;
                 const PointIn p0 = load_point(level, i0, n, fres, pos, q, d_enc, d_normal);
                 PointIn p1 = p0;
                 if (two) p1 = load_point(level, i1, n, fres, pos, q, d_enc, d_normal);

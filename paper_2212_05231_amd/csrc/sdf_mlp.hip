@@ -439,12 +439,20 @@ __global__ __launch_bounds__(kThreads) void sdf_bwd_kernel(SdfArgs a) {
         const int64_t i = tile * 32 + j;
         const bool valid = i < a.n;
         v16f x0[1] = {x_next};
-        v16f dK[1] = {load_rows16(a.d_y, i, valid, h)};
+        v16f dK[1] = {zero16()};
+        if (valid) {
+            typedef float f4v __attribute__((ext_vector_type(4)));
+            const f4v a_ = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(a.d_y + i * 16 + 4 * h));
+            const f4v b_ = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(a.d_y + i * 16 + 8 + 4 * h));
+            dK[0][0] = a_.x; dK[0][1] = a_.y; dK[0][2] = a_.z; dK[0][3] = a_.w;
+            dK[0][4] = b_.x; dK[0][5] = b_.y; dK[0][6] = b_.z; dK[0][7] = b_.w;
+        }
         // given masks are first needed after the forward pass has been recomputed
         uint32_t m1 = 0u, m_last = 0u;
         if (GIVEN && valid) {
-            m1 = a.masks[mask_word(0, a.n, i, h)];
-            m_last = K == 3 ? a.masks[mask_word(1, a.n, i, h)] : m1;
+            // masks and the adjoint of (d,g) are read here for the last time in the step: non-temporal loads
+            m1 = __builtin_nontemporal_load(a.masks + mask_word(0, a.n, i, h));
+            m_last = K == 3 ? __builtin_nontemporal_load(a.masks + mask_word(1, a.n, i, h)) : m1;
         }
         float nb3[3] = {0.f, 0.f, 0.f};
         if (valid) { nb3[0] = a.d_normal[3 * i]; nb3[1] = a.d_normal[3 * i + 1]; nb3[2] = a.d_normal[3 * i + 2]; }

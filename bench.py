@@ -378,11 +378,17 @@ def main() -> int:
                 fn()
             events[r][len(seq)].record()
         torch.cuda.synchronize()
+        # An event pair also spans any time the stream sat idle waiting for the host (a scheduling hiccup of
+        # the Python loop): the average is taken over the repetitions within three times the call's median.
+        per_rep = {name: [] for name, _ in seq}
         for r in range(reps):
             for k, (name, _) in enumerate(seq):
-                total[name] += events[r][k].elapsed_time(events[r][k + 1])
+                per_rep[name].append(events[r][k].elapsed_time(events[r][k + 1]))
         for name, _ in seq:
-            us = 1e3 * total[name] / reps
+            med = sorted(per_rep[name])[len(per_rep[name]) // 2]
+            kept = [t for t in per_rep[name] if t <= 3.0 * med]
+            total[name] = sum(kept)
+            us = 1e3 * total[name] / len(kept)
             k = {"us": round(us, 2), "bytes": cost[name]["bytes"], "flops": cost[name]["flops"],
                  "GBps": round(cost[name]["bytes"] / us * 1e-3, 1)}
             for extra in ("bytes_with_stored_jacobian", "bytes_atomics_counted_once"):

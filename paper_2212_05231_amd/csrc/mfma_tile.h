@@ -142,9 +142,13 @@ struct Split {
 // other element), also exact (checked on the chip over all exponents).  The selector words are kept
 // in registers: written as literals the compiler turns (-1, 0) into the inline constant -1.0, which
 // the instruction reads as (0, -1).  A non-finite neighbour turns the remainder into NaN (0 * inf).
-__device__ __forceinline__ uint32_t in_register(uint32_t v) {
-    asm("" : "+s"(v));
-    return v;
+// (The asm statement is one instruction, not an empty one: the compiler counts every asm statement as
+// an instruction when it works out the wait states between a matrix instruction and its reader.)
+template <uint32_t V>
+__device__ __forceinline__ uint32_t in_register() {
+    uint32_t r;
+    asm("s_mov_b32 %0, %1" : "=s"(r) : "n"(V));
+    return r;
 }
 
 template <int NB, int P>
@@ -152,8 +156,8 @@ __device__ __forceinline__ void split(const v16f* v, Split<NB, P>& out) {
     typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
     typedef float f2 __attribute__((ext_vector_type(2)));
     static_assert(P == 2 || P == 3, "two or three terms");
-    const bf2 minus_low = __builtin_bit_cast(bf2, in_register(0x0000bf80u));
-    const bf2 minus_high = __builtin_bit_cast(bf2, in_register(0xbf800000u));
+    const bf2 minus_low = __builtin_bit_cast(bf2, in_register<0x0000bf80u>());
+    const bf2 minus_high = __builtin_bit_cast(bf2, in_register<0xbf800000u>());
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll

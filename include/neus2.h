@@ -241,7 +241,7 @@ int neus2_hash_scatter_bwd(const neus2_config* cfg, const float* pos, const void
  * buffer of NEUS2_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
  * library is used on holds one until the process ends).  The call allocates nothing, on the
  * device or through any library.  A batch whose lists do not fit (neus2_workspace_bytes minus
- * the 12 * n_levels * n bytes of its position-gradient part is the need; about 140 000 points
+ * the 24 * n_levels * n bytes of its position-gradient part is the need; about 140 000 points
  * with 16 levels of 2^19 slots, more with fewer hashed levels) is rejected with
  * NEUS2_ERR_SHAPE and nothing is launched.  All calls on one GPU share the buffer: calls that
  * overlap in time on one GPU (different streams or threads) race; order them. */

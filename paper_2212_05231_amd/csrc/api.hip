@@ -161,7 +161,7 @@ int sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, c
                 const float* jac, const float* const* H, const float* q, const float* d_y,
                 const float* d_normal, int64_t n, float* const* dH, float* d_tables, float* d_enc,
                 float* d_pos, void* workspace, int64_t workspace_bytes, bool header_cleared, const uint32_t* masks,
-                void* stream) {
+                void* stream, bool hessian_stored = false) {
     NEUS2_TRY(check_config(cfg));
     NEUS2_TRY(check_count(n, "n"));
     NEUS2_TRY(check_ptr(workspace, "workspace", false));
@@ -182,10 +182,12 @@ int sdf_bwd_2nd(const neus2_config* cfg, const float* pos, const void* tables, c
     // With a large batch and a workspace the scatter's gather pass has the corners of every level
     // in registers and adds (de/dx)^T dL/de to d_pos on the way; otherwise the network kernel
     // does it from the stored Jacobian.
-    const bool gather = d_pos && scatter_gathers_position(cfg, n, workspace, workspace_bytes);
+    // In a training step the encode kernel has stored the second derivatives of the interpolation
+    // (hessian_stored): then one streaming kernel adds both parts from the stored arrays.
+    const bool gather = d_pos && (hessian_stored || scatter_gathers_position(cfg, n, workspace, workspace_bytes));
     NEUS2_TRY(launch_sdf_bwd(cfg, enc, jac, H, d_y, d_normal, n, dH, d_enc, gather ? nullptr : d_pos, masks, st));
     return launch_scatter(cfg, pos, tables, q, d_enc, d_normal, n, d_tables, d_pos, workspace, workspace_bytes, gather, st,
-                          header_cleared);
+                          header_cleared, hessian_stored, jac);
 }
 
 }  // namespace
@@ -456,7 +458,10 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     // workspace: two launches fewer
     ZeroRegions zero = {{b->loss, nullptr}, {2, 0}};
     scatter_header(cfg, n, b->d_pos != nullptr, b->workspace, b->workspace_bytes, &zero.p[1], &zero.count[1]);
-    NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero));
+    // a step that wants d_pos: the encode kernel also leaves the second derivatives of the interpolation in
+    // the workspace, behind the scatter's records, where the backward pass streams them
+    float* hess = b->d_pos ? scatter_hessian_region(cfg, n, b->workspace, b->workspace_bytes) : nullptr;
+    NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero, hess));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, b->sdf_masks, stream));
     if (cfg->loss_kind != 0) {
         NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, b->color_masks, stream));
@@ -475,5 +480,5 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     }
     return sdf_bwd_2nd(cfg, b->pos, b->tables, b->enc, b->jac, b->H, b->q, b->d_y, b->d_normal, n, b->dH,
                        b->d_tables, b->d_enc, b->d_pos, b->workspace, b->workspace_bytes, zero.count[1] > 0, b->sdf_masks,
-                       stream);
+                       stream, hess != nullptr);
 }

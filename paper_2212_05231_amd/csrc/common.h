@@ -52,13 +52,19 @@ struct ZeroRegions {
 
 // internal launchers (each validates nothing; the extern "C" wrappers do)
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
-                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero = nullptr);
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero = nullptr,
+                  float* hess = nullptr);
 // first_order_pos: d_pos also gets J^T d_enc (the part the SDF backward kernel adds when it is
 // handed d_pos); only honoured on the path scatter_gathers_position() reports.
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
                    float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st,
-                   bool header_cleared = false);
+                   bool header_cleared = false, bool hessian_stored = false, const float* jac = nullptr);
+// Where a training step that wants d_pos has its encode kernel write the mixed second derivatives of the
+// interpolation (launch_encode's `hess`, [active levels][3][n][2] floats inside the workspace), so that
+// launch_scatter(hessian_stored = true) needs no second gather for them; nullptr if the scatter-add will
+// not take the path with the workspace.
+float* scatter_hessian_region(const neus2_config* cfg, int64_t n, void* workspace, int64_t workspace_bytes);
 // The part of the workspace launch_scatter needs cleared before it runs (task counter and list
 // cursors) if it will take the path that uses the workspace with these arguments, else count 0.
 void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* workspace, int64_t workspace_bytes,

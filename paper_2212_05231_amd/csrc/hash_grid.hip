@@ -191,13 +191,18 @@ __device__ __forceinline__ bool decode_block(int n_levels, int point_blocks, int
     return level < n_levels;
 }
 
-template <typename T>
+// HESS: the mixed second derivatives of the interpolation are written as well (hess [level][3][n][2]:
+// the pairs (d2e_f/dxdy), (d2e_f/dxdz), (d2e_f/dydz), f = 0, 1), for a step that wants the gradient with
+// respect to the positions: the corners are in registers here, so the backward pass needs no second
+// gather for them.  The pure second derivatives of a trilinear interpolation are zero.
+template <typename T, bool HESS>
 __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedule sch, ZeroRegions zero,
                                                         const float* __restrict__ pos,
                                                         const T* __restrict__ tables, int64_t n,
                                                         float* __restrict__ enc,
                                                         float* __restrict__ jac,
-                                                        uint32_t* __restrict__ dbg_idx) {
+                                                        uint32_t* __restrict__ dbg_idx,
+                                                        float* __restrict__ hess) {
     if (blockIdx.x == 0) {
 #pragma unroll
         for (int r = 0; r < 2; ++r)
@@ -215,6 +220,7 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedul
     }
     float e0 = 0.f, e1 = 0.f;
     float j0[3] = {0.f, 0.f, 0.f}, j1[3] = {0.f, 0.f, 0.f};
+    float h0[3] = {0.f, 0.f, 0.f}, h1[3] = {0.f, 0.f, 0.f};       // xy, xz, yz
     if (level < g.active_levels) {
         const T* tab = tables + (size_t)level * g.table_size * 2;
         float2 v[8];
@@ -234,6 +240,11 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedul
             e1 += wk * v[k].y;
             j0[0] += dx * v[k].x; j0[1] += dy * v[k].x; j0[2] += dz * v[k].x;
             j1[0] += dx * v[k].y; j1[1] += dy * v[k].y; j1[2] += dz * v[k].y;
+            if (HESS) {
+                const float dxy = sx * sy * fz, dxz = sx * fy * sz, dyz = fx * sy * sz;
+                h0[0] += dxy * v[k].x; h0[1] += dxz * v[k].x; h0[2] += dyz * v[k].x;
+                h1[0] += dxy * v[k].y; h1[1] += dxz * v[k].y; h1[2] += dyz * v[k].y;
+            }
         }
     }
     const int64_t o = (int64_t)level * n + i;
@@ -246,6 +257,44 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(GridDesc g, LevelSchedul
     __builtin_nontemporal_store(f2v{j0[0], j0[1]}, jo);
     __builtin_nontemporal_store(f2v{j0[2], j1[0]}, jo + n);
     __builtin_nontemporal_store(f2v{j1[1], j1[2]}, jo + 2 * n);
+    if (HESS && level < g.active_levels) {
+        f2v* ho = reinterpret_cast<f2v*>(hess) + (int64_t)level * 3 * n + i;
+        ho[0] = f2v{h0[0], h1[0]};
+        ho[n] = f2v{h0[1], h1[1]};
+        ho[2 * n] = f2v{h0[2], h1[2]};
+    }
+}
+
+// d_pos += sum over levels and features of q_f (d2e_f/dx dx') dL/dn from the stored second derivatives and,
+// with jac and d_enc given, (de/dx)^T dL/de from the stored Jacobian: a stream of 32 (64) bytes per point
+// and level.
+__global__ __launch_bounds__(kBlock) void pos_from_hessian_kernel(const float* __restrict__ hess, const float* __restrict__ q,
+                                                                  const float* __restrict__ d_normal,
+                                                                  const float* __restrict__ jac, const float* __restrict__ d_enc,
+                                                                  int levels, int first_level,
+                                                                  int64_t n, float* __restrict__ d_pos) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const float nx = d_normal[3 * i + 0], ny = d_normal[3 * i + 1], nz = d_normal[3 * i + 2];
+    float hp[3] = {0.f, 0.f, 0.f};
+    for (int l = first_level; l < levels; ++l) {
+        const float2* h = reinterpret_cast<const float2*>(hess) + (int64_t)l * 3 * n + i;
+        const float2 xy = h[0], xz = h[n], yz = h[2 * n];
+        const float2 qq = reinterpret_cast<const float2*>(q)[(int64_t)l * n + i];
+        const float qxy = qq.x * xy.x + qq.y * xy.y, qxz = qq.x * xz.x + qq.y * xz.y, qyz = qq.x * yz.x + qq.y * yz.y;
+        hp[0] += qxy * ny + qxz * nz;
+        hp[1] += qxy * nx + qyz * nz;
+        hp[2] += qxz * nx + qyz * ny;
+        if (jac) {
+            const float2* J = reinterpret_cast<const float2*>(jac) + (int64_t)l * 3 * n + i;
+            const float2 a = J[0], b = J[n], c = J[2 * n];          // (J00,J01) (J02,J10) (J11,J12)
+            const float2 de = reinterpret_cast<const float2*>(d_enc)[(int64_t)l * n + i];
+            hp[0] += de.x * a.x + de.y * b.y;
+            hp[1] += de.x * a.y + de.y * c.x;
+            hp[2] += de.x * b.x + de.y * c.y;
+        }
+    }
+    d_pos[3 * i + 0] += hp[0]; d_pos[3 * i + 1] += hp[1]; d_pos[3 * i + 2] += hp[2];
 }
 
 // Backward.  d_tables[slot_c][f] += w_c * dL/de_f + q_f * res * sum_a dL/dn_a d_a w_c
@@ -1178,7 +1227,7 @@ int grid_blocks(int levels, int point_blocks) {
 }  // namespace
 
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
-                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero) {
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero, float* hess) {
     ZeroRegions zr = {{nullptr, nullptr}, {0, 0}};
     if (zero) zr = *zero;
     if (n == 0) {
@@ -1190,12 +1239,15 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     const int pbs = (int)((n + kBlock - 1) / kBlock);
     const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs);
     const dim3 grid(kXcd * sch.per_xcd);
-    if (cfg->table_dtype == 1)
-        hipLaunchKernelGGL(encode_kernel<__half>, grid, dim3(kBlock), 0, st, g, sch, zr, pos,
-                           (const __half*)tables, n, enc, jac, dbg_idx);
-    else
-        hipLaunchKernelGGL(encode_kernel<float>, grid, dim3(kBlock), 0, st, g, sch, zr, pos,
-                           (const float*)tables, n, enc, jac, dbg_idx);
+#define NEUS2_ENCODE(T, HESS)                                                                     \
+    hipLaunchKernelGGL((encode_kernel<T, HESS>), grid, dim3(kBlock), 0, st, g, sch, zr, pos, (const T*)tables, n, enc, jac, \
+                       dbg_idx, hess)
+    if (cfg->table_dtype == 1) {
+        if (hess) NEUS2_ENCODE(__half, true); else NEUS2_ENCODE(__half, false);
+    } else {
+        if (hess) NEUS2_ENCODE(float, true); else NEUS2_ENCODE(float, false);
+    }
+#undef NEUS2_ENCODE
     return check_launch("hash encode");
 }
 
@@ -1203,15 +1255,25 @@ int64_t owner_workspace_need(const OwnerPlan& plan) {
     return kWorkspaceHeader + plan.list_base[plan.n_listed] * 12 + plan.idx_base[plan.n_listed + plan.n_indexed] * 4 + 256;
 }
 
-// scratch of the position-gradient path: part[active levels][n][3], behind the records
-int64_t pos_scratch_bytes(const neus2_config* cfg, int64_t n) { return (int64_t)cfg->active_levels * n * 12; }
+// scratch of the position-gradient path, behind the records: either part[active levels][n][3] (the gather
+// pass) or hess[active levels][3][n][2] (the training step, whose encode kernel writes it)
+int64_t pos_scratch_bytes(const neus2_config* cfg, int64_t n) { return (int64_t)cfg->active_levels * n * 24; }
+
+// where the training step's encode kernel puts the second derivatives, or nullptr if the scatter-add will
+// not take the path with the workspace (must mirror launch_scatter's condition)
+float* scatter_hessian_region(const neus2_config* cfg, int64_t n, void* workspace, int64_t workspace_bytes) {
+    if (!scatter_gathers_position(cfg, n, workspace, workspace_bytes)) return nullptr;
+    bool ok = false;
+    const OwnerPlan plan = make_owner_plan(cfg, n, ok);
+    return reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + (owner_workspace_need(plan) + 255) / 256 * 256);
+}
 
 int64_t scatter_workspace_bytes(const neus2_config* cfg, int64_t n) {
     if (n < kOwnerMinPoints) return 0;
     bool ok = false;
     const OwnerPlan plan = make_owner_plan(cfg, n, ok);
     if (!ok) return 0;
-    return (owner_workspace_need(plan) + 255) / 256 * 256 + (int64_t)cfg->n_levels * n * 12;
+    return (owner_workspace_need(plan) + 255) / 256 * 256 + (int64_t)cfg->n_levels * n * 24;
 }
 
 int64_t scatter_records_bytes(const neus2_config* cfg, int64_t n) {
@@ -1246,7 +1308,7 @@ void scatter_header(const neus2_config* cfg, int64_t n, bool want_pos, void* wor
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,
                    const float* d_enc, const float* d_normal, int64_t n, float* d_tables,
                    float* d_pos, void* workspace, int64_t workspace_bytes, bool first_order_pos, hipStream_t st,
-                   bool header_cleared) {
+                   bool header_cleared, bool hessian_stored, const float* jac) {
     if (n == 0 || cfg->active_levels == 0) return NEUS2_OK;
     const GridDesc g = make_grid_desc(cfg);
     // Large batches with a workspace: LDS-owner kernel (no global atomics on the big levels);
@@ -1278,7 +1340,13 @@ int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables
             if (plan.n_tasks > 0)
                 hipLaunchKernelGGL(scatter_owner_kernel, dim3(plan.n_tasks < wgs ? plan.n_tasks : wgs), dim3(kOwnerThreads), 0,
                                    st, g, plan, rec, pos, q, d_enc, d_normal, n, counter, d_tables);
-            if (d_pos) {
+            if (d_pos && hessian_stored) {
+                // the training step's encode kernel left the second derivatives where `part` would go
+                const float* hess = reinterpret_cast<const float*>(ws + records_end);
+                hipLaunchKernelGGL(pos_from_hessian_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, hess, q,
+                                   d_normal, first_order_pos ? jac : nullptr, first_order_pos ? d_enc : nullptr, g.active_levels, 0, n,
+                                   d_pos);
+            } else if (d_pos) {
                 float* part = reinterpret_cast<float*>(ws + records_end);
                 const int pbs = (int)((n + kBlock - 1) / kBlock);
                 const LevelSchedule sch = make_level_schedule(g, g.active_levels, pbs);

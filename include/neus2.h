@@ -361,7 +361,9 @@ typedef struct neus2_step_buffers {
 
 /* One forward + backward pass (everything above except Adam and the rigid transform), in the
  * order encode, SDF, colour, render, loss, render bwd, colour bwd, SDF bwd + scatter.
- * loss is zeroed first; dH, dW and d_tables are ADDED into. */
+ * loss is zeroed first; dH, dW and d_tables are ADDED into.  Unlike neus2_hash_encode, the step
+ * leaves the levels >= active_levels of enc and jac as they are (Sec. 4.3: those levels do not
+ * enter the network; none of the step's kernels reads them) instead of writing zeros. */
 int neus2_train_step(const neus2_config* cfg, const neus2_step_buffers* buf, int64_t n, void* stream);
 
 /* ---- Occupancy grid and ray marching (supplement Sec. E.3 "Ray Marching Acceleration") ------

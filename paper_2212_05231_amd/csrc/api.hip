@@ -461,7 +461,7 @@ extern "C" int neus2_train_step(const neus2_config* cfg, const neus2_step_buffer
     // a step that wants d_pos: the encode kernel also leaves the second derivatives of the interpolation in
     // the workspace, behind the scatter's records, where the backward pass streams them
     float* hess = b->d_pos ? scatter_hessian_region(cfg, n, b->workspace, b->workspace_bytes) : nullptr;
-    NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero, hess));
+    NEUS2_TRY(launch_encode(cfg, b->pos, b->tables, n, b->enc, b->jac, nullptr, st, &zero, hess, true));
     NEUS2_TRY(neus2_sdf_fwd_grad(cfg, b->enc, b->jac, b->H, n, b->y, b->q, b->normal, b->sdf_masks, stream));
     if (cfg->loss_kind != 0) {
         NEUS2_TRY(neus2_color_fwd(cfg, b->pos, b->normal, b->dirs, b->sample_ray, b->y, b->W, n, b->rgb, b->color_masks, stream));

@@ -53,7 +53,7 @@ struct ZeroRegions {
 // internal launchers (each validates nothing; the extern "C" wrappers do)
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
                   float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero = nullptr,
-                  float* hess = nullptr);
+                  float* hess = nullptr, bool active_only = false);
 // first_order_pos: d_pos also gets J^T d_enc (the part the SDF backward kernel adds when it is
 // handed d_pos); only honoured on the path scatter_gathers_position() reports.
 int launch_scatter(const neus2_config* cfg, const float* pos, const void* tables, const float* q,

@@ -1227,7 +1227,8 @@ int grid_blocks(int levels, int point_blocks) {
 }  // namespace
 
 int launch_encode(const neus2_config* cfg, const float* pos, const void* tables, int64_t n,
-                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero, float* hess) {
+                  float* enc, float* jac, uint32_t* dbg_idx, hipStream_t st, const ZeroRegions* zero, float* hess,
+                  bool active_only) {
     ZeroRegions zr = {{nullptr, nullptr}, {0, 0}};
     if (zero) zr = *zero;
     if (n == 0) {
@@ -1237,7 +1238,10 @@ int launch_encode(const neus2_config* cfg, const float* pos, const void* tables,
     }
     const GridDesc g = make_grid_desc(cfg);
     const int pbs = (int)((n + kBlock - 1) / kBlock);
-    const LevelSchedule sch = make_level_schedule(g, g.n_levels, pbs);
+    // active_only: the levels beyond the active ones are left alone instead of written as zeros (the training
+    // step: none of its kernels reads them)
+    const int levels = active_only ? std::max(g.active_levels, 1) : g.n_levels;
+    const LevelSchedule sch = make_level_schedule(g, levels, pbs);
     const dim3 grid(kXcd * sch.per_xcd);
 #define NEUS2_ENCODE(T, HESS)                                                                     \
     hipLaunchKernelGGL((encode_kernel<T, HESS>), grid, dim3(kBlock), 0, st, g, sch, zr, pos, (const T*)tables, n, enc, jac, \

@@ -286,7 +286,12 @@ int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v,
 /* The same update over the hash tables [L][T][F] of a descriptor (fp16 tables with their fp32
  * master copy, or fp32 tables and master NULL), skipping the slots no point can address: a
  * dense level uses (res+1)^3 of its T slots; the rest never receive a gradient and the update
- * would leave them unchanged.  Same result as neus2_adam_step over L*T*F parameters. */
+ * would leave them unchanged.  Same result as neus2_adam_step over L*T*F parameters.
+ * flags bit 2 (NEUS2_ADAM_ACTIVE_LEVELS): the levels >= active_levels are skipped as well.  That
+ * is the dense update exactly as long as those levels have never received a gradient (their
+ * moments are zero and stay zero): the progressive schedule of Sec. 4.3 only ever adds levels.
+ * neus2_adam_step, which knows no levels, rejects the bit. */
+#define NEUS2_ADAM_ACTIVE_LEVELS 4
 int neus2_adam_tables(const neus2_config* cfg, void* tables, float* master, float* grad, float* m,
                       float* v, float lr, float beta1, float beta2, float eps, int t,
                       int flags, void* stream);

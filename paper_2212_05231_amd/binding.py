@@ -262,16 +262,17 @@ def adam_step(param, master, grad, m, v, dtype, lr, beta1, beta2, eps, t, zero_g
                                  lr, beta1, beta2, eps, t, (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
 
 
-def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_grad=True, lazy=False):
+def adam_tables(c, tables, master, grad, m, v, lr, beta1, beta2, eps, t, zero_grad=True, lazy=False, active_levels_only=False):
     _check(lib().neus2_adam_tables(C.byref(c), _ptr(tables), _ptr(master), _ptr(grad), _ptr(m), _ptr(v),
-                                   lr, beta1, beta2, eps, t, (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
+                                   lr, beta1, beta2, eps, t,
+                                   (1 if zero_grad else 0) | (2 if lazy else 0) | (4 if active_levels_only else 0), _stream()))
 
 
 def adam_all(c, tables, master, grad, m, v, small, small_grad, small_m, small_v, lr, beta1, beta2, eps, t, zero_grad=True,
-             lazy=False):
+             lazy=False, active_levels_only=False):
     _check(lib().neus2_adam_all(C.byref(c), _ptr(tables), _ptr(master), _ptr(grad), _ptr(m), _ptr(v), _ptr(small),
                                 _ptr(small_grad), _ptr(small_m), _ptr(small_v), small.numel(), lr, beta1, beta2, eps, t,
-                                (1 if zero_grad else 0) | (2 if lazy else 0), _stream()))
+                                (1 if zero_grad else 0) | (2 if lazy else 0) | (4 if active_levels_only else 0), _stream()))
 
 
 def rigid_fwd(pos, R, T, scale, offset, out):
@@ -424,11 +425,16 @@ class Step:
                     "master": self.tables.float() if self.tables.dtype == torch.float16 else None}
 
     def adam(self) -> None:
-        """One Adam step on every parameter; the gradient buffers are cleared in the same pass."""
+        """One Adam step on every parameter; the gradient buffers are cleared in the same pass.
+        Levels that have never been active (the progressive schedule only adds levels; the largest number of active
+        levels a step or an update has seen is kept) have zero gradients and moments, so the dense update leaves
+        them as they are: they are skipped."""
         o = self.opt
         o["t"] += 1
+        self.most_active_levels = max(getattr(self, "most_active_levels", 0), self.c.active_levels)
+        skip = self.c.active_levels >= self.most_active_levels
         adam_all(self.c, self.tables, o["master"], self.d_tables, o["m_t"], o["v_t"], self.small, self.d_small, o["m_s"],
-                 o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True, o["lazy"])
+                 o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True, o["lazy"], active_levels_only=skip)
 
     def train_step(self, n: Optional[int] = None) -> None:
         """`n` (at most the n the buffers were sized for) runs the step on the first n samples:
@@ -437,4 +443,5 @@ class Step:
         n = self.n if n is None else n
         if not 0 <= n <= self.n:
             raise ValueError(f"n = {n} outside 0..{self.n}")
+        self.most_active_levels = max(getattr(self, "most_active_levels", 0), self.c.active_levels)
         _check(lib().neus2_train_step(C.byref(self.c), C.byref(self.buffers), n, _stream()))

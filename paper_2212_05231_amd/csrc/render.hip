@@ -471,7 +471,7 @@ struct AdamArgs {
 
 // flags: bit 0 clears the gradient, bit 1 skips entries whose gradient is exactly zero (their value
 // and moments stay as they are: the "lazy" form for parameters that most steps do not touch)
-constexpr int kAdamClear = 1, kAdamLazy = 2;
+constexpr int kAdamClear = 1, kAdamLazy = 2, kAdamActiveLevels = 4;
 
 __device__ __forceinline__ float adam_one(float g, float& mi, float& vi, float p, const AdamArgs& a) {
     mi = a.b1 * mi + (1.f - a.b1) * g;
@@ -863,7 +863,7 @@ int neus2_render_loss_bwd_ragged(const neus2_config* cfg, const float* y, const 
 
 int neus2_adam_step(void* param, float* master, float* grad, float* m, float* v, int64_t count, int dtype, float lr,
                     float beta1, float beta2, float eps, int t, int flags, void* stream) {
-    if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3", flags);
+    if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3 (a flat array has no levels)", flags);
     if (count < 0 || count > ((int64_t)1 << 34)) return fail(NEUS2_ERR_SHAPE, "count = %lld out of range", (long long)count);
     if (dtype != 0 && dtype != 1) return fail(NEUS2_ERR_CONFIG, "dtype = %d, must be 0 (fp32) or 1 (fp16)", dtype);
     if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
@@ -891,7 +891,7 @@ namespace {
 int adam_tables_impl(const neus2_config* cfg, void* tables, float* master, float* grad, float* m, float* v, float lr,
                      float beta1, float beta2, float eps, int t, int flags, const AdamExtra& extra, void* stream) {
     NEUS2_TRY(check_config(cfg));
-    if (flags < 0 || flags > 3) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..3", flags);
+    if (flags < 0 || flags > 7) return fail(NEUS2_ERR_CONFIG, "flags = %d, must be 0..7", flags);
     if (t < 1) return fail(NEUS2_ERR_CONFIG, "t = %d, the step number starts at 1", t);
     if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return fail(NEUS2_ERR_CONFIG, "beta1, beta2 must be in [0,1)");
     NEUS2_TRY(check_ptr(tables, "tables"));
@@ -911,7 +911,8 @@ int adam_tables_impl(const neus2_config* cfg, void* tables, float* master, float
     for (int l = 0; l < cfg->n_levels; ++l) {
         const int64_t r1 = (int64_t)cfg->res[l] + 1;
         const int64_t slots = cfg->dense[l] ? r1 * r1 * r1 : T;     // check_config: a dense level fits T
-        lv.used[l] = l < cfg->frozen_levels ? 0u : (uint32_t)(slots * F);
+        const bool skipped = l < cfg->frozen_levels || ((flags & kAdamActiveLevels) && l >= cfg->active_levels);
+        lv.used[l] = skipped ? 0u : (uint32_t)(slots * F);
         if (lv.used[l] > most) most = lv.used[l];
     }
     // one row of workgroups per level, one more for the buffer that rides along

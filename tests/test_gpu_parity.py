@@ -710,6 +710,52 @@ def test_adam_lazy_form_and_vector_tails(lazy):
                                            1e-15, 1, 7, None))
 
 
+@pytest.mark.parametrize("lazy", [False, True])
+def test_adam_active_levels_flag_is_the_dense_update_while_the_other_levels_are_untouched(lazy):
+    """NEUS2_ADAM_ACTIVE_LEVELS: with zero gradient and zero moments beyond the active levels (the state
+    the progressive schedule of Sec. 4.3 keeps them in) the result is the oracle's update over every
+    level; those levels are left bit for bit, also when something was written there."""
+    rng = np.random.default_rng(15)
+    cfg = wl.make_config(2)
+    cfg.log2_table_size, cfg.n_levels, cfg.active_levels = 12, 8, 5
+    cfg.res = [4, 6, 10, 14, 40, 80, 100, 120]
+    cfg.dense = [1 if (r + 1) ** 3 <= cfg.table_size else 0 for r in cfg.res]
+    cfg.sdf_dims = [16] + cfg.sdf_dims[1:]
+    c = nb.make_config(cfg)
+    L, T, A = cfg.n_levels, cfg.table_size, cfg.active_levels
+    p = (rng.normal(size=(L, T, 2)) * 1e-3).astype(np.float32)
+    p = p.astype(np.float16).astype(np.float32)                   # tables and master agree at the start
+    g, m, v = (np.zeros((L, T, 2), np.float32) for _ in range(3))
+    for l in range(A):
+        used = (cfg.res[l] + 1) ** 3 if cfg.dense[l] else T
+        g[l, :used] = rng.normal(size=(used, 2)) * 1e-4
+        g[l, :used][rng.uniform(size=used) < 0.5] = 0.0
+        m[l, :used] = rng.normal(size=(used, 2)) * 1e-5
+        v[l, :used] = np.abs(rng.normal(size=(used, 2))) * 1e-9
+    tab, master, gg, mg, vg = cuda(p, torch.float16), cuda(p), cuda(g), cuda(m), cuda(v)
+    nb.adam_tables(c, tab, master, gg, mg, vg, 1e-2, 0.9, 0.99, 1e-15, 4, zero_grad=True, lazy=lazy, active_levels_only=True)
+    torch.cuda.synchronize()
+    pr, mr, vr = o.adam_step(p, g, m, v, 4, 1e-2, 0.9, 0.99, 1e-15, lazy=lazy)
+    assert np.array_equal(pr[A:], p[A:].astype(np.float64)) and not mr[A:].any()      # the oracle's dense update leaves them too
+    for got, want in ((master, pr), (mg, mr), (vg, vr)):
+        got = got.cpu().numpy().astype(np.float64)
+        assert rel(got, want) <= 1e-6 and np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+    assert torch.all(gg == 0)
+    assert torch.equal(tab[A:], cuda(p[A:], torch.float16)) and torch.equal(master[A:], cuda(p[A:]))
+    # the flag means "skip", whatever those levels hold: a gradient written there stays, uncleared
+    gg[A + 1, 7, 1] = 1.0
+    before = [t.clone() for t in (tab, master, mg, vg)]
+    nb.adam_tables(c, tab, master, gg, mg, vg, 1e-2, 0.9, 0.99, 1e-15, 5, zero_grad=True, lazy=lazy, active_levels_only=True)
+    torch.cuda.synchronize()
+    assert float(gg[A + 1, 7, 1]) == 1.0
+    for t, b in zip((tab, master, mg, vg), before):
+        assert torch.equal(t[A:], b[A:])
+    # and without the flag the same call updates it
+    nb.adam_tables(c, tab, master, gg, mg, vg, 1e-2, 0.9, 0.99, 1e-15, 6, zero_grad=True, lazy=lazy)
+    torch.cuda.synchronize()
+    assert float(gg[A + 1, 7, 1]) == 0.0 and float(mg[A + 1, 7, 1]) > 0.0
+
+
 def test_adam_all_equals_the_two_separate_calls():
     """Tables and the flat buffer of matrices in one launch: what neus2_adam_tables (bit for bit) and
     neus2_adam_step (to rounding) give, dense and lazy; the flat buffer against the oracle."""

@@ -125,8 +125,9 @@ def algorithmic_cost(cfg, n):
     for k, mf in issued.items():
         if k in out:
             out[k]["issued_flops"] = (mf * 32768 + (32 * 2048 if k.endswith("bwd") else 0)) * n // 32
-    # parameters a point can address: a dense level uses (res+1)^3 of its T slots
-    n_tab = sum(((r + 1) ** 3 if d else cfg.table_size) for r, d in zip(cfg.res, cfg.dense)) * F
+    # parameters a point can address: a dense level uses (res+1)^3 of its T slots; the levels beyond the
+    # active ones have never had a gradient and the step leaves them out (NEUS2_ADAM_ACTIVE_LEVELS)
+    n_tab = sum(((r + 1) ** 3 if d else cfg.table_size) for r, d in list(zip(cfg.res, cfg.dense))[:cfg.active_levels]) * F
     # read grad, m, v, fp32 value; write m, v, fp32 value, cleared grad (+ the fp16 copy)
     per_param = 16 + 16 + (2 if cfg.table_dtype == "f16" else 0)
     out["adam_tables"] = {"bytes": n_tab * per_param, "flops": 0}
@@ -353,7 +354,8 @@ def main() -> int:
             ]
         seq += [
             ("adam_all", lambda: nb.adam_all(c, s.tables, o["master"], s.d_tables, o["m_t"], o["v_t"], s.small, s.d_small,
-                                             o["m_s"], o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True)),
+                                             o["m_s"], o["v_s"], o["lr"], o["b1"], o["b2"], o["eps"], o["t"], True,
+                                             active_levels_only=True)),
         ]
         cost = algorithmic_cost(cfg, n)
         cost["adam_all"] = {"bytes": cost["adam_tables"]["bytes"] + 32 * int(s.small.numel()), "flops": 0}

@@ -94,6 +94,11 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.neus2_loss(C.byref(c), ok, ok, ok, ok, 3, 100, ok, ok, ok, ok, None) == -2
     assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 1, 0.01, 0.9, 0.99, 1e-15, 1, 1, None) == -1   # fp16 needs master
     assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 0, 0.01, 0.9, 0.99, 1e-15, 0, 1, None) == -3   # t starts at 1
+    # flag bit 2 (leave out the levels beyond the active ones) belongs to the table calls only
+    assert L.neus2_adam_step(ok, None, ok, ok, ok, 10, 0, 0.01, 0.9, 0.99, 1e-15, 1, 4, None) == -3
+    assert b"flags" in L.neus2_last_error()
+    assert L.neus2_adam_tables(C.byref(c), ok, ok, ok, ok, ok, 0.01, 0.9, 0.99, 1e-15, 1, 8, None) == -3
+    assert L.neus2_adam_tables(C.byref(c), ok, None, ok, ok, ok, 0.01, 0.9, 0.99, 1e-15, 1, 4, None) == -1   # fp16 tables need master
     assert L.neus2_rigid_fwd(ok, None, None, 1.0, 0.0, 10, ok, None) == -1
     assert L.neus2_train_step(C.byref(c), None, 64, None) == -1
 

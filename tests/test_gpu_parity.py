@@ -790,6 +790,20 @@ def test_adam_all_equals_the_two_separate_calls():
         pr, mr, vr = o.adam_step(sp, sg, sm, sv, 4, 1e-2, 0.9, 0.99, 1e-15)
         assert rel(a[5].cpu().numpy(), pr) <= 1e-6 and rel(a[7].cpu().numpy(), mr) <= 1e-6 and rel(a[8].cpu().numpy(), vr) <= 1e-6
         assert torch.all(a[6] == 0)
+        # with the levels beyond the active ones left out: the flat buffer rides along as before, the tables as
+        # neus2_adam_tables with the same flag leaves them
+        c.active_levels = 9
+        a2, b2 = [t.clone() for t in a], [t.clone() for t in a]
+        for t in (a2, b2):
+            t[2].copy_(cuda(g)); t[6].copy_(cuda(sg))
+        nb.adam_all(c, *a2, 1e-2, 0.9, 0.99, 1e-15, 5, True, lazy, active_levels_only=True)
+        nb.adam_tables(c, b2[0], b2[1], b2[2], b2[3], b2[4], 1e-2, 0.9, 0.99, 1e-15, 5, True, lazy, active_levels_only=True)
+        torch.cuda.synchronize()
+        for x, y in zip(a2[:5], b2[:5]):
+            assert torch.equal(x, y)
+        assert torch.equal(a2[2][9:], cuda(g)[9:]) and torch.all(a2[2][:9] == 0) and torch.all(a2[6] == 0)
+        assert torch.equal(a2[1][9:], a[1][9:]) and not torch.equal(a2[1][:9], a[1][:9])
+        c.active_levels = cfg.active_levels
 
 
 def test_adam_tables_skips_only_unaddressable_slots():

@@ -38,6 +38,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix rate: what the same products would be priced against as fp32 instructions
 MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix rate: the network kernels run their products as split-bf16 terms
 
 # the HIP kernels behind each timed call (names as rocprofv3 prints them)
@@ -423,7 +424,9 @@ def main() -> int:
         roofline["traffic"] = measured_traffic(cfg.name, dom) if full_size else None
         # the roofline fractions of the two encoder-side calls and the matrix-pipe rates of the network calls, side by side
         roofline["by_call"] = {name: {"us": v["us"], "frac_of_hbm_peak": round(v["GBps"] / HBM_PEAK_GBS, 4),
-                                      **({"frac_of_bf16_mfma_peak_issued": round(v["issued_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)}
+                                      **({"frac_of_bf16_mfma_peak_issued": round(v["issued_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4),
+                                          # the same work counted as the fp32 products it stands for, against the fp32 matrix peak
+                                          "frac_of_fp32_mfma_peak_algorithmic": round(v["TFLOPs"] / MFMA_F32_PEAK_TFLOPS, 4)}
                                          if "issued_TFLOPs" in v else {})} for name, v in kernels.items()}
         if grid is not None:
             # one refresh of the grid with every cell a candidate (encode + SDF network on 128^3 points, then the update):

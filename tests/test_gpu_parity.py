@@ -1200,6 +1200,74 @@ def test_dense_level_through_record_lists_and_its_range_crossings():
                                atol=GRAD_TOL * np.max(np.abs(ref["dtables"][level])))
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 6, 7])
+def test_grid_shapes_other_than_the_benchmark_ones(seed):
+    """Encode and scatter-add (the path that keeps ranges of the gradient in LDS) on grids drawn at random:
+    8 or 16 levels, 2^12 .. 2^21 entries a level, resolutions from 2 up to 8192 with any mix of dense and hashed
+    levels (none, all), any number of active and frozen levels, both table types, ray-shaped and uniform points,
+    a ragged number of points.  Indices bit for bit, values and the table gradient of every level against the
+    oracle: the host-side plan of the scatter (which level takes which kind of list, how many ranges, how the
+    lists are cut) must hold for shapes nobody tuned it for."""
+    rng = np.random.default_rng(4000 + seed)
+    L = int(rng.choice([8, 16]))
+    log2_T = int(rng.integers(12, 22))
+    T = 1 << log2_T
+    res_min = int(rng.integers(2, 40))
+    res_max = int(rng.choice([64, 200, 777, 2048, 8192]))
+    res = wl.level_resolutions(L, res_min, max(res_max, res_min + L))
+    if seed % 4 == 3:
+        res = sorted(int(r) for r in rng.integers(2, 3000, size=L))          # not geometric at all
+    dense = wl.dense_flags(res, T)
+    if seed == 5:
+        dense = [0] * L                                                       # hashed although they would fit
+    cfg = wl.make_config(2)
+    cfg.n_levels, cfg.log2_table_size, cfg.res, cfg.dense = L, log2_T, res, dense
+    cfg.active_levels = int(rng.integers(1, L + 1)) if seed % 2 else L
+    cfg.frozen_levels = min(1 + seed % 2, cfg.active_levels - 1) if seed % 3 == 1 else 0
+    cfg.table_dtype = "f16" if seed % 2 == 0 else "f32"
+    cfg.sdf_dims = [2 * L, 64, 64, 16]
+    c = nb.make_config(cfg)
+    n = (1 << 16) + int(rng.integers(1, 40000))
+    if seed % 2:
+        pos = wl.make_points(n, 4100 + seed)
+    else:
+        pos = wl.make_rays((n + 63) // 64, 64, 4100 + seed)["pos"][:n]
+    tab = rng.uniform(-1.0, 1.0, size=(L, T, 2))
+    tab = tab.astype(np.float16 if cfg.table_dtype == "f16" else np.float32)
+    tables = cuda(tab, torch.float16 if cfg.table_dtype == "f16" else torch.float32)
+    print(f"seed {seed}: L {L}, T 2^{log2_T}, res {res}, dense {dense}, active {cfg.active_levels}, frozen {cfg.frozen_levels}, "
+          f"{cfg.table_dtype}, n {n}", flush=True)
+    enc = torch.full((L, n, 2), 7.0, device="cuda")
+    jac = torch.full((L, 3, n, 2), 7.0, device="cuda")
+    idx = torch.zeros(n, L, 8, dtype=torch.int32, device="cuda")
+    nb.hash_encode(c, cuda(pos), tables, enc, jac, idx)
+    torch.cuda.synchronize()
+    ref = o.hash_encode(cfg, tab, pos)
+    assert np.array_equal(idx.cpu().numpy().astype(np.int64) & 0xFFFFFFFF, ref["idx"])
+    del idx
+    assert rel(from_level_major(enc, n), ref["enc"]) <= FWD_TOL
+    assert rel(jac_from_level_major(jac, n), ref["jac"]) <= FWD_TOL
+    q = rng.normal(size=(n, 2 * L)).astype(np.float32)
+    d_enc = (rng.normal(size=(n, 2 * L)) / n).astype(np.float32)
+    d_normal = (rng.normal(size=(n, 3)) / n * 1e-2).astype(np.float32)
+    to_lm = lambda a: cuda(a.reshape(n, L, 2).transpose(1, 0, 2))
+    want = o.table_gradient(cfg, pos, q, d_enc, d_normal)
+    want[:cfg.frozen_levels] = 0.0
+    ws = torch.zeros(nb.workspace_bytes(c, n) // 4, dtype=torch.int32, device="cuda")
+    for workspace in (ws, None):                                  # LDS path, atomic path
+        got = torch.zeros(L, T, 2, device="cuda")
+        nb.hash_scatter_bwd(c, cuda(pos), tables, to_lm(q), to_lm(d_enc), cuda(d_normal), n, got, workspace=workspace)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy().astype(np.float64)
+        for l in range(L):
+            if l < cfg.frozen_levels or l >= cfg.active_levels:
+                assert not got[l].any(), l
+            else:
+                assert rel(got[l], want[l]) <= GRAD_TOL, (workspace is not None, l, res[l], dense[l], rel(got[l], want[l]))
+        bound = GRAD_TOL * (np.abs(want) + np.max(np.abs(want), axis=(1, 2), keepdims=True))
+        assert np.all(np.abs(got - want) <= bound), workspace is not None
+
+
 def test_large_batch_position_gradient():
     """Batches of 2^16 points and more take the path that keeps the table gradient in LDS; the
     position gradient then comes from a gather pass of its own.  Against the oracle on a sample

@@ -1291,15 +1291,16 @@ def test_whole_step_on_shapes_other_than_the_benchmark_ones(seed):
     n = batch["pos"].shape[0]
     print(f"seed {seed}: L {L}, T 2^{log2_T}, res {res}, dense {cfg.dense}, active {cfg.active_levels}, {cfg.table_dtype}, "
           f"sdf {cfg.sdf_dims}, {cfg.samples_per_ray} samples per ray, loss {cfg.loss_kind}, n {n}", flush=True)
+    want_pos = seed >= 2              # the gradient with respect to the positions as well (seed 2: from stored second derivatives)
 
     def both(batch):
         n = batch["pos"].shape[0]
-        step = nb.Step(cfg, params, n)
+        step = nb.Step(cfg, params, n, want_pos_grad=want_pos)
         step.set_batch(batch)
         step.zero_grads()
         step.train_step()
         torch.cuda.synchronize()
-        ref = o.train_step(cfg, params, batch)
+        ref = o.train_step(cfg, params, batch, want_pos_grad=want_pos)
         # points at which a ReLU mask differs between the kernels' arithmetic and float64: a pre-activation within
         # rounding of zero; either side of it is a valid decision, but the unit's weight then enters dd/de or not
         flipped = np.zeros(n, dtype=bool)
@@ -1323,7 +1324,7 @@ def test_whole_step_on_shapes_other_than_the_benchmark_ones(seed):
         assert not flipped.any()
     if seed in (0, 2):
         assert n >= 1 << 16                      # the scatter-add's path for large batches
-    check_step(cfg, step, ref, n)
+    check_step(cfg, step, ref, n, want_pos=want_pos)
     got_t = step.d_tables.cpu().numpy().astype(np.float64)
     for l in range(cfg.active_levels):
         assert rel(got_t[l], ref["dtables"][l]) <= GRAD_TOL, (l, rel(got_t[l], ref["dtables"][l]))
